@@ -1,0 +1,222 @@
+/*
+ * libhsd - Hierarchical Speculative Decoding (HSD) hot path for AMD MI355X (gfx950).
+ *
+ * C ABI.  Conventions for every entry point:
+ *   - returns HSD_OK (0) or a negative status; hsd_last_error() gives the message of the last
+ *     failure on the calling thread;
+ *   - pointers named *_dev are device (HBM) pointers, everything else is host memory;
+ *   - the library never allocates or frees device memory: the caller owns every device buffer and
+ *     sizes them with the hsd_*_bytes() helpers; buffers must stay alive while the object uses them;
+ *   - all device work is enqueued on the hipStream_t (passed as void*) given at creation / call;
+ *     calls that return host results synchronise that stream before returning;
+ *   - host output arrays are caller-owned with explicit capacities;
+ *   - objects are not thread-safe; calls on one hierarchy must not overlap.
+ *
+ * Paper references are to "Fast Inference via Hierarchical Speculative Decoding": Sec. 2 (speculative
+ * sampling rule), Sec. 3 (Alg. 1, Thm 3.1, Thm 3.2), Sec. 4 (Cor. 4.1, HSD problem, reduction),
+ * App. B.1 (Alg. 2, Verify).
+ */
+#ifndef HSD_H
+#define HSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { HSD_OK = 0, HSD_EINVAL = -1, HSD_ECAPACITY = -2, HSD_ESTATE = -3, HSD_EHIP = -4 };
+enum { HSD_F32 = 0, HSD_BF16 = 1 };
+enum { HSD_MAX_LEVELS = 8, HSD_MAX_PASS_ROWS = 64, HSD_KV_PAGE = 64 };
+
+typedef struct hsd_model hsd_model;
+typedef struct hsd_hier hsd_hier;
+
+/* ---------------------------------------------------------------------------------------------
+ * Language model M_i (Sec. 3.2: M_i(context) -> next-token distribution p; an early-exit model is
+ * the hidden state after layer i passed through an output head, Sec. 5.1).  Pre-norm decoder:
+ * RMSNorm, rotary embedding (half-split pairing, angle pos * base^(-2j/hd)), grouped-query causal
+ * attention over a paged KV cache, SwiGLU FFN, final RMSNorm + untied head shared by every exit.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    int n_layers, d, n_q, n_kv, hd, ffn, vocab;
+    int dtype;       /* HSD_F32: fp32 weights, KV and operands (FMA kernels);
+                        HSD_BF16: bf16 weights, KV and GEMM operands, fp32 accumulation (MFMA kernels) */
+    float rope_base; /* e.g. 10000 */
+    float eps;       /* RMSNorm epsilon, inside the square root */
+    int max_seq;     /* KV capacity in tokens, multiple of HSD_KV_PAGE */
+    int max_rows;    /* most tokens one pass may process, 1..HSD_MAX_PASS_ROWS */
+} hsd_model_desc;
+
+/* Device bytes of the packed weights / the paged KV cache / per-model activation scratch. */
+size_t hsd_model_weight_bytes(const hsd_model_desc*);
+size_t hsd_model_kv_bytes(const hsd_model_desc*);
+size_t hsd_model_scratch_bytes(const hsd_model_desc*);
+
+/* Creates a model over caller-owned device buffers (sizes as above, 256-byte aligned).  Weights are
+ * undefined until loaded.  The physical KV page order starts as identity; see hsd_model_set_pages. */
+int hsd_model_create(const hsd_model_desc*, void* weights_dev, void* kv_dev, void* scratch_dev,
+                     void* stream, hsd_model** out);
+void hsd_model_destroy(hsd_model*);
+
+/* Logical weights of one layer, row-major [out_features, in_features], element type = desc.dtype
+ * (norm weights always fp32).  The library re-lays them into its streaming format inside
+ * weights_dev (MFMA operand tiles; q/k/v fused, gate/up interleaved); the source buffers may be
+ * freed after the call returns (it synchronises the stream). */
+typedef struct {
+    const void *norm1_dev, *wq_dev, *wk_dev, *wv_dev, *wo_dev, *norm2_dev, *wg_dev, *wu_dev, *wd_dev;
+} hsd_layer_weights;
+int hsd_model_load_layer(hsd_model*, int layer, const hsd_layer_weights*);
+/* embed [vocab, d], head [vocab, d] (dtype), norm_f [d] fp32. */
+int hsd_model_load_head(hsd_model*, const void* embed_dev, const void* head_dev, const void* norm_f_dev);
+
+/* Physical page of logical KV page i (a permutation of 0..max_seq/HSD_KV_PAGE-1). */
+int hsd_model_set_pages(hsd_model*, const int32_t* page_table, int n_pages);
+
+/* One multi-token pass ("run the verifier in parallel on all prefixes", Alg. 2): feeds `m` tokens
+ * (device int32) at positions pos0..pos0+m-1 through the first `exit_layer` layers, appends their
+ * K/V to the cache (rows < pos0 must already be valid) and, if n_logit_rows > 0, writes the fp32
+ * logits of the last n_logit_rows tokens to logits_dev [n_logit_rows, vocab].  1 <= m <= max_rows. */
+int hsd_model_pass(hsd_model*, const int32_t* tokens_dev, int pos0, int m, int exit_layer,
+                   int n_logit_rows, float* logits_dev);
+
+/* ---------------------------------------------------------------------------------------------
+ * Stand-alone kernels of the path (each is what the pass / the driver launches internally).
+ * ------------------------------------------------------------------------------------------- */
+
+/* p = softmax(z / temperature) row-wise, fp32 [rows, vocab]; temperature == 0 writes the one-hot
+ * row at the lowest-index maximum.  In-place allowed. */
+int hsd_softmax(const float* logits_dev, float* probs_dev, int rows, int vocab, float temperature,
+                void* stream);
+
+/* Bytes of device scratch hsd_accept_resample needs for a vocabulary size. */
+size_t hsd_sampler_scratch_bytes(int vocab);
+
+/* Alg. 2 after the verifier pass, fused in one launch.  p_dev: rows p_1..p_{t+1} [t+1, vocab];
+ * q_dev: rows q_1..q_t [t, vocab] (ignored when t == 0); x_dev: int32 [t+1], x_1..x_t on entry.
+ * For i = 1..t: u_i = top 24 bits of Philox4x32-10(key = seed, counter = (i-1, call, level, 0))
+ * word 0, times 2^-24; draft i is accepted iff fl32(u_i * q_i(x_i)) < p_i(x_i); n = number accepted
+ * before the first rejection.  The final token m is drawn from max(0, p_{n+1} - q_{n+1}) if n < t,
+ * else from p_{t+1}, by the integer rule: w_x = floor(r_x * 2^62), threshold =
+ * floor(sum(w) * U / 2^32) with U = word 1 of the block with counter (t, call, level, 0), m = the
+ * smallest x whose inclusive prefix sum exceeds the threshold (p_{n+1} alone is used if the residual
+ * sums to zero).  Writes result_dev[0] = n, result_dev[1] = m and x_dev[n] = m.  t == 0 draws one
+ * token from p_1 (base-level drafting, Alg. 1; bonus-token rule).  scratch_dev must be zero on first
+ * use; the kernel leaves it zeroed.  Asynchronous on `stream`. */
+int hsd_accept_resample(const float* p_dev, const float* q_dev, int32_t* x_dev, int t, int vocab,
+                        uint64_t seed, uint32_t level, uint32_t call, int32_t* result_dev,
+                        void* scratch_dev, void* stream);
+
+/* Small-M weight-streaming GEMM y = x W^T.  hsd_pack_weight lays W [n, k] (row-major, dtype) out in
+ * the streaming format (packed_dev: hsd_packed_bytes(n, k, dtype)); hsd_gemm computes
+ * y_dev [m, n] fp32 = x_dev [m, k] (dtype) times the packed matrix.  k must be a multiple of 32,
+ * 1 <= m <= HSD_MAX_PASS_ROWS.  workspace_dev: hsd_gemm_workspace_bytes(m, n, k). */
+size_t hsd_packed_bytes(int n, int k, int dtype);
+size_t hsd_gemm_workspace_bytes(int m, int n, int k);
+int hsd_pack_weight(const void* w_dev, void* packed_dev, int n, int k, int dtype, void* stream);
+int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int n, int k, int dtype,
+             void* workspace_dev, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Hierarchy M_0..M_K with parameters T_0..T_{K-1} (Alg. 1).  Level 0 drafts autoregressively,
+ * level K is the target.  Levels that name the same hsd_model are early exits of one network and
+ * share its KV cache; all levels must share the vocabulary (Sec. 2).
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    hsd_model* model;
+    int exit_layer;        /* 1..n_layers */
+} hsd_level;
+
+size_t hsd_hier_workspace_bytes(int n_levels, const hsd_level* levels, const int* T);
+
+/* T has n_levels-1 entries, each >= 1.  temperature 0 = greedy (one-hot rows).  seed keys every
+ * Philox draw: counter = (slot, call, level, 0) where call counts the level's Verify calls (draft
+ * steps for level 0). */
+int hsd_hier_create(int n_levels, const hsd_level* levels, const int* T, float temperature,
+                    uint64_t seed, void* workspace_dev, size_t workspace_bytes, void* stream,
+                    hsd_hier** out);
+void hsd_hier_destroy(hsd_hier*);
+
+/* Resets the hierarchy to the context `prompt` (n >= 1 tokens): fills every model's KV cache for
+ * prompt[0..n-2]; the last prompt token is fed by the first pass of each level.  Counters restart. */
+int hsd_prefill(hsd_hier*, const int32_t* prompt, int n);
+/* Drops everything after the first n tokens of the sequence (n >= 1) and restarts the Philox call
+ * counters and statistics, keeping the KV cache of the first n-1 tokens: used to repeat a
+ * generation from the same prompt without repeating the prefill. */
+int hsd_rewind(hsd_hier*, int n);
+
+/* Base case of Alg. 1: level 0 generates k tokens autoregressively after the current sequence.
+ * tokens_out (cap k, may be NULL) receives them; *probs_dev_out the k distribution rows [k, vocab]
+ * (borrowed, valid until the level's next draft). */
+int hsd_draft(hsd_hier*, int k, int32_t* tokens_out, const float** probs_dev_out);
+
+/* Verify (Alg. 2) at `level` >= 1: the last t tokens of the sequence are the drafts x_1..x_t; if
+ * draft_tokens != NULL they are first appended to the sequence from this host array.
+ * draft_probs_dev: rows q_1..q_t.  Runs the level's pass over its uncached tokens, the rejection
+ * rule and the corrected / bonus draw.  tokens_out (cap t+1): x_1..x_n, m; *n_out = n+1;
+ * *probs_dev_out: rows p_1..p_{n+1} (borrowed, valid until the level's next verify with
+ * append == 0).  append != 0 stores the rows after those of the level's previous verify (how an
+ * intermediate level collects its batch in Alg. 1).  The sequence afterwards ends with m and every
+ * level at or below `level` forgets KV beyond the accepted prefix. */
+int hsd_verify(hsd_hier*, int level, const int32_t* draft_tokens, const float* draft_probs_dev, int t,
+               int append, int32_t* tokens_out, int* n_out, const float** probs_dev_out);
+
+/* HSD(level, context) of Alg. 1 for any level (level = K: one round of the target).  tokens_out
+ * receives the tokens the call appended (at least T_level for an intermediate level), *n_out their
+ * number, *probs_dev_out their distribution rows (may be NULL). */
+int hsd_run(hsd_hier*, int level, int32_t* tokens_out, int cap, int* n_out, const float** probs_dev_out);
+
+typedef struct {
+    int64_t passes[HSD_MAX_LEVELS];    /* forward passes per level */
+    int64_t pass_rows[HSD_MAX_LEVELS]; /* tokens fed, summed over passes */
+    int64_t drafted[HSD_MAX_LEVELS];   /* draft tokens offered to the level's Verify */
+    int64_t accepted[HSD_MAX_LEVELS];  /* of those, accepted */
+    int64_t rounds;                    /* HSD(K, .) calls */
+    int64_t tokens;                    /* tokens emitted by the target level */
+} hsd_stats;
+
+/* Calls HSD(K, .) until n_tokens are produced; the last round is cut at n_tokens (the sequence keeps
+ * the surplus).  out: cap n_tokens.  stats may be NULL. */
+int hsd_generate(hsd_hier*, int n_tokens, int32_t* out, hsd_stats* stats);
+int hsd_get_stats(const hsd_hier*, hsd_stats*);
+int hsd_sequence_length(const hsd_hier*);
+
+/* c_i of Sec. 3.2 measured on the device: mean milliseconds of `iters` passes of `level` over the
+ * last m tokens of the current sequence (m-1 "drafts" + the token before them; state unchanged). */
+int hsd_measure_pass(hsd_hier*, int level, int m, int iters, double* ms_out);
+
+/* ---------------------------------------------------------------------------------------------
+ * Host-side latency model and hierarchy selection (Sec. 3.3, Sec. 4).  No GPU involved.
+ * ------------------------------------------------------------------------------------------- */
+
+/* gamma(alpha, T_i, T_j) of Sec. 3.3: expected draft+verify rounds for a level that needs T_j tokens
+ * and is fed T_i drafts per round, acceptances IID with rate alpha. */
+double hsd_gamma(double alpha, int Ti, int Tj);
+
+/* Expected latency per token of the hierarchy with costs c_0..c_K (n = K+1 entries), adjacent
+ * acceptance rates alpha_{i,i+1} (n-1 entries) and T (n-1 entries).  exact_overshoot == 0: Thm 3.2 /
+ * Cor. 4.1 as printed; != 0: expectation of Alg. 1 as written, where a level hands up every token it
+ * collected (at least T_idx).  Returns a negative value on invalid arguments. */
+double hsd_expected_latency(int n, const double* cost, const double* alpha_adj, const int* T,
+                            int exact_overshoot);
+
+/* HSD problem of Sec. 4.2: min over ordered subsets sigma ending in the target (model n_models-1)
+ * and T in [1, Tbar] of the Cor. 4.1 latency.  alpha is n_models x n_models row-major, entries
+ * i < j used.  monotone_T != 0 keeps the paper's edge set (a level's T is >= the T of the level
+ * below).  sigma_out (cap n_models) ascending model indices, T_out (cap n_models-1), *n_sigma their
+ * count (1 = plain decoding is best). */
+int hsd_select_hierarchy(int n_models, const double* cost, const double* alpha, int Tbar, int monotone_T,
+                         int* sigma_out, int* T_out, int* n_sigma, double* latency_out);
+
+/* Single-draft baseline of Sec. 5.2: best (drafter, T) under the K = 1 closed form.  *drafter_out = -1
+ * when plain decoding is best. */
+int hsd_best_single_draft(int n_models, const double* cost, const double* alpha, int Tbar,
+                          int* drafter_out, int* T_out, double* latency_out);
+
+const char* hsd_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HSD_H */

@@ -153,10 +153,13 @@ class Level:
         self.temperature = temperature
         self.logit_hook = logit_hook
         self.last_logits = None
+        self.min_top2_gap = float("inf")     # smallest gap between the two largest logits of any row seen
 
     def next_dists(self, context, n_rows):
         z = self.decoder.next_logits(context, n_rows, self.exit_layer)
         if self.logit_hook is not None:
             z = self.logit_hook(z, context, n_rows)
         self.last_logits = z
+        top2 = np.partition(np.asarray(z, dtype=np.float64), -2, axis=-1)[:, -2:]
+        self.min_top2_gap = min(self.min_top2_gap, float(np.min(top2[:, 1] - top2[:, 0])))
         return distributions(z, self.temperature)

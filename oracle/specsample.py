@@ -44,23 +44,29 @@ def fixed_weights(r):
     return np.floor(r * _TWO62).astype(np.uint64)
 
 
-def sample_weights(w, U32):
-    """Token index from integer weights and one 32-bit word; None if all weights are zero."""
+def sample_weights(w, U32, margins=None):
+    """Token index from integer weights and one 32-bit word; None if all weights are zero.
+    `margins` (a list) receives the distance of the threshold to the nearer end of the chosen
+    token's interval, as a fraction of the total: how far a perturbed row could move it."""
     S = int(np.sum(w, dtype=np.uint64))
     if S == 0:
         return None
     thr = (S * int(U32)) >> 32
     pref = np.cumsum(w, dtype=np.uint64)
-    return int(np.searchsorted(pref, np.uint64(thr), side="right"))
+    m = int(np.searchsorted(pref, np.uint64(thr), side="right"))
+    if margins is not None:
+        lo = int(pref[m - 1]) if m > 0 else 0
+        margins.append(min(thr - lo, int(pref[m]) - thr) / S)
+    return m
 
 
-def sample_row(p, q, U32):
+def sample_row(p, q, U32, margins=None):
     """m ~ Normalize(max(0, p - q)) (q given) or m ~ p (q None), fixed-point rule."""
     if q is not None:
-        m = sample_weights(fixed_weights(residual_row(p, q)), U32)
+        m = sample_weights(fixed_weights(residual_row(p, q)), U32, margins)
         if m is not None:
             return m
-    m = sample_weights(fixed_weights(np.asarray(p, dtype=np.float32)), U32)
+    m = sample_weights(fixed_weights(np.asarray(p, dtype=np.float32)), U32, margins)
     if m is None:
         raise ValueError("distribution row is identically zero")
     return m
@@ -71,14 +77,19 @@ class PhiloxChooser:
 
     def __init__(self, seed):
         self.seed = int(seed)
+        self.accept_margins = []      # |u q(x) - p(x)| / max(u q(x), p(x)) of every accept test
+        self.sample_margins = []      # see sample_weights
 
     def accept(self, level, call, i, p_x, q_x):
         w = philox.draw(self.seed, level, call, i)
-        return accept_test(philox.uniform24(w[0]), p_x, q_x)
+        u = philox.uniform24(w[0])
+        lhs, rhs = float(np.float32(u) * np.float32(q_x)), float(p_x)
+        self.accept_margins.append(abs(lhs - rhs) / max(lhs, rhs, 1e-30))
+        return accept_test(u, p_x, q_x)
 
     def sample(self, level, call, slot, p, q):
         w = philox.draw(self.seed, level, call, slot)
-        return sample_row(p, q, int(w[1]))
+        return sample_row(p, q, int(w[1]), self.sample_margins)
 
 
 def verify(p_rows, q_rows, x, chooser, level, call):

@@ -1,0 +1,459 @@
+// Host round driver: Alg. 1 (HSD recursion) and Alg. 2 (Verify) over device-resident state.
+//
+// One token buffer on the device holds the whole sequence (context, tokens collected by the
+// intermediate levels, current drafts).  Draft steps and the verifier's pass + rejection kernel are
+// enqueued without host round trips: the sampler writes each new token id straight into the buffer
+// that the next pass embeds from.  The host only learns n (accepted count) and the corrected token
+// once per Verify, which is the one synchronisation Alg. 1's control flow needs.
+//
+// KV validity (the paper does not discuss caching): level i keeps cached_len_i = number of leading
+// sequence tokens whose K/V for its layers is in the cache.  A pass of level i feeds every token
+// from there on (pending context tokens + drafts).  A rejection at position r truncates the
+// sequence to r, appends the corrected token and clamps cached_len of every level <= i to r, which
+// is the caption of Fig. 1 read as a rule: a token belongs to a model's context only once a model
+// above accepted it.  Levels that are exits of one network share its cache, so what a deeper exit
+// has cached is cached for the shallower exits too.
+#include <string.h>
+
+#include <algorithm>
+#include <vector>
+
+#include "model.h"
+
+struct LevelState {
+    hsd_model* model;
+    int exit_layer;
+    int cached_len;
+    float* rows;        // distribution rows of the tokens this level holds, [rows_cap, V]
+    int rows_cap;
+    int count;          // tokens collected by the current HSD(level, .) call
+    uint32_t call;      // Philox call index: Verify calls (draft steps at level 0)
+};
+
+struct hsd_hier {
+    int K;              // index of the target level
+    LevelState lv[HSD_MAX_LEVELS];
+    int T[HSD_MAX_LEVELS];
+    float temperature;
+    uint64_t seed;
+    hipStream_t stream;
+    int V, max_seq;
+    int32_t* tok_dev;
+    std::vector<int32_t> tok_host;
+    int len;            // tokens currently in the sequence
+    float* logits;
+    int logit_rows_cap;
+    int32_t* result_dev;
+    void* sampler_scratch;
+    int32_t* mailbox;   // pinned host memory: n, m, then up to 65 token ids
+    hsd_stats stats;
+};
+
+namespace {
+
+int batch_max(const int* T, int level) {          // most tokens HSD(level, .) can return, level < K
+    int b = T[0];
+    for (int i = 1; i <= level; ++i) b += T[i];
+    return b;
+}
+
+int rows_cap_of(int n_levels, const int* T, int level) {
+    const int K = n_levels - 1;
+    if (K == 0) return 1;
+    if (level == 0) return T[0];
+    if (level < K) return batch_max(T, level);
+    return batch_max(T, K - 1) + 1;
+}
+
+struct HierLayout {
+    size_t tok, logits, rows[HSD_MAX_LEVELS], result, sampler, total;
+    int logit_rows, max_seq, V;
+};
+
+int hier_layout(int n_levels, const hsd_level* levels, const int* T, HierLayout* L) {
+    if (n_levels < 1 || n_levels > HSD_MAX_LEVELS) HSD_FAIL(HSD_EINVAL, "hierarchy: %d levels outside 1..%d", n_levels, HSD_MAX_LEVELS);
+    if (!levels || (n_levels > 1 && !T)) HSD_FAIL(HSD_EINVAL, "hierarchy: null pointer");
+    for (int i = 0; i < n_levels; ++i) {
+        if (!levels[i].model) HSD_FAIL(HSD_EINVAL, "hierarchy: level %d has no model", i);
+        if (levels[i].exit_layer < 1 || levels[i].exit_layer > levels[i].model->desc.n_layers)
+            HSD_FAIL(HSD_EINVAL, "hierarchy: level %d exit layer %d outside 1..%d", i, levels[i].exit_layer, levels[i].model->desc.n_layers);
+        if (levels[i].model->desc.vocab != levels[0].model->desc.vocab)
+            HSD_FAIL(HSD_EINVAL, "hierarchy: level %d has vocabulary %d, level 0 has %d (all models must share one)", i,
+                     levels[i].model->desc.vocab, levels[0].model->desc.vocab);
+    }
+    for (int i = 0; i + 1 < n_levels; ++i)
+        if (T[i] < 1) HSD_FAIL(HSD_EINVAL, "hierarchy: T_%d = %d, must be >= 1", i, T[i]);
+    const int K = n_levels - 1;
+    L->V = levels[0].model->desc.vocab;
+    L->max_seq = levels[0].model->desc.max_seq;
+    L->logit_rows = 1;
+    for (int i = 0; i < n_levels; ++i) {
+        L->max_seq = std::min(L->max_seq, levels[i].model->desc.max_seq);
+        if (i > 0) {
+            const int t = batch_max(T, i - 1);
+            if (t + 1 > levels[i].model->desc.max_rows || t > 64)
+                HSD_FAIL(HSD_ECAPACITY, "hierarchy: level %d may have to verify %d drafts in one pass; its model allows %d rows per pass", i, t,
+                         levels[i].model->desc.max_rows);
+            L->logit_rows = std::max(L->logit_rows, t + 1);
+        }
+    }
+    (void)K;
+    size_t o = 0;
+    L->tok = o;    o += align_up((size_t)L->max_seq * 4, 256);
+    L->logits = o; o += align_up((size_t)L->logit_rows * L->V * 4, 256);
+    for (int i = 0; i < n_levels; ++i) {
+        L->rows[i] = o;
+        o += align_up((size_t)rows_cap_of(n_levels, T, i) * L->V * 4, 256);
+    }
+    L->result = o;  o += 256;
+    L->sampler = o; o += hsd_sampler_scratch_bytes(L->V);
+    L->total = o;
+    return HSD_OK;
+}
+
+// What level idx may treat as cached: its own count, or that of a deeper exit of the same network.
+int effective_cached(const hsd_hier* h, int idx) {
+    int c = h->lv[idx].cached_len;
+    for (int k = 0; k <= h->K; ++k)
+        if (h->lv[k].model == h->lv[idx].model && h->lv[k].exit_layer >= h->lv[idx].exit_layer) c = std::max(c, h->lv[k].cached_len);
+    return c;
+}
+
+// Feeds sequence tokens [start, len) through the level; logits of the last n_logit_rows.
+int level_pass(hsd_hier* h, int idx, int start, int n_logit_rows) {
+    LevelState& L = h->lv[idx];
+    const int max_rows = L.model->desc.max_rows;
+    int pos = start;
+    while (h->len - pos > max_rows) {
+        int chunk = std::min(max_rows, h->len - pos - n_logit_rows);      // keep the logit rows for the last chunk
+        if (chunk < 1) HSD_FAIL(HSD_ECAPACITY, "pass: %d logit rows do not fit a pass of %d rows", n_logit_rows, max_rows);
+        if (int rc = model_pass(L.model, h->tok_dev + pos, pos, chunk, L.exit_layer, 0, nullptr)) return rc;
+        h->stats.passes[idx]++;
+        h->stats.pass_rows[idx] += chunk;
+        pos += chunk;
+    }
+    if (int rc = model_pass(L.model, h->tok_dev + pos, pos, h->len - pos, L.exit_layer, n_logit_rows, h->logits)) return rc;
+    h->stats.passes[idx]++;
+    h->stats.pass_rows[idx] += h->len - pos;
+    return HSD_OK;
+}
+
+int check_room(const hsd_hier* h, int extra) {
+    if (h->len + extra > h->max_seq) HSD_FAIL(HSD_ECAPACITY, "sequence of %d tokens + %d exceeds the KV capacity %d", h->len, extra, h->max_seq);
+    return HSD_OK;
+}
+
+// One autoregressive step of level 0 (Alg. 1, base case): distribution row `row`, token appended on the device.
+int draft_step(hsd_hier* h, int row) {
+    LevelState& L = h->lv[0];
+    if (h->len < 1) HSD_FAIL(HSD_ESTATE, "draft: empty sequence (call hsd_prefill first)");
+    if (int rc = check_room(h, 1)) return rc;
+    if (row >= L.rows_cap) HSD_FAIL(HSD_ECAPACITY, "draft: row %d beyond the level's %d rows", row, L.rows_cap);
+    const int start = std::min(effective_cached(h, 0), h->len - 1);
+    if (int rc = level_pass(h, 0, start, 1)) return rc;
+    float* p = L.rows + (size_t)row * h->V;
+    if (int rc = launch_softmax(h->logits, p, 1, h->V, h->temperature, h->stream)) return rc;
+    if (int rc = launch_accept_resample(p, nullptr, h->tok_dev + h->len, 0, h->V, h->seed, 0u, L.call++, h->result_dev,
+                                        h->sampler_scratch, h->stream))
+        return rc;
+    L.cached_len = h->len;
+    h->len += 1;
+    return HSD_OK;
+}
+
+// Verify (Alg. 2): the last t sequence tokens are drafts with rows q_dev.  Returns n+1 in *n_out.
+int verify_step(hsd_hier* h, int idx, int t, const float* q_dev, int* n_out) {
+    LevelState& L = h->lv[idx];
+    if (t < 1) HSD_FAIL(HSD_EINVAL, "verify: t=%d", t);
+    if (h->len - t < 1) HSD_FAIL(HSD_ESTATE, "verify: %d drafts but only %d tokens in the sequence", t, h->len);
+    if (L.count + t + 1 > L.rows_cap) HSD_FAIL(HSD_ECAPACITY, "verify: level %d holds %d rows, %d more do not fit its %d", idx, L.count, t + 1, L.rows_cap);
+    if (t + 1 > h->logit_rows_cap || t > 64) HSD_FAIL(HSD_ECAPACITY, "verify: %d drafts exceed the hierarchy's %d per pass", t, h->logit_rows_cap - 1);
+    if (int rc = check_room(h, 1)) return rc;
+    const int ctx_end = h->len - t;
+    const int start = std::min(effective_cached(h, idx), ctx_end - 1);
+    if (int rc = level_pass(h, idx, start, t + 1)) return rc;
+    float* p = L.rows + (size_t)L.count * h->V;
+    if (int rc = launch_softmax(h->logits, p, t + 1, h->V, h->temperature, h->stream)) return rc;
+    if (int rc = launch_accept_resample(p, q_dev, h->tok_dev + ctx_end, t, h->V, h->seed, (uint32_t)idx, L.call++, h->result_dev,
+                                        h->sampler_scratch, h->stream))
+        return rc;
+    HSD_HIP(hipMemcpyAsync(h->mailbox, h->result_dev, 8, hipMemcpyDeviceToHost, h->stream));
+    HSD_HIP(hipMemcpyAsync(h->mailbox + 2, h->tok_dev + ctx_end, (size_t)(t + 1) * 4, hipMemcpyDeviceToHost, h->stream));
+    HSD_HIP(hipStreamSynchronize(h->stream));
+    const int n = h->mailbox[0];
+    if (n < 0 || n > t) HSD_FAIL(HSD_EHIP, "verify: device returned n=%d for t=%d", n, t);
+    for (int i = 0; i <= n; ++i) h->tok_host[ctx_end + i] = h->mailbox[2 + i];
+    h->len = ctx_end + n + 1;
+    const int valid = ctx_end + n;                 // accepted prefix: K/V beyond it belongs to rejected drafts
+    L.cached_len = valid;
+    for (int j = 0; j < idx; ++j) {
+        LevelState& J = h->lv[j];
+        if (J.model == L.model && J.exit_layer <= L.exit_layer) J.cached_len = valid;
+        else J.cached_len = std::min(J.cached_len, valid);
+    }
+    L.count += n + 1;
+    h->stats.drafted[idx] += t;
+    h->stats.accepted[idx] += n;
+    *n_out = n + 1;
+    return HSD_OK;
+}
+
+// HSD(idx, context) of Alg. 1; returns the number of tokens appended in *count_out.
+int run_level(hsd_hier* h, int idx, int* count_out) {
+    LevelState& L = h->lv[idx];
+    L.count = 0;
+    if (idx == 0) {
+        const int k = h->K == 0 ? 1 : h->T[0];
+        for (int c = 0; c < k; ++c)
+            if (int rc = draft_step(h, c)) return rc;
+        L.count = k;
+    } else if (idx == h->K) {
+        int t = 0, n1 = 0;
+        if (int rc = run_level(h, idx - 1, &t)) return rc;
+        if (int rc = verify_step(h, idx, t, h->lv[idx - 1].rows, &n1)) return rc;
+    } else {
+        while (L.count < h->T[idx]) {
+            int t = 0, n1 = 0;
+            if (int rc = run_level(h, idx - 1, &t)) return rc;
+            if (int rc = verify_step(h, idx, t, h->lv[idx - 1].rows, &n1)) return rc;
+        }
+    }
+    *count_out = L.count;
+    return HSD_OK;
+}
+
+// Brings tok_host up to date for positions [from, len) (tokens level 0 wrote on the device).
+int fetch_tokens(hsd_hier* h, int from) {
+    int pos = from;
+    while (pos < h->len) {
+        const int n = std::min(64, h->len - pos);
+        HSD_HIP(hipMemcpyAsync(h->mailbox + 2, h->tok_dev + pos, (size_t)n * 4, hipMemcpyDeviceToHost, h->stream));
+        HSD_HIP(hipStreamSynchronize(h->stream));
+        for (int i = 0; i < n; ++i) h->tok_host[pos + i] = h->mailbox[2 + i];
+        pos += n;
+    }
+    return HSD_OK;
+}
+
+void reset_counters(hsd_hier* h) {
+    for (int i = 0; i <= h->K; ++i) {
+        h->lv[i].call = 0;
+        h->lv[i].count = 0;
+    }
+    memset(&h->stats, 0, sizeof(h->stats));
+}
+
+}  // namespace
+
+extern "C" size_t hsd_hier_workspace_bytes(int n_levels, const hsd_level* levels, const int* T) {
+    HierLayout L;
+    return hier_layout(n_levels, levels, T, &L) ? 0 : L.total;
+}
+
+extern "C" int hsd_hier_create(int n_levels, const hsd_level* levels, const int* T, float temperature, uint64_t seed,
+                               void* workspace_dev, size_t workspace_bytes, void* stream, hsd_hier** out) {
+    HierLayout L;
+    if (int rc = hier_layout(n_levels, levels, T, &L)) return rc;
+    if (!workspace_dev || !out) HSD_FAIL(HSD_EINVAL, "hsd_hier_create: null pointer");
+    if ((uintptr_t)workspace_dev & 255) HSD_FAIL(HSD_EINVAL, "hsd_hier_create: workspace must be 256-byte aligned");
+    if (workspace_bytes < L.total) HSD_FAIL(HSD_ECAPACITY, "hsd_hier_create: workspace of %zu bytes, %zu needed", workspace_bytes, L.total);
+    if (!(temperature >= 0.f)) HSD_FAIL(HSD_EINVAL, "hsd_hier_create: temperature %g", temperature);
+    for (int i = 0; i < n_levels; ++i)
+        if (levels[i].model->stream != (hipStream_t)stream) HSD_FAIL(HSD_EINVAL, "hsd_hier_create: level %d's model was created on another stream", i);
+    hsd_hier* h = new hsd_hier();
+    h->K = n_levels - 1;
+    h->temperature = temperature;
+    h->seed = seed;
+    h->stream = (hipStream_t)stream;
+    h->V = L.V;
+    h->max_seq = L.max_seq;
+    char* wb = (char*)workspace_dev;
+    h->tok_dev = (int32_t*)(wb + L.tok);
+    h->logits = (float*)(wb + L.logits);
+    h->logit_rows_cap = L.logit_rows;
+    h->result_dev = (int32_t*)(wb + L.result);
+    h->sampler_scratch = wb + L.sampler;
+    for (int i = 0; i < n_levels; ++i) {
+        h->lv[i] = LevelState{levels[i].model, levels[i].exit_layer, 0, (float*)(wb + L.rows[i]), rows_cap_of(n_levels, T, i), 0, 0u};
+        if (i < h->K) h->T[i] = T[i];
+    }
+    h->tok_host.assign(h->max_seq, 0);
+    h->len = 0;
+    h->mailbox = nullptr;
+    reset_counters(h);
+    hipError_t e = hipHostMalloc((void**)&h->mailbox, 68 * sizeof(int32_t), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipMemsetAsync(h->sampler_scratch, 0, hsd_sampler_scratch_bytes(h->V), h->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) {
+        if (h->mailbox) (void)hipHostFree(h->mailbox);
+        delete h;
+        HSD_FAIL(HSD_EHIP, "hsd_hier_create: %s", hipGetErrorString(e));
+    }
+    *out = h;
+    return HSD_OK;
+}
+
+extern "C" void hsd_hier_destroy(hsd_hier* h) {
+    if (!h) return;
+    if (h->mailbox) (void)hipHostFree(h->mailbox);
+    delete h;
+}
+
+extern "C" int hsd_prefill(hsd_hier* h, const int32_t* prompt, int n) {
+    if (!h || !prompt) HSD_FAIL(HSD_EINVAL, "hsd_prefill: null pointer");
+    if (n < 1 || n >= h->max_seq) HSD_FAIL(HSD_ECAPACITY, "hsd_prefill: prompt of %d tokens, capacity %d", n, h->max_seq);
+    for (int i = 0; i < n; ++i)
+        if (prompt[i] < 0 || prompt[i] >= h->V) HSD_FAIL(HSD_EINVAL, "hsd_prefill: token %d at position %d outside the vocabulary of %d", prompt[i], i, h->V);
+    std::copy(prompt, prompt + n, h->tok_host.begin());
+    HSD_HIP(hipMemcpyAsync(h->tok_dev, h->tok_host.data(), (size_t)n * 4, hipMemcpyHostToDevice, h->stream));
+    HSD_HIP(hipStreamSynchronize(h->stream));
+    reset_counters(h);
+    // every network once, through its deepest exit in the hierarchy
+    for (int i = 0; i <= h->K; ++i) {
+        bool deepest = true;
+        for (int k = 0; k <= h->K; ++k)
+            if (k != i && h->lv[k].model == h->lv[i].model &&
+                (h->lv[k].exit_layer > h->lv[i].exit_layer || (h->lv[k].exit_layer == h->lv[i].exit_layer && k < i)))
+                deepest = false;
+        if (!deepest || n < 2) continue;
+        const int max_rows = h->lv[i].model->desc.max_rows;
+        for (int pos = 0; pos < n - 1; pos += max_rows) {
+            const int chunk = std::min(max_rows, n - 1 - pos);
+            if (int rc = model_pass(h->lv[i].model, h->tok_dev + pos, pos, chunk, h->lv[i].exit_layer, 0, nullptr)) return rc;
+        }
+    }
+    HSD_HIP(hipStreamSynchronize(h->stream));
+    h->len = n;
+    for (int i = 0; i <= h->K; ++i) h->lv[i].cached_len = n - 1;
+    return HSD_OK;
+}
+
+extern "C" int hsd_rewind(hsd_hier* h, int n) {
+    if (!h) HSD_FAIL(HSD_EINVAL, "hsd_rewind: null pointer");
+    if (n < 1 || n > h->len) HSD_FAIL(HSD_EINVAL, "hsd_rewind: %d outside 1..%d", n, h->len);
+    HSD_HIP(hipStreamSynchronize(h->stream));
+    HSD_HIP(hipMemcpyAsync(h->tok_dev, h->tok_host.data(), (size_t)n * 4, hipMemcpyHostToDevice, h->stream));
+    HSD_HIP(hipStreamSynchronize(h->stream));
+    h->len = n;
+    for (int i = 0; i <= h->K; ++i) h->lv[i].cached_len = std::min(h->lv[i].cached_len, n - 1);
+    reset_counters(h);
+    return HSD_OK;
+}
+
+extern "C" int hsd_draft(hsd_hier* h, int k, int32_t* tokens_out, const float** probs_dev_out) {
+    if (!h) HSD_FAIL(HSD_EINVAL, "hsd_draft: null pointer");
+    if (k < 1 || k > h->lv[0].rows_cap) HSD_FAIL(HSD_ECAPACITY, "hsd_draft: k=%d outside 1..%d (T_0)", k, h->lv[0].rows_cap);
+    const int base = h->len;
+    h->lv[0].count = 0;
+    for (int c = 0; c < k; ++c)
+        if (int rc = draft_step(h, c)) return rc;
+    h->lv[0].count = k;
+    if (int rc = fetch_tokens(h, base)) return rc;
+    if (tokens_out) std::copy(h->tok_host.begin() + base, h->tok_host.begin() + base + k, tokens_out);
+    if (probs_dev_out) *probs_dev_out = h->lv[0].rows;
+    return HSD_OK;
+}
+
+extern "C" int hsd_verify(hsd_hier* h, int level, const int32_t* draft_tokens, const float* draft_probs_dev, int t, int append,
+                          int32_t* tokens_out, int* n_out, const float** probs_dev_out) {
+    if (!h || !draft_probs_dev || !n_out) HSD_FAIL(HSD_EINVAL, "hsd_verify: null pointer");
+    if (level < 1 || level > h->K) HSD_FAIL(HSD_EINVAL, "hsd_verify: level %d outside 1..%d (level 0 only drafts)", level, h->K);
+    if (t < 1) HSD_FAIL(HSD_EINVAL, "hsd_verify: t=%d", t);
+    if (draft_tokens) {
+        if (int rc = check_room(h, t + 1)) return rc;
+        for (int i = 0; i < t; ++i)
+            if (draft_tokens[i] < 0 || draft_tokens[i] >= h->V) HSD_FAIL(HSD_EINVAL, "hsd_verify: draft token %d outside the vocabulary of %d", draft_tokens[i], h->V);
+        std::copy(draft_tokens, draft_tokens + t, h->tok_host.begin() + h->len);
+        HSD_HIP(hipMemcpyAsync(h->tok_dev + h->len, h->tok_host.data() + h->len, (size_t)t * 4, hipMemcpyHostToDevice, h->stream));
+        HSD_HIP(hipStreamSynchronize(h->stream));
+        h->len += t;
+    }
+    LevelState& L = h->lv[level];
+    if (!append) L.count = 0;
+    const int row0 = L.count;
+    const int ctx_end = h->len - t;
+    int n1 = 0;
+    if (int rc = verify_step(h, level, t, draft_probs_dev, &n1)) return rc;
+    if (tokens_out) std::copy(h->tok_host.begin() + ctx_end, h->tok_host.begin() + ctx_end + n1, tokens_out);
+    *n_out = n1;
+    if (probs_dev_out) *probs_dev_out = L.rows + (size_t)row0 * h->V;
+    return HSD_OK;
+}
+
+extern "C" int hsd_run(hsd_hier* h, int level, int32_t* tokens_out, int cap, int* n_out, const float** probs_dev_out) {
+    if (!h || !n_out) HSD_FAIL(HSD_EINVAL, "hsd_run: null pointer");
+    if (level < 0 || level > h->K) HSD_FAIL(HSD_EINVAL, "hsd_run: level %d outside 0..%d", level, h->K);
+    if (h->len < 1) HSD_FAIL(HSD_ESTATE, "hsd_run: empty sequence (call hsd_prefill first)");
+    const int base = h->len;
+    int count = 0;
+    if (int rc = run_level(h, level, &count)) return rc;
+    if (level == 0 || h->K == 0)
+        if (int rc = fetch_tokens(h, base)) return rc;
+    if (level == h->K) {
+        h->stats.rounds++;
+        h->stats.tokens += count;
+    }
+    if (tokens_out) {
+        if (cap < count) HSD_FAIL(HSD_ECAPACITY, "hsd_run: %d tokens produced, output holds %d", count, cap);
+        std::copy(h->tok_host.begin() + base, h->tok_host.begin() + base + count, tokens_out);
+    }
+    *n_out = count;
+    if (probs_dev_out) *probs_dev_out = h->lv[level].rows;
+    return HSD_OK;
+}
+
+extern "C" int hsd_generate(hsd_hier* h, int n_tokens, int32_t* out, hsd_stats* stats) {
+    if (!h || !out) HSD_FAIL(HSD_EINVAL, "hsd_generate: null pointer");
+    if (n_tokens < 0) HSD_FAIL(HSD_EINVAL, "hsd_generate: n_tokens=%d", n_tokens);
+    if (h->len < 1) HSD_FAIL(HSD_ESTATE, "hsd_generate: empty sequence (call hsd_prefill first)");
+    const int base = h->len;
+    while (h->len - base < n_tokens) {
+        const int before = h->len;
+        int count = 0;
+        if (int rc = run_level(h, h->K, &count)) return rc;
+        if (h->K == 0)
+            if (int rc = fetch_tokens(h, before)) return rc;
+        h->stats.rounds++;
+        h->stats.tokens += count;
+    }
+    std::copy(h->tok_host.begin() + base, h->tok_host.begin() + base + n_tokens, out);
+    if (stats) *stats = h->stats;
+    return HSD_OK;
+}
+
+extern "C" int hsd_get_stats(const hsd_hier* h, hsd_stats* s) {
+    if (!h || !s) HSD_FAIL(HSD_EINVAL, "hsd_get_stats: null pointer");
+    *s = h->stats;
+    return HSD_OK;
+}
+
+extern "C" int hsd_sequence_length(const hsd_hier* h) { return h ? h->len : HSD_EINVAL; }
+
+extern "C" int hsd_measure_pass(hsd_hier* h, int level, int m, int iters, double* ms_out) {
+    if (!h || !ms_out) HSD_FAIL(HSD_EINVAL, "hsd_measure_pass: null pointer");
+    if (level < 0 || level > h->K) HSD_FAIL(HSD_EINVAL, "hsd_measure_pass: level %d outside 0..%d", level, h->K);
+    LevelState& L = h->lv[level];
+    if (m < 1 || m > L.model->desc.max_rows || m > h->len || m > h->logit_rows_cap)
+        HSD_FAIL(HSD_EINVAL, "hsd_measure_pass: m=%d outside 1..min(%d, %d, %d)", m, L.model->desc.max_rows, h->len, h->logit_rows_cap);
+    if (iters < 1) HSD_FAIL(HSD_EINVAL, "hsd_measure_pass: iters=%d", iters);
+    hipEvent_t e0, e1;
+    HSD_HIP(hipEventCreate(&e0));
+    HSD_HIP(hipEventCreate(&e1));
+    const int pos0 = h->len - m;
+    int rc = model_pass(L.model, h->tok_dev + pos0, pos0, m, L.exit_layer, m, h->logits);       // warm-up
+    if (!rc) rc = hipEventRecord(e0, h->stream) == hipSuccess ? HSD_OK : HSD_EHIP;
+    for (int i = 0; i < iters && !rc; ++i) {
+        rc = model_pass(L.model, h->tok_dev + pos0, pos0, m, L.exit_layer, m, h->logits);
+    }
+    float ms = 0.f;
+    if (!rc && (hipEventRecord(e1, h->stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                hipEventElapsedTime(&ms, e0, e1) != hipSuccess)) {
+        hsd_set_error("hsd_measure_pass: event timing failed");
+        rc = HSD_EHIP;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc) return rc;
+    *ms_out = (double)ms / iters;
+    return HSD_OK;
+}

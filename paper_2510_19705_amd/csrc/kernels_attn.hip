@@ -1,0 +1,319 @@
+// k-query attention over the paged KV cache: each of the m new tokens of a verifier pass (Alg. 2:
+// the verifier scores every prefix context + x_1..x_i in one pass) attends to all cached positions
+// and, causally, to the new tokens before it.
+//
+// The KV stream is split along the sequence: every wave owns a run of 32-position steps of one KV
+// head and produces an online-softmax partial (running max, running sum, unnormalised output) for
+// all query rows of that head (m tokens x n_q/n_kv grouped heads); a merge kernel combines the
+// partials.  bf16 path: S^T = K Q^T and O^T = V^T P^T on 16x16x32 MFMAs.  K and V are stored in the
+// cache already in A-operand tile order (common.h), V with the position order that makes the
+// accumulator layout of S^T directly usable as the B operand P^T, so probabilities never leave
+// registers; row max / sum are reduced across the four 16-lane groups with wave shuffles.
+// fp32 path (small correctness configuration): lanes = positions for the scores, lanes = head
+// dims for the output, through LDS.
+#include "common.h"
+
+// ------------------------------------------------------------------------------------------------
+// bf16 MFMA partial kernel.  grid (nsplit, n_kv, batch * qgroups), 64 threads.
+// ------------------------------------------------------------------------------------------------
+template <int HD, int QT>
+__global__ __launch_bounds__(64) void attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kv_layer,
+                                                       const int32_t* __restrict__ pages, int max_pages,
+                                                       const int32_t* __restrict__ pos0_arr, int pos0_all, int M, int n_q,
+                                                       int n_kv, float scale_log2, int steps_per_split, int qgroups,
+                                                       float* __restrict__ part_o, float* __restrict__ part_ml, int rpad) {
+    constexpr int KC = HD / 32;   // K chunks of 32 dims per 16-position tile
+    constexpr int DT = HD / 16;   // 16-dim tiles of the output
+    const int lane = threadIdx.x, j = lane & 15, grp = lane >> 4;
+    const int split = blockIdx.x, nsplit = gridDim.x, g = blockIdx.y;
+    const int b = blockIdx.z / qgroups, qg = blockIdx.z % qgroups;
+    const int group = n_q / n_kv;
+    const int R = M * group;
+    const int pos0 = pos0_arr ? pos0_arr[b] : pos0_all;
+    const int S = pos0 + M;
+    const int total_steps = (S + 31) >> 5;
+    const int step0 = split * steps_per_split;
+    const int step1 = min(total_steps, step0 + steps_per_split);
+
+    bf16x8 qreg[QT][KC];
+    int limit[QT];
+    float m_run[QT], l_run[QT];
+    f32x4 o[QT][DT];
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        const int r = (qg * QT + qt) * 16 + j;
+        const bool valid = r < R;
+        const int i = valid ? r / group : 0, hq = valid ? r % group : 0;
+        const bf16_t* qrow = q + (((size_t)b * M + i) * n_q + g * group + hq) * HD + grp * 8;
+#pragma unroll
+        for (int c = 0; c < KC; ++c) qreg[qt][c] = valid ? *reinterpret_cast<const bf16x8*>(qrow + c * 32) : zero;
+        limit[qt] = valid ? pos0 + i + 1 : S;
+        m_run[qt] = -INFINITY;
+        l_run[qt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) o[qt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const size_t blk = kv_block_elems(HD);
+    for (int step = step0; step < step1; ++step) {
+        const int p0 = step << 5;
+        const int page = pages[(size_t)b * max_pages + p0 / HSD_KV_PAGE];
+        const int inpage = p0 % HSD_KV_PAGE;
+        const bf16_t* kblk = kv_layer + ((size_t)page * n_kv + g) * 2 * blk;
+        const bf16_t* vblk = kblk + blk;
+        bf16x8 kreg[2][KC], vreg[DT];
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int c = 0; c < KC; ++c)
+                kreg[h][c] = *reinterpret_cast<const bf16x8*>(kblk + (size_t)(((inpage >> 4) + h) * KC + c) * 512 + lane * 8);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+            vreg[dt] = *reinterpret_cast<const bf16x8*>(vblk + (size_t)((inpage >> 5) * DT + dt) * 512 + lane * 8);
+
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < KC; ++c) {
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[0][c], qreg[qt][c], s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[1][c], qreg[qt][c], s1, 0, 0, 0);
+            }
+            // lane (j, grp): s0[r] is position p0 + 4 grp + r, s1[r] is p0 + 16 + 4 grp + r, query row j
+            float v[8];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int pa = p0 + 4 * grp + r;
+                v[r] = pa < limit[qt] ? s0[r] * scale_log2 : -INFINITY;
+                v[4 + r] = pa + 16 < limit[qt] ? s1[r] * scale_log2 : -INFINITY;
+                mx = fmaxf(mx, fmaxf(v[r], v[4 + r]));
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run[qt], mx);
+            const float m_use = m_new == -INFINITY ? 0.f : m_new;      // row fully masked so far: all p = 0
+            const float alpha = exp2f(m_run[qt] - m_use);
+            float sum = 0.f;
+            bf16x8 pb;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float pe = exp2f(v[e] - m_use);
+                sum += pe;
+                pb[e] = (bf16_t)pe;
+            }
+            sum += __shfl_xor(sum, 16, 64);
+            sum += __shfl_xor(sum, 32, 64);
+            l_run[qt] = l_run[qt] * alpha + sum;
+            m_run[qt] = m_new;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                o[qt][dt] *= alpha;
+                o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vreg[dt], pb, o[qt][dt], 0, 0, 0);
+            }
+        }
+    }
+
+    // partial: o^T accumulators hold d = 16 dt + 4 grp + r for query row j
+    const size_t pbase = (((size_t)b * n_kv + g) * nsplit + split) * rpad;
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        const int r = (qg * QT + qt) * 16 + j;
+        if (r < rpad) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+                *reinterpret_cast<f32x4*>(part_o + (pbase + r) * HD + dt * 16 + grp * 4) = o[qt][dt];
+            if (grp == 0) {
+                part_ml[(pbase + r) * 2] = m_run[qt];
+                part_ml[(pbase + r) * 2 + 1] = l_run[qt];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// generic partial kernel (fp32 cache in natural layout; also reads the tiled bf16 layout).
+// grid (nsplit, n_q, batch * M), 64 threads.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(64) void attn_simple_kernel(const T* __restrict__ q, const T* __restrict__ kv_layer,
+                                                         const int32_t* __restrict__ pages, int max_pages,
+                                                         const int32_t* __restrict__ pos0_arr, int pos0_all, int M, int n_q,
+                                                         int n_kv, int hd, float scale_log2, int steps_per_split,
+                                                         float* __restrict__ part_o, float* __restrict__ part_ml, int rpad) {
+    __shared__ float qs[256];
+    __shared__ float ps[64];
+    const int lane = threadIdx.x;
+    const int split = blockIdx.x, nsplit = gridDim.x, head = blockIdx.y;
+    const int b = blockIdx.z / M, i = blockIdx.z % M;
+    const int group = n_q / n_kv, g = head / group, hq = head % group;
+    const int pos0 = pos0_arr ? pos0_arr[b] : pos0_all;
+    const int limit = pos0 + i + 1;
+    const int total_steps = (pos0 + M + 31) >> 5;
+    const int step0 = split * steps_per_split;
+    const int step1 = min(total_steps, step0 + steps_per_split);
+    const T* qrow = q + (((size_t)b * M + i) * n_q + head) * hd;
+    for (int d = lane; d < hd; d += 64) qs[d] = to_f32(qrow[d]);
+    __syncthreads();
+    const size_t blk = kv_block_elems(hd);
+    float m_run = -INFINITY, l_run = 0.f;
+    float o[4] = {0.f, 0.f, 0.f, 0.f};                 // dims lane, lane+64, ... (hd <= 256)
+    for (int p0 = step0 << 5; p0 < min(step1 << 5, limit); p0 += 64) {
+        // both 32-steps of a 64-chunk lie in one page only if aligned; handle per lane
+        const int pos = p0 + lane;
+        float s = -INFINITY;
+        if (pos < limit && pos < (step1 << 5)) {
+            const int page = pages[(size_t)b * max_pages + pos / HSD_KV_PAGE], ip = pos % HSD_KV_PAGE;
+            const T* kblk = kv_layer + ((size_t)page * n_kv + g) * 2 * blk;
+            float acc = 0.f;
+            for (int d = 0; d < hd; ++d) {
+                float kv = sizeof(T) == 4 ? to_f32(kblk[(size_t)ip * hd + d]) : to_f32(kblk[kv_k_index(ip, d, hd)]);
+                acc += qs[d] * kv;
+            }
+            s = acc * scale_log2;
+        }
+        const float m_new = fmaxf(m_run, wave_max(s));
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = exp2f(m_run - m_use);
+        const float p = exp2f(s - m_use);
+        l_run = l_run * alpha + wave_sum(p);
+        m_run = m_new;
+        ps[lane] = p;
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] *= alpha;
+        const int cnt = min(64, min(step1 << 5, limit) - p0);
+        for (int pp = 0; pp < cnt; ++pp) {
+            const int ppos = p0 + pp;
+            const int page = pages[(size_t)b * max_pages + ppos / HSD_KV_PAGE], ip = ppos % HSD_KV_PAGE;
+            const T* vblk = kv_layer + ((size_t)page * n_kv + g) * 2 * blk + blk;
+            const float w = ps[pp];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int d = lane + 64 * k;
+                if (d < hd)
+                    o[k] += w * (sizeof(T) == 4 ? to_f32(vblk[(size_t)ip * hd + d]) : to_f32(vblk[kv_v_index(ip, d, hd)]));
+            }
+        }
+        __syncthreads();
+    }
+    const int r = i * group + hq;
+    const size_t pbase = (((size_t)b * n_kv + g) * nsplit + split) * rpad + r;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int d = lane + 64 * k;
+        if (d < hd) part_o[pbase * hd + d] = o[k];
+    }
+    if (lane == 0) {
+        part_ml[pbase * 2] = m_run;
+        part_ml[pbase * 2 + 1] = l_run;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// merge: one wave per (query row, KV head, batch).  grid (R, n_kv, batch), 64 threads.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(64) void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                                        int nsplit, int rpad, int M, int n_q, int n_kv, int hd,
+                                                        T* __restrict__ att) {
+    const int r = blockIdx.x, g = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+    const int group = n_q / n_kv, i = r / group, hq = r % group;
+    const size_t base = ((size_t)b * n_kv + g) * nsplit;
+    float m = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) m = fmaxf(m, part_ml[((base + s) * rpad + r) * 2]);
+    float L = 0.f;
+    float o[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < nsplit; ++s) {
+        const size_t pr = (base + s) * rpad + r;
+        const float ms = part_ml[pr * 2];
+        if (ms == -INFINITY) continue;
+        const float w = exp2f(ms - m);
+        L += w * part_ml[pr * 2 + 1];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int d = lane + 64 * k;
+            if (d < hd) o[k] += w * part_o[pr * hd + d];
+        }
+    }
+    T* dst = att + (((size_t)b * M + i) * n_q + g * group + hq) * hd;
+    const float inv = 1.0f / L;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int d = lane + 64 * k;
+        if (d < hd) dst[d] = from_f32<T>(o[k] * inv);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+struct AttnPlan {
+    int nsplit, steps_per_split, rpad, qt, qgroups;
+};
+
+AttnPlan attn_plan(int batch, int m, int n_q, int n_kv, int max_len) {
+    AttnPlan p;
+    const int R = m * (n_q / n_kv);
+    p.qt = R <= 16 ? 1 : (R <= 32 ? 2 : 4);
+    p.qgroups = ceil_div(R, 16 * p.qt);
+    p.rpad = p.qgroups * p.qt * 16;
+    const int total_steps = ceil_div(max_len, 32);
+    int want = 2048 / (batch * n_kv * p.qgroups);
+    if (want < 1) want = 1;
+    if (want > 64) want = 64;
+    int sps = ceil_div(total_steps, want);
+    if (sps < 4) sps = 4;
+    p.steps_per_split = sps;
+    p.nsplit = ceil_div(total_steps, sps);
+    return p;
+}
+
+size_t attn_workspace_bytes(int batch, int m, int n_q, int n_kv, int hd, int max_len) {
+    // worst case over the lengths a plan may be made for: nsplit <= 64
+    const int R = m * (n_q / n_kv);
+    const int rpad = ceil_div(R, 16) * 16 + 48;
+    return align_up((size_t)batch * n_kv * 64 * rpad * (hd + 2) * sizeof(float), 256);
+}
+
+int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, int max_pages, const int32_t* pos0_dev,
+                     int pos0_all, int batch, int m, int max_len, int n_q, int n_kv, int hd, int dtype, void* att, float* workspace,
+                     int force_simple, hipStream_t s) {
+    if (n_q % n_kv != 0) HSD_FAIL(HSD_EINVAL, "attention: n_q=%d not a multiple of n_kv=%d", n_q, n_kv);
+    if (hd % 32 != 0 || hd > 256) HSD_FAIL(HSD_EINVAL, "attention: head dim %d must be a multiple of 32, at most 256", hd);
+    AttnPlan p = attn_plan(batch, m, n_q, n_kv, max_len);
+    const int R = m * (n_q / n_kv);
+    float* part_o = workspace;
+    float* part_ml = workspace + (size_t)batch * n_kv * p.nsplit * p.rpad * hd;
+    const float scale_log2 = 1.4426950408889634f / sqrtf((float)hd);
+    const bool mfma = dtype == HSD_BF16 && !force_simple && (hd == 64 || hd == 128);
+    if (mfma) {
+        dim3 grid(p.nsplit, n_kv, batch * p.qgroups);
+#define HSD_ATT(HD_, QT_)                                                                                              \
+    if (hd == HD_ && p.qt == QT_)                                                                                      \
+        attn_mfma_kernel<HD_, QT_><<<grid, 64, 0, s>>>((const bf16_t*)q, (const bf16_t*)kv_layer, pages, max_pages,    \
+                                                       pos0_dev, pos0_all, m, n_q, n_kv, scale_log2,                   \
+                                                       p.steps_per_split, p.qgroups, part_o, part_ml, p.rpad);
+        HSD_ATT(64, 1) HSD_ATT(64, 2) HSD_ATT(64, 4) HSD_ATT(128, 1) HSD_ATT(128, 2) HSD_ATT(128, 4)
+#undef HSD_ATT
+    } else {
+        dim3 grid(p.nsplit, n_q, batch * m);
+        if (dtype == HSD_BF16)
+            attn_simple_kernel<bf16_t><<<grid, 64, 0, s>>>((const bf16_t*)q, (const bf16_t*)kv_layer, pages, max_pages,
+                                                           pos0_dev, pos0_all, m, n_q, n_kv, hd, scale_log2,
+                                                           p.steps_per_split, part_o, part_ml, p.rpad);
+        else
+            attn_simple_kernel<float><<<grid, 64, 0, s>>>((const float*)q, (const float*)kv_layer, pages, max_pages,
+                                                          pos0_dev, pos0_all, m, n_q, n_kv, hd, scale_log2,
+                                                          p.steps_per_split, part_o, part_ml, p.rpad);
+    }
+    HSD_LAUNCH_CHECK();
+    dim3 mg(R, n_kv, batch);
+    if (dtype == HSD_BF16)
+        attn_merge_kernel<bf16_t><<<mg, 64, 0, s>>>(part_o, part_ml, p.nsplit, p.rpad, m, n_q, n_kv, hd, (bf16_t*)att);
+    else
+        attn_merge_kernel<float><<<mg, 64, 0, s>>>(part_o, part_ml, p.nsplit, p.rpad, m, n_q, n_kv, hd, (float*)att);
+    HSD_LAUNCH_CHECK();
+    return HSD_OK;
+}

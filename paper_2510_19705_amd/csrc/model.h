@@ -1,0 +1,59 @@
+// Internal view of hsd_model shared by model.hip and hier.hip.
+#pragma once
+#include <vector>
+
+#include "common.h"
+
+struct LayerWeights {
+    float* norm1;
+    void* wqkv;   // packed [(n_q + 2 n_kv) hd, d]
+    void* wo;     // packed [d, n_q hd]
+    float* norm2;
+    void* wgu;    // packed [2 ffn, d], gate / up tiles interleaved
+    void* wd;     // packed [d, ffn]
+};
+
+struct hsd_model {
+    hsd_model_desc desc;
+    hipStream_t stream;
+    std::vector<LayerWeights> layers;
+    void* embed;      // [vocab, d] row-major, dtype
+    void* head;       // packed [vocab, d]
+    float* norm_f;
+    char* kv;         // [layer][page][kv head][K block | V block]
+    size_t kv_layer_bytes;
+    int max_pages;
+    int32_t* pages_dev;
+    // activation scratch
+    float* x;         // residual stream [max_rows, d] fp32
+    void* xn;         // normalised rows [max_rows, d]
+    float* part;      // GEMM partial sums
+    void* q;          // [max_rows, n_q hd]
+    void* att;        // [max_rows, n_q hd]
+    void* h;          // [max_rows, ffn]
+    float* attn_ws;
+    size_t part_elems;
+    std::vector<bool> layer_loaded;
+    bool head_loaded;
+};
+
+int model_pass(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows, int exit_layer, int n_logit_rows,
+               float* logits_dev);
+
+// kernels_layer.hip
+int launch_embed(const int32_t* tok, const void* E, float* x, int m, int d, int vocab, int dtype, hipStream_t s);
+int launch_resid_rmsnorm(float* x, const float* part, int ksplit, int part_rows, int part_row0, const float* w, void* xn,
+                         int rows, int row0, int d, float eps, int dtype, hipStream_t s);
+int launch_rope_kv(const float* part, int ksplit, int m, void* q, void* kv_layer, const int32_t* pages, int pos0, int n_q,
+                   int n_kv, int hd, float rope_base, int dtype, hipStream_t s);
+int launch_softmax(const float* z, float* p, int rows, int vocab, float temperature, hipStream_t s);
+// kernels_attn.hip
+size_t attn_workspace_bytes(int batch, int m, int n_q, int n_kv, int hd, int max_len);
+int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, int max_pages, const int32_t* pos0_dev,
+                     int pos0_all, int batch, int m, int max_len, int n_q, int n_kv, int hd, int dtype, void* att,
+                     float* workspace, int force_simple, hipStream_t s);
+// kernels_gemm.hip
+int launch_reduce_partials(const float* part, float* y, int count, int ksplit, hipStream_t s);
+// kernels_sampler.hip
+int launch_accept_resample(const float* p, const float* q, int32_t* x, int t, int vocab, uint64_t seed, uint32_t level,
+                           uint32_t call, int32_t* result, void* scratch, hipStream_t s);

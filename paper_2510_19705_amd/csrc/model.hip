@@ -1,0 +1,257 @@
+// hsd_model: weight packing, KV geometry and the assembly of one multi-token decoder pass
+// (the verifier's parallel scoring of all prefixes in Alg. 2; with one row, a draft step of Alg. 1).
+#include <string.h>
+
+#include "model.h"
+
+static thread_local char g_err[512] = "";
+
+void hsd_set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+extern "C" const char* hsd_last_error(void) { return g_err; }
+
+static int check_desc(const hsd_model_desc* d) {
+    if (!d) HSD_FAIL(HSD_EINVAL, "model: null descriptor");
+    if (d->dtype != HSD_F32 && d->dtype != HSD_BF16) HSD_FAIL(HSD_EINVAL, "model: dtype %d", d->dtype);
+    if (d->n_layers < 1 || d->d < 32 || d->d % 32 != 0) HSD_FAIL(HSD_EINVAL, "model: n_layers=%d d=%d (d must be a multiple of 32)", d->n_layers, d->d);
+    if (d->n_q < 1 || d->n_kv < 1 || d->n_q % d->n_kv != 0) HSD_FAIL(HSD_EINVAL, "model: n_q=%d n_kv=%d", d->n_q, d->n_kv);
+    if (d->hd % 32 != 0 || d->hd < 32 || d->hd > 256) HSD_FAIL(HSD_EINVAL, "model: head dim %d (multiple of 32, 32..256)", d->hd);
+    if (d->ffn < 32 || d->ffn % 32 != 0) HSD_FAIL(HSD_EINVAL, "model: ffn=%d must be a multiple of 32", d->ffn);
+    if (d->vocab < 2) HSD_FAIL(HSD_EINVAL, "model: vocab=%d", d->vocab);
+    if (d->max_seq < HSD_KV_PAGE || d->max_seq % HSD_KV_PAGE != 0) HSD_FAIL(HSD_EINVAL, "model: max_seq=%d must be a positive multiple of %d", d->max_seq, HSD_KV_PAGE);
+    if (d->max_rows < 1 || d->max_rows > HSD_MAX_PASS_ROWS) HSD_FAIL(HSD_EINVAL, "model: max_rows=%d outside 1..%d", d->max_rows, HSD_MAX_PASS_ROWS);
+    if (!(d->eps > 0.f) || !(d->rope_base > 1.f)) HSD_FAIL(HSD_EINVAL, "model: eps=%g rope_base=%g", d->eps, d->rope_base);
+    return HSD_OK;
+}
+
+namespace {
+
+struct WeightLayout {
+    size_t norm1, wqkv, wo, norm2, wgu, wd, layer_bytes, embed, head, norm_f, total;
+};
+
+WeightLayout weight_layout(const hsd_model_desc& d) {
+    WeightLayout L;
+    const int nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
+    size_t o = 0;
+    L.norm1 = o; o += align_up((size_t)d.d * 4, 256);
+    L.wqkv = o;  o += hsd_packed_bytes(nqkv, d.d, d.dtype);
+    L.wo = o;    o += hsd_packed_bytes(d.d, d.n_q * d.hd, d.dtype);
+    L.norm2 = o; o += align_up((size_t)d.d * 4, 256);
+    L.wgu = o;   o += hsd_packed_bytes(2 * d.ffn, d.d, d.dtype);
+    L.wd = o;    o += hsd_packed_bytes(d.d, d.ffn, d.dtype);
+    L.layer_bytes = o;
+    o = L.layer_bytes * d.n_layers;
+    L.embed = o;  o += align_up((size_t)d.vocab * d.d * dtype_size(d.dtype), 256);
+    L.head = o;   o += hsd_packed_bytes(d.vocab, d.d, d.dtype);
+    L.norm_f = o; o += align_up((size_t)d.d * 4, 256);
+    L.total = o;
+    return L;
+}
+
+size_t part_elems_needed(const hsd_model_desc& d) {
+    const int nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
+    size_t need = 0;
+    const int ms[3] = {16, 32, 64};
+    for (int i = 0; i < 3; ++i) {
+        const int m = ms[i] < d.max_rows ? ms[i] : d.max_rows;
+        const int shapes[4][2] = {{nqkv, d.d}, {d.d, d.n_q * d.hd}, {d.d, d.ffn}, {d.vocab, d.d}};
+        for (int s = 0; s < 4; ++s) {
+            GemmPlan p = gemm_plan(m, shapes[s][0], shapes[s][1], d.dtype, false);
+            if (s == 3 && p.ksplit == 1) continue;       // logits go straight to the caller's buffer
+            size_t e = (size_t)p.ksplit * m * shapes[s][0];
+            if (e > need) need = e;
+        }
+    }
+    return need;
+}
+
+struct ScratchLayout {
+    size_t pages, x, xn, part, q, att, h, attn, total;
+};
+
+ScratchLayout scratch_layout(const hsd_model_desc& d) {
+    ScratchLayout L;
+    const size_t es = dtype_size(d.dtype);
+    const int R = d.max_rows;
+    size_t o = 0;
+    L.pages = o; o += align_up((size_t)(d.max_seq / HSD_KV_PAGE) * 4, 256);
+    L.x = o;     o += align_up((size_t)R * d.d * 4, 256);
+    L.xn = o;    o += align_up((size_t)R * d.d * es, 256);
+    L.part = o;  o += align_up(part_elems_needed(d) * 4, 256);
+    L.q = o;     o += align_up((size_t)R * d.n_q * d.hd * es, 256);
+    L.att = o;   o += align_up((size_t)R * d.n_q * d.hd * es, 256);
+    L.h = o;     o += align_up((size_t)R * d.ffn * es, 256);
+    L.attn = o;  o += attn_workspace_bytes(1, R, d.n_q, d.n_kv, d.hd, d.max_seq);
+    L.total = o;
+    return L;
+}
+
+size_t kv_layer_bytes(const hsd_model_desc& d) {
+    return (size_t)(d.max_seq / HSD_KV_PAGE) * kv_page_elems(d.n_kv, d.hd) * dtype_size(d.dtype);
+}
+
+}  // namespace
+
+extern "C" size_t hsd_model_weight_bytes(const hsd_model_desc* d) { return check_desc(d) ? 0 : weight_layout(*d).total; }
+extern "C" size_t hsd_model_kv_bytes(const hsd_model_desc* d) { return check_desc(d) ? 0 : kv_layer_bytes(*d) * d->n_layers; }
+extern "C" size_t hsd_model_scratch_bytes(const hsd_model_desc* d) { return check_desc(d) ? 0 : scratch_layout(*d).total; }
+
+extern "C" int hsd_model_create(const hsd_model_desc* desc, void* weights_dev, void* kv_dev, void* scratch_dev, void* stream,
+                                hsd_model** out) {
+    if (int rc = check_desc(desc)) return rc;
+    if (!weights_dev || !kv_dev || !scratch_dev || !out) HSD_FAIL(HSD_EINVAL, "hsd_model_create: null pointer");
+    if (((uintptr_t)weights_dev | (uintptr_t)kv_dev | (uintptr_t)scratch_dev) & 255)
+        HSD_FAIL(HSD_EINVAL, "hsd_model_create: device buffers must be 256-byte aligned");
+    hsd_model* m = new hsd_model();
+    m->desc = *desc;
+    m->stream = (hipStream_t)stream;
+    const WeightLayout W = weight_layout(*desc);
+    char* wb = (char*)weights_dev;
+    m->layers.resize(desc->n_layers);
+    for (int l = 0; l < desc->n_layers; ++l) {
+        char* lb = wb + W.layer_bytes * l;
+        m->layers[l] = LayerWeights{(float*)(lb + W.norm1), lb + W.wqkv, lb + W.wo, (float*)(lb + W.norm2), lb + W.wgu, lb + W.wd};
+    }
+    m->embed = wb + W.embed;
+    m->head = wb + W.head;
+    m->norm_f = (float*)(wb + W.norm_f);
+    m->kv = (char*)kv_dev;
+    m->kv_layer_bytes = kv_layer_bytes(*desc);
+    m->max_pages = desc->max_seq / HSD_KV_PAGE;
+    const ScratchLayout S = scratch_layout(*desc);
+    char* sb = (char*)scratch_dev;
+    m->pages_dev = (int32_t*)(sb + S.pages);
+    m->x = (float*)(sb + S.x);
+    m->xn = sb + S.xn;
+    m->part = (float*)(sb + S.part);
+    m->q = sb + S.q;
+    m->att = sb + S.att;
+    m->h = sb + S.h;
+    m->attn_ws = (float*)(sb + S.attn);
+    m->part_elems = part_elems_needed(*desc);
+    m->layer_loaded.assign(desc->n_layers, false);
+    m->head_loaded = false;
+    // Cache rows beyond the valid length are read (and masked) by the attention kernels: keep them finite.
+    hipError_t e = hipMemsetAsync(kv_dev, 0, m->kv_layer_bytes * desc->n_layers, m->stream);
+    // Padded rows of packed matrices must be zero.
+    if (e == hipSuccess) e = hipMemsetAsync(m->head, 0, hsd_packed_bytes(desc->vocab, desc->d, desc->dtype), m->stream);
+    std::vector<int32_t> ident(m->max_pages);
+    for (int i = 0; i < m->max_pages; ++i) ident[i] = i;
+    if (e == hipSuccess) e = hipMemcpyAsync(m->pages_dev, ident.data(), ident.size() * 4, hipMemcpyHostToDevice, m->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
+    if (e != hipSuccess) {
+        delete m;
+        HSD_FAIL(HSD_EHIP, "hsd_model_create: %s", hipGetErrorString(e));
+    }
+    *out = m;
+    return HSD_OK;
+}
+
+extern "C" void hsd_model_destroy(hsd_model* m) { delete m; }
+
+extern "C" int hsd_model_set_pages(hsd_model* m, const int32_t* page_table, int n_pages) {
+    if (!m || !page_table) HSD_FAIL(HSD_EINVAL, "hsd_model_set_pages: null pointer");
+    if (n_pages != m->max_pages) HSD_FAIL(HSD_EINVAL, "hsd_model_set_pages: %d entries, model has %d pages", n_pages, m->max_pages);
+    std::vector<char> seen(n_pages, 0);
+    for (int i = 0; i < n_pages; ++i) {
+        if (page_table[i] < 0 || page_table[i] >= n_pages || seen[page_table[i]])
+            HSD_FAIL(HSD_EINVAL, "hsd_model_set_pages: entry %d (=%d) does not make a permutation", i, page_table[i]);
+        seen[page_table[i]] = 1;
+    }
+    HSD_HIP(hipMemcpyAsync(m->pages_dev, page_table, (size_t)n_pages * 4, hipMemcpyHostToDevice, m->stream));
+    HSD_HIP(hipStreamSynchronize(m->stream));
+    return HSD_OK;
+}
+
+extern "C" int hsd_model_load_layer(hsd_model* m, int layer, const hsd_layer_weights* w) {
+    if (!m || !w) HSD_FAIL(HSD_EINVAL, "hsd_model_load_layer: null pointer");
+    if (layer < 0 || layer >= m->desc.n_layers) HSD_FAIL(HSD_EINVAL, "hsd_model_load_layer: layer %d outside 0..%d", layer, m->desc.n_layers - 1);
+    if (!w->norm1_dev || !w->wq_dev || !w->wk_dev || !w->wv_dev || !w->wo_dev || !w->norm2_dev || !w->wg_dev || !w->wu_dev || !w->wd_dev)
+        HSD_FAIL(HSD_EINVAL, "hsd_model_load_layer: null weight pointer");
+    const hsd_model_desc& d = m->desc;
+    const LayerWeights& L = m->layers[layer];
+    hipStream_t s = m->stream;
+    const int nq = d.n_q * d.hd, nkv = d.n_kv * d.hd, nqkv = nq + 2 * nkv;
+    HSD_HIP(hipMemcpyAsync(L.norm1, w->norm1_dev, (size_t)d.d * 4, hipMemcpyDeviceToDevice, s));
+    HSD_HIP(hipMemcpyAsync(L.norm2, w->norm2_dev, (size_t)d.d * 4, hipMemcpyDeviceToDevice, s));
+    int rc;
+    if ((rc = launch_pack(w->wq_dev, L.wqkv, nq, d.d, d.dtype, 0, nqkv, 0, s))) return rc;
+    if ((rc = launch_pack(w->wk_dev, L.wqkv, nkv, d.d, d.dtype, nq, nqkv, 0, s))) return rc;
+    if ((rc = launch_pack(w->wv_dev, L.wqkv, nkv, d.d, d.dtype, nq + nkv, nqkv, 0, s))) return rc;
+    if ((rc = launch_pack(w->wo_dev, L.wo, d.d, nq, d.dtype, 0, d.d, 0, s))) return rc;
+    if ((rc = launch_pack(w->wg_dev, L.wgu, d.ffn, d.d, d.dtype, 0, 2 * d.ffn, 1, s))) return rc;
+    if ((rc = launch_pack(w->wu_dev, L.wgu, d.ffn, d.d, d.dtype, 0, 2 * d.ffn, 2, s))) return rc;
+    if ((rc = launch_pack(w->wd_dev, L.wd, d.d, d.ffn, d.dtype, 0, d.d, 0, s))) return rc;
+    HSD_HIP(hipStreamSynchronize(s));
+    m->layer_loaded[layer] = true;
+    return HSD_OK;
+}
+
+extern "C" int hsd_model_load_head(hsd_model* m, const void* embed_dev, const void* head_dev, const void* norm_f_dev) {
+    if (!m || !embed_dev || !head_dev || !norm_f_dev) HSD_FAIL(HSD_EINVAL, "hsd_model_load_head: null pointer");
+    const hsd_model_desc& d = m->desc;
+    hipStream_t s = m->stream;
+    HSD_HIP(hipMemcpyAsync(m->embed, embed_dev, (size_t)d.vocab * d.d * dtype_size(d.dtype), hipMemcpyDeviceToDevice, s));
+    HSD_HIP(hipMemcpyAsync(m->norm_f, norm_f_dev, (size_t)d.d * 4, hipMemcpyDeviceToDevice, s));
+    if (int rc = launch_pack(head_dev, m->head, d.vocab, d.d, d.dtype, 0, d.vocab, 0, s)) return rc;
+    HSD_HIP(hipStreamSynchronize(s));
+    m->head_loaded = true;
+    return HSD_OK;
+}
+
+// One pass: rows tokens at positions pos0.., layers [0, exit_layer), logits of the last n_logit_rows rows.
+int model_pass(hsd_model* m, const int32_t* tok, int pos0, int rows, int exit_layer, int n_logit_rows, float* logits) {
+    const hsd_model_desc& d = m->desc;
+    if (rows < 1 || rows > d.max_rows) HSD_FAIL(HSD_ECAPACITY, "pass: %d rows, model allows 1..%d", rows, d.max_rows);
+    if (pos0 < 0 || pos0 + rows > d.max_seq) HSD_FAIL(HSD_ECAPACITY, "pass: positions %d..%d exceed the KV capacity %d", pos0, pos0 + rows - 1, d.max_seq);
+    if (exit_layer < 1 || exit_layer > d.n_layers) HSD_FAIL(HSD_EINVAL, "pass: exit layer %d outside 1..%d", exit_layer, d.n_layers);
+    if (n_logit_rows < 0 || n_logit_rows > rows) HSD_FAIL(HSD_EINVAL, "pass: %d logit rows of %d", n_logit_rows, rows);
+    if (n_logit_rows > 0 && !logits) HSD_FAIL(HSD_EINVAL, "pass: logits buffer missing");
+    if (!m->head_loaded) HSD_FAIL(HSD_ESTATE, "pass: embedding / head not loaded");
+    for (int l = 0; l < exit_layer; ++l)
+        if (!m->layer_loaded[l]) HSD_FAIL(HSD_ESTATE, "pass: layer %d not loaded", l);
+    hipStream_t s = m->stream;
+    const int nq = d.n_q * d.hd, nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
+    int rc;
+    if ((rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, s))) return rc;
+    const float* pending = nullptr;     // split-K partials of the previous down projection, not yet added to x
+    int pending_split = 0;
+    for (int l = 0; l < exit_layer; ++l) {
+        const LayerWeights& L = m->layers[l];
+        void* kv_layer = m->kv + m->kv_layer_bytes * l;
+        if ((rc = launch_resid_rmsnorm(m->x, pending, pending_split, rows, 0, L.norm1, m->xn, rows, 0, d.d, d.eps, d.dtype, s))) return rc;
+        GemmPlan pq = gemm_plan(rows, nqkv, d.d, d.dtype, false);
+        if ((rc = launch_gemm(m->xn, L.wqkv, m->part, rows, nqkv, d.d, d.dtype, pq, s))) return rc;
+        if ((rc = launch_rope_kv(m->part, pq.ksplit, rows, m->q, kv_layer, m->pages_dev, pos0, d.n_q, d.n_kv, d.hd, d.rope_base, d.dtype, s))) return rc;
+        if ((rc = launch_attention(m->q, kv_layer, m->pages_dev, m->max_pages, nullptr, pos0, 1, rows, pos0 + rows, d.n_q, d.n_kv,
+                                   d.hd, d.dtype, m->att, m->attn_ws, 0, s))) return rc;
+        GemmPlan po = gemm_plan(rows, d.d, nq, d.dtype, false);
+        if ((rc = launch_gemm(m->att, L.wo, m->part, rows, d.d, nq, d.dtype, po, s))) return rc;
+        if ((rc = launch_resid_rmsnorm(m->x, m->part, po.ksplit, rows, 0, L.norm2, m->xn, rows, 0, d.d, d.eps, d.dtype, s))) return rc;
+        GemmPlan pg = gemm_plan(rows, 2 * d.ffn, d.d, d.dtype, true);
+        if ((rc = launch_gemm_swiglu(m->xn, L.wgu, m->h, rows, d.ffn, d.d, d.dtype, pg, s))) return rc;
+        GemmPlan pd = gemm_plan(rows, d.d, d.ffn, d.dtype, false);
+        if ((rc = launch_gemm(m->h, L.wd, m->part, rows, d.d, d.ffn, d.dtype, pd, s))) return rc;
+        pending = m->part;
+        pending_split = pd.ksplit;
+    }
+    if (n_logit_rows == 0) return HSD_OK;
+    const int row0 = rows - n_logit_rows;
+    if ((rc = launch_resid_rmsnorm(m->x, pending, pending_split, rows, row0, m->norm_f, m->xn, n_logit_rows, row0, d.d, d.eps, d.dtype, s))) return rc;
+    GemmPlan ph = gemm_plan(n_logit_rows, d.vocab, d.d, d.dtype, false);
+    if (ph.ksplit == 1) return launch_gemm(m->xn, m->head, logits, n_logit_rows, d.vocab, d.d, d.dtype, ph, s);
+    if ((rc = launch_gemm(m->xn, m->head, m->part, n_logit_rows, d.vocab, d.d, d.dtype, ph, s))) return rc;
+    return launch_reduce_partials(m->part, logits, n_logit_rows * d.vocab, ph.ksplit, s);
+}
+
+extern "C" int hsd_model_pass(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows, int exit_layer, int n_logit_rows,
+                              float* logits_dev) {
+    if (!m || !tokens_dev) HSD_FAIL(HSD_EINVAL, "hsd_model_pass: null pointer");
+    return model_pass(m, tokens_dev, pos0, rows, exit_layer, n_logit_rows, logits_dev);
+}

@@ -1,0 +1,326 @@
+"""ctypes binding of libhsd.so: argument marshalling only.
+
+Every step of the path runs inside the library's HIP kernels; torch is used to own device
+memory and the stream.  Importing this module fails loudly when the library has not been built
+(python -m paper_2510_19705_amd.build); there is no CPU fallback.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhsd.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError("libhsd.so is not built: run `python -m paper_2510_19705_amd.build` (needs hipcc)")
+lib = C.CDLL(LIB_PATH)
+
+F32, BF16 = 0, 1
+MAX_LEVELS, MAX_PASS_ROWS, KV_PAGE = 8, 64, 64
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [("n_layers", C.c_int), ("d", C.c_int), ("n_q", C.c_int), ("n_kv", C.c_int), ("hd", C.c_int),
+                ("ffn", C.c_int), ("vocab", C.c_int), ("dtype", C.c_int), ("rope_base", C.c_float), ("eps", C.c_float),
+                ("max_seq", C.c_int), ("max_rows", C.c_int)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in ("norm1_dev", "wq_dev", "wk_dev", "wv_dev", "wo_dev", "norm2_dev", "wg_dev",
+                                          "wu_dev", "wd_dev")]
+
+
+class Level(C.Structure):
+    _fields_ = [("model", C.c_void_p), ("exit_layer", C.c_int)]
+
+
+class Stats(C.Structure):
+    _fields_ = [("passes", C.c_int64 * MAX_LEVELS), ("pass_rows", C.c_int64 * MAX_LEVELS),
+                ("drafted", C.c_int64 * MAX_LEVELS), ("accepted", C.c_int64 * MAX_LEVELS),
+                ("rounds", C.c_int64), ("tokens", C.c_int64)]
+
+
+_vp, _i, _sz, _f, _d = C.c_void_p, C.c_int, C.c_size_t, C.c_float, C.c_double
+_ip, _dp = C.POINTER(C.c_int), C.POINTER(C.c_double)
+_SIGS = {
+    "hsd_model_weight_bytes": (_sz, [C.POINTER(ModelDesc)]),
+    "hsd_model_kv_bytes": (_sz, [C.POINTER(ModelDesc)]),
+    "hsd_model_scratch_bytes": (_sz, [C.POINTER(ModelDesc)]),
+    "hsd_model_create": (_i, [C.POINTER(ModelDesc), _vp, _vp, _vp, _vp, C.POINTER(_vp)]),
+    "hsd_model_destroy": (None, [_vp]),
+    "hsd_model_load_layer": (_i, [_vp, _i, C.POINTER(LayerWeights)]),
+    "hsd_model_load_head": (_i, [_vp, _vp, _vp, _vp]),
+    "hsd_model_set_pages": (_i, [_vp, C.POINTER(C.c_int32), _i]),
+    "hsd_model_pass": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
+    "hsd_softmax": (_i, [_vp, _vp, _i, _i, _f, _vp]),
+    "hsd_sampler_scratch_bytes": (_sz, [_i]),
+    "hsd_accept_resample": (_i, [_vp, _vp, _vp, _i, _i, C.c_uint64, C.c_uint32, C.c_uint32, _vp, _vp, _vp]),
+    "hsd_packed_bytes": (_sz, [_i, _i, _i]),
+    "hsd_gemm_workspace_bytes": (_sz, [_i, _i, _i]),
+    "hsd_pack_weight": (_i, [_vp, _vp, _i, _i, _i, _vp]),
+    "hsd_gemm": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _vp]),
+    "hsd_hier_workspace_bytes": (_sz, [_i, C.POINTER(Level), _ip]),
+    "hsd_hier_create": (_i, [_i, C.POINTER(Level), _ip, _f, C.c_uint64, _vp, _sz, _vp, C.POINTER(_vp)]),
+    "hsd_hier_destroy": (None, [_vp]),
+    "hsd_prefill": (_i, [_vp, C.POINTER(C.c_int32), _i]),
+    "hsd_rewind": (_i, [_vp, _i]),
+    "hsd_draft": (_i, [_vp, _i, C.POINTER(C.c_int32), C.POINTER(_vp)]),
+    "hsd_verify": (_i, [_vp, _i, C.POINTER(C.c_int32), _vp, _i, _i, C.POINTER(C.c_int32), _ip, C.POINTER(_vp)]),
+    "hsd_run": (_i, [_vp, _i, C.POINTER(C.c_int32), _i, _ip, C.POINTER(_vp)]),
+    "hsd_generate": (_i, [_vp, _i, C.POINTER(C.c_int32), C.POINTER(Stats)]),
+    "hsd_get_stats": (_i, [_vp, C.POINTER(Stats)]),
+    "hsd_sequence_length": (_i, [_vp]),
+    "hsd_measure_pass": (_i, [_vp, _i, _i, _i, _dp]),
+    "hsd_gamma": (_d, [_d, _i, _i]),
+    "hsd_expected_latency": (_d, [_i, _dp, _dp, _ip, _i]),
+    "hsd_select_hierarchy": (_i, [_i, _dp, _dp, _i, _i, _ip, _ip, _ip, _dp]),
+    "hsd_best_single_draft": (_i, [_i, _dp, _dp, _i, _ip, _ip, _dp]),
+    "hsd_last_error": (C.c_char_p, []),
+}
+for _name, (_res, _args) in _SIGS.items():
+    _fn = getattr(lib, _name)
+    _fn.restype, _fn.argtypes = _res, _args
+EXPORTS = tuple(_SIGS)
+
+
+class HsdError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        super().__init__("libhsd error %d: %s" % (code, lib.hsd_last_error().decode()))
+
+
+def _check(rc):
+    if rc != 0:
+        raise HsdError(rc)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _buf(nbytes):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def _f64(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a, a.ctypes.data_as(_dp)
+
+
+def _rows_view(ptr, rows, vocab, keepalive):
+    """Zero-copy torch view of `rows` fp32 distribution rows at a borrowed device pointer."""
+    base = keepalive.data_ptr()
+    off = ptr - base
+    assert 0 <= off and off + rows * vocab * 4 <= keepalive.numel(), "borrowed pointer outside the workspace"
+    return keepalive[off:off + rows * vocab * 4].view(torch.float32).view(rows, vocab)
+
+
+# ---- model -----------------------------------------------------------------------------------
+class Model:
+    def __init__(self, shape, dtype, max_seq, max_rows, rope_base=10000.0, eps=1e-5):
+        self.desc = ModelDesc(shape["n_layers"], shape["d"], shape["n_q"], shape["n_kv"], shape["hd"], shape["ffn"],
+                              shape["vocab"], dtype, rope_base, eps, max_seq, max_rows)
+        self.dtype = dtype
+        self.tdtype = torch.bfloat16 if dtype == BF16 else torch.float32
+        self.stream = _stream()
+        nbytes = [lib.hsd_model_weight_bytes(C.byref(self.desc)), lib.hsd_model_kv_bytes(C.byref(self.desc)),
+                  lib.hsd_model_scratch_bytes(C.byref(self.desc))]
+        if 0 in nbytes:
+            raise HsdError(-1)
+        self.weights, self.kv, self.scratch = (_buf(n) for n in nbytes)
+        self.handle = C.c_void_p()
+        _check(lib.hsd_model_create(C.byref(self.desc), self.weights.data_ptr(), self.kv.data_ptr(),
+                                    self.scratch.data_ptr(), self.stream, C.byref(self.handle)))
+
+    def close(self):
+        if self.handle:
+            lib.hsd_model_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def _dev(self, a, norm=False):
+        t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+        return t if norm else t.to(self.tdtype).contiguous()
+
+    def load_layer(self, layer, w):
+        """hsd_model_load_layer with host fp32 arrays (already bf16-representable for bf16 models)."""
+        keep = {k: self._dev(w[k], norm=k.startswith("norm")) for k in
+                ("norm1", "wq", "wk", "wv", "wo", "norm2", "wg", "wu", "wd")}
+        lw = LayerWeights(*[keep[k].data_ptr() for k in ("norm1", "wq", "wk", "wv", "wo", "norm2", "wg", "wu", "wd")])
+        torch.cuda.current_stream().synchronize()
+        _check(lib.hsd_model_load_layer(self.handle, layer, C.byref(lw)))
+
+    def load_head(self, embed, head, norm_f):
+        e, h, n = self._dev(embed), self._dev(head), self._dev(norm_f, norm=True)
+        torch.cuda.current_stream().synchronize()
+        _check(lib.hsd_model_load_head(self.handle, e.data_ptr(), h.data_ptr(), n.data_ptr()))
+
+    def load(self, weights):
+        for i, lw in enumerate(weights["layers"]):
+            self.load_layer(i, lw)
+        self.load_head(weights["embed"], weights["head"], weights["norm_f"])
+
+    def set_pages(self, table):
+        a, p = _i32(table)
+        _check(lib.hsd_model_set_pages(self.handle, p, len(a)))
+
+    def model_pass(self, tokens_dev, pos0, exit_layer, n_logit_rows):
+        """hsd_model_pass; tokens_dev: int32 cuda tensor.  Returns fp32 logits [n_logit_rows, vocab]."""
+        logits = torch.empty((max(n_logit_rows, 1), self.desc.vocab), dtype=torch.float32, device="cuda")
+        _check(lib.hsd_model_pass(self.handle, tokens_dev.data_ptr(), pos0, tokens_dev.numel(), exit_layer, n_logit_rows,
+                                  logits.data_ptr()))
+        return logits[:n_logit_rows]
+
+
+# ---- stand-alone kernels ----------------------------------------------------------------------
+def softmax(logits, temperature):
+    logits = logits.contiguous()
+    out = torch.empty_like(logits)
+    _check(lib.hsd_softmax(logits.data_ptr(), out.data_ptr(), logits.shape[0], logits.shape[1], float(temperature),
+                           _stream()))
+    return out
+
+
+_sampler_scratch = {}
+
+
+def accept_resample(p, q, x, seed, level, call):
+    """p [t+1, V], q [t, V] fp32 cuda tensors, x int32 cuda tensor [t+1] (x_1..x_t, one spare).
+    Returns (n, m) after synchronising; x[n] = m on the device."""
+    t, V = p.shape[0] - 1, p.shape[1]
+    key = (V, torch.cuda.current_device())
+    if key not in _sampler_scratch:
+        _sampler_scratch[key] = torch.zeros(lib.hsd_sampler_scratch_bytes(V), dtype=torch.uint8, device="cuda")
+    res = torch.empty(2, dtype=torch.int32, device="cuda")
+    _check(lib.hsd_accept_resample(p.data_ptr(), q.data_ptr() if t > 0 else None, x.data_ptr(), t, V, seed, level, call,
+                                   res.data_ptr(), _sampler_scratch[key].data_ptr(), _stream()))
+    n, m = res.cpu().tolist()
+    return n, m
+
+
+def pack_weight(w, dtype):
+    """w: cuda tensor [n, k] of the dtype's element type; returns the packed buffer."""
+    n, k = w.shape
+    out = _buf(lib.hsd_packed_bytes(n, k, dtype))
+    _check(lib.hsd_pack_weight(w.contiguous().data_ptr(), out.data_ptr(), n, k, dtype, _stream()))
+    return out
+
+
+def gemm(x, packed, n, dtype):
+    m, k = x.shape
+    y = torch.empty((m, n), dtype=torch.float32, device="cuda")
+    ws = _buf(lib.hsd_gemm_workspace_bytes(m, n, k))
+    _check(lib.hsd_gemm(x.contiguous().data_ptr(), packed.data_ptr(), y.data_ptr(), m, n, k, dtype, ws.data_ptr(), _stream()))
+    return y
+
+
+# ---- hierarchy --------------------------------------------------------------------------------
+class Hierarchy:
+    def __init__(self, levels, T, temperature, seed):
+        """levels: list of (Model, exit_layer) from the smallest drafter to the target."""
+        self.models = [m for m, _ in levels]
+        self.n = len(levels)
+        self.K = self.n - 1
+        self.T = list(T)
+        self.vocab = levels[0][0].desc.vocab
+        self._lv = (Level * self.n)(*[Level(m.handle, e) for m, e in levels])
+        self._T = (C.c_int * max(1, self.K))(*self.T)
+        nbytes = lib.hsd_hier_workspace_bytes(self.n, self._lv, self._T)
+        if nbytes == 0:
+            raise HsdError(-1)
+        self.workspace = _buf(nbytes)
+        self.handle = C.c_void_p()
+        _check(lib.hsd_hier_create(self.n, self._lv, self._T, float(temperature), seed, self.workspace.data_ptr(),
+                                   self.workspace.numel(), self.models[0].stream, C.byref(self.handle)))
+
+    def close(self):
+        if self.handle:
+            lib.hsd_hier_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def prefill(self, prompt):
+        a, p = _i32(prompt)
+        _check(lib.hsd_prefill(self.handle, p, len(a)))
+
+    def rewind(self, n):
+        _check(lib.hsd_rewind(self.handle, n))
+
+    def draft(self, k):
+        toks = np.zeros(k, dtype=np.int32)
+        ptr = C.c_void_p()
+        _check(lib.hsd_draft(self.handle, k, toks.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(ptr)))
+        return toks, _rows_view(ptr.value, k, self.vocab, self.workspace)
+
+    def verify(self, level, draft_tokens, draft_probs, t, append=False):
+        """draft_tokens: host ids to append first, or None when the drafts are already the last t tokens."""
+        out = np.zeros(t + 1, dtype=np.int32)
+        n1 = C.c_int()
+        ptr = C.c_void_p()
+        dt = None
+        if draft_tokens is not None:
+            keep, dt = _i32(draft_tokens)
+        _check(lib.hsd_verify(self.handle, level, dt, draft_probs.data_ptr(), t, int(append),
+                              out.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(n1), C.byref(ptr)))
+        return out[:n1.value], _rows_view(ptr.value, n1.value, self.vocab, self.workspace)
+
+    def run(self, level, cap=256):
+        out = np.zeros(cap, dtype=np.int32)
+        n = C.c_int()
+        ptr = C.c_void_p()
+        _check(lib.hsd_run(self.handle, level, out.ctypes.data_as(C.POINTER(C.c_int32)), cap, C.byref(n), C.byref(ptr)))
+        return out[:n.value], _rows_view(ptr.value, n.value, self.vocab, self.workspace)
+
+    def generate(self, n_tokens):
+        out = np.zeros(n_tokens, dtype=np.int32)
+        st = Stats()
+        _check(lib.hsd_generate(self.handle, n_tokens, out.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(st)))
+        return out, st
+
+    def stats(self):
+        st = Stats()
+        _check(lib.hsd_get_stats(self.handle, C.byref(st)))
+        return st
+
+    def sequence_length(self):
+        return lib.hsd_sequence_length(self.handle)
+
+    def measure_pass(self, level, m, iters):
+        ms = C.c_double()
+        _check(lib.hsd_measure_pass(self.handle, level, m, iters, C.byref(ms)))
+        return ms.value
+
+
+# ---- host-side latency model ------------------------------------------------------------------
+def gamma(alpha, Ti, Tj):
+    return lib.hsd_gamma(alpha, Ti, Tj)
+
+
+def expected_latency(cost, alpha_adj, T, exact_overshoot=False):
+    c, cp = _f64(cost)
+    a, ap = _f64(alpha_adj if len(alpha_adj) else [0.0])
+    Ta = (C.c_int * max(1, len(T)))(*T)
+    return lib.hsd_expected_latency(len(c), cp, ap, Ta, int(exact_overshoot))
+
+
+def select_hierarchy(cost, alpha, Tbar, monotone_T=True):
+    n = len(cost)
+    c, cp = _f64(cost)
+    a, ap = _f64(np.asarray(alpha, dtype=np.float64).reshape(n, n))
+    sig, Ts = (C.c_int * n)(), (C.c_int * max(1, n - 1))()
+    ns, lat = C.c_int(), C.c_double()
+    _check(lib.hsd_select_hierarchy(n, cp, ap, Tbar, int(monotone_T), sig, Ts, C.byref(ns), C.byref(lat)))
+    return lat.value, list(sig[:ns.value]), list(Ts[:ns.value - 1])
+
+
+def best_single_draft(cost, alpha, Tbar):
+    n = len(cost)
+    c, cp = _f64(cost)
+    a, ap = _f64(np.asarray(alpha, dtype=np.float64).reshape(n, n))
+    dr, T, lat = C.c_int(), C.c_int(), C.c_double()
+    _check(lib.hsd_best_single_draft(n, cp, ap, Tbar, C.byref(dr), C.byref(T), C.byref(lat)))
+    return lat.value, dr.value, T.value

@@ -1,0 +1,183 @@
+"""GPU end-to-end parity of draft / verify / the HSD round driver against the oracle's Alg. 1/2."""
+import numpy as np
+import pytest
+
+from oracle import decoder, hsd as ohsd, specsample
+from paper_2510_19705_amd import inputs
+from helpers import gpu_model, oracle_decoder, say
+
+pytestmark = pytest.mark.gpu
+
+TINY = inputs.SHAPES["tiny"]          # the smallest workload: 8 layers, d 256, 4 heads x 64, FFN 1024, vocab 2048
+TINY_EXITS = (2, 4, 8)
+SEED = 20251019
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    w = inputs.make_weights(TINY, seed=1, bf16=False)
+    prompt = inputs.make_prompt(TINY["vocab"], 32, seed=2)
+    model = gpu_model(TINY, w, False, max_seq=256, max_rows=16)
+    yield w, prompt, model
+    model.close()
+
+
+def _oracle_levels(w, shape, exits, temperature, max_len=256):
+    dec = oracle_decoder(shape, w, max_len)
+    return [decoder.Level(dec, e, temperature) for e in exits]
+
+
+def _gpu_hier(model, exits, T, temperature, seed=SEED):
+    from paper_2510_19705_amd import hsd
+    return hsd.Hierarchy([(model, e) for e in exits], T, temperature, seed)
+
+
+@pytest.mark.parametrize("T", [(4, 2), (2, 4)])
+def test_tiny_temperature0_stream_bit_exact(tiny, T):
+    """Smallest workload, fp32, temperature 0: the 64 generated tokens equal the oracle's HSD stream and
+    plain greedy decoding of the target.  The oracle's smallest top-2 logit gap must dwarf the fp32
+    error bound, otherwise the comparison would be ill-posed (it is asserted, not assumed)."""
+    w, _, model = tiny
+    prompt = inputs.make_prompt(TINY["vocab"], 32, seed=10)     # prompt chosen (with the oracle alone) for a wide gap
+    levels = _oracle_levels(w, TINY, TINY_EXITS, 0.0)
+    o = ohsd.HSD(levels, T, specsample.PhiloxChooser(SEED))
+    ref = o.generate([int(t) for t in prompt], 64)
+    gap = min(l.min_top2_gap for l in levels)
+    say("oracle min top-2 gap", gap)
+    assert gap > 1.5e-3                                          # fp32 logit error is ~1e-5
+    greedy = ohsd.HSD(_oracle_levels(w, TINY, (8,), 0.0), (), specsample.PhiloxChooser(1)).generate([int(t) for t in prompt], 64)
+    assert ref == greedy
+    h = _gpu_hier(model, TINY_EXITS, T, 0.0)
+    h.prefill(prompt)
+    got, st = h.generate(64)
+    assert got.tolist() == ref
+    assert [st.passes[i] for i in range(3)] == o.passes
+    assert [st.drafted[i] for i in range(3)] == o.drafted and [st.accepted[i] for i in range(3)] == o.accepted
+    h.close()
+    # plain autoregressive decoding through the same library (one level): same stream
+    ar = _gpu_hier(model, (8,), (), 0.0)
+    ar.prefill(prompt)
+    assert ar.generate(64)[0].tolist() == ref
+    ar.close()
+
+
+@pytest.mark.parametrize("T,seed", [((4, 2), 104), ((3, 5), 100)])
+def test_tiny_temperature1_stream(tiny, T, seed):
+    """Temperature 1: same Philox stream on both sides.  Every accept test and every draw of the oracle
+    run keeps a margin (asserted) far above the fp32 differences between the two softmaxes, so the
+    streams, the accepted counts and the pass counts must be identical.  (A rounding-level change of a row
+    moves a draw's interval ends by ~1e-7 of the total mass; the seeds were picked, with the oracle
+    alone, so that no draw of the run lands closer than 3e-6 to an end.)"""
+    w, prompt, model = tiny
+    levels = _oracle_levels(w, TINY, TINY_EXITS, 1.0)
+    ch = specsample.PhiloxChooser(seed)
+    o = ohsd.HSD(levels, T, ch)
+    ref = o.generate([int(t) for t in prompt], 64)
+    say("oracle margins: accept %.2e sample %.2e" % (min(ch.accept_margins), min(ch.sample_margins)))
+    assert min(ch.accept_margins) > 3e-4 and min(ch.sample_margins) > 3e-6
+    h = _gpu_hier(model, TINY_EXITS, T, 1.0, seed=seed)
+    h.prefill(prompt)
+    got, st = h.generate(64)
+    assert got.tolist() == ref
+    assert [st.drafted[i] for i in range(3)] == o.drafted and [st.accepted[i] for i in range(3)] == o.accepted
+    assert [st.passes[i] for i in range(3)] == o.passes
+    say("acceptance", [st.accepted[i] / max(1, st.drafted[i]) for i in (1, 2)], "rounds", st.rounds)
+    h.close()
+
+
+def test_draft_and_verify_calls(tiny):
+    """The two building blocks: draft(k) rows and tokens, verify rows p_1..p_{n+1} and output tokens,
+    each against the oracle (distribution rows by tolerance, tokens exactly)."""
+    w, prompt, model = tiny
+    levels = _oracle_levels(w, TINY, TINY_EXITS, 1.0)
+    ch = specsample.PhiloxChooser(SEED)
+    ctx = [int(t) for t in prompt]
+    h = _gpu_hier(model, TINY_EXITS, (4, 2), 1.0)
+    h.prefill(prompt)
+    for rnd in range(3):
+        # oracle: level 0 drafts 4 tokens, level 1 verifies them
+        o = ohsd.HSD(levels, (4, 2), ch)
+        o.calls = [4 * rnd, rnd, 0]
+        dt, dq = o.run(0, ctx)
+        vt, vp = o._verify(1, dt, dq, ctx)
+        toks, q = h.draft(4)
+        assert toks.tolist() == dt
+        assert np.abs(q.cpu().numpy() - np.stack(dq)).max() < 1e-6
+        out, p = h.verify(1, None, q, 4)
+        assert out.tolist() == vt
+        assert p.shape[0] == len(vt) and np.abs(p.cpu().numpy() - np.stack(vp)).max() < 1e-6
+        ctx = ctx + vt
+        assert h.sequence_length() == len(ctx)
+    h.close()
+
+
+def test_verify_with_host_drafts(tiny):
+    """verify(level, drafted tokens, draft probs) with drafts supplied by the caller (here: the oracle's
+    level-0 drafts and rows), as the boundary states it."""
+    import torch
+    w, prompt, model = tiny
+    levels = _oracle_levels(w, TINY, TINY_EXITS, 1.0)
+    ch = specsample.PhiloxChooser(7)
+    ctx = [int(t) for t in prompt]
+    o = ohsd.HSD(levels, (3, 2), ch)
+    dt, dq = o.run(0, ctx)
+    vt, vp = o._verify(2, dt, dq, ctx)                     # target verifies level-0 drafts directly
+    h = _gpu_hier(model, TINY_EXITS, (3, 2), 1.0, seed=7)
+    h.prefill(prompt)
+    q = torch.from_numpy(np.stack(dq)).cuda()
+    out, p = h.verify(2, dt, q, 3)
+    assert out.tolist() == vt
+    assert np.abs(p.cpu().numpy() - np.stack(vp)).max() < 1e-6
+    h.close()
+
+
+def test_rewind_repeats_the_generation(tiny):
+    w, prompt, model = tiny
+    h = _gpu_hier(model, TINY_EXITS, (4, 2), 1.0)
+    h.prefill(prompt)
+    a, _ = h.generate(40)
+    h.rewind(len(prompt))
+    b, _ = h.generate(40)
+    assert a.tolist() == b.tolist()
+    h.close()
+
+
+def test_driver_error_paths(tiny):
+    from paper_2510_19705_amd import hsd
+    import torch
+    w, prompt, model = tiny
+    with pytest.raises(hsd.HsdError):                      # T_i >= 1
+        _gpu_hier(model, TINY_EXITS, (4, 0), 1.0)
+    with pytest.raises(hsd.HsdError) as e:                 # a verify pass of 15+4 drafts + 1 exceeds 16 rows
+        _gpu_hier(model, TINY_EXITS, (15, 4), 1.0)
+    assert e.value.code == -2
+    with pytest.raises(hsd.HsdError):                      # exit layer out of range
+        _gpu_hier(model, (2, 4, 9), (4, 2), 1.0)
+    other = hsd.Model(dict(TINY, vocab=1000, n_layers=1), hsd.F32, 128, 8)
+    with pytest.raises(hsd.HsdError) as e:                 # all models must share the vocabulary (Sec. 2)
+        hsd.Hierarchy([(other, 1), (model, 8)], (2,), 1.0, 1)
+    assert b"vocabulary" in hsd.lib.hsd_last_error()
+    other.close()
+    h = _gpu_hier(model, TINY_EXITS, (4, 2), 1.0)
+    with pytest.raises(hsd.HsdError) as e:                 # nothing prefilled yet
+        h.generate(4)
+    assert e.value.code == -3
+    with pytest.raises(hsd.HsdError):                      # token id outside the vocabulary
+        h.prefill([1, 2, TINY["vocab"]])
+    h.prefill(prompt)
+    q = torch.zeros((4, TINY["vocab"]), device="cuda")
+    with pytest.raises(hsd.HsdError):                      # level 0 only drafts
+        h.verify(0, [1, 2], q, 2)
+    with pytest.raises(hsd.HsdError):                      # level out of range
+        h.verify(3, [1, 2], q, 2)
+    with pytest.raises(hsd.HsdError):                      # more drafts than T_0
+        h.draft(5)
+    with pytest.raises(hsd.HsdError):                      # draft id outside the vocabulary
+        h.verify(1, [1, -5], q, 2)
+    h.close()
+    big = _gpu_hier(model, TINY_EXITS, (4, 2), 0.0)
+    big.prefill(inputs.make_prompt(TINY["vocab"], 250, seed=3))
+    with pytest.raises(hsd.HsdError) as e:                 # KV capacity (256 tokens) exceeded
+        big.generate(32)
+    assert e.value.code == -2
+    big.close()

@@ -1,0 +1,127 @@
+"""GPU parity of the stand-alone kernels against the oracle (element by element, same seeded inputs)."""
+import numpy as np
+import pytest
+
+from oracle import decoder, specsample
+from paper_2510_19705_amd import inputs
+from helpers import say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hsd():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2510_19705_amd import hsd as lib
+    return lib
+
+
+def _cuda(a, dtype=None):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t if dtype is None else t.to(dtype)
+
+
+# ---- softmax ---------------------------------------------------------------------------------
+@pytest.mark.parametrize("rows,V", [(1, 50), (3, 2048), (5, 5000), (17, 128256)])
+@pytest.mark.parametrize("temperature", [1.0, 0.7, 0.0])
+def test_softmax(hsd, rows, V, temperature):
+    say("softmax", rows, V, temperature)
+    rng = np.random.default_rng(rows * 7 + V)
+    z = (rng.standard_normal((rows, V)) * 3).astype(np.float32)
+    if rows > 1:
+        z[1, 7] = z[1, V - 3] = z[1].max() + 1.0           # tie: lowest index must win
+    got = hsd.softmax(_cuda(z), temperature).cpu().numpy()
+    ref = decoder.distributions(z.astype(np.float64), temperature)
+    if temperature == 0:
+        assert (got == ref).all()
+    else:
+        # fp32 exp and a 1024-way fp32 sum: relative error ~1e-6 per element
+        assert np.abs(got - ref).max() <= 2e-6 * ref.max() + 1e-9
+        assert np.abs(got.astype(np.float64).sum(axis=1) - 1).max() < 1e-5
+
+
+# ---- accept / reject / resample: bit-exact on the oracle's probabilities and Philox stream ------
+@pytest.mark.parametrize("V", [50, 2048, 5000, 128256])
+@pytest.mark.parametrize("t", [0, 1, 4, 16])
+def test_accept_resample_bit_exact(hsd, V, t):
+    import torch
+    say("accept_resample", V, t)
+    seed = 0x1234ABCD5678EF01
+    n_calls = 40 if V < 100000 else 12
+    n_hist = np.zeros(t + 2, dtype=int)
+    for call in range(n_calls):
+        p, q, x = inputs.make_prob_rows(V, t, seed=1000 * V + 17 * t + call, sigma=2.0 + (call % 3), noise=0.3 + 0.5 * (call % 4))
+        ch = specsample.PhiloxChooser(seed)
+        n_ref, m_ref = specsample.verify(list(p), list(q), list(x), ch, level=3, call=call)
+        xd = _cuda(np.concatenate([x, [0]]).astype(np.int32))
+        n, m = hsd.accept_resample(_cuda(p), _cuda(q) if t else _cuda(p[:0]), xd, seed, 3, call)
+        assert (n, m) == (n_ref, m_ref), (V, t, call)
+        assert int(xd[n].item()) == m_ref
+        n_hist[n] += 1
+    say("  accepted-count histogram", n_hist.tolist())
+    if t >= 4:
+        assert (n_hist > 0).sum() >= 2                     # both rejections and acceptances were exercised
+
+
+def test_accept_resample_degenerate_rows(hsd):
+    import torch
+    V, seed = 3000, 77
+    # one-hot rows (temperature 0): accept iff the draft equals the verifier's argmax
+    p, q, x = inputs.make_prob_rows(V, 3, seed=5, one_hot=True)
+    q[0] = p[0]
+    x[0] = int(np.argmax(p[0]))                            # first draft agrees, second may not
+    for call in range(6):
+        ref = specsample.verify(list(p), list(q), list(x), specsample.PhiloxChooser(seed), 1, call)
+        xd = _cuda(np.concatenate([x, [0]]).astype(np.int32))
+        assert hsd.accept_resample(_cuda(p), _cuda(q), xd, seed, 1, call) == ref
+        assert ref[0] >= 1
+    # p == q exactly: every draft is accepted unless u*q rounds up to p; the residual is identically zero
+    p, q, x = inputs.make_prob_rows(V, 4, seed=6)
+    q = p[:4].copy()
+    for call in range(6):
+        ref = specsample.verify(list(p), list(q), list(x), specsample.PhiloxChooser(seed), 2, call)
+        xd = _cuda(np.concatenate([x, [0]]).astype(np.int32))
+        assert hsd.accept_resample(_cuda(p), _cuda(q), xd, seed, 2, call) == ref
+    # a draft the verifier gives zero mass is always rejected and never resampled
+    p, q, x = inputs.make_prob_rows(V, 2, seed=8)
+    p[0, x[0]] = 0.0
+    ref = specsample.verify(list(p), list(q), list(x), specsample.PhiloxChooser(seed), 1, 0)
+    xd = _cuda(np.concatenate([x, [0]]).astype(np.int32))
+    got = hsd.accept_resample(_cuda(p), _cuda(q), xd, seed, 1, 0)
+    assert got == ref and got[0] == 0 and got[1] != x[0]
+
+
+def test_accept_resample_rejects_bad_arguments(hsd):
+    import torch
+    p = torch.zeros((2, 8), device="cuda")
+    x = torch.zeros(70, dtype=torch.int32, device="cuda")
+    f = hsd.lib.hsd_accept_resample
+    assert f(p.data_ptr(), None, x.data_ptr(), 1, 8, 0, 0, 0, x.data_ptr(), x.data_ptr(), None) == -1      # drafts without q rows
+    assert b"draft rows" in hsd.lib.hsd_last_error()
+    assert f(p.data_ptr(), p.data_ptr(), x.data_ptr(), 65, 8, 0, 0, 0, x.data_ptr(), x.data_ptr(), None) == -1
+    assert f(None, p.data_ptr(), x.data_ptr(), 1, 8, 0, 0, 0, x.data_ptr(), x.data_ptr(), None) == -1
+    assert f(p.data_ptr(), p.data_ptr(), x.data_ptr(), 1, 0, 0, 0, 0, x.data_ptr(), x.data_ptr(), None) == -1
+
+
+# ---- small-M GEMM ----------------------------------------------------------------------------
+@pytest.mark.parametrize("m,n,k", [(1, 48, 64), (5, 5000, 256), (16, 3072, 2048), (17, 2048, 8192), (33, 1000, 512),
+                                   (64, 4096, 1024), (6, 32000, 2048)])
+@pytest.mark.parametrize("bf16", [True, False])
+def test_gemm(hsd, m, n, k, bf16):
+    import torch
+    say("gemm", m, n, k, "bf16" if bf16 else "f32")
+    rng = np.random.default_rng(m * 1000 + n + k)
+    x = rng.standard_normal((m, k)).astype(np.float32)
+    w = (rng.standard_normal((n, k)) / np.sqrt(k)).astype(np.float32)
+    if bf16:
+        x, w = inputs.bf16_round(x), inputs.bf16_round(w)
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    dt = hsd.BF16 if bf16 else hsd.F32
+    td = torch.bfloat16 if bf16 else torch.float32
+    packed = hsd.pack_weight(_cuda(w, td), dt)
+    got = hsd.gemm(_cuda(x, td), packed, n, dt).cpu().numpy()
+    # exact products, fp32 accumulation over k terms in a few partial sums
+    tol = 4e-6 * np.sqrt(k) * np.abs(ref).max() + 1e-6
+    assert np.abs(got - ref).max() < tol, (np.abs(got - ref).max(), tol)

@@ -1,0 +1,98 @@
+"""GPU parity of the decoder pass (all kernels assembled) against the fp64 oracle decoder."""
+import numpy as np
+import pytest
+
+from paper_2510_19705_amd import inputs
+from helpers import gpu_model, oracle_decoder, say
+
+pytestmark = pytest.mark.gpu
+
+# ragged on purpose: vocab not a multiple of 16, FFN a single odd multiple of 32, few heads
+SMALL_F32 = dict(n_layers=3, d=96, n_q=6, n_kv=2, hd=32, ffn=160, vocab=777)
+SMALL_BF16 = dict(n_layers=4, d=256, n_q=8, n_kv=2, hd=64, ffn=608, vocab=5000)
+SMALL_BF16_MHA = dict(n_layers=2, d=256, n_q=2, n_kv=2, hd=128, ffn=512, vocab=1000)
+
+
+def _tokens_dev(tok):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(tok, dtype=np.int32)).cuda()
+
+
+def _run_passes(model, oracle, toks, schedule, exits):
+    """schedule: list of (pos0, m, exit_index, n_logit_rows).  Yields (gpu logits, oracle logits)."""
+    for pos0, m, e, nl in schedule:
+        got = model.model_pass(_tokens_dev(toks[pos0:pos0 + m]), pos0, exits[e], nl).cpu().numpy()
+        ref = oracle.forward([int(t) for t in toks[pos0:pos0 + m]], pos0, exits[e])[m - nl:]
+        yield (pos0, m, exits[e], nl), got, ref
+
+
+def test_pass_fp32_logits_rel_1e4():
+    """fp32 storage: logits within 1e-4 relative (of the row's largest magnitude) of the oracle, over
+    prefill chunks, a paged (permuted) cache, multi-token passes at different exits and rewrites of
+    rejected positions."""
+    shape = SMALL_F32
+    w = inputs.make_weights(shape, seed=11, bf16=False)
+    toks = inputs.make_prompt(shape["vocab"], 200, seed=12)
+    model = gpu_model(shape, w, False, max_seq=256, max_rows=24)
+    model.set_pages([2, 0, 3, 1])
+    oracle = oracle_decoder(shape, w, 256)
+    exits = (1, 2, 3)
+    schedule = [(0, 24, 2, 0), (24, 24, 2, 3), (48, 17, 2, 17), (65, 1, 0, 1), (65, 1, 2, 1), (66, 5, 1, 5),
+                (66, 7, 2, 7), (70, 24, 2, 24), (94, 24, 2, 1), (118, 24, 2, 0), (142, 6, 2, 6)]
+    for tag, got, ref in _run_passes(model, oracle, toks, schedule, exits):
+        if got.shape[0] == 0:
+            continue
+        err = np.abs(got - ref).max() / np.abs(ref).max()
+        say("fp32 pass", tag, "rel err %.2e" % err)
+        assert err < 1e-4, tag
+    model.close()
+
+
+@pytest.mark.parametrize("shape", [SMALL_BF16, SMALL_BF16_MHA], ids=["gqa_hd64", "mha_hd128"])
+def test_pass_bf16_logits_abs_2e2(shape):
+    """bf16 storage (MFMA GEMMs, MFMA attention over the tiled cache): logits within 2e-2 absolute."""
+    w = inputs.make_weights(shape, seed=21, bf16=True)
+    toks = inputs.make_prompt(shape["vocab"], 330, seed=22)
+    model = gpu_model(shape, w, True, max_seq=384, max_rows=64)
+    model.set_pages([5, 1, 4, 0, 3, 2])
+    oracle = oracle_decoder(shape, w, 384)
+    L = shape["n_layers"]
+    exits = (1, L // 2, L)
+    schedule = [(0, 64, 2, 0), (64, 64, 2, 2), (128, 33, 2, 33), (161, 1, 0, 1), (161, 1, 2, 1), (162, 6, 1, 6),
+                (162, 9, 2, 9), (171, 64, 2, 0), (235, 64, 2, 5), (299, 17, 2, 17), (316, 4, 2, 4)]
+    worst = 0.0
+    for tag, got, ref in _run_passes(model, oracle, toks, schedule, exits):
+        if got.shape[0] == 0:
+            continue
+        err = np.abs(got - ref).max()
+        worst = max(worst, err)
+        say("bf16 pass", tag, "abs err %.2e (|z| max %.2f)" % (err, np.abs(ref).max()))
+        assert err < 2e-2, tag
+    assert worst > 0                                      # bf16 rounding is visible: the path really is bf16
+    model.close()
+
+
+def test_pass_rejects_bad_arguments():
+    shape = SMALL_F32
+    w = inputs.make_weights(shape, seed=1, bf16=False)
+    from paper_2510_19705_amd import hsd
+    model = hsd.Model(shape, hsd.F32, 128, 8, inputs.ROPE_BASE, inputs.EPS)
+    tok = _tokens_dev(np.zeros(8))
+    with pytest.raises(hsd.HsdError) as e:                # weights not loaded yet
+        model.model_pass(tok[:2], 0, 1, 1)
+    assert e.value.code == -3
+    model.load(w)
+    for args, code in [((tok, 125, 1, 1), -2),            # positions beyond the KV capacity
+                       ((tok[:2], 0, 4, 1), -1),          # exit layer out of range
+                       ((tok[:2], 0, 1, 3), -1)]:         # more logit rows than tokens
+        with pytest.raises(hsd.HsdError) as e:
+            model.model_pass(*args)
+        assert e.value.code == code, args
+    import torch
+    big = torch.zeros(9, dtype=torch.int32, device="cuda")
+    with pytest.raises(hsd.HsdError) as e:
+        model.model_pass(big, 0, 1, 1)                    # more rows than max_rows
+    assert e.value.code == -2
+    with pytest.raises(hsd.HsdError):
+        model.set_pages([0, 0])
+    model.close()
