@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Bench of the HSD hot path on one MI355X.
+
+Workload (benchmark configs[1]): 1B-shaped early-exit hierarchy, bf16, batch 1 - 16 layers,
+d 2048, 32 query / 8 KV heads x 64, FFN 8192, vocab 32000, drafters = exits after layers 2 and 6
+sharing the final norm and head; prompt of 512 uniform-random ids, 256 generated tokens,
+temperature 1.  Random-init weights (the paper's checkpoints and prompts are not available offline).
+
+One step = one full generation of 256 tokens by HSD from the prefilled prompt (rewind + generate:
+every draft pass, verify pass, softmax, accept/reject/resample kernel and the round driver).
+The (T_0, T_1) sweep {2,4,6} x {1,2,4}, the single-draft sweep and plain autoregressive decoding are
+measured first (untimed part); the timed steps run the best HSD setting.
+
+Prints ONE JSON line.  `value` = generated tokens per second of HSD with everything resident in HBM.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PROMPT, GEN, TEMPERATURE, SEED = 512, 256, 1.0, 20251019
+EXITS = (2, 6, 16)
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def gemm_site_bytes(shape, site, m):
+    """Algorithmic bytes of one launch: the weight matrix once + activations in and out."""
+    d, F, V = shape["d"], shape["ffn"], shape["vocab"]
+    nq, nkv = shape["n_q"] * shape["hd"], shape["n_kv"] * shape["hd"]
+    n, k, out_b = {"qkv": (nq + 2 * nkv, d, 4), "o": (d, nq, 4), "gateup": (2 * F, d, 1), "down": (d, F, 4),
+                   "head": (V, d, 4)}[site]
+    return n * k * 2 + m * k * 2 + m * n * out_b
+
+
+def pass_bytes(shape, exit_layer, m, s_total, n_logit_rows):
+    """Algorithmic bytes of one pass: weights of the layers run + head once, KV read and written,
+    logits and probability rows."""
+    d, F, V = shape["d"], shape["ffn"], shape["vocab"]
+    nq, nkv = shape["n_q"] * shape["hd"], shape["n_kv"] * shape["hd"]
+    layer_w = (d * (nq + 2 * nkv) + nq * d + 3 * d * F) * 2
+    kv = exit_layer * (2 * s_total * nkv * 2 + 2 * m * nkv * 2)
+    return exit_layer * layer_w + V * d * 2 + kv + n_logit_rows * V * 8
+
+
+def timed_generation(h, torch, n_prompt, n_gen, repeats):
+    best = None
+    for _ in range(repeats):
+        h.rewind(n_prompt)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        out, st = h.generate(n_gen)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        if best is None or dt < best[0]:
+            best = (dt, st)
+    return best
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the sweeps; run HSD at T=(4,2) only")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, 'How the path would shard').")
+        sys.exit(2)
+
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    from paper_2510_19705_amd import hsd, inputs
+
+    shape = inputs.SHAPES["1b"]
+    t0 = time.time()
+    weights = inputs.make_weights(shape, seed=SEED, bf16=True)
+    prompt = inputs.make_prompt(shape["vocab"], PROMPT, seed=SEED + 1)
+    log("weights generated in %.1f s" % (time.time() - t0))
+    model = hsd.Model(shape, hsd.BF16, 1024, 64, inputs.ROPE_BASE, inputs.EPS)
+    model.load(weights)
+    log("model loaded (%.2f GB packed)" % (model.weights.numel() / 1e9))
+
+    def make(levels, T):
+        h = hsd.Hierarchy([(model, e) for e in levels], T, TEMPERATURE, SEED)
+        h.prefill(prompt)
+        return h
+
+    results = {}
+
+    def measure(name, levels, T, repeats=2):
+        h = make(levels, T)
+        h.generate(GEN)                                   # warm-up
+        dt, st = timed_generation(h, torch, PROMPT, GEN, repeats)
+        n = len(levels)
+        results[name] = {"levels": list(levels), "T": list(T), "tokens_per_s": GEN / dt,
+                         "acceptance": [st.accepted[i] / max(1, st.drafted[i]) for i in range(1, n)],
+                         "passes": [st.passes[i] for i in range(n)], "rounds": st.rounds}
+        h.close()
+        return results[name]
+
+    # ---- untimed part: sweeps ---------------------------------------------------------------------
+    ar = measure("autoregressive", (16,), ())
+    log("autoregressive target: %.1f tok/s" % ar["tokens_per_s"])
+    best_hsd, best_single = ("hsd_T4_2", None), (None, None)
+    if args.no_sweep:
+        r = measure("hsd_T4_2", EXITS, (4, 2))
+        best_hsd = ("hsd_T4_2", r)
+    else:
+        for k1 in (2, 4, 6):
+            for k2 in (1, 2, 4):
+                name = "hsd_T%d_%d" % (k1, k2)
+                r = measure(name, EXITS, (k1, k2))
+                log("%s: %.1f tok/s acceptance %s" % (name, r["tokens_per_s"], ["%.2f" % a for a in r["acceptance"]]))
+                if best_hsd[1] is None or r["tokens_per_s"] > best_hsd[1]["tokens_per_s"]:
+                    best_hsd = (name, r)
+        for e in EXITS[:-1]:
+            for T in (1, 2, 3, 4, 6, 8):
+                name = "single_exit%d_T%d" % (e, T)
+                r = measure(name, (e, 16), (T,))
+                log("%s: %.1f tok/s acceptance %.2f" % (name, r["tokens_per_s"], r["acceptance"][0]))
+                if best_single[1] is None or r["tokens_per_s"] > best_single[1]["tokens_per_s"]:
+                    best_single = (name, r)
+    T_best = tuple(best_hsd[1]["T"])
+
+    # ---- timed steps: HSD at the best setting ---------------------------------------------------
+    h = make(EXITS, T_best)
+    for _ in range(args.warmup):
+        h.rewind(PROMPT)
+        h.generate(GEN)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        h.rewind(PROMPT)
+        h.generate(GEN)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    value = GEN * args.steps / elapsed
+    st = h.stats()
+
+    # ---- per-pass HBM fraction (c_i of the latency model, measured at the M the level sees) --------
+    passes = {}
+    for lvl, e in enumerate(EXITS):
+        m = 1 if lvl == 0 else min(int(round(st.pass_rows[lvl] / max(1, st.passes[lvl]))), T_best[0] + (T_best[1] if lvl == 2 else 0) + 1)
+        m = max(1, m)
+        ms = h.measure_pass(lvl, m, 50)
+        b = pass_bytes(shape, e, m, h.sequence_length(), m)
+        passes["exit%d" % e] = {"rows": m, "ms": ms, "algorithmic_GB": b / 1e9, "GBps": b / ms / 1e6,
+                                "hbm_frac": b / ms / 1e6 / HBM_PEAK_GBS}
+
+    # ---- roofline of the dominant kernel: one more step with per-site event brackets ------------
+    h.rewind(PROMPT)
+    model.profile_begin(60000)
+    h.generate(GEN)
+    sites = model.profile_end()
+    st2 = h.stats()
+    gemm_sites = {k: v for k, v in sites.items() if k != "attn" and v[0] > 0}
+    dom = max(gemm_sites, key=lambda k: gemm_sites[k][1])
+    launches, total_ms = sites[dom]
+    rows_avg = sum(st2.pass_rows[i] for i in range(3)) / max(1, sum(st2.passes[i] for i in range(3)))
+    logit_rows_avg = (st2.passes[0] + st2.drafted[1] + st2.passes[1] + st2.drafted[2] + st2.passes[2]) / max(
+        1, sum(st2.passes[i] for i in range(3)))
+    m_avg = logit_rows_avg if dom == "head" else rows_avg
+    bytes_per_launch = gemm_site_bytes(shape, dom, m_avg)
+    avg_us = total_ms / launches * 1e3
+    achieved = bytes_per_launch / (avg_us * 1e-6) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % dom)
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+    roofline = {"bound": "hbm", "kernel": "gemm_bf16_kernel (%s projection)" % dom, "achieved": achieved,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                "avg_launch_us": avg_us, "launches": launches, "bytes_per_launch": bytes_per_launch,
+                "sites_ms": {k: round(v[1], 3) for k, v in sites.items()},
+                "sites_launches": {k: v[0] for k, v in sites.items()}}
+    h.close()
+
+    # ---- CPU baseline: the oracle on a bounded sample of the same workload ------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import decoder, hsd as ohsd, specsample
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            threads = os.cpu_count()
+        t0 = time.time()
+        spec = decoder.Spec(shape["n_layers"], shape["d"], shape["n_q"], shape["n_kv"], shape["hd"], shape["ffn"],
+                            shape["vocab"], inputs.ROPE_BASE, inputs.EPS)
+        dec = decoder.Decoder(spec, weights, PROMPT + GEN + 32)
+        log("oracle set up in %.1f s" % (time.time() - t0))
+        levels = [decoder.Level(dec, e, TEMPERATURE) for e in EXITS]
+        o = ohsd.HSD(levels, T_best, specsample.PhiloxChooser(SEED))
+        n_p, n_g = PROMPT, 128
+        o.levels[2].next_dists([int(t) for t in prompt[:n_p]], 1)      # prefill, untimed like the GPU's
+        t0 = time.perf_counter()
+        o.generate([int(t) for t in prompt[:n_p]], n_g)
+        dt = time.perf_counter() - t0
+        cpu = {"value": n_g / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+               "sample": "same 1B-shaped hierarchy and T, fp64 numpy oracle, prompt %d tokens (prefill untimed), first %d "
+                         "generated tokens (%.1f s)" % (n_p, n_g, dt)}
+
+    out = {
+        "metric": "HSD tokens/sec at bs=1 vs best single-draft; verify-pass HBM GB/s / peak",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "1B-shaped early-exit hierarchy (16 layers, d 2048, 32q/8kv x 64, FFN 8192, vocab 32000), "
+                               "exits 2/6/16, bf16, batch 1, prompt 512, generate 256, temperature 1",
+                   "T": list(T_best), "global_batch": 1, "seq_len": PROMPT + GEN},
+        "hsd": best_hsd[1], "best_single_draft": best_single[1], "autoregressive": ar,
+        "hsd_vs_best_single_draft": (best_hsd[1]["tokens_per_s"] / best_single[1]["tokens_per_s"]) if best_single[1] else None,
+        "hsd_vs_autoregressive": best_hsd[1]["tokens_per_s"] / ar["tokens_per_s"],
+        "sweep": {k: round(v["tokens_per_s"], 1) for k, v in results.items()},
+        "verify_pass": passes,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    model.close()
+
+
+if __name__ == "__main__":
+    main()

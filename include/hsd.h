@@ -81,12 +81,26 @@ int hsd_model_set_pages(hsd_model*, const int32_t* page_table, int n_pages);
 int hsd_model_pass(hsd_model*, const int32_t* tokens_dev, int pos0, int m, int exit_layer,
                    int n_logit_rows, float* logits_dev);
 
+/* Per-site device timing of a model's passes, for roofline accounting.  Between begin and end every
+ * launch at the sites below is bracketed by two events on the model's stream (up to max_launches
+ * launches, later ones are not timed; the brackets add a little host and device overhead, so throughput
+ * is measured without them).  end synchronises the stream and returns launches and total
+ * milliseconds per site. */
+enum { HSD_SITE_QKV = 0, HSD_SITE_ATTN = 1, HSD_SITE_O = 2, HSD_SITE_GATEUP = 3, HSD_SITE_DOWN = 4, HSD_SITE_HEAD = 5,
+       HSD_N_SITES = 6 };
+typedef struct {
+    int64_t launches[HSD_N_SITES];
+    double ms[HSD_N_SITES];
+} hsd_site_times;
+int hsd_profile_begin(hsd_model*, int max_launches);
+int hsd_profile_end(hsd_model*, hsd_site_times* out);
+
 /* ---------------------------------------------------------------------------------------------
  * Stand-alone kernels of the path (each is what the pass / the driver launches internally).
  * ------------------------------------------------------------------------------------------- */
 
 /* p = softmax(z / temperature) row-wise, fp32 [rows, vocab]; temperature == 0 writes the one-hot
- * row at the lowest-index maximum.  In-place allowed. */
+ * row at the lowest-index maximum.  logits_dev and probs_dev must not overlap. */
 int hsd_softmax(const float* logits_dev, float* probs_dev, int rows, int vocab, float temperature,
                 void* stream);
 

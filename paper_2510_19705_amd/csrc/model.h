@@ -35,6 +35,11 @@ struct hsd_model {
     size_t part_elems;
     std::vector<bool> layer_loaded;
     bool head_loaded;
+    // optional per-site event timing (hsd_profile_begin / hsd_profile_end)
+    bool prof_on;
+    size_t prof_used;
+    std::vector<hipEvent_t> prof_events;   // pairs
+    std::vector<int> prof_site;
 };
 
 int model_pass(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows, int exit_layer, int n_logit_rows,

@@ -137,6 +137,8 @@ extern "C" int hsd_model_create(const hsd_model_desc* desc, void* weights_dev, v
     m->part_elems = part_elems_needed(*desc);
     m->layer_loaded.assign(desc->n_layers, false);
     m->head_loaded = false;
+    m->prof_on = false;
+    m->prof_used = 0;
     // Cache rows beyond the valid length are read (and masked) by the attention kernels: keep them finite.
     hipError_t e = hipMemsetAsync(kv_dev, 0, m->kv_layer_bytes * desc->n_layers, m->stream);
     // Padded rows of packed matrices must be zero.
@@ -153,7 +155,58 @@ extern "C" int hsd_model_create(const hsd_model_desc* desc, void* weights_dev, v
     return HSD_OK;
 }
 
-extern "C" void hsd_model_destroy(hsd_model* m) { delete m; }
+extern "C" void hsd_model_destroy(hsd_model* m) {
+    if (!m) return;
+    for (hipEvent_t e : m->prof_events) (void)hipEventDestroy(e);
+    delete m;
+}
+
+extern "C" int hsd_profile_begin(hsd_model* m, int max_launches) {
+    if (!m || max_launches < 1 || max_launches > (1 << 20)) HSD_FAIL(HSD_EINVAL, "hsd_profile_begin: bad arguments");
+    while (m->prof_events.size() < (size_t)2 * max_launches) {
+        hipEvent_t e;
+        HSD_HIP(hipEventCreate(&e));
+        m->prof_events.push_back(e);
+    }
+    m->prof_site.assign(max_launches, -1);
+    m->prof_used = 0;
+    m->prof_on = true;
+    return HSD_OK;
+}
+
+extern "C" int hsd_profile_end(hsd_model* m, hsd_site_times* out) {
+    if (!m || !out) HSD_FAIL(HSD_EINVAL, "hsd_profile_end: null pointer");
+    if (!m->prof_on) HSD_FAIL(HSD_ESTATE, "hsd_profile_end: profiling was not started");
+    m->prof_on = false;
+    HSD_HIP(hipStreamSynchronize(m->stream));
+    memset(out, 0, sizeof(*out));
+    for (size_t i = 0; i < m->prof_used; ++i) {
+        float ms = 0.f;
+        HSD_HIP(hipEventElapsedTime(&ms, m->prof_events[2 * i], m->prof_events[2 * i + 1]));
+        out->launches[m->prof_site[i]]++;
+        out->ms[m->prof_site[i]] += ms;
+    }
+    return HSD_OK;
+}
+
+namespace {
+// Brackets one launch with events when profiling is on.
+struct SiteTimer {
+    hsd_model* m;
+    bool active;
+    size_t slot;
+    SiteTimer(hsd_model* m_, int site) : m(m_), active(false), slot(0) {
+        if (m->prof_on && m->prof_used < m->prof_site.size()) {
+            slot = m->prof_used++;
+            m->prof_site[slot] = site;
+            active = hipEventRecord(m->prof_events[2 * slot], m->stream) == hipSuccess;
+        }
+    }
+    ~SiteTimer() {
+        if (active) (void)hipEventRecord(m->prof_events[2 * slot + 1], m->stream);
+    }
+};
+}  // namespace
 
 extern "C" int hsd_model_set_pages(hsd_model* m, const int32_t* page_table, int n_pages) {
     if (!m || !page_table) HSD_FAIL(HSD_EINVAL, "hsd_model_set_pages: null pointer");
@@ -227,17 +280,32 @@ int model_pass(hsd_model* m, const int32_t* tok, int pos0, int rows, int exit_la
         void* kv_layer = m->kv + m->kv_layer_bytes * l;
         if ((rc = launch_resid_rmsnorm(m->x, pending, pending_split, rows, 0, L.norm1, m->xn, rows, 0, d.d, d.eps, d.dtype, s))) return rc;
         GemmPlan pq = gemm_plan(rows, nqkv, d.d, d.dtype, false);
-        if ((rc = launch_gemm(m->xn, L.wqkv, m->part, rows, nqkv, d.d, d.dtype, pq, s))) return rc;
+        {
+            SiteTimer t(m, HSD_SITE_QKV);
+            if ((rc = launch_gemm(m->xn, L.wqkv, m->part, rows, nqkv, d.d, d.dtype, pq, s))) return rc;
+        }
         if ((rc = launch_rope_kv(m->part, pq.ksplit, rows, m->q, kv_layer, m->pages_dev, pos0, d.n_q, d.n_kv, d.hd, d.rope_base, d.dtype, s))) return rc;
-        if ((rc = launch_attention(m->q, kv_layer, m->pages_dev, m->max_pages, nullptr, pos0, 1, rows, pos0 + rows, d.n_q, d.n_kv,
-                                   d.hd, d.dtype, m->att, m->attn_ws, 0, s))) return rc;
+        {
+            SiteTimer t(m, HSD_SITE_ATTN);
+            if ((rc = launch_attention(m->q, kv_layer, m->pages_dev, m->max_pages, nullptr, pos0, 1, rows, pos0 + rows, d.n_q, d.n_kv,
+                                       d.hd, d.dtype, m->att, m->attn_ws, 0, s))) return rc;
+        }
         GemmPlan po = gemm_plan(rows, d.d, nq, d.dtype, false);
-        if ((rc = launch_gemm(m->att, L.wo, m->part, rows, d.d, nq, d.dtype, po, s))) return rc;
+        {
+            SiteTimer t(m, HSD_SITE_O);
+            if ((rc = launch_gemm(m->att, L.wo, m->part, rows, d.d, nq, d.dtype, po, s))) return rc;
+        }
         if ((rc = launch_resid_rmsnorm(m->x, m->part, po.ksplit, rows, 0, L.norm2, m->xn, rows, 0, d.d, d.eps, d.dtype, s))) return rc;
         GemmPlan pg = gemm_plan(rows, 2 * d.ffn, d.d, d.dtype, true);
-        if ((rc = launch_gemm_swiglu(m->xn, L.wgu, m->h, rows, d.ffn, d.d, d.dtype, pg, s))) return rc;
+        {
+            SiteTimer t(m, HSD_SITE_GATEUP);
+            if ((rc = launch_gemm_swiglu(m->xn, L.wgu, m->h, rows, d.ffn, d.d, d.dtype, pg, s))) return rc;
+        }
         GemmPlan pd = gemm_plan(rows, d.d, d.ffn, d.dtype, false);
-        if ((rc = launch_gemm(m->h, L.wd, m->part, rows, d.d, d.ffn, d.dtype, pd, s))) return rc;
+        {
+            SiteTimer t(m, HSD_SITE_DOWN);
+            if ((rc = launch_gemm(m->h, L.wd, m->part, rows, d.d, d.ffn, d.dtype, pd, s))) return rc;
+        }
         pending = m->part;
         pending_split = pd.ksplit;
     }
@@ -245,8 +313,11 @@ int model_pass(hsd_model* m, const int32_t* tok, int pos0, int rows, int exit_la
     const int row0 = rows - n_logit_rows;
     if ((rc = launch_resid_rmsnorm(m->x, pending, pending_split, rows, row0, m->norm_f, m->xn, n_logit_rows, row0, d.d, d.eps, d.dtype, s))) return rc;
     GemmPlan ph = gemm_plan(n_logit_rows, d.vocab, d.d, d.dtype, false);
-    if (ph.ksplit == 1) return launch_gemm(m->xn, m->head, logits, n_logit_rows, d.vocab, d.d, d.dtype, ph, s);
-    if ((rc = launch_gemm(m->xn, m->head, m->part, n_logit_rows, d.vocab, d.d, d.dtype, ph, s))) return rc;
+    {
+        SiteTimer t(m, HSD_SITE_HEAD);
+        if (ph.ksplit == 1) return launch_gemm(m->xn, m->head, logits, n_logit_rows, d.vocab, d.d, d.dtype, ph, s);
+        if ((rc = launch_gemm(m->xn, m->head, m->part, n_logit_rows, d.vocab, d.d, d.dtype, ph, s))) return rc;
+    }
     return launch_reduce_partials(m->part, logits, n_logit_rows * d.vocab, ph.ksplit, s);
 }
 

@@ -35,6 +35,14 @@ class Level(C.Structure):
     _fields_ = [("model", C.c_void_p), ("exit_layer", C.c_int)]
 
 
+N_SITES = 6
+SITE_NAMES = ("qkv", "attn", "o", "gateup", "down", "head")
+
+
+class SiteTimes(C.Structure):
+    _fields_ = [("launches", C.c_int64 * N_SITES), ("ms", C.c_double * N_SITES)]
+
+
 class Stats(C.Structure):
     _fields_ = [("passes", C.c_int64 * MAX_LEVELS), ("pass_rows", C.c_int64 * MAX_LEVELS),
                 ("drafted", C.c_int64 * MAX_LEVELS), ("accepted", C.c_int64 * MAX_LEVELS),
@@ -53,6 +61,8 @@ _SIGS = {
     "hsd_model_load_head": (_i, [_vp, _vp, _vp, _vp]),
     "hsd_model_set_pages": (_i, [_vp, C.POINTER(C.c_int32), _i]),
     "hsd_model_pass": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
+    "hsd_profile_begin": (_i, [_vp, _i]),
+    "hsd_profile_end": (_i, [_vp, C.POINTER(SiteTimes)]),
     "hsd_softmax": (_i, [_vp, _vp, _i, _i, _f, _vp]),
     "hsd_sampler_scratch_bytes": (_sz, [_i]),
     "hsd_accept_resample": (_i, [_vp, _vp, _vp, _i, _i, C.c_uint64, C.c_uint32, C.c_uint32, _vp, _vp, _vp]),
@@ -165,6 +175,14 @@ class Model:
             self.load_layer(i, lw)
         self.load_head(weights["embed"], weights["head"], weights["norm_f"])
 
+    def profile_begin(self, max_launches):
+        _check(lib.hsd_profile_begin(self.handle, max_launches))
+
+    def profile_end(self):
+        st = SiteTimes()
+        _check(lib.hsd_profile_end(self.handle, C.byref(st)))
+        return {SITE_NAMES[i]: (st.launches[i], st.ms[i]) for i in range(N_SITES)}
+
     def set_pages(self, table):
         a, p = _i32(table)
         _check(lib.hsd_model_set_pages(self.handle, p, len(a)))
@@ -231,10 +249,11 @@ class Hierarchy:
         self._lv = (Level * self.n)(*[Level(m.handle, e) for m, e in levels])
         self._T = (C.c_int * max(1, self.K))(*self.T)
         nbytes = lib.hsd_hier_workspace_bytes(self.n, self._lv, self._T)
-        if nbytes == 0:
-            raise HsdError(-1)
-        self.workspace = _buf(nbytes)
         self.handle = C.c_void_p()
+        if nbytes == 0:      # invalid hierarchy: let create report the status code
+            _check(lib.hsd_hier_create(self.n, self._lv, self._T, float(temperature), seed, None, 0,
+                                       self.models[0].stream, C.byref(self.handle)))
+        self.workspace = _buf(nbytes)
         _check(lib.hsd_hier_create(self.n, self._lv, self._T, float(temperature), seed, self.workspace.data_ptr(),
                                    self.workspace.numel(), self.models[0].stream, C.byref(self.handle)))
 
