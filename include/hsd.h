@@ -125,12 +125,12 @@ int hsd_accept_resample(const float* p_dev, const float* q_dev, int32_t* x_dev, 
 /* Small-M weight-streaming GEMM y = x W^T.  hsd_pack_weight lays W [n, k] (row-major, dtype) out in
  * the streaming format (packed_dev: hsd_packed_bytes(n, k, dtype)); hsd_gemm computes
  * y_dev [m, n] fp32 = x_dev [m, k] (dtype) times the packed matrix.  k must be a multiple of 32,
- * 1 <= m <= HSD_MAX_PASS_ROWS.  workspace_dev: hsd_gemm_workspace_bytes(m, n, k). */
+ * 1 <= m <= HSD_MAX_PASS_ROWS.  This is the kernel the pass uses for every projection (there with the
+ * neighbouring element-wise steps fused into its operand load and epilogue). */
 size_t hsd_packed_bytes(int n, int k, int dtype);
-size_t hsd_gemm_workspace_bytes(int m, int n, int k);
 int hsd_pack_weight(const void* w_dev, void* packed_dev, int n, int k, int dtype, void* stream);
 int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int n, int k, int dtype,
-             void* workspace_dev, void* stream);
+             void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Hierarchy M_0..M_K with parameters T_0..T_{K-1} (Alg. 1).  Level 0 drafts autoregressively,

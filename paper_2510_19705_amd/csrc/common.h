@@ -85,18 +85,35 @@ __host__ __device__ __forceinline__ size_t packed_index(int n, int k, int K) {
     return tile * 512 + lane * 8 + (k & 7);
 }
 
-// ---- launchers shared between translation units ----------------------------------------------
-struct GemmPlan {
-    int ksplit;     // cross-workgroup split of K; partial sums land in [ksplit][m][n] fp32
-    int nt;         // 16-column tiles per workgroup
-    int waves;      // waves per workgroup (they split the workgroup's K range)
+// ---- GEMM launch interface (kernels_gemm.hip) ---------------------------------------------------
+enum { A_BF16 = 0, A_NORM = 1 };                                       // A operand source
+enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_ROPE = 3 };   // epilogue
+
+struct GemmArgs {
+    const void* a;                      // A_BF16: bf16 [M, K]; A_NORM: fp32 residual rows [M, K]
+    const float* norm_w;                // A_NORM: RMSNorm weight [K]
+    const unsigned long long* ss_in;    // A_NORM: per row, sum of squares * 2^24
+    unsigned long long* ss_zero;        // A_NORM: buffer the next producer will add into (cleared here), or null
+    float eps;
+    const bf16x8* wp;                   // packed W [N, K]
+    int M, N, K;
+    float* out_f32;                     // EPI_STORE: y [M, N]; EPI_RESID: residual rows [M, N], updated in place
+    unsigned long long* ss_out;         // EPI_RESID: per row, += sum of squares of the new residual * 2^24
+    bf16_t* out_bf16;                   // EPI_SWIGLU: h [M, N/2]; EPI_ROPE: q [M, n_q, hd]
+    bf16_t* kv_layer;                   // EPI_ROPE: this layer's KV pages
+    const int32_t* pages;
+    int pos0, n_q, n_kv, hd;
+    float rope_base;
 };
-GemmPlan gemm_plan(int m, int n, int k, int dtype, bool swiglu);
-// y partials [ksplit][m][n] fp32 = x [m,k] (dtype) * packed W^T
-int launch_gemm(const void* x, const void* wp, float* part, int m, int n, int k, int dtype, const GemmPlan& p,
-                hipStream_t s);
-// h [m, f] (dtype) = silu(gate) * up, W packed with gate/up rows interleaved in 16-row tiles (n = 2f)
-int launch_gemm_swiglu(const void* x, const void* wp, void* h, int m, int f, int k, int dtype, const GemmPlan& p,
-                       hipStream_t s);
-int launch_pack(const void* w, void* packed, int n, int k, int dtype, int row_offset, int n_total,
-                int interleave, hipStream_t s);
+
+struct GemmPlan {
+    int nt;       // 16-column tiles per workgroup
+    int waves;    // waves per workgroup; they split K
+};
+GemmPlan gemm_plan(int m, int n, int k, int epi);
+void gemm_tune(int epilogue, int nt, int waves);
+int launch_gemm_bf16(const GemmArgs& g, int asrc, int epi, const GemmPlan& p, hipStream_t s);
+int launch_gemm_f32(const float* x, const float* w, float* out, int m, int n, int k, bool swiglu, hipStream_t s);
+// interleave: 0 plain rows at row_offset, 1 / 2 gate / up of a fused SwiGLU matrix, 3 attention heads of hd rows
+// with each 16-dim block followed by the block of its RoPE partners
+int launch_pack(const void* w, void* packed, int n, int k, int dtype, int row_offset, int interleave, int hd, hipStream_t s);

@@ -14,17 +14,50 @@
 #include "common.h"
 
 // ------------------------------------------------------------------------------------------------
-// bf16 MFMA partial kernel.  grid (nsplit, n_kv, batch * qgroups), 64 threads.
+// bf16 MFMA kernel.  grid (nsplit, n_kv, batch * qgroups), NW waves per workgroup.  The waves of a
+// workgroup take the 32-position steps of the workgroup's range round-robin and combine their
+// online-softmax states through LDS.  With nsplit == 1 the normalised output is written directly;
+// otherwise one partial per workgroup goes to the merge kernel.
 // ------------------------------------------------------------------------------------------------
+template <int HD>
+struct KvTiles {
+    bf16x8 k[2][HD / 32];
+    bf16x8 v[HD / 16];
+};
+
+template <int HD>
+__device__ __forceinline__ void load_kv(KvTiles<HD>& t, const bf16_t* __restrict__ kv_layer, const int32_t* __restrict__ pages,
+                                        size_t page_base, int step, int n_kv, int g, int lane) {
+    constexpr int KC = HD / 32, DT = HD / 16;
+    const int p0 = step << 5;
+    const int page = pages[page_base + p0 / HSD_KV_PAGE];
+    const int inpage = p0 % HSD_KV_PAGE;
+    const size_t blk = kv_block_elems(HD);
+    const bf16_t* kblk = kv_layer + ((size_t)page * n_kv + g) * 2 * blk;
+    const bf16_t* vblk = kblk + blk;
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int c = 0; c < KC; ++c)
+            t.k[h][c] = *reinterpret_cast<const bf16x8*>(kblk + (size_t)(((inpage >> 4) + h) * KC + c) * 512 + lane * 8);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+        t.v[dt] = *reinterpret_cast<const bf16x8*>(vblk + (size_t)((inpage >> 5) * DT + dt) * 512 + lane * 8);
+}
+
 template <int HD, int QT>
-__global__ __launch_bounds__(64) void attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kv_layer,
-                                                       const int32_t* __restrict__ pages, int max_pages,
-                                                       const int32_t* __restrict__ pos0_arr, int pos0_all, int M, int n_q,
-                                                       int n_kv, float scale_log2, int steps_per_split, int qgroups,
-                                                       float* __restrict__ part_o, float* __restrict__ part_ml, int rpad) {
+__global__ __launch_bounds__(512) void attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kv_layer,
+                                                        const int32_t* __restrict__ pages, int max_pages,
+                                                        const int32_t* __restrict__ pos0_arr, int pos0_all, int M, int n_q,
+                                                        int n_kv, float scale_log2, int steps_per_split, int qgroups,
+                                                        float* __restrict__ part_o, float* __restrict__ part_ml, int rpad,
+                                                        bf16_t* __restrict__ att) {
+    extern __shared__ float lds[];                 // [NW][QT*16][HD + 2]: o, then running max and sum
     constexpr int KC = HD / 32;   // K chunks of 32 dims per 16-position tile
     constexpr int DT = HD / 16;   // 16-dim tiles of the output
-    const int lane = threadIdx.x, j = lane & 15, grp = lane >> 4;
+    constexpr int RS = HD + 2;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
+    const int j = lane & 15, grp = lane >> 4;
     const int split = blockIdx.x, nsplit = gridDim.x, g = blockIdx.y;
     const int b = blockIdx.z / qgroups, qg = blockIdx.z % qgroups;
     const int group = n_q / n_kv;
@@ -55,30 +88,21 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(const bf16_t* __restrict_
         for (int dt = 0; dt < DT; ++dt) o[qt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    const size_t blk = kv_block_elems(HD);
-    for (int step = step0; step < step1; ++step) {
+    const size_t page_base = (size_t)b * max_pages;
+    KvTiles<HD> cur, nxt;
+    int step = step0 + wave;
+    if (step < step1) load_kv<HD>(cur, kv_layer, pages, page_base, step, n_kv, g, lane);
+    for (; step < step1; step += NW) {
+        const bool more = step + NW < step1;
+        if (more) load_kv<HD>(nxt, kv_layer, pages, page_base, step + NW, n_kv, g, lane);   // in flight during the math
         const int p0 = step << 5;
-        const int page = pages[(size_t)b * max_pages + p0 / HSD_KV_PAGE];
-        const int inpage = p0 % HSD_KV_PAGE;
-        const bf16_t* kblk = kv_layer + ((size_t)page * n_kv + g) * 2 * blk;
-        const bf16_t* vblk = kblk + blk;
-        bf16x8 kreg[2][KC], vreg[DT];
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int c = 0; c < KC; ++c)
-                kreg[h][c] = *reinterpret_cast<const bf16x8*>(kblk + (size_t)(((inpage >> 4) + h) * KC + c) * 512 + lane * 8);
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-            vreg[dt] = *reinterpret_cast<const bf16x8*>(vblk + (size_t)((inpage >> 5) * DT + dt) * 512 + lane * 8);
-
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
             f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int c = 0; c < KC; ++c) {
-                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[0][c], qreg[qt][c], s0, 0, 0, 0);
-                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[1][c], qreg[qt][c], s1, 0, 0, 0);
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[0][c], qreg[qt][c], s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[1][c], qreg[qt][c], s1, 0, 0, 0);
             }
             // lane (j, grp): s0[r] is position p0 + 4 grp + r, s1[r] is p0 + 16 + 4 grp + r, query row j
             float v[8];
@@ -110,23 +134,52 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(const bf16_t* __restrict_
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
                 o[qt][dt] *= alpha;
-                o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vreg[dt], pb, o[qt][dt], 0, 0, 0);
+                o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.v[dt], pb, o[qt][dt], 0, 0, 0);
             }
         }
+        if (more) cur = nxt;
     }
 
-    // partial: o^T accumulators hold d = 16 dt + 4 grp + r for query row j
-    const size_t pbase = (((size_t)b * n_kv + g) * nsplit + split) * rpad;
+    // this wave's state to LDS: o^T accumulators hold d = 16 dt + 4 grp + r for query row j
+    float* mine = lds + (size_t)wave * (QT * 16) * RS;
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
-        const int r = (qg * QT + qt) * 16 + j;
-        if (r < rpad) {
+        float* rowp = mine + (qt * 16 + j) * RS;
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-                *reinterpret_cast<f32x4*>(part_o + (pbase + r) * HD + dt * 16 + grp * 4) = o[qt][dt];
-            if (grp == 0) {
-                part_ml[(pbase + r) * 2] = m_run[qt];
-                part_ml[(pbase + r) * 2 + 1] = l_run[qt];
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) rowp[dt * 16 + grp * 4 + r] = o[qt][dt][r];
+        if (grp == 0) {
+            rowp[HD] = m_run[qt];
+            rowp[HD + 1] = l_run[qt];
+        }
+    }
+    __syncthreads();
+    const size_t pbase = (((size_t)b * n_kv + g) * nsplit + split) * rpad;
+    for (int idx = tid; idx < QT * 16 * HD; idx += blockDim.x) {
+        const int rl = idx / HD, d = idx % HD;
+        const int r = qg * QT * 16 + rl;
+        float m = -INFINITY;
+        for (int w = 0; w < NW; ++w) m = fmaxf(m, lds[((size_t)w * QT * 16 + rl) * RS + HD]);
+        float L = 0.f, acc = 0.f;
+        if (m != -INFINITY) {
+            for (int w = 0; w < NW; ++w) {
+                const float* rowp = lds + ((size_t)w * QT * 16 + rl) * RS;
+                const float wgt = exp2f(rowp[HD] - m);          // exp2(-inf) = 0 for idle waves
+                L += wgt * rowp[HD + 1];
+                acc += wgt * rowp[d];
+            }
+        }
+        if (nsplit == 1) {
+            if (r < R) {
+                const int i = r / group, hq = r % group;
+                att[(((size_t)b * M + i) * n_q + g * group + hq) * HD + d] = (bf16_t)(acc / L);
+            }
+        } else if (r < rpad) {
+            part_o[(pbase + r) * HD + d] = acc;
+            if (d == 0) {
+                part_ml[(pbase + r) * 2] = m;
+                part_ml[(pbase + r) * 2 + 1] = L;
             }
         }
     }
@@ -250,16 +303,33 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(const float* __restrict_
 // host side
 // ------------------------------------------------------------------------------------------------
 struct AttnPlan {
-    int nsplit, steps_per_split, rpad, qt, qgroups;
+    int nsplit, steps_per_split, rpad, qt, qgroups, nw;
 };
 
-AttnPlan attn_plan(int batch, int m, int n_q, int n_kv, int max_len) {
+AttnPlan attn_plan(int batch, int m, int n_q, int n_kv, int hd, int max_len, bool mfma) {
     AttnPlan p;
     const int R = m * (n_q / n_kv);
     p.qt = R <= 16 ? 1 : (R <= 32 ? 2 : 4);
     p.qgroups = ceil_div(R, 16 * p.qt);
     p.rpad = p.qgroups * p.qt * 16;
     const int total_steps = ceil_div(max_len, 32);
+    if (mfma) {
+        const int per_wave = p.qt * 16 * (hd + 2) * 4;               // LDS bytes of one wave's state
+        p.nw = 65536 / per_wave;
+        if (p.nw > 8) p.nw = 8;
+        if (p.nw < 1) p.nw = 1;
+        // one workgroup per (head, query group) while its waves get at most ~6 steps each; beyond that
+        // split the sequence over workgroups (at most 64) and merge
+        int want = ceil_div(total_steps, p.nw * 6);
+        const int cap = 2048 / (batch * n_kv * p.qgroups) > 0 ? 2048 / (batch * n_kv * p.qgroups) : 1;
+        if (want > cap) want = cap;
+        if (want > 64) want = 64;
+        if (want < 1) want = 1;
+        p.steps_per_split = ceil_div(total_steps, want);
+        p.nsplit = ceil_div(total_steps, p.steps_per_split);
+        return p;
+    }
+    p.nw = 1;
     int want = 2048 / (batch * n_kv * p.qgroups);
     if (want < 1) want = 1;
     if (want > 64) want = 64;
@@ -282,19 +352,19 @@ int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, 
                      int force_simple, hipStream_t s) {
     if (n_q % n_kv != 0) HSD_FAIL(HSD_EINVAL, "attention: n_q=%d not a multiple of n_kv=%d", n_q, n_kv);
     if (hd % 32 != 0 || hd > 256) HSD_FAIL(HSD_EINVAL, "attention: head dim %d must be a multiple of 32, at most 256", hd);
-    AttnPlan p = attn_plan(batch, m, n_q, n_kv, max_len);
+    const bool mfma = dtype == HSD_BF16 && !force_simple && (hd == 64 || hd == 128);
+    AttnPlan p = attn_plan(batch, m, n_q, n_kv, hd, max_len, mfma);
     const int R = m * (n_q / n_kv);
     float* part_o = workspace;
     float* part_ml = workspace + (size_t)batch * n_kv * p.nsplit * p.rpad * hd;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)hd);
-    const bool mfma = dtype == HSD_BF16 && !force_simple && (hd == 64 || hd == 128);
     if (mfma) {
         dim3 grid(p.nsplit, n_kv, batch * p.qgroups);
 #define HSD_ATT(HD_, QT_)                                                                                              \
     if (hd == HD_ && p.qt == QT_)                                                                                      \
-        attn_mfma_kernel<HD_, QT_><<<grid, 64, 0, s>>>((const bf16_t*)q, (const bf16_t*)kv_layer, pages, max_pages,    \
-                                                       pos0_dev, pos0_all, m, n_q, n_kv, scale_log2,                   \
-                                                       p.steps_per_split, p.qgroups, part_o, part_ml, p.rpad);
+        attn_mfma_kernel<HD_, QT_><<<grid, p.nw * 64, (size_t)p.nw * QT_ * 16 * (HD_ + 2) * 4, s>>>(                    \
+            (const bf16_t*)q, (const bf16_t*)kv_layer, pages, max_pages, pos0_dev, pos0_all, m, n_q, n_kv, scale_log2, \
+            p.steps_per_split, p.qgroups, part_o, part_ml, p.rpad, (bf16_t*)att);
         HSD_ATT(64, 1) HSD_ATT(64, 2) HSD_ATT(64, 4) HSD_ATT(128, 1) HSD_ATT(128, 2) HSD_ATT(128, 4)
 #undef HSD_ATT
     } else {
@@ -309,6 +379,7 @@ int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, 
                                                           p.steps_per_split, part_o, part_ml, p.rpad);
     }
     HSD_LAUNCH_CHECK();
+    if (mfma && p.nsplit == 1) return HSD_OK;            // the kernel wrote the normalised output itself
     dim3 mg(R, n_kv, batch);
     if (dtype == HSD_BF16)
         attn_merge_kernel<bf16_t><<<mg, 64, 0, s>>>(part_o, part_ml, p.nsplit, p.rpad, m, n_q, n_kv, hd, (bf16_t*)att);

@@ -3,17 +3,6 @@
 // next to the weight and KV streams; they exist to keep every step of the pass on the device.
 #include "common.h"
 
-// x[m, :] = E[tok[m], :] as fp32 (the residual stream is fp32 for both storage types)
-template <typename T>
-__global__ void embed_kernel(const int32_t* __restrict__ tok, const T* __restrict__ E, float* __restrict__ x, int d,
-                             int vocab) {
-    int t = tok[blockIdx.x];
-    t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);          // ids are validated on the host; never read out of bounds
-    const T* src = E + (size_t)t * d;
-    float* dst = x + (size_t)blockIdx.x * d;
-    for (int i = threadIdx.x; i < d; i += blockDim.x) dst[i] = to_f32(src[i]);
-}
-
 __device__ __forceinline__ float block_sum_256(float v, float* sh) {
     v = wave_sum(v);
     if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
@@ -22,6 +11,32 @@ __device__ __forceinline__ float block_sum_256(float v, float* sh) {
     for (int w = 0; w < (int)(blockDim.x >> 6); ++w) s += sh[w];
     __syncthreads();
     return s;
+}
+
+// x[m, :] = E[tok[m], :] as fp32 (the residual stream is fp32 for both storage types).  With ss != null
+// also the row's sum of squares in the fixed-point form the normalising GEMMs read (times 2^24), and the
+// second accumulator cleared for the first producer of the pass.
+template <typename T>
+__global__ void embed_kernel(const int32_t* __restrict__ tok, const T* __restrict__ E, float* __restrict__ x, int d,
+                             int vocab, unsigned long long* __restrict__ ss, unsigned long long* __restrict__ ss_other) {
+    __shared__ float sh[16];
+    int t = tok[blockIdx.x];
+    t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);          // ids are validated on the host; never read out of bounds
+    const T* src = E + (size_t)t * d;
+    float* dst = x + (size_t)blockIdx.x * d;
+    float acc = 0.f;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) {
+        const float v = to_f32(src[i]);
+        dst[i] = v;
+        acc += v * v;
+    }
+    if (ss) {
+        acc = block_sum_256(acc, sh);
+        if (threadIdx.x == 0) {
+            ss[blockIdx.x] = (unsigned long long)((double)acc * 16777216.0 + 0.5);
+            ss_other[blockIdx.x] = 0ull;
+        }
+    }
 }
 
 // Row r (grid.x) of x: x += sum_s part[s][r] (fixed order; part may be null), then
@@ -141,11 +156,12 @@ __global__ void softmax_kernel(const float* __restrict__ z, float* __restrict__ 
 }
 
 // ---- launchers --------------------------------------------------------------------------------
-int launch_embed(const int32_t* tok, const void* E, float* x, int m, int d, int vocab, int dtype, hipStream_t s) {
+int launch_embed(const int32_t* tok, const void* E, float* x, int m, int d, int vocab, int dtype, unsigned long long* ss,
+                 unsigned long long* ss_other, hipStream_t s) {
     if (dtype == HSD_BF16)
-        embed_kernel<bf16_t><<<m, 256, 0, s>>>(tok, (const bf16_t*)E, x, d, vocab);
+        embed_kernel<bf16_t><<<m, 256, 0, s>>>(tok, (const bf16_t*)E, x, d, vocab, ss, ss_other);
     else
-        embed_kernel<float><<<m, 256, 0, s>>>(tok, (const float*)E, x, d, vocab);
+        embed_kernel<float><<<m, 256, 0, s>>>(tok, (const float*)E, x, d, vocab, ss, ss_other);
     HSD_LAUNCH_CHECK();
     return HSD_OK;
 }

@@ -27,7 +27,8 @@ struct hsd_model {
     // activation scratch
     float* x;         // residual stream [max_rows, d] fp32
     void* xn;         // normalised rows [max_rows, d]
-    float* part;      // GEMM partial sums
+    float* part;      // fp32 path: GEMM outputs waiting to be added to the residual stream
+    unsigned long long* ss[2];   // bf16 path: per-row sums of squares (fixed point) for the two norms of a layer
     void* q;          // [max_rows, n_q hd]
     void* att;        // [max_rows, n_q hd]
     void* h;          // [max_rows, ffn]
@@ -46,7 +47,8 @@ int model_pass(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows, int 
                float* logits_dev);
 
 // kernels_layer.hip
-int launch_embed(const int32_t* tok, const void* E, float* x, int m, int d, int vocab, int dtype, hipStream_t s);
+int launch_embed(const int32_t* tok, const void* E, float* x, int m, int d, int vocab, int dtype, unsigned long long* ss,
+                 unsigned long long* ss_other, hipStream_t s);
 int launch_resid_rmsnorm(float* x, const float* part, int ksplit, int part_rows, int part_row0, const float* w, void* xn,
                          int rows, int row0, int d, float eps, int dtype, hipStream_t s);
 int launch_rope_kv(const float* part, int ksplit, int m, void* q, void* kv_layer, const int32_t* pages, int pos0, int n_q,
@@ -57,8 +59,6 @@ size_t attn_workspace_bytes(int batch, int m, int n_q, int n_kv, int hd, int max
 int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, int max_pages, const int32_t* pos0_dev,
                      int pos0_all, int batch, int m, int max_len, int n_q, int n_kv, int hd, int dtype, void* att,
                      float* workspace, int force_simple, hipStream_t s);
-// kernels_gemm.hip
-int launch_reduce_partials(const float* part, float* y, int count, int ksplit, hipStream_t s);
 // kernels_sampler.hip
 int launch_accept_resample(const float* p, const float* q, int32_t* x, int t, int vocab, uint64_t seed, uint32_t level,
                            uint32_t call, int32_t* result, void* scratch, hipStream_t s);

@@ -55,24 +55,13 @@ WeightLayout weight_layout(const hsd_model_desc& d) {
 }
 
 size_t part_elems_needed(const hsd_model_desc& d) {
+    // fp32 path: the widest GEMM output that waits for its consumer (fused QKV or a residual update)
     const int nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
-    size_t need = 0;
-    const int ms[3] = {16, 32, 64};
-    for (int i = 0; i < 3; ++i) {
-        const int m = ms[i] < d.max_rows ? ms[i] : d.max_rows;
-        const int shapes[4][2] = {{nqkv, d.d}, {d.d, d.n_q * d.hd}, {d.d, d.ffn}, {d.vocab, d.d}};
-        for (int s = 0; s < 4; ++s) {
-            GemmPlan p = gemm_plan(m, shapes[s][0], shapes[s][1], d.dtype, false);
-            if (s == 3 && p.ksplit == 1) continue;       // logits go straight to the caller's buffer
-            size_t e = (size_t)p.ksplit * m * shapes[s][0];
-            if (e > need) need = e;
-        }
-    }
-    return need;
+    return (size_t)d.max_rows * (nqkv > d.d ? nqkv : d.d);
 }
 
 struct ScratchLayout {
-    size_t pages, x, xn, part, q, att, h, attn, total;
+    size_t pages, ss, x, xn, part, q, att, h, attn, total;
 };
 
 ScratchLayout scratch_layout(const hsd_model_desc& d) {
@@ -81,6 +70,7 @@ ScratchLayout scratch_layout(const hsd_model_desc& d) {
     const int R = d.max_rows;
     size_t o = 0;
     L.pages = o; o += align_up((size_t)(d.max_seq / HSD_KV_PAGE) * 4, 256);
+    L.ss = o;    o += align_up((size_t)2 * HSD_MAX_PASS_ROWS * 8, 256);
     L.x = o;     o += align_up((size_t)R * d.d * 4, 256);
     L.xn = o;    o += align_up((size_t)R * d.d * es, 256);
     L.part = o;  o += align_up(part_elems_needed(d) * 4, 256);
@@ -127,6 +117,8 @@ extern "C" int hsd_model_create(const hsd_model_desc* desc, void* weights_dev, v
     const ScratchLayout S = scratch_layout(*desc);
     char* sb = (char*)scratch_dev;
     m->pages_dev = (int32_t*)(sb + S.pages);
+    m->ss[0] = (unsigned long long*)(sb + S.ss);
+    m->ss[1] = m->ss[0] + HSD_MAX_PASS_ROWS;
     m->x = (float*)(sb + S.x);
     m->xn = sb + S.xn;
     m->part = (float*)(sb + S.part);
@@ -230,17 +222,18 @@ extern "C" int hsd_model_load_layer(hsd_model* m, int layer, const hsd_layer_wei
     const hsd_model_desc& d = m->desc;
     const LayerWeights& L = m->layers[layer];
     hipStream_t s = m->stream;
-    const int nq = d.n_q * d.hd, nkv = d.n_kv * d.hd, nqkv = nq + 2 * nkv;
+    const int nq = d.n_q * d.hd, nkv = d.n_kv * d.hd;
     HSD_HIP(hipMemcpyAsync(L.norm1, w->norm1_dev, (size_t)d.d * 4, hipMemcpyDeviceToDevice, s));
     HSD_HIP(hipMemcpyAsync(L.norm2, w->norm2_dev, (size_t)d.d * 4, hipMemcpyDeviceToDevice, s));
     int rc;
-    if ((rc = launch_pack(w->wq_dev, L.wqkv, nq, d.d, d.dtype, 0, nqkv, 0, s))) return rc;
-    if ((rc = launch_pack(w->wk_dev, L.wqkv, nkv, d.d, d.dtype, nq, nqkv, 0, s))) return rc;
-    if ((rc = launch_pack(w->wv_dev, L.wqkv, nkv, d.d, d.dtype, nq + nkv, nqkv, 0, s))) return rc;
-    if ((rc = launch_pack(w->wo_dev, L.wo, d.d, nq, d.dtype, 0, d.d, 0, s))) return rc;
-    if ((rc = launch_pack(w->wg_dev, L.wgu, d.ffn, d.d, d.dtype, 0, 2 * d.ffn, 1, s))) return rc;
-    if ((rc = launch_pack(w->wu_dev, L.wgu, d.ffn, d.d, d.dtype, 0, 2 * d.ffn, 2, s))) return rc;
-    if ((rc = launch_pack(w->wd_dev, L.wd, d.d, d.ffn, d.dtype, 0, d.d, 0, s))) return rc;
+    const int qkv_mode = d.dtype == HSD_BF16 ? 3 : 0;     // bf16: RoPE partners in adjacent tiles for the fused epilogue
+    if ((rc = launch_pack(w->wq_dev, L.wqkv, nq, d.d, d.dtype, 0, qkv_mode, d.hd, s))) return rc;
+    if ((rc = launch_pack(w->wk_dev, L.wqkv, nkv, d.d, d.dtype, nq, qkv_mode, d.hd, s))) return rc;
+    if ((rc = launch_pack(w->wv_dev, L.wqkv, nkv, d.d, d.dtype, nq + nkv, qkv_mode, d.hd, s))) return rc;
+    if ((rc = launch_pack(w->wo_dev, L.wo, d.d, nq, d.dtype, 0, 0, 0, s))) return rc;
+    if ((rc = launch_pack(w->wg_dev, L.wgu, d.ffn, d.d, d.dtype, 0, 1, 0, s))) return rc;
+    if ((rc = launch_pack(w->wu_dev, L.wgu, d.ffn, d.d, d.dtype, 0, 2, 0, s))) return rc;
+    if ((rc = launch_pack(w->wd_dev, L.wd, d.d, d.ffn, d.dtype, 0, 0, 0, s))) return rc;
     HSD_HIP(hipStreamSynchronize(s));
     m->layer_loaded[layer] = true;
     return HSD_OK;
@@ -252,10 +245,114 @@ extern "C" int hsd_model_load_head(hsd_model* m, const void* embed_dev, const vo
     hipStream_t s = m->stream;
     HSD_HIP(hipMemcpyAsync(m->embed, embed_dev, (size_t)d.vocab * d.d * dtype_size(d.dtype), hipMemcpyDeviceToDevice, s));
     HSD_HIP(hipMemcpyAsync(m->norm_f, norm_f_dev, (size_t)d.d * 4, hipMemcpyDeviceToDevice, s));
-    if (int rc = launch_pack(head_dev, m->head, d.vocab, d.d, d.dtype, 0, d.vocab, 0, s)) return rc;
+    if (int rc = launch_pack(head_dev, m->head, d.vocab, d.d, d.dtype, 0, 0, 0, s)) return rc;
     HSD_HIP(hipStreamSynchronize(s));
     m->head_loaded = true;
     return HSD_OK;
+}
+
+// fp32 storage: plain kernels, one per step (the small correctness configuration).
+static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, int exit_layer, int n_logit_rows, float* logits) {
+    const hsd_model_desc& d = m->desc;
+    hipStream_t s = m->stream;
+    const int nq = d.n_q * d.hd, nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
+    int rc;
+    if ((rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, nullptr, nullptr, s))) return rc;
+    const float* pending = nullptr;     // output of the previous down projection, not yet added to x
+    for (int l = 0; l < exit_layer; ++l) {
+        const LayerWeights& L = m->layers[l];
+        void* kv_layer = m->kv + m->kv_layer_bytes * l;
+        if ((rc = launch_resid_rmsnorm(m->x, pending, 1, rows, 0, L.norm1, m->xn, rows, 0, d.d, d.eps, d.dtype, s))) return rc;
+        {
+            SiteTimer t(m, HSD_SITE_QKV);
+            if ((rc = launch_gemm_f32((const float*)m->xn, (const float*)L.wqkv, m->part, rows, nqkv, d.d, false, s))) return rc;
+        }
+        if ((rc = launch_rope_kv(m->part, 1, rows, m->q, kv_layer, m->pages_dev, pos0, d.n_q, d.n_kv, d.hd, d.rope_base, d.dtype, s))) return rc;
+        {
+            SiteTimer t(m, HSD_SITE_ATTN);
+            if ((rc = launch_attention(m->q, kv_layer, m->pages_dev, m->max_pages, nullptr, pos0, 1, rows, pos0 + rows, d.n_q, d.n_kv,
+                                       d.hd, d.dtype, m->att, m->attn_ws, 0, s))) return rc;
+        }
+        {
+            SiteTimer t(m, HSD_SITE_O);
+            if ((rc = launch_gemm_f32((const float*)m->att, (const float*)L.wo, m->part, rows, d.d, nq, false, s))) return rc;
+        }
+        if ((rc = launch_resid_rmsnorm(m->x, m->part, 1, rows, 0, L.norm2, m->xn, rows, 0, d.d, d.eps, d.dtype, s))) return rc;
+        {
+            SiteTimer t(m, HSD_SITE_GATEUP);
+            if ((rc = launch_gemm_f32((const float*)m->xn, (const float*)L.wgu, (float*)m->h, rows, 2 * d.ffn, d.d, true, s))) return rc;
+        }
+        {
+            SiteTimer t(m, HSD_SITE_DOWN);
+            if ((rc = launch_gemm_f32((const float*)m->h, (const float*)L.wd, m->part, rows, d.d, d.ffn, false, s))) return rc;
+        }
+        pending = m->part;
+    }
+    if (n_logit_rows == 0) return HSD_OK;
+    const int row0 = rows - n_logit_rows;
+    if ((rc = launch_resid_rmsnorm(m->x, pending, 1, rows, row0, m->norm_f, m->xn, n_logit_rows, row0, d.d, d.eps, d.dtype, s))) return rc;
+    SiteTimer t(m, HSD_SITE_HEAD);
+    return launch_gemm_f32((const float*)m->xn, (const float*)m->head, logits, n_logit_rows, d.vocab, d.d, false, s);
+}
+
+// bf16 storage: five launches per layer.  Both RMSNorms are folded into the A-operand load of the GEMM
+// that follows them (the row sums of squares travel in m->ss[0] for the layer's first norm and the
+// final norm, m->ss[1] for the second), RoPE and the KV append into the QKV epilogue, the residual adds
+// into the O and down projections, SwiGLU into the gate/up projection.
+static int pass_bf16(hsd_model* m, const int32_t* tok, int pos0, int rows, int exit_layer, int n_logit_rows, float* logits) {
+    const hsd_model_desc& d = m->desc;
+    hipStream_t s = m->stream;
+    const int nq = d.n_q * d.hd, nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
+    int rc;
+    if ((rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, m->ss[0], m->ss[1], s))) return rc;
+    for (int l = 0; l < exit_layer; ++l) {
+        const LayerWeights& L = m->layers[l];
+        bf16_t* kv_layer = (bf16_t*)(m->kv + m->kv_layer_bytes * l);
+        {
+            GemmArgs g = {};
+            g.a = m->x; g.norm_w = L.norm1; g.ss_in = m->ss[0]; g.ss_zero = m->ss[1]; g.eps = d.eps;
+            g.wp = (const bf16x8*)L.wqkv; g.M = rows; g.N = nqkv; g.K = d.d;
+            g.out_bf16 = (bf16_t*)m->q; g.kv_layer = kv_layer; g.pages = m->pages_dev;
+            g.pos0 = pos0; g.n_q = d.n_q; g.n_kv = d.n_kv; g.hd = d.hd; g.rope_base = d.rope_base;
+            SiteTimer t(m, HSD_SITE_QKV);
+            if ((rc = launch_gemm_bf16(g, A_NORM, EPI_ROPE, gemm_plan(rows, nqkv, d.d, EPI_ROPE), s))) return rc;
+        }
+        {
+            SiteTimer t(m, HSD_SITE_ATTN);
+            if ((rc = launch_attention(m->q, kv_layer, m->pages_dev, m->max_pages, nullptr, pos0, 1, rows, pos0 + rows, d.n_q, d.n_kv,
+                                       d.hd, d.dtype, m->att, m->attn_ws, 0, s))) return rc;
+        }
+        {
+            GemmArgs g = {};
+            g.a = m->att; g.wp = (const bf16x8*)L.wo; g.M = rows; g.N = d.d; g.K = nq;
+            g.out_f32 = m->x; g.ss_out = m->ss[1];
+            SiteTimer t(m, HSD_SITE_O);
+            if ((rc = launch_gemm_bf16(g, A_BF16, EPI_RESID, gemm_plan(rows, d.d, nq, EPI_RESID), s))) return rc;
+        }
+        {
+            GemmArgs g = {};
+            g.a = m->x; g.norm_w = L.norm2; g.ss_in = m->ss[1]; g.ss_zero = m->ss[0]; g.eps = d.eps;
+            g.wp = (const bf16x8*)L.wgu; g.M = rows; g.N = 2 * d.ffn; g.K = d.d;
+            g.out_bf16 = (bf16_t*)m->h;
+            SiteTimer t(m, HSD_SITE_GATEUP);
+            if ((rc = launch_gemm_bf16(g, A_NORM, EPI_SWIGLU, gemm_plan(rows, 2 * d.ffn, d.d, EPI_SWIGLU), s))) return rc;
+        }
+        {
+            GemmArgs g = {};
+            g.a = m->h; g.wp = (const bf16x8*)L.wd; g.M = rows; g.N = d.d; g.K = d.ffn;
+            g.out_f32 = m->x; g.ss_out = m->ss[0];
+            SiteTimer t(m, HSD_SITE_DOWN);
+            if ((rc = launch_gemm_bf16(g, A_BF16, EPI_RESID, gemm_plan(rows, d.d, d.ffn, EPI_RESID), s))) return rc;
+        }
+    }
+    if (n_logit_rows == 0) return HSD_OK;
+    const int row0 = rows - n_logit_rows;
+    GemmArgs g = {};
+    g.a = m->x + (size_t)row0 * d.d; g.norm_w = m->norm_f; g.ss_in = m->ss[0] + row0; g.ss_zero = nullptr; g.eps = d.eps;
+    g.wp = (const bf16x8*)m->head; g.M = n_logit_rows; g.N = d.vocab; g.K = d.d;
+    g.out_f32 = logits;
+    SiteTimer t(m, HSD_SITE_HEAD);
+    return launch_gemm_bf16(g, A_NORM, EPI_STORE, gemm_plan(n_logit_rows, d.vocab, d.d, EPI_STORE), s);
 }
 
 // One pass: rows tokens at positions pos0.., layers [0, exit_layer), logits of the last n_logit_rows rows.
@@ -269,56 +366,8 @@ int model_pass(hsd_model* m, const int32_t* tok, int pos0, int rows, int exit_la
     if (!m->head_loaded) HSD_FAIL(HSD_ESTATE, "pass: embedding / head not loaded");
     for (int l = 0; l < exit_layer; ++l)
         if (!m->layer_loaded[l]) HSD_FAIL(HSD_ESTATE, "pass: layer %d not loaded", l);
-    hipStream_t s = m->stream;
-    const int nq = d.n_q * d.hd, nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
-    int rc;
-    if ((rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, s))) return rc;
-    const float* pending = nullptr;     // split-K partials of the previous down projection, not yet added to x
-    int pending_split = 0;
-    for (int l = 0; l < exit_layer; ++l) {
-        const LayerWeights& L = m->layers[l];
-        void* kv_layer = m->kv + m->kv_layer_bytes * l;
-        if ((rc = launch_resid_rmsnorm(m->x, pending, pending_split, rows, 0, L.norm1, m->xn, rows, 0, d.d, d.eps, d.dtype, s))) return rc;
-        GemmPlan pq = gemm_plan(rows, nqkv, d.d, d.dtype, false);
-        {
-            SiteTimer t(m, HSD_SITE_QKV);
-            if ((rc = launch_gemm(m->xn, L.wqkv, m->part, rows, nqkv, d.d, d.dtype, pq, s))) return rc;
-        }
-        if ((rc = launch_rope_kv(m->part, pq.ksplit, rows, m->q, kv_layer, m->pages_dev, pos0, d.n_q, d.n_kv, d.hd, d.rope_base, d.dtype, s))) return rc;
-        {
-            SiteTimer t(m, HSD_SITE_ATTN);
-            if ((rc = launch_attention(m->q, kv_layer, m->pages_dev, m->max_pages, nullptr, pos0, 1, rows, pos0 + rows, d.n_q, d.n_kv,
-                                       d.hd, d.dtype, m->att, m->attn_ws, 0, s))) return rc;
-        }
-        GemmPlan po = gemm_plan(rows, d.d, nq, d.dtype, false);
-        {
-            SiteTimer t(m, HSD_SITE_O);
-            if ((rc = launch_gemm(m->att, L.wo, m->part, rows, d.d, nq, d.dtype, po, s))) return rc;
-        }
-        if ((rc = launch_resid_rmsnorm(m->x, m->part, po.ksplit, rows, 0, L.norm2, m->xn, rows, 0, d.d, d.eps, d.dtype, s))) return rc;
-        GemmPlan pg = gemm_plan(rows, 2 * d.ffn, d.d, d.dtype, true);
-        {
-            SiteTimer t(m, HSD_SITE_GATEUP);
-            if ((rc = launch_gemm_swiglu(m->xn, L.wgu, m->h, rows, d.ffn, d.d, d.dtype, pg, s))) return rc;
-        }
-        GemmPlan pd = gemm_plan(rows, d.d, d.ffn, d.dtype, false);
-        {
-            SiteTimer t(m, HSD_SITE_DOWN);
-            if ((rc = launch_gemm(m->h, L.wd, m->part, rows, d.d, d.ffn, d.dtype, pd, s))) return rc;
-        }
-        pending = m->part;
-        pending_split = pd.ksplit;
-    }
-    if (n_logit_rows == 0) return HSD_OK;
-    const int row0 = rows - n_logit_rows;
-    if ((rc = launch_resid_rmsnorm(m->x, pending, pending_split, rows, row0, m->norm_f, m->xn, n_logit_rows, row0, d.d, d.eps, d.dtype, s))) return rc;
-    GemmPlan ph = gemm_plan(n_logit_rows, d.vocab, d.d, d.dtype, false);
-    {
-        SiteTimer t(m, HSD_SITE_HEAD);
-        if (ph.ksplit == 1) return launch_gemm(m->xn, m->head, logits, n_logit_rows, d.vocab, d.d, d.dtype, ph, s);
-        if ((rc = launch_gemm(m->xn, m->head, m->part, n_logit_rows, d.vocab, d.d, d.dtype, ph, s))) return rc;
-    }
-    return launch_reduce_partials(m->part, logits, n_logit_rows * d.vocab, ph.ksplit, s);
+    return d.dtype == HSD_BF16 ? pass_bf16(m, tok, pos0, rows, exit_layer, n_logit_rows, logits)
+                               : pass_f32(m, tok, pos0, rows, exit_layer, n_logit_rows, logits);
 }
 
 extern "C" int hsd_model_pass(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows, int exit_layer, int n_logit_rows,

@@ -67,9 +67,8 @@ _SIGS = {
     "hsd_sampler_scratch_bytes": (_sz, [_i]),
     "hsd_accept_resample": (_i, [_vp, _vp, _vp, _i, _i, C.c_uint64, C.c_uint32, C.c_uint32, _vp, _vp, _vp]),
     "hsd_packed_bytes": (_sz, [_i, _i, _i]),
-    "hsd_gemm_workspace_bytes": (_sz, [_i, _i, _i]),
     "hsd_pack_weight": (_i, [_vp, _vp, _i, _i, _i, _vp]),
-    "hsd_gemm": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _vp]),
+    "hsd_gemm": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "hsd_hier_workspace_bytes": (_sz, [_i, C.POINTER(Level), _ip]),
     "hsd_hier_create": (_i, [_i, C.POINTER(Level), _ip, _f, C.c_uint64, _vp, _sz, _vp, C.POINTER(_vp)]),
     "hsd_hier_destroy": (None, [_vp]),
@@ -232,8 +231,7 @@ def pack_weight(w, dtype):
 def gemm(x, packed, n, dtype):
     m, k = x.shape
     y = torch.empty((m, n), dtype=torch.float32, device="cuda")
-    ws = _buf(lib.hsd_gemm_workspace_bytes(m, n, k))
-    _check(lib.hsd_gemm(x.contiguous().data_ptr(), packed.data_ptr(), y.data_ptr(), m, n, k, dtype, ws.data_ptr(), _stream()))
+    _check(lib.hsd_gemm(x.contiguous().data_ptr(), packed.data_ptr(), y.data_ptr(), m, n, k, dtype, _stream()))
     return y
 
 
