@@ -87,7 +87,7 @@ def main():
     weights = inputs.make_weights(shape, seed=SEED, bf16=True)
     prompt = inputs.make_prompt(shape["vocab"], PROMPT, seed=SEED + 1)
     log("weights generated in %.1f s" % (time.time() - t0))
-    model = hsd.Model(shape, hsd.BF16, 1024, 64, inputs.ROPE_BASE, inputs.EPS)
+    model = hsd.Model(shape, hsd.BF16, 1024, 64, inputs.ROPE_BASE, inputs.EPS, rows_copy_layers=EXITS[0])
     model.load(weights)
     log("model loaded (%.2f GB packed)" % (model.weights.numel() / 1e9))
 

@@ -28,6 +28,7 @@ extern "C" {
 
 enum { HSD_OK = 0, HSD_EINVAL = -1, HSD_ECAPACITY = -2, HSD_ESTATE = -3, HSD_EHIP = -4 };
 enum { HSD_F32 = 0, HSD_BF16 = 1 };
+enum { HSD_LAYOUT_TILES = 0, HSD_LAYOUT_ROWS = 1 };
 enum { HSD_MAX_LEVELS = 8, HSD_MAX_PASS_ROWS = 64, HSD_KV_PAGE = 64 };
 
 typedef struct hsd_model hsd_model;
@@ -47,6 +48,10 @@ typedef struct {
     float eps;       /* RMSNorm epsilon, inside the square root */
     int max_seq;     /* KV capacity in tokens, multiple of HSD_KV_PAGE */
     int max_rows;    /* most tokens one pass may process, 1..HSD_MAX_PASS_ROWS */
+    int rows_copy_layers; /* bf16: the first rows_copy_layers layers (0..n_layers) keep a second, row-major copy of
+                        their narrow projections (q/k/v, o, down), which passes of one or two tokens stream with
+                        the row kernel.  Meant for the layers the base drafter M_0 runs autoregressively (Alg. 1);
+                        costs 45% more weight memory for those layers. */
 } hsd_model_desc;
 
 /* Device bytes of the packed weights / the paged KV cache / per-model activation scratch. */
@@ -122,15 +127,25 @@ int hsd_accept_resample(const float* p_dev, const float* q_dev, int32_t* x_dev, 
                         uint64_t seed, uint32_t level, uint32_t call, int32_t* result_dev,
                         void* scratch_dev, void* stream);
 
-/* Small-M weight-streaming GEMM y = x W^T.  hsd_pack_weight lays W [n, k] (row-major, dtype) out in
- * the streaming format (packed_dev: hsd_packed_bytes(n, k, dtype)); hsd_gemm computes
- * y_dev [m, n] fp32 = x_dev [m, k] (dtype) times the packed matrix.  k must be a multiple of 32,
- * 1 <= m <= HSD_MAX_PASS_ROWS.  This is the kernel the pass uses for every projection (there with the
- * neighbouring element-wise steps fused into its operand load and epilogue). */
+/* Small-M weight-streaming GEMM y = x W^T, y_dev [m, n] fp32 = x_dev [m, k] (dtype) times W [n, k].
+ * hsd_pack_weight copies W (row-major, dtype) into the streaming format (packed_dev:
+ * hsd_packed_bytes(n, k, dtype)).  bf16 has two formats, each with its kernel, both used by the pass:
+ *   HSD_LAYOUT_TILES - MFMA operand tiles; workgroups own 16-column tiles (wide matrices: gate/up, head);
+ *   HSD_LAYOUT_ROWS  - row-major; workgroups own 2-4 output features and use packed bf16 dot products
+ *                      (narrow matrices: q/k/v, attention output, FFN down), m above 16 in several launches.
+ * fp32 ignores the layout.  k must be a multiple of 32, 1 <= m <= HSD_MAX_PASS_ROWS.
+ * workspace_dev: hsd_gemm_workspace_bytes(m, n, k). */
 size_t hsd_packed_bytes(int n, int k, int dtype);
-int hsd_pack_weight(const void* w_dev, void* packed_dev, int n, int k, int dtype, void* stream);
-int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int n, int k, int dtype,
-             void* stream);
+size_t hsd_gemm_workspace_bytes(int m, int n, int k);
+int hsd_pack_weight(const void* w_dev, void* packed_dev, int n, int k, int dtype, int layout, void* stream);
+int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int n, int k, int dtype, int layout,
+             void* workspace_dev, void* stream);
+
+/* Overrides of the GEMM launch heuristics, for tuning sweeps (process-wide; 0 restores the heuristic).
+ * key 0..3 = epilogue kind (store, residual, SwiGLU, RoPE) of the tiled kernel: nt column tiles per
+ * workgroup, ksplit workgroups along K, waves per workgroup.  key 100: nt = most tokens the row kernel
+ * serves before the MFMA kernel takes over on row-major weights. */
+int hsd_tune(int key, int nt, int ksplit, int waves);
 
 /* ---------------------------------------------------------------------------------------------
  * Hierarchy M_0..M_K with parameters T_0..T_{K-1} (Alg. 1).  Level 0 drafts autoregressively,

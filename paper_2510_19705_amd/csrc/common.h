@@ -9,6 +9,7 @@
 
 typedef __bf16 bf16_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 void hsd_set_error(const char* fmt, ...);
@@ -86,20 +87,26 @@ __host__ __device__ __forceinline__ size_t packed_index(int n, int k, int K) {
 }
 
 // ---- GEMM launch interface (kernels_gemm.hip) ---------------------------------------------------
-enum { A_BF16 = 0, A_NORM = 1 };                                       // A operand source
 enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_ROPE = 3 };   // epilogue
+enum { SS_SLOTS = 16 };   // accumulators per row for the sums of squares (spreads the atomics)
 
 struct GemmArgs {
-    const void* a;                      // A_BF16: bf16 [M, K]; A_NORM: fp32 residual rows [M, K]
-    const float* norm_w;                // A_NORM: RMSNorm weight [K]
-    const unsigned long long* ss_in;    // A_NORM: per row, sum of squares * 2^24
-    unsigned long long* ss_zero;        // A_NORM: buffer the next producer will add into (cleared here), or null
-    float eps;
-    const bf16x8* wp;                   // packed W [N, K]
+    const bf16_t* a;                    // activations [M, K]
+    const bf16x8* wp;                   // W [N, K]: MFMA tiles (launch_gemm_bf16) or row-major (launch_gemv_bf16)
     int M, N, K;
+    float* part;                        // split-K partial tiles (ksplit > 1)
+    int* tickets;                       // one arrival counter per column group, zero between launches
+    // consumers of a normalised input: rows of `a` are x * w_norm, the 1/rms factor is applied in the epilogue
+    const unsigned long long* ss_in;    // [SS_SLOTS][HSD_MAX_PASS_ROWS]: per row, sum of squares of x times 2^24, spread over the
+                                        // slots; null: no scaling (EPI_STORE only)
+    unsigned long long* ss_zero;        // accumulator the next producer will add into (cleared here), or null
+    float eps;
+    // outputs
     float* out_f32;                     // EPI_STORE: y [M, N]; EPI_RESID: residual rows [M, N], updated in place
-    unsigned long long* ss_out;         // EPI_RESID: per row, += sum of squares of the new residual * 2^24
-    bf16_t* out_bf16;                   // EPI_SWIGLU: h [M, N/2]; EPI_ROPE: q [M, n_q, hd]
+    unsigned long long* ss_out;         // EPI_RESID: per row, += sum of squares of the new residual times 2^24
+    const float* norm_w;                // EPI_RESID: weight of the norm that reads the new residual
+    bf16_t* out_bf16;                   // EPI_RESID: bf16(new residual * norm_w) [M, N] (or null); EPI_SWIGLU: h [M, N/2];
+                                        // EPI_ROPE: q [M, n_q, hd]
     bf16_t* kv_layer;                   // EPI_ROPE: this layer's KV pages
     const int32_t* pages;
     int pos0, n_q, n_kv, hd;
@@ -108,12 +115,18 @@ struct GemmArgs {
 
 struct GemmPlan {
     int nt;       // 16-column tiles per workgroup
-    int waves;    // waves per workgroup; they split K
+    int ksplit;   // workgroups along K per column group
+    int waves;    // waves per workgroup; they split the workgroup's K slice
 };
 GemmPlan gemm_plan(int m, int n, int k, int epi);
-void gemm_tune(int epilogue, int nt, int waves);
-int launch_gemm_bf16(const GemmArgs& g, int asrc, int epi, const GemmPlan& p, hipStream_t s);
+size_t gemm_part_bytes(int m, int n, int k, int epi);
+void gemm_tune(int epilogue, int nt, int ksplit, int waves);
+int launch_gemm_bf16(const GemmArgs& g, int epi, const GemmPlan& p, hipStream_t s);   // W in MFMA tiles
+extern int g_gemv_max_m;
+int launch_gemv_bf16(const GemmArgs& g, int epi, hipStream_t s);   // row-major W: EPI_STORE, EPI_RESID, EPI_ROPE
 int launch_gemm_f32(const float* x, const float* w, float* out, int m, int n, int k, bool swiglu, hipStream_t s);
 // interleave: 0 plain rows at row_offset, 1 / 2 gate / up of a fused SwiGLU matrix, 3 attention heads of hd rows
-// with each 16-dim block followed by the block of its RoPE partners
-int launch_pack(const void* w, void* packed, int n, int k, int dtype, int row_offset, int interleave, int hd, hipStream_t s);
+// with each 16-dim block followed by the block of its RoPE partners, 4 heads with each dim followed by its partner.
+// rows_layout: bf16 destination row-major instead of MFMA tiles.
+int launch_pack(const void* w, void* packed, int n, int k, int dtype, int row_offset, int interleave, int hd, int rows_layout,
+                hipStream_t s);

@@ -5,14 +5,18 @@
 // load), so these kernels are bound by the HBM stream of W.
 //
 // bf16: W is pre-laid in 1 KiB tiles in the lane order of the 16x16x32 MFMA B operand (one wave-wide
-// 16-byte load per MFMA, each wave walking a contiguous run of tiles).  A workgroup owns NT column
-// tiles over the whole K range, its waves split K and reduce through LDS, so every output element is
-// final inside one workgroup and the neighbouring element-wise steps are fused in:
-//   A operand  - bf16 activations, or the fp32 residual stream normalised on the fly (RMSNorm: the
-//                row sums of squares come from the producing kernel as fixed-point integers added
-//                with atomics, so their value does not depend on the order of arrival);
-//   epilogue   - plain store (LM head), residual add + sums of squares for the next norm,
-//                SwiGLU on interleaved gate/up tiles, or RoPE + KV-cache append + q store.
+// 16-byte load per MFMA, each wave walking a contiguous run of tiles).  HBM peak needs every CU
+// pulling, so the grid is (column groups of NT tiles) x (ksplit slices of K), about a thousand
+// workgroups whatever the matrix shape.  Inside a workgroup the waves split the slice and reduce
+// through LDS; across the ksplit workgroups of a column group the partial tiles go through memory and
+// the LAST one to arrive (a ticket counter) adds them in slice order, so the result does not depend
+// on arrival order, and runs the epilogue.  The element-wise neighbours of each projection are fused:
+//   RMSNorm   - the producer of the residual stream also stores bf16(x * w_norm) and adds each row's
+//               sum of squares, as a fixed-point integer, into an accumulator with atomics (integer
+//               addition: order-free); since a GEMM is linear in a per-row scale, the consumer feeds
+//               the un-normalised rows to the MFMAs and multiplies by 1/rms in its epilogue;
+//   epilogue  - plain store (LM head), residual add (+ the two products above), SwiGLU on interleaved
+//               gate/up tiles, or RoPE + KV-cache append + q store.
 // fp32 (small correctness configuration): one wave per output column with plain FMAs, unfused.
 #include "common.h"
 
@@ -26,6 +30,11 @@ __device__ __forceinline__ int dest_row(int r, int row_offset, int interleave, i
     //    by the block of its rotation partners [hd/2 + 16 jb, ...), so that one pair of tiles holds
     //    both halves of 16 RoPE pairs.
     if (interleave == 0) return row_offset + r;
+    if (interleave == 4) {      // heads of hd rows, each dim directly followed by its RoPE partner: 2 j, 2 j + 1
+        const int head = r / hd, j = r % hd, half = hd >> 1;
+        const int hi = j >= half, jj = j - hi * half;
+        return row_offset + head * hd + 2 * jj + hi;
+    }
     if (interleave == 3) {
         const int head = r / hd, j = r % hd, half = hd >> 1;
         const int hi = j >= half, jj = j - hi * half;
@@ -35,13 +44,15 @@ __device__ __forceinline__ int dest_row(int r, int row_offset, int interleave, i
 }
 
 __global__ void pack_bf16_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ packed, int n, int k,
-                                 int row_offset, int interleave, int hd) {
+                                 int row_offset, int interleave, int hd, int rows_layout) {
     const int k8 = k >> 3;
     size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)n * k8) return;
     int r = (int)(idx / k8), c = (int)(idx % k8) * 8;
     bf16x8 v = *reinterpret_cast<const bf16x8*>(w + (size_t)r * k + c);
-    *reinterpret_cast<bf16x8*>(packed + packed_index(dest_row(r, row_offset, interleave, hd), c, k)) = v;
+    const int dr = dest_row(r, row_offset, interleave, hd);
+    bf16_t* dst = rows_layout ? packed + (size_t)dr * k + c : packed + packed_index(dr, c, k);
+    *reinterpret_cast<bf16x8*>(dst) = v;
 }
 
 __global__ void pack_f32_kernel(const float* __restrict__ w, float* __restrict__ packed, int n, int k,
@@ -55,15 +66,15 @@ __global__ void pack_f32_kernel(const float* __restrict__ w, float* __restrict__
 }
 
 int launch_pack(const void* w, void* packed, int n, int k, int dtype, int row_offset, int interleave, int hd,
-                hipStream_t s) {
+                int rows_layout, hipStream_t s) {
     if (k % 32 != 0) HSD_FAIL(HSD_EINVAL, "pack: k=%d is not a multiple of 32", k);
     if (row_offset % 16 != 0) HSD_FAIL(HSD_EINVAL, "pack: row offset %d is not a multiple of 16", row_offset);
     if (interleave != 0 && n % 16 != 0) HSD_FAIL(HSD_EINVAL, "pack: interleaved matrices need n %% 16 == 0 (n=%d)", n);
-    if (interleave == 3 && (hd % 32 != 0 || n % hd != 0)) HSD_FAIL(HSD_EINVAL, "pack: head layout needs hd %% 32 == 0 and whole heads");
+    if ((interleave == 3 || interleave == 4) && (hd % 32 != 0 || n % hd != 0)) HSD_FAIL(HSD_EINVAL, "pack: head layout needs hd %% 32 == 0 and whole heads");
     if (dtype == HSD_BF16) {
         size_t total = (size_t)n * (k / 8);
         pack_bf16_kernel<<<dim3((unsigned)((total + 255) / 256)), 256, 0, s>>>((const bf16_t*)w, (bf16_t*)packed, n, k,
-                                                                              row_offset, interleave, hd);
+                                                                              row_offset, interleave, hd, rows_layout);
     } else {
         size_t total = (size_t)n * (k / 4);
         pack_f32_kernel<<<dim3((unsigned)((total + 255) / 256)), 256, 0, s>>>((const float*)w, (float*)packed, n, k,
@@ -76,28 +87,61 @@ int launch_pack(const void* w, void* packed, int n, int k, int dtype, int row_of
 // ------------------------------------------------------------------------------------------------
 // bf16 MFMA kernel
 // ------------------------------------------------------------------------------------------------
-template <int ASRC>
-__device__ __forceinline__ bf16x8 load_a(const void* rowp, const float* nw, int kt, float inv, bool valid) {
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (!valid) return zero;
-    if constexpr (ASRC == A_BF16) {
-        return *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16_t*>(rowp) + (size_t)kt * 32);
+// 1 / sqrt(mean(x^2) + eps) of row m from its fixed-point sum of squares (times 2^24), which the
+// producers spread over SS_SLOTS accumulators to keep the atomics from queueing on one address
+__device__ __forceinline__ float row_inv_rms(const unsigned long long* ss, int m, int d, float eps) {
+    unsigned long long t = 0;
+#pragma unroll
+    for (int sl = 0; sl < SS_SLOTS; ++sl) t += ss[sl * HSD_MAX_PASS_ROWS + m];
+    const float v = (float)((double)t * (1.0 / 16777216.0));
+    return 1.0f / sqrtf(v / (float)d + eps);
+}
+
+__device__ __forceinline__ void ss_clear(unsigned long long* ss, int tid, int nthreads) {
+    for (int i = tid; i < SS_SLOTS * HSD_MAX_PASS_ROWS; i += nthreads) ss[i] = 0ull;
+}
+
+__device__ __forceinline__ void ss_add(unsigned long long* ss, int m, float sum_sq) {
+    atomicAdd(ss + (blockIdx.x % SS_SLOTS) * HSD_MAX_PASS_ROWS + m, (unsigned long long)((double)sum_sq * 16777216.0 + 0.5));
+}
+
+// RoPE on one (dim j, dim j + hd/2) pair of token row ml of `head` (q heads, then k heads, then v heads, which are
+// not rotated), then the q store or the KV-cache append through the page table.  Angle in fp64.
+__device__ __forceinline__ void rope_store(const GemmArgs& g, int head, int j, int ml, float a, float b) {
+    const int hd = g.hd, half = hd >> 1;
+    const int pos = g.pos0 + ml;
+    const bool is_q = head < g.n_q, is_v = head >= g.n_q + g.n_kv;
+    float ra = a, rb = b;
+    if (!is_v) {
+        const double ang = (double)pos * exp2(-2.0 * (double)j / (double)hd * log2((double)g.rope_base));
+        double sn, cs;
+        sincos(ang, &sn, &cs);
+        ra = (float)((double)a * cs - (double)b * sn);
+        rb = (float)((double)b * cs + (double)a * sn);
+    }
+    if (is_q) {
+        bf16_t* dst = g.out_bf16 + ((size_t)ml * g.n_q + head) * hd;
+        dst[j] = (bf16_t)ra;
+        dst[j + half] = (bf16_t)rb;
+        return;
+    }
+    const int kvh = is_v ? head - g.n_q - g.n_kv : head - g.n_q;
+    const int page = g.pages[pos / HSD_KV_PAGE], ip = pos % HSD_KV_PAGE;
+    bf16_t* blk = g.kv_layer + (size_t)page * kv_page_elems(g.n_kv, hd) + (size_t)kvh * 2 * kv_block_elems(hd) +
+                  (is_v ? kv_block_elems(hd) : 0);
+    if (is_v) {
+        blk[kv_v_index(ip, j, hd)] = (bf16_t)ra;
+        blk[kv_v_index(ip, j + half, hd)] = (bf16_t)rb;
     } else {
-        const float* xp = reinterpret_cast<const float*>(rowp) + (size_t)kt * 32;
-        const float4 v0 = *reinterpret_cast<const float4*>(xp), v1 = *reinterpret_cast<const float4*>(xp + 4);
-        const float4 w0 = *reinterpret_cast<const float4*>(nw + (size_t)kt * 32), w1 = *reinterpret_cast<const float4*>(nw + (size_t)kt * 32 + 4);
-        bf16x8 a;
-        a[0] = (bf16_t)(v0.x * inv * w0.x); a[1] = (bf16_t)(v0.y * inv * w0.y);
-        a[2] = (bf16_t)(v0.z * inv * w0.z); a[3] = (bf16_t)(v0.w * inv * w0.w);
-        a[4] = (bf16_t)(v1.x * inv * w1.x); a[5] = (bf16_t)(v1.y * inv * w1.y);
-        a[6] = (bf16_t)(v1.z * inv * w1.z); a[7] = (bf16_t)(v1.w * inv * w1.w);
-        return a;
+        blk[kv_k_index(ip, j, hd)] = (bf16_t)ra;
+        blk[kv_k_index(ip, j + half, hd)] = (bf16_t)rb;
     }
 }
 
-template <int NT, int MT, int ASRC, int EPI>
+template <int NT, int MT, int EPI>
 __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
     extern __shared__ float red[];
+    __shared__ bool sh_last;
     constexpr int U = (8 / (NT * MT)) > 0 ? (8 / (NT * MT)) : 1;     // k-steps whose loads are issued together
     constexpr int TOTAL = MT * NT * 256;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
@@ -105,9 +149,12 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
     const int KT = K >> 5;
     const int ntiles = (N + 15) >> 4;
     const int ntile0 = blockIdx.x * NT;
-    const int per = (KT + nwaves - 1) / nwaves;
-    const int kb = wave * per;
-    const int ke = min(KT, kb + per);
+    const int ksplit = gridDim.y;
+    const int per_wg = (KT + ksplit - 1) / ksplit;
+    const int kt0 = blockIdx.y * per_wg, kt1 = min(KT, kt0 + per_wg);
+    const int per = (kt1 - kt0 + nwaves - 1) / nwaves;
+    const int kb = kt0 + wave * per;
+    const int ke = min(kt1, kb + per);
     const int row = lane & 15, grp = lane >> 4;
 
     f32x4 acc[MT][NT];
@@ -116,34 +163,24 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    auto koff = [&](int kt) -> size_t { return (size_t)kt * 32 + grp * 8; };   // of this lane group's 8 elements in an A row
     const bf16x8* bp[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const int t = min(ntile0 + nt, ntiles - 1);     // clamp: tiles past the edge are computed, never stored
         bp[nt] = g.wp + (size_t)t * KT * 64 + lane;
     }
-
-    // A rows of this lane; for the normalising source also 1/rms of those rows
-    const void* ap[MT];
+    auto load_b = [&](int nt, int kt) -> bf16x8 { return __builtin_nontemporal_load(bp[nt] + (size_t)kt * 64); };
+    const bf16_t* ap[MT];
     bool av[MT];
-    float inv[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m = mt * 16 + row;
         av[mt] = m < M;
-        const size_t off = (size_t)(av[mt] ? m : 0) * K + grp * 8;
-        ap[mt] = ASRC == A_BF16 ? (const void*)(reinterpret_cast<const bf16_t*>(g.a) + off)
-                                : (const void*)(reinterpret_cast<const float*>(g.a) + off);
-        inv[mt] = 1.f;
-        if constexpr (ASRC == A_NORM) {
-            const float ss = (float)((double)g.ss_in[av[mt] ? m : 0] * (1.0 / 16777216.0));
-            inv[mt] = 1.0f / sqrtf(ss / (float)K + g.eps);
-        }
+        ap[mt] = g.a + (size_t)(av[mt] ? m : 0) * K;
     }
-    const float* nw = ASRC == A_NORM ? g.norm_w + grp * 8 : nullptr;
-    if constexpr (ASRC == A_NORM) {
-        if (g.ss_zero && blockIdx.x == 0 && tid < HSD_MAX_PASS_ROWS) g.ss_zero[tid] = 0ull;   // ready for the next producer
-    }
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (g.ss_zero && blockIdx.x == 0 && blockIdx.y == 0) ss_clear(g.ss_zero, tid, blockDim.x);   // for the next producer
 
     int kt = kb;
     for (; kt + U <= ke; kt += U) {
@@ -151,11 +188,12 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) b[u][nt] = __builtin_nontemporal_load(bp[nt] + (size_t)(kt + u) * 64);
+            for (int nt = 0; nt < NT; ++nt) b[u][nt] = load_b(nt, kt + u);
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) a[u][mt] = load_a<ASRC>(ap[mt], nw, kt + u, inv[mt], av[mt]);
+            for (int mt = 0; mt < MT; ++mt)
+                a[u][mt] = av[mt] ? *reinterpret_cast<const bf16x8*>(ap[mt] + koff(kt + u)) : zero;
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -167,9 +205,9 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
     for (; kt < ke; ++kt) {
         bf16x8 b[NT], a[MT];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) b[nt] = __builtin_nontemporal_load(bp[nt] + (size_t)kt * 64);
+        for (int nt = 0; nt < NT; ++nt) b[nt] = load_b(nt, kt);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) a[mt] = load_a<ASRC>(ap[mt], nw, kt, inv[mt], av[mt]);
+        for (int mt = 0; mt < MT; ++mt) a[mt] = av[mt] ? *reinterpret_cast<const bf16x8*>(ap[mt] + koff(kt)) : zero;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -178,7 +216,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
     }
 
     // cross-wave reduction through LDS: red[wave][tile][r][lane]; element (tile, r, lane) is
-    // row 16 mt + 4 (lane / 16) + r, column 16 (ntile0 + nt) + lane % 16
+    // row 16 mt + 4 (lane / 16) + r, column 16 (ntile0 + nt) + lane % 16.  Result in red[0 .. TOTAL).
     float* mine = red + wave * TOTAL;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -187,12 +225,45 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) mine[(mt * NT + nt) * 256 + r * 64 + lane] = acc[mt][nt][r];
     __syncthreads();
-
-    if constexpr (EPI == EPI_STORE || EPI == EPI_RESID) {
-        float* sq = red + nwaves * TOTAL;                  // [MT*16][NT*16] squares of the new residual values
+    if (ksplit == 1) {
         for (int idx = tid; idx < TOTAL; idx += blockDim.x) {
             float s = 0.f;
             for (int w = 0; w < nwaves; ++w) s += red[w * TOTAL + idx];
+            red[idx] = s;
+        }
+    } else {
+        // Partial tile of this K slice to memory; the last slice to arrive adds them in slice order.
+        // The exchange uses device-scope relaxed atomic stores and loads (performed at the level all
+        // XCDs share, no cache-wide write-back or invalidate as a device-scope fence would cost on
+        // every one of ~1000 workgroups); each wave waits for its stores to be acknowledged before the
+        // workgroup takes its ticket.
+        float* slot = g.part + ((size_t)blockIdx.x * ksplit) * TOTAL;
+        for (int idx = tid; idx < TOTAL; idx += blockDim.x) {
+            float s = 0.f;
+            for (int w = 0; w < nwaves; ++w) s += red[w * TOTAL + idx];
+            __hip_atomic_store(slot + (size_t)blockIdx.y * TOTAL + idx, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");     // this wave's stores have completed
+        __syncthreads();
+        if (tid == 0)
+            sh_last = __hip_atomic_fetch_add(g.tickets + blockIdx.x, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == ksplit - 1;
+        __syncthreads();
+        if (!sh_last) return;
+        for (int idx = tid; idx < TOTAL; idx += blockDim.x) {
+            float s = 0.f;
+            for (int k = 0; k < ksplit; ++k)
+                s += __hip_atomic_load(slot + (size_t)k * TOTAL + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            red[idx] = s;
+        }
+        if (tid == 0) __hip_atomic_store(g.tickets + blockIdx.x, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
+    }
+    __syncthreads();
+
+    // ---- epilogue on the final sums red[tile][r][lane] ----
+    if constexpr (EPI == EPI_STORE || EPI == EPI_RESID) {
+        float* sq = red + nwaves * TOTAL;                  // [MT*16][NT*16] squares of the new residual values
+        for (int idx = tid; idx < TOTAL; idx += blockDim.x) {
+            const float s = red[idx];
             const int tile = idx >> 8, rem = idx & 255, r = rem >> 6, l = rem & 63;
             const int mt = tile / NT, nt = tile % NT;
             const int ml = mt * 16 + 4 * (l >> 4) + r;
@@ -200,7 +271,12 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
             float v = 0.f;
             if (ml < M && n < N) {
                 float* dst = g.out_f32 + (size_t)ml * N + n;
-                v = EPI == EPI_RESID ? *dst + s : s;
+                if constexpr (EPI == EPI_RESID) {
+                    v = *dst + s;
+                    if (g.out_bf16) g.out_bf16[(size_t)ml * N + n] = (bf16_t)(v * g.norm_w[n]);
+                } else {
+                    v = g.ss_in ? s * row_inv_rms(g.ss_in, ml, K, g.eps) : s;
+                }
                 *dst = v;
             }
             if constexpr (EPI == EPI_RESID) sq[ml * (NT * 16) + nt * 16 + (l & 15)] = v * v;
@@ -210,7 +286,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
             if (tid < M) {
                 float s = 0.f;
                 for (int c = 0; c < NT * 16; ++c) s += sq[tid * (NT * 16) + c];
-                atomicAdd(g.ss_out + tid, (unsigned long long)((double)s * 16777216.0 + 0.5));
+                ss_add(g.ss_out, tid, s);
             }
         }
     } else if constexpr (EPI == EPI_SWIGLU) {
@@ -220,58 +296,117 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
         for (int idx = tid; idx < HALF; idx += blockDim.x) {
             const int pair = idx >> 8, rem = idx & 255, r = rem >> 6, l = rem & 63;
             const int mt = pair / (NT / 2), j = pair % (NT / 2);
-            float gt = 0.f, up = 0.f;
-            for (int w = 0; w < nwaves; ++w) {
-                gt += red[w * TOTAL + (mt * NT + 2 * j) * 256 + rem];
-                up += red[w * TOTAL + (mt * NT + 2 * j + 1) * 256 + rem];
-            }
             const int ml = mt * 16 + 4 * (l >> 4) + r;
             const int f = ((ntile0 >> 1) + j) * 16 + (l & 15);
-            if (ml < M && f < F) g.out_bf16[(size_t)ml * F + f] = (bf16_t)(gt / (1.f + __expf(-gt)) * up);
+            if (ml < M && f < F) {
+                const float inv = row_inv_rms(g.ss_in, ml, K, g.eps);
+                const float gt = red[(mt * NT + 2 * j) * 256 + rem] * inv;
+                const float up = red[(mt * NT + 2 * j + 1) * 256 + rem] * inv;
+                g.out_bf16[(size_t)ml * F + f] = (bf16_t)(gt / (1.f + __expf(-gt)) * up);
+            }
         }
     } else {
         // EPI_ROPE: tile pairs hold dims [16 jb, 16 jb + 16) and their partners hd/2 further of one head
-        const int hd = g.hd, half = hd >> 1, pairs_per_head = hd >> 5;
+        const int hd = g.hd, pairs_per_head = hd >> 5;
         constexpr int HALF = MT * (NT / 2) * 256;
         for (int idx = tid; idx < HALF; idx += blockDim.x) {
             const int pair = idx >> 8, rem = idx & 255, r = rem >> 6, l = rem & 63;
             const int mt = pair / (NT / 2), jp = pair % (NT / 2);
-            float a = 0.f, b = 0.f;
-            for (int w = 0; w < nwaves; ++w) {
-                a += red[w * TOTAL + (mt * NT + 2 * jp) * 256 + rem];
-                b += red[w * TOTAL + (mt * NT + 2 * jp + 1) * 256 + rem];
-            }
             const int ml = mt * 16 + 4 * (l >> 4) + r;
             const int gp = (ntile0 >> 1) + jp;                      // global pair index
             const int head = gp / pairs_per_head, j = (gp % pairs_per_head) * 16 + (l & 15);
             if (ml >= M || head >= g.n_q + 2 * g.n_kv) continue;
-            const int pos = g.pos0 + ml;
-            const bool is_q = head < g.n_q, is_v = head >= g.n_q + g.n_kv;
-            float ra = a, rb = b;
-            if (!is_v) {
-                const double ang = (double)pos * exp2(-2.0 * (double)j / (double)hd * log2((double)g.rope_base));
-                double sn, cs;
-                sincos(ang, &sn, &cs);
-                ra = (float)((double)a * cs - (double)b * sn);
-                rb = (float)((double)b * cs + (double)a * sn);
-            }
-            if (is_q) {
-                bf16_t* dst = g.out_bf16 + ((size_t)ml * g.n_q + head) * hd;
-                dst[j] = (bf16_t)ra;
-                dst[j + half] = (bf16_t)rb;
-            } else {
-                const int kvh = is_v ? head - g.n_q - g.n_kv : head - g.n_q;
-                const int page = g.pages[pos / HSD_KV_PAGE], ip = pos % HSD_KV_PAGE;
-                bf16_t* blk = g.kv_layer + (size_t)page * kv_page_elems(g.n_kv, hd) + (size_t)kvh * 2 * kv_block_elems(hd) +
-                              (is_v ? kv_block_elems(hd) : 0);
-                if (is_v) {
-                    blk[kv_v_index(ip, j, hd)] = (bf16_t)ra;
-                    blk[kv_v_index(ip, j + half, hd)] = (bf16_t)rb;
-                } else {
-                    blk[kv_k_index(ip, j, hd)] = (bf16_t)ra;
-                    blk[kv_k_index(ip, j + half, hd)] = (bf16_t)rb;
+            const float inv = row_inv_rms(g.ss_in, ml, K, g.eps);
+            const float a = red[(mt * NT + 2 * jp) * 256 + rem] * inv;
+            const float b = red[(mt * NT + 2 * jp + 1) * 256 + rem] * inv;
+            rope_store(g, head, j, ml, a, b);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// bf16 row kernel for the narrow projections (q/k/v, attention output, FFN down) with m <= 16 rows.
+// With N / 16 column tiles in the low hundreds the MFMA tiling cannot give every CU its share of the
+// stream without exchanging partial sums between workgroups, which costs more than it saves.  Here W
+// is row-major, a workgroup owns only R output features over the whole K range (its waves split K and
+// reduce through LDS), so there are N / R workgroups and every output is final where it is computed.
+// The dot products use the packed bf16 dot instruction; the activations are read from L1/L2.
+// ------------------------------------------------------------------------------------------------
+template <int R, int MB, int EPI>
+__global__ __launch_bounds__(512) void gemv_bf16_kernel(const GemmArgs g) {
+    constexpr int LPR = 64 / R;                        // lanes per weight row
+    __shared__ float red[8][R][MB];
+    __shared__ float sq[R][MB];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+    const int M = g.M, N = g.N, K = g.K;
+    const int KC = K >> 3;                             // 16-byte chunks per row
+    const int n0 = blockIdx.x * R;
+    const int r = lane / LPR, cl = lane % LPR;
+    const int n = min(n0 + r, N - 1);                  // clamp: rows past the edge are computed, never stored
+    const int per = (KC + nwaves - 1) / nwaves;
+    const int c0 = wave * per, c1 = min(KC, c0 + per);
+    if (g.ss_zero && blockIdx.x == 0) ss_clear(g.ss_zero, tid, blockDim.x);
+
+    float acc[MB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m) acc[m] = 0.f;
+    const bf16x8* wrow = reinterpret_cast<const bf16x8*>(g.wp) + (size_t)n * KC;
+    const bf16x8* arow = reinterpret_cast<const bf16x8*>(g.a);
+#pragma unroll 4
+    for (int c = c0 + cl; c < c1; c += LPR) {
+        const bf16x8 w = __builtin_nontemporal_load(wrow + c);
+#pragma unroll
+        for (int m = 0; m < MB; ++m) {
+            if (m < M) {
+                const bf16x8 a = arow[(size_t)m * KC + c];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bf16x2 wp2 = {w[2 * e], w[2 * e + 1]}, ap2 = {a[2 * e], a[2 * e + 1]};
+                    acc[m] = __builtin_amdgcn_fdot2_f32_bf16(wp2, ap2, acc[m], false);
                 }
             }
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+#pragma unroll
+        for (int o = LPR / 2; o > 0; o >>= 1) acc[m] += __shfl_xor(acc[m], o, 64);
+        if (cl == 0) red[wave][r][m] = acc[m];
+    }
+    __syncthreads();
+    const int er = tid / MB, em = tid % MB;            // epilogue element of this thread: row er, token em
+    const bool active = tid < R * MB && em < M && n0 + er < N;
+    float s = 0.f;
+    if (tid < R * MB)
+        for (int w = 0; w < nwaves; ++w) s += red[w][er][em];
+
+    if constexpr (EPI == EPI_STORE) {
+        if (active) g.out_f32[(size_t)em * N + n0 + er] = g.ss_in ? s * row_inv_rms(g.ss_in, em, K, g.eps) : s;
+    } else if constexpr (EPI == EPI_RESID) {
+        float v = 0.f;
+        if (active) {
+            const size_t at = (size_t)em * N + n0 + er;
+            v = g.out_f32[at] + s;
+            g.out_f32[at] = v;
+            if (g.out_bf16) g.out_bf16[at] = (bf16_t)(v * g.norm_w[n0 + er]);
+        }
+        if (tid < R * MB) sq[er][em] = v * v;
+        __syncthreads();
+        if (tid < M) {
+            float t = 0.f;
+#pragma unroll
+            for (int i = 0; i < R; ++i) t += sq[i][tid];
+            ss_add(g.ss_out, tid, t);
+        }
+    } else {
+        // EPI_ROPE (R == 2): the two rows are dim j of a head and its rotation partner j + hd/2
+        if (tid < R * MB) sq[er][em] = s;
+        __syncthreads();
+        const int half = g.hd >> 1;
+        const int head = blockIdx.x / half, j = blockIdx.x % half;
+        if (tid < M && head < g.n_q + 2 * g.n_kv) {
+            const float inv = row_inv_rms(g.ss_in, tid, K, g.eps);
+            rope_store(g, head, j, tid, sq[0][tid] * inv, sq[1][tid] * inv);
         }
     }
 }
@@ -323,28 +458,50 @@ __global__ void gemm_f32_kernel(const float* __restrict__ x, const float* __rest
 // host side
 // ------------------------------------------------------------------------------------------------
 static int g_tune_nt[4] = {0, 0, 0, 0};      // optional overrides per epilogue kind (0 = heuristic)
+static int g_tune_ksplit[4] = {0, 0, 0, 0};
 static int g_tune_waves = 0;
+int g_gemv_max_m = 2;            // most tokens of a pass served from the row-major copies
 
-void gemm_tune(int epilogue, int nt, int waves) {
-    if (epilogue >= 0 && epilogue < 4) g_tune_nt[epilogue] = nt;
+void gemm_tune(int epilogue, int nt, int ksplit, int waves) {
+    if (epilogue == 100) { g_gemv_max_m = nt; return; }
+    if (epilogue >= 0 && epilogue < 4) {
+        g_tune_nt[epilogue] = nt;
+        g_tune_ksplit[epilogue] = ksplit;
+    }
     g_tune_waves = waves;
 }
 
 GemmPlan gemm_plan(int m, int n, int k, int epi) {
-    GemmPlan p{1, 8};
+    GemmPlan p{1, 1, 8};
     const int mt = m <= 16 ? 1 : (m <= 32 ? 2 : 4);
     const int ntiles = ceil_div(n, 16), KT = k / 32;
     switch (epi) {
         case EPI_ROPE: p.nt = 2; break;
-        case EPI_SWIGLU: p.nt = ntiles >= 1024 && mt <= 2 ? 4 : 2; break;
-        case EPI_RESID: p.nt = ntiles >= 1024 ? 2 : 1; break;
-        default: p.nt = ntiles >= 4096 && mt <= 2 ? 4 : (ntiles >= 512 ? 2 : 1); break;
+        case EPI_SWIGLU: p.nt = ntiles >= 4096 && mt <= 2 ? 4 : 2; break;
+        case EPI_RESID: p.nt = ntiles >= 2048 ? 2 : 1; break;
+        default: p.nt = ntiles >= 8192 && mt <= 2 ? 4 : (ntiles >= 1024 ? 2 : 1); break;
     }
-    if (epi != EPI_ROPE && epi >= 0 && epi < 4 && g_tune_nt[epi]) p.nt = g_tune_nt[epi];
+    if (epi != EPI_ROPE && g_tune_nt[epi]) p.nt = g_tune_nt[epi];
     if (mt == 4 && p.nt > 2) p.nt = 2;
+    // about a thousand workgroups: every CU must be pulling for the HBM stream to reach its peak
+    // Splitting K across workgroups costs a round trip through memory for the partial tiles, which only pays for
+    // plain stores of narrow matrices; the fused epilogues keep K inside the workgroup.
+    const int groups = ceil_div(ntiles, p.nt);
+    p.ksplit = epi == EPI_STORE ? (1024 + groups / 2) / groups : 1;
+    if (g_tune_ksplit[epi]) p.ksplit = g_tune_ksplit[epi];
+    if (p.ksplit > 8) p.ksplit = 8;
+    if (p.ksplit > KT) p.ksplit = KT;
+    if (p.ksplit < 1) p.ksplit = 1;
+    const int per_wg = ceil_div(KT, p.ksplit);
     p.waves = g_tune_waves ? g_tune_waves : 8;
-    while (p.waves > 1 && KT < 2 * p.waves) p.waves >>= 1;
+    if (p.waves > per_wg) p.waves = per_wg;
     return p;
+}
+
+size_t gemm_part_bytes(int m, int n, int k, int epi) {
+    const GemmPlan p = gemm_plan(m, n, k, epi);
+    const int mt = m <= 16 ? 1 : (m <= 32 ? 2 : 4);
+    return p.ksplit == 1 ? 0 : (size_t)ceil_div(ceil_div(n, 16), p.nt) * p.ksplit * mt * p.nt * 256 * sizeof(float);
 }
 
 static size_t gemm_lds_bytes(const GemmPlan& p, int m, int epi) {
@@ -354,10 +511,11 @@ static size_t gemm_lds_bytes(const GemmPlan& p, int m, int epi) {
     return b;
 }
 
-template <int NT, int MT, int ASRC, int EPI>
+template <int NT, int MT, int EPI>
 static void launch_inst(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     const int ntiles = ceil_div(g.N, 16);
-    gemm_bf16_kernel<NT, MT, ASRC, EPI><<<ceil_div(ntiles, NT), p.waves * 64, gemm_lds_bytes(p, g.M, EPI), s>>>(g);
+    dim3 grid(ceil_div(ntiles, NT), p.ksplit);
+    gemm_bf16_kernel<NT, MT, EPI><<<grid, p.waves * 64, gemm_lds_bytes(p, g.M, EPI), s>>>(g);
 }
 
 static int check_gemm(int m, int n, int k) {
@@ -366,24 +524,69 @@ static int check_gemm(int m, int n, int k) {
     return HSD_OK;
 }
 
-int launch_gemm_bf16(const GemmArgs& g, int asrc, int epi, const GemmPlan& p, hipStream_t s) {
+int launch_gemm_bf16(const GemmArgs& g, int epi, const GemmPlan& p, hipStream_t s) {
     if (int rc = check_gemm(g.M, g.N, g.K)) return rc;
+    if (p.ksplit > 1 && (!g.part || !g.tickets)) HSD_FAIL(HSD_EINVAL, "gemm: split-K launch without partial / ticket buffers");
     const int mt = g.M <= 16 ? 1 : (g.M <= 32 ? 2 : 4);
-#define HSD_CASE(NT_, MT_, A_, E_)                                         \
-    if (p.nt == NT_ && mt == MT_ && asrc == A_ && epi == E_) {             \
-        launch_inst<NT_, MT_, A_, E_>(g, p, s);                            \
-        HSD_LAUNCH_CHECK();                                                \
-        return HSD_OK;                                                     \
+#define HSD_CASE(NT_, MT_, E_)                                  \
+    if (p.nt == NT_ && mt == MT_ && epi == E_) {                \
+        launch_inst<NT_, MT_, E_>(g, p, s);                     \
+        HSD_LAUNCH_CHECK();                                     \
+        return HSD_OK;                                          \
     }
-#define HSD_MTS(NT_, A_, E_) HSD_CASE(NT_, 1, A_, E_) HSD_CASE(NT_, 2, A_, E_) HSD_CASE(NT_, 4, A_, E_)
-    HSD_MTS(1, A_BF16, EPI_STORE) HSD_MTS(2, A_BF16, EPI_STORE) HSD_CASE(4, 1, A_BF16, EPI_STORE) HSD_CASE(4, 2, A_BF16, EPI_STORE)
-    HSD_MTS(1, A_NORM, EPI_STORE) HSD_MTS(2, A_NORM, EPI_STORE) HSD_CASE(4, 1, A_NORM, EPI_STORE) HSD_CASE(4, 2, A_NORM, EPI_STORE)
-    HSD_MTS(1, A_BF16, EPI_RESID) HSD_MTS(2, A_BF16, EPI_RESID)
-    HSD_MTS(2, A_NORM, EPI_SWIGLU) HSD_CASE(4, 1, A_NORM, EPI_SWIGLU) HSD_CASE(4, 2, A_NORM, EPI_SWIGLU)
-    HSD_MTS(2, A_NORM, EPI_ROPE)
+#define HSD_MTS(NT_, E_) HSD_CASE(NT_, 1, E_) HSD_CASE(NT_, 2, E_) HSD_CASE(NT_, 4, E_)
+    HSD_MTS(1, EPI_STORE) HSD_MTS(2, EPI_STORE) HSD_CASE(4, 1, EPI_STORE) HSD_CASE(4, 2, EPI_STORE)
+    HSD_MTS(1, EPI_RESID) HSD_MTS(2, EPI_RESID)
+    HSD_MTS(2, EPI_SWIGLU) HSD_CASE(4, 1, EPI_SWIGLU) HSD_CASE(4, 2, EPI_SWIGLU)
+    HSD_MTS(2, EPI_ROPE)
 #undef HSD_MTS
 #undef HSD_CASE
-    HSD_FAIL(HSD_EINVAL, "gemm: no kernel for nt=%d m=%d source=%d epilogue=%d", p.nt, g.M, asrc, epi);
+    HSD_FAIL(HSD_EINVAL, "gemm: no kernel for nt=%d m=%d epilogue=%d", p.nt, g.M, epi);
+}
+
+template <int R, int EPI>
+static int launch_gemv_mb(const GemmArgs& g, hipStream_t s) {
+    const int grid = ceil_div(g.N, R);
+    int waves = 8;
+    while (waves > 1 && (g.K >> 3) < waves * (64 / R)) waves >>= 1;     // at least one chunk per lane
+    const int mb = g.M <= 1 ? 1 : (g.M <= 2 ? 2 : (g.M <= 4 ? 4 : (g.M <= 8 ? 8 : 16)));
+    switch (mb) {
+        case 1: gemv_bf16_kernel<R, 1, EPI><<<grid, waves * 64, 0, s>>>(g); break;
+        case 2: gemv_bf16_kernel<R, 2, EPI><<<grid, waves * 64, 0, s>>>(g); break;
+        case 4: gemv_bf16_kernel<R, 4, EPI><<<grid, waves * 64, 0, s>>>(g); break;
+        case 8: gemv_bf16_kernel<R, 8, EPI><<<grid, waves * 64, 0, s>>>(g); break;
+        default: gemv_bf16_kernel<R, 16, EPI><<<grid, waves * 64, 0, s>>>(g); break;
+    }
+    HSD_LAUNCH_CHECK();
+    return HSD_OK;
+}
+
+// Row-major W: 16 tokens per launch (the pass only sends one or two tokens here; more would make the
+// per-token activation reads outweigh the weight stream, and the tiled kernel serves them).
+int launch_gemv_bf16(const GemmArgs& g0, int epi, hipStream_t s) {
+    if (int rc = check_gemm(g0.M, g0.N, g0.K)) return rc;
+    if (epi == EPI_ROPE && g0.N != (g0.n_q + 2 * g0.n_kv) * g0.hd) HSD_FAIL(HSD_EINVAL, "gemv: q/k/v width mismatch");
+    for (int m0 = 0; m0 < g0.M; m0 += 16) {
+        GemmArgs g = g0;
+        g.M = g0.M - m0 < 16 ? g0.M - m0 : 16;
+        g.a = g0.a + (size_t)m0 * g0.K;
+        if (g.ss_in) g.ss_in = g0.ss_in + m0;
+        if (g.ss_out) g.ss_out = g0.ss_out + m0;
+        if (m0 > 0) g.ss_zero = nullptr;
+        if (epi == EPI_ROPE) {
+            g.out_bf16 = g0.out_bf16 + (size_t)m0 * g0.n_q * g0.hd;
+            g.pos0 = g0.pos0 + m0;
+        } else {
+            g.out_f32 = g0.out_f32 + (size_t)m0 * g0.N;
+            if (g0.out_bf16) g.out_bf16 = g0.out_bf16 + (size_t)m0 * g0.N;
+        }
+        int rc;
+        if (epi == EPI_ROPE) rc = launch_gemv_mb<2, EPI_ROPE>(g, s);
+        else if (epi == EPI_RESID) rc = g.N <= 4096 ? launch_gemv_mb<2, EPI_RESID>(g, s) : launch_gemv_mb<4, EPI_RESID>(g, s);
+        else rc = g.N <= 4096 ? launch_gemv_mb<2, EPI_STORE>(g, s) : launch_gemv_mb<4, EPI_STORE>(g, s);
+        if (rc) return rc;
+    }
+    return HSD_OK;
 }
 
 int launch_gemm_f32(const float* x, const float* w, float* out, int m, int n, int k, bool swiglu, hipStream_t s) {
@@ -399,29 +602,52 @@ int launch_gemm_f32(const float* x, const float* w, float* out, int m, int n, in
 // ------------------------------------------------------------------------------------------------
 // C ABI
 // ------------------------------------------------------------------------------------------------
+extern "C" int hsd_tune(int key, int nt, int ksplit, int waves) {
+    gemm_tune(key, nt, ksplit, waves);
+    return HSD_OK;
+}
+
 extern "C" size_t hsd_packed_bytes(int n, int k, int dtype) {
     return align_up((size_t)ceil_div(n, 16) * 16 * k * dtype_size(dtype), 256);
 }
 
-extern "C" int hsd_pack_weight(const void* w_dev, void* packed_dev, int n, int k, int dtype, void* stream) {
-    if (!w_dev || !packed_dev || n < 1 || (dtype != HSD_F32 && dtype != HSD_BF16))
+extern "C" int hsd_pack_weight(const void* w_dev, void* packed_dev, int n, int k, int dtype, int layout, void* stream) {
+    if (!w_dev || !packed_dev || n < 1 || (dtype != HSD_F32 && dtype != HSD_BF16) || (layout != HSD_LAYOUT_TILES && layout != HSD_LAYOUT_ROWS))
         HSD_FAIL(HSD_EINVAL, "hsd_pack_weight: bad arguments");
     hipStream_t s = (hipStream_t)stream;
     HSD_HIP(hipMemsetAsync(packed_dev, 0, hsd_packed_bytes(n, k, dtype), s));
-    return launch_pack(w_dev, packed_dev, n, k, dtype, 0, 0, 0, s);
+    return launch_pack(w_dev, packed_dev, n, k, dtype, 0, 0, 0, layout == HSD_LAYOUT_ROWS, s);
 }
 
-extern "C" int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int n, int k, int dtype,
-                        void* stream) {
-    if (!x_dev || !packed_dev || !y_dev || (dtype != HSD_F32 && dtype != HSD_BF16))
+extern "C" size_t hsd_gemm_workspace_bytes(int m, int n, int k) {
+    if (m < 1 || m > HSD_MAX_PASS_ROWS || n < 1 || k < 32) return 0;
+    return align_up(gemm_part_bytes(m, n, k, EPI_STORE), 256) + align_up((size_t)ceil_div(n, 16) * sizeof(int), 256);
+}
+
+extern "C" int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int n, int k, int dtype, int layout,
+                        void* workspace_dev, void* stream) {
+    if (!x_dev || !packed_dev || !y_dev || !workspace_dev || (dtype != HSD_F32 && dtype != HSD_BF16) ||
+        (layout != HSD_LAYOUT_TILES && layout != HSD_LAYOUT_ROWS))
         HSD_FAIL(HSD_EINVAL, "hsd_gemm: bad arguments");
     if (int rc = check_gemm(m, n, k)) return rc;
     hipStream_t s = (hipStream_t)stream;
     if (dtype == HSD_F32) return launch_gemm_f32((const float*)x_dev, (const float*)packed_dev, y_dev, m, n, k, false, s);
+    if (layout == HSD_LAYOUT_ROWS) {
+        GemmArgs g = {};
+        g.a = (const bf16_t*)x_dev;
+        g.wp = (const bf16x8*)packed_dev;
+        g.M = m; g.N = n; g.K = k;
+        g.out_f32 = y_dev;
+        return launch_gemv_bf16(g, EPI_STORE, s);
+    }
+    const size_t part_bytes = align_up(gemm_part_bytes(m, n, k, EPI_STORE), 256);
     GemmArgs g = {};
-    g.a = x_dev;
+    g.a = (const bf16_t*)x_dev;
     g.wp = (const bf16x8*)packed_dev;
     g.M = m; g.N = n; g.K = k;
     g.out_f32 = y_dev;
-    return launch_gemm_bf16(g, A_BF16, EPI_STORE, gemm_plan(m, n, k, EPI_STORE), s);
+    g.part = (float*)workspace_dev;
+    g.tickets = (int*)((char*)workspace_dev + part_bytes);
+    HSD_HIP(hipMemsetAsync(g.tickets, 0, (size_t)ceil_div(n, 16) * sizeof(int), s));
+    return launch_gemm_bf16(g, EPI_STORE, gemm_plan(m, n, k, EPI_STORE), s);
 }

@@ -14,11 +14,12 @@ __device__ __forceinline__ float block_sum_256(float v, float* sh) {
 }
 
 // x[m, :] = E[tok[m], :] as fp32 (the residual stream is fp32 for both storage types).  With ss != null
-// also the row's sum of squares in the fixed-point form the normalising GEMMs read (times 2^24), and the
-// second accumulator cleared for the first producer of the pass.
+// also what the first normalising GEMM of the pass reads: xn = bf16(x * norm_w), the row's sum of squares
+// in fixed point (times 2^24), and the second accumulator cleared for the first producer of the pass.
 template <typename T>
 __global__ void embed_kernel(const int32_t* __restrict__ tok, const T* __restrict__ E, float* __restrict__ x, int d,
-                             int vocab, unsigned long long* __restrict__ ss, unsigned long long* __restrict__ ss_other) {
+                             int vocab, unsigned long long* __restrict__ ss, unsigned long long* __restrict__ ss_other,
+                             const float* __restrict__ norm_w, bf16_t* __restrict__ xn) {
     __shared__ float sh[16];
     int t = tok[blockIdx.x];
     t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);          // ids are validated on the host; never read out of bounds
@@ -28,13 +29,15 @@ __global__ void embed_kernel(const int32_t* __restrict__ tok, const T* __restric
     for (int i = threadIdx.x; i < d; i += blockDim.x) {
         const float v = to_f32(src[i]);
         dst[i] = v;
+        if (xn) xn[(size_t)blockIdx.x * d + i] = (bf16_t)(v * norm_w[i]);
         acc += v * v;
     }
     if (ss) {
         acc = block_sum_256(acc, sh);
-        if (threadIdx.x == 0) {
-            ss[blockIdx.x] = (unsigned long long)((double)acc * 16777216.0 + 0.5);
-            ss_other[blockIdx.x] = 0ull;
+        if (threadIdx.x < SS_SLOTS) {      // the row's total in slot 0, every other slot of both accumulators cleared
+            const int at = threadIdx.x * HSD_MAX_PASS_ROWS + blockIdx.x;
+            ss[at] = threadIdx.x == 0 ? (unsigned long long)((double)acc * 16777216.0 + 0.5) : 0ull;
+            ss_other[at] = 0ull;
         }
     }
 }
@@ -157,11 +160,11 @@ __global__ void softmax_kernel(const float* __restrict__ z, float* __restrict__ 
 
 // ---- launchers --------------------------------------------------------------------------------
 int launch_embed(const int32_t* tok, const void* E, float* x, int m, int d, int vocab, int dtype, unsigned long long* ss,
-                 unsigned long long* ss_other, hipStream_t s) {
+                 unsigned long long* ss_other, const float* norm_w, void* xn, hipStream_t s) {
     if (dtype == HSD_BF16)
-        embed_kernel<bf16_t><<<m, 256, 0, s>>>(tok, (const bf16_t*)E, x, d, vocab, ss, ss_other);
+        embed_kernel<bf16_t><<<m, 256, 0, s>>>(tok, (const bf16_t*)E, x, d, vocab, ss, ss_other, norm_w, (bf16_t*)xn);
     else
-        embed_kernel<float><<<m, 256, 0, s>>>(tok, (const float*)E, x, d, vocab, ss, ss_other);
+        embed_kernel<float><<<m, 256, 0, s>>>(tok, (const float*)E, x, d, vocab, nullptr, nullptr, nullptr, nullptr);
     HSD_LAUNCH_CHECK();
     return HSD_OK;
 }

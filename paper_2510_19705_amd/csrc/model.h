@@ -11,6 +11,10 @@ struct LayerWeights {
     float* norm2;
     void* wgu;    // packed [2 ffn, d], gate / up tiles interleaved
     void* wd;     // packed [d, ffn]
+    // bf16, first rows_copy_layers layers only: row-major copies for passes of one or two tokens
+    void* wqkv_rows;   // [(n_q + 2 n_kv) hd, d], every dim followed by its RoPE partner
+    void* wo_rows;     // [d, n_q hd]
+    void* wd_rows;     // [d, ffn]
 };
 
 struct hsd_model {
@@ -26,8 +30,9 @@ struct hsd_model {
     int32_t* pages_dev;
     // activation scratch
     float* x;         // residual stream [max_rows, d] fp32
-    void* xn;         // normalised rows [max_rows, d]
-    float* part;      // fp32 path: GEMM outputs waiting to be added to the residual stream
+    void* xn;         // input rows of the next normalising GEMM [max_rows, d] (bf16 path: x * w_norm, scaled by 1/rms later)
+    float* part;      // fp32 path: GEMM outputs waiting to be added to the residual stream; bf16 path: split-K partial tiles
+    int* tickets;     // bf16 path: arrival counters of the split-K column groups
     unsigned long long* ss[2];   // bf16 path: per-row sums of squares (fixed point) for the two norms of a layer
     void* q;          // [max_rows, n_q hd]
     void* att;        // [max_rows, n_q hd]
@@ -48,7 +53,7 @@ int model_pass(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows, int 
 
 // kernels_layer.hip
 int launch_embed(const int32_t* tok, const void* E, float* x, int m, int d, int vocab, int dtype, unsigned long long* ss,
-                 unsigned long long* ss_other, hipStream_t s);
+                 unsigned long long* ss_other, const float* norm_w, void* xn, hipStream_t s);
 int launch_resid_rmsnorm(float* x, const float* part, int ksplit, int part_rows, int part_row0, const float* w, void* xn,
                          int rows, int row0, int d, float eps, int dtype, hipStream_t s);
 int launch_rope_kv(const float* part, int ksplit, int m, void* q, void* kv_layer, const int32_t* pages, int pos0, int n_q,

@@ -26,13 +26,14 @@ static int check_desc(const hsd_model_desc* d) {
     if (d->max_seq < HSD_KV_PAGE || d->max_seq % HSD_KV_PAGE != 0) HSD_FAIL(HSD_EINVAL, "model: max_seq=%d must be a positive multiple of %d", d->max_seq, HSD_KV_PAGE);
     if (d->max_rows < 1 || d->max_rows > HSD_MAX_PASS_ROWS) HSD_FAIL(HSD_EINVAL, "model: max_rows=%d outside 1..%d", d->max_rows, HSD_MAX_PASS_ROWS);
     if (!(d->eps > 0.f) || !(d->rope_base > 1.f)) HSD_FAIL(HSD_EINVAL, "model: eps=%g rope_base=%g", d->eps, d->rope_base);
+    if (d->rows_copy_layers < 0 || d->rows_copy_layers > d->n_layers) HSD_FAIL(HSD_EINVAL, "model: rows_copy_layers=%d outside 0..%d", d->rows_copy_layers, d->n_layers);
     return HSD_OK;
 }
 
 namespace {
 
 struct WeightLayout {
-    size_t norm1, wqkv, wo, norm2, wgu, wd, layer_bytes, embed, head, norm_f, total;
+    size_t norm1, wqkv, wo, norm2, wgu, wd, layer_bytes, embed, head, norm_f, rows, rows_qkv, rows_o, rows_d, rows_layer_bytes, total;
 };
 
 WeightLayout weight_layout(const hsd_model_desc& d) {
@@ -50,18 +51,43 @@ WeightLayout weight_layout(const hsd_model_desc& d) {
     L.embed = o;  o += align_up((size_t)d.vocab * d.d * dtype_size(d.dtype), 256);
     L.head = o;   o += hsd_packed_bytes(d.vocab, d.d, d.dtype);
     L.norm_f = o; o += align_up((size_t)d.d * 4, 256);
+    L.rows = o;
+    size_t r = 0;
+    L.rows_qkv = r; r += hsd_packed_bytes(nqkv, d.d, d.dtype);
+    L.rows_o = r;   r += hsd_packed_bytes(d.d, d.n_q * d.hd, d.dtype);
+    L.rows_d = r;   r += hsd_packed_bytes(d.d, d.ffn, d.dtype);
+    L.rows_layer_bytes = r;
+    o += r * (d.dtype == HSD_BF16 ? d.rows_copy_layers : 0);
     L.total = o;
     return L;
 }
 
 size_t part_elems_needed(const hsd_model_desc& d) {
-    // fp32 path: the widest GEMM output that waits for its consumer (fused QKV or a residual update)
     const int nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
-    return (size_t)d.max_rows * (nqkv > d.d ? nqkv : d.d);
+    if (d.dtype != HSD_BF16)   // the widest GEMM output that waits for its consumer (fused QKV or a residual update)
+        return (size_t)d.max_rows * (nqkv > d.d ? nqkv : d.d);
+    size_t need = 0;           // split-K partial tiles of the largest launch
+    const int ms[3] = {16, 32, 64};
+    for (int i = 0; i < 3; ++i) {
+        const int m = ms[i] < d.max_rows ? ms[i] : d.max_rows;
+        const size_t b[2] = {gemm_part_bytes(m, 2 * d.ffn, d.d, EPI_SWIGLU), gemm_part_bytes(m, d.vocab, d.d, EPI_STORE)};
+        for (int j = 0; j < 2; ++j)
+            if (b[j] / 4 > need) need = b[j] / 4;
+    }
+    return need;
+}
+
+size_t ticket_count(const hsd_model_desc& d) {
+    const int nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
+    int n = d.vocab;
+    if (2 * d.ffn > n) n = 2 * d.ffn;
+    if (nqkv > n) n = nqkv;
+    if (d.d > n) n = d.d;
+    return (size_t)ceil_div(n, 16);
 }
 
 struct ScratchLayout {
-    size_t pages, ss, x, xn, part, q, att, h, attn, total;
+    size_t pages, ss, tickets, x, xn, part, q, att, h, attn, total;
 };
 
 ScratchLayout scratch_layout(const hsd_model_desc& d) {
@@ -70,7 +96,8 @@ ScratchLayout scratch_layout(const hsd_model_desc& d) {
     const int R = d.max_rows;
     size_t o = 0;
     L.pages = o; o += align_up((size_t)(d.max_seq / HSD_KV_PAGE) * 4, 256);
-    L.ss = o;    o += align_up((size_t)2 * HSD_MAX_PASS_ROWS * 8, 256);
+    L.ss = o;    o += align_up((size_t)2 * SS_SLOTS * HSD_MAX_PASS_ROWS * 8, 256);
+    L.tickets = o; o += align_up(ticket_count(d) * 4, 256);
     L.x = o;     o += align_up((size_t)R * d.d * 4, 256);
     L.xn = o;    o += align_up((size_t)R * d.d * es, 256);
     L.part = o;  o += align_up(part_elems_needed(d) * 4, 256);
@@ -106,7 +133,10 @@ extern "C" int hsd_model_create(const hsd_model_desc* desc, void* weights_dev, v
     m->layers.resize(desc->n_layers);
     for (int l = 0; l < desc->n_layers; ++l) {
         char* lb = wb + W.layer_bytes * l;
-        m->layers[l] = LayerWeights{(float*)(lb + W.norm1), lb + W.wqkv, lb + W.wo, (float*)(lb + W.norm2), lb + W.wgu, lb + W.wd};
+        const bool copy = desc->dtype == HSD_BF16 && l < desc->rows_copy_layers;
+        char* rb = wb + W.rows + W.rows_layer_bytes * l;
+        m->layers[l] = LayerWeights{(float*)(lb + W.norm1), lb + W.wqkv, lb + W.wo, (float*)(lb + W.norm2), lb + W.wgu, lb + W.wd,
+                                    copy ? rb + W.rows_qkv : nullptr, copy ? rb + W.rows_o : nullptr, copy ? rb + W.rows_d : nullptr};
     }
     m->embed = wb + W.embed;
     m->head = wb + W.head;
@@ -118,7 +148,8 @@ extern "C" int hsd_model_create(const hsd_model_desc* desc, void* weights_dev, v
     char* sb = (char*)scratch_dev;
     m->pages_dev = (int32_t*)(sb + S.pages);
     m->ss[0] = (unsigned long long*)(sb + S.ss);
-    m->ss[1] = m->ss[0] + HSD_MAX_PASS_ROWS;
+    m->ss[1] = m->ss[0] + SS_SLOTS * HSD_MAX_PASS_ROWS;
+    m->tickets = (int*)(sb + S.tickets);
     m->x = (float*)(sb + S.x);
     m->xn = sb + S.xn;
     m->part = (float*)(sb + S.part);
@@ -133,6 +164,7 @@ extern "C" int hsd_model_create(const hsd_model_desc* desc, void* weights_dev, v
     m->prof_used = 0;
     // Cache rows beyond the valid length are read (and masked) by the attention kernels: keep them finite.
     hipError_t e = hipMemsetAsync(kv_dev, 0, m->kv_layer_bytes * desc->n_layers, m->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(m->tickets, 0, ticket_count(*desc) * 4, m->stream);
     // Padded rows of packed matrices must be zero.
     if (e == hipSuccess) e = hipMemsetAsync(m->head, 0, hsd_packed_bytes(desc->vocab, desc->d, desc->dtype), m->stream);
     std::vector<int32_t> ident(m->max_pages);
@@ -226,14 +258,22 @@ extern "C" int hsd_model_load_layer(hsd_model* m, int layer, const hsd_layer_wei
     HSD_HIP(hipMemcpyAsync(L.norm1, w->norm1_dev, (size_t)d.d * 4, hipMemcpyDeviceToDevice, s));
     HSD_HIP(hipMemcpyAsync(L.norm2, w->norm2_dev, (size_t)d.d * 4, hipMemcpyDeviceToDevice, s));
     int rc;
-    const int qkv_mode = d.dtype == HSD_BF16 ? 3 : 0;     // bf16: RoPE partners in adjacent tiles for the fused epilogue
-    if ((rc = launch_pack(w->wq_dev, L.wqkv, nq, d.d, d.dtype, 0, qkv_mode, d.hd, s))) return rc;
-    if ((rc = launch_pack(w->wk_dev, L.wqkv, nkv, d.d, d.dtype, nq, qkv_mode, d.hd, s))) return rc;
-    if ((rc = launch_pack(w->wv_dev, L.wqkv, nkv, d.d, d.dtype, nq + nkv, qkv_mode, d.hd, s))) return rc;
-    if ((rc = launch_pack(w->wo_dev, L.wo, d.d, nq, d.dtype, 0, 0, 0, s))) return rc;
-    if ((rc = launch_pack(w->wg_dev, L.wgu, d.ffn, d.d, d.dtype, 0, 1, 0, s))) return rc;
-    if ((rc = launch_pack(w->wu_dev, L.wgu, d.ffn, d.d, d.dtype, 0, 2, 0, s))) return rc;
-    if ((rc = launch_pack(w->wd_dev, L.wd, d.d, d.ffn, d.dtype, 0, 0, 0, s))) return rc;
+    // bf16: MFMA tiles; q/k/v with each 16-dim block next to the block of its RoPE partners, gate/up interleaved
+    const int qkv_mode = d.dtype == HSD_BF16 ? 3 : 0;
+    if ((rc = launch_pack(w->wq_dev, L.wqkv, nq, d.d, d.dtype, 0, qkv_mode, d.hd, 0, s))) return rc;
+    if ((rc = launch_pack(w->wk_dev, L.wqkv, nkv, d.d, d.dtype, nq, qkv_mode, d.hd, 0, s))) return rc;
+    if ((rc = launch_pack(w->wv_dev, L.wqkv, nkv, d.d, d.dtype, nq + nkv, qkv_mode, d.hd, 0, s))) return rc;
+    if ((rc = launch_pack(w->wo_dev, L.wo, d.d, nq, d.dtype, 0, 0, 0, 0, s))) return rc;
+    if ((rc = launch_pack(w->wg_dev, L.wgu, d.ffn, d.d, d.dtype, 0, 1, 0, 0, s))) return rc;
+    if ((rc = launch_pack(w->wu_dev, L.wgu, d.ffn, d.d, d.dtype, 0, 2, 0, 0, s))) return rc;
+    if ((rc = launch_pack(w->wd_dev, L.wd, d.d, d.ffn, d.dtype, 0, 0, 0, 0, s))) return rc;
+    if (L.wqkv_rows) {   // row-major copies, q/k/v with every dim directly followed by its RoPE partner
+        if ((rc = launch_pack(w->wq_dev, L.wqkv_rows, nq, d.d, d.dtype, 0, 4, d.hd, 1, s))) return rc;
+        if ((rc = launch_pack(w->wk_dev, L.wqkv_rows, nkv, d.d, d.dtype, nq, 4, d.hd, 1, s))) return rc;
+        if ((rc = launch_pack(w->wv_dev, L.wqkv_rows, nkv, d.d, d.dtype, nq + nkv, 4, d.hd, 1, s))) return rc;
+        if ((rc = launch_pack(w->wo_dev, L.wo_rows, d.d, nq, d.dtype, 0, 0, 0, 1, s))) return rc;
+        if ((rc = launch_pack(w->wd_dev, L.wd_rows, d.d, d.ffn, d.dtype, 0, 0, 0, 1, s))) return rc;
+    }
     HSD_HIP(hipStreamSynchronize(s));
     m->layer_loaded[layer] = true;
     return HSD_OK;
@@ -245,7 +285,7 @@ extern "C" int hsd_model_load_head(hsd_model* m, const void* embed_dev, const vo
     hipStream_t s = m->stream;
     HSD_HIP(hipMemcpyAsync(m->embed, embed_dev, (size_t)d.vocab * d.d * dtype_size(d.dtype), hipMemcpyDeviceToDevice, s));
     HSD_HIP(hipMemcpyAsync(m->norm_f, norm_f_dev, (size_t)d.d * 4, hipMemcpyDeviceToDevice, s));
-    if (int rc = launch_pack(head_dev, m->head, d.vocab, d.d, d.dtype, 0, 0, 0, s)) return rc;
+    if (int rc = launch_pack(head_dev, m->head, d.vocab, d.d, d.dtype, 0, 0, 0, 0, s)) return rc;
     HSD_HIP(hipStreamSynchronize(s));
     m->head_loaded = true;
     return HSD_OK;
@@ -257,7 +297,7 @@ static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, int ex
     hipStream_t s = m->stream;
     const int nq = d.n_q * d.hd, nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
     int rc;
-    if ((rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, nullptr, nullptr, s))) return rc;
+    if ((rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, nullptr, nullptr, nullptr, nullptr, s))) return rc;
     const float* pending = nullptr;     // output of the previous down projection, not yet added to x
     for (int l = 0; l < exit_layer; ++l) {
         const LayerWeights& L = m->layers[l];
@@ -295,27 +335,31 @@ static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, int ex
     return launch_gemm_f32((const float*)m->xn, (const float*)m->head, logits, n_logit_rows, d.vocab, d.d, false, s);
 }
 
-// bf16 storage: five launches per layer.  Both RMSNorms are folded into the A-operand load of the GEMM
-// that follows them (the row sums of squares travel in m->ss[0] for the layer's first norm and the
-// final norm, m->ss[1] for the second), RoPE and the KV append into the QKV epilogue, the residual adds
-// into the O and down projections, SwiGLU into the gate/up projection.
+// bf16 storage: five launches per layer.  RoPE and the KV append live in the QKV epilogue, SwiGLU in the
+// gate/up epilogue, the residual adds in the O and down projections.  Those two also prepare the next
+// RMSNorm: they store bf16(x * w_norm) into m->xn and add the rows' sums of squares into m->ss[1]
+// (second norm of the layer) or m->ss[0] (first norm of the next layer, or the final norm at the exit);
+// the GEMM that consumes m->xn multiplies by 1/rms in its epilogue.
 static int pass_bf16(hsd_model* m, const int32_t* tok, int pos0, int rows, int exit_layer, int n_logit_rows, float* logits) {
     const hsd_model_desc& d = m->desc;
     hipStream_t s = m->stream;
     const int nq = d.n_q * d.hd, nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
     int rc;
-    if ((rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, m->ss[0], m->ss[1], s))) return rc;
+    if ((rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, m->ss[0], m->ss[1], m->layers[0].norm1, m->xn, s))) return rc;
+    GemmArgs base = {};
+    base.M = rows; base.part = m->part; base.tickets = m->tickets; base.eps = d.eps;
     for (int l = 0; l < exit_layer; ++l) {
         const LayerWeights& L = m->layers[l];
         bf16_t* kv_layer = (bf16_t*)(m->kv + m->kv_layer_bytes * l);
+        const bool rowk = L.wqkv_rows && rows <= g_gemv_max_m;     // one or two tokens: stream the row-major copies
         {
-            GemmArgs g = {};
-            g.a = m->x; g.norm_w = L.norm1; g.ss_in = m->ss[0]; g.ss_zero = m->ss[1]; g.eps = d.eps;
-            g.wp = (const bf16x8*)L.wqkv; g.M = rows; g.N = nqkv; g.K = d.d;
+            GemmArgs g = base;
+            g.a = (const bf16_t*)m->xn; g.ss_in = m->ss[0]; g.ss_zero = m->ss[1];
+            g.wp = (const bf16x8*)(rowk ? L.wqkv_rows : L.wqkv); g.N = nqkv; g.K = d.d;
             g.out_bf16 = (bf16_t*)m->q; g.kv_layer = kv_layer; g.pages = m->pages_dev;
             g.pos0 = pos0; g.n_q = d.n_q; g.n_kv = d.n_kv; g.hd = d.hd; g.rope_base = d.rope_base;
             SiteTimer t(m, HSD_SITE_QKV);
-            if ((rc = launch_gemm_bf16(g, A_NORM, EPI_ROPE, gemm_plan(rows, nqkv, d.d, EPI_ROPE), s))) return rc;
+            if ((rc = rowk ? launch_gemv_bf16(g, EPI_ROPE, s) : launch_gemm_bf16(g, EPI_ROPE, gemm_plan(rows, nqkv, d.d, EPI_ROPE), s))) return rc;
         }
         {
             SiteTimer t(m, HSD_SITE_ATTN);
@@ -323,36 +367,39 @@ static int pass_bf16(hsd_model* m, const int32_t* tok, int pos0, int rows, int e
                                        d.hd, d.dtype, m->att, m->attn_ws, 0, s))) return rc;
         }
         {
-            GemmArgs g = {};
-            g.a = m->att; g.wp = (const bf16x8*)L.wo; g.M = rows; g.N = d.d; g.K = nq;
-            g.out_f32 = m->x; g.ss_out = m->ss[1];
+            GemmArgs g = base;
+            g.a = (const bf16_t*)m->att; g.wp = (const bf16x8*)(rowk ? L.wo_rows : L.wo); g.N = d.d; g.K = nq;
+            g.out_f32 = m->x; g.ss_out = m->ss[1]; g.norm_w = L.norm2; g.out_bf16 = (bf16_t*)m->xn;
             SiteTimer t(m, HSD_SITE_O);
-            if ((rc = launch_gemm_bf16(g, A_BF16, EPI_RESID, gemm_plan(rows, d.d, nq, EPI_RESID), s))) return rc;
+            if ((rc = rowk ? launch_gemv_bf16(g, EPI_RESID, s) : launch_gemm_bf16(g, EPI_RESID, gemm_plan(rows, d.d, nq, EPI_RESID), s))) return rc;
         }
         {
-            GemmArgs g = {};
-            g.a = m->x; g.norm_w = L.norm2; g.ss_in = m->ss[1]; g.ss_zero = m->ss[0]; g.eps = d.eps;
-            g.wp = (const bf16x8*)L.wgu; g.M = rows; g.N = 2 * d.ffn; g.K = d.d;
+            GemmArgs g = base;
+            g.a = (const bf16_t*)m->xn; g.ss_in = m->ss[1]; g.ss_zero = m->ss[0];
+            g.wp = (const bf16x8*)L.wgu; g.N = 2 * d.ffn; g.K = d.d;
             g.out_bf16 = (bf16_t*)m->h;
             SiteTimer t(m, HSD_SITE_GATEUP);
-            if ((rc = launch_gemm_bf16(g, A_NORM, EPI_SWIGLU, gemm_plan(rows, 2 * d.ffn, d.d, EPI_SWIGLU), s))) return rc;
+            if ((rc = launch_gemm_bf16(g, EPI_SWIGLU, gemm_plan(rows, 2 * d.ffn, d.d, EPI_SWIGLU), s))) return rc;
         }
         {
-            GemmArgs g = {};
-            g.a = m->h; g.wp = (const bf16x8*)L.wd; g.M = rows; g.N = d.d; g.K = d.ffn;
+            GemmArgs g = base;
+            g.a = (const bf16_t*)m->h; g.wp = (const bf16x8*)(rowk ? L.wd_rows : L.wd); g.N = d.d; g.K = d.ffn;
             g.out_f32 = m->x; g.ss_out = m->ss[0];
+            g.norm_w = l + 1 == exit_layer ? m->norm_f : m->layers[l + 1].norm1;
+            g.out_bf16 = (bf16_t*)m->xn;
             SiteTimer t(m, HSD_SITE_DOWN);
-            if ((rc = launch_gemm_bf16(g, A_BF16, EPI_RESID, gemm_plan(rows, d.d, d.ffn, EPI_RESID), s))) return rc;
+            if ((rc = rowk ? launch_gemv_bf16(g, EPI_RESID, s) : launch_gemm_bf16(g, EPI_RESID, gemm_plan(rows, d.d, d.ffn, EPI_RESID), s))) return rc;
         }
     }
     if (n_logit_rows == 0) return HSD_OK;
     const int row0 = rows - n_logit_rows;
-    GemmArgs g = {};
-    g.a = m->x + (size_t)row0 * d.d; g.norm_w = m->norm_f; g.ss_in = m->ss[0] + row0; g.ss_zero = nullptr; g.eps = d.eps;
-    g.wp = (const bf16x8*)m->head; g.M = n_logit_rows; g.N = d.vocab; g.K = d.d;
+    GemmArgs g = base;
+    g.M = n_logit_rows;
+    g.a = (const bf16_t*)m->xn + (size_t)row0 * d.d; g.ss_in = m->ss[0] + row0;
+    g.wp = (const bf16x8*)m->head; g.N = d.vocab; g.K = d.d;
     g.out_f32 = logits;
     SiteTimer t(m, HSD_SITE_HEAD);
-    return launch_gemm_bf16(g, A_NORM, EPI_STORE, gemm_plan(n_logit_rows, d.vocab, d.d, EPI_STORE), s);
+    return launch_gemm_bf16(g, EPI_STORE, gemm_plan(n_logit_rows, d.vocab, d.d, EPI_STORE), s);
 }
 
 // One pass: rows tokens at positions pos0.., layers [0, exit_layer), logits of the last n_logit_rows rows.

@@ -17,13 +17,14 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 
 F32, BF16 = 0, 1
+LAYOUT_TILES, LAYOUT_ROWS = 0, 1
 MAX_LEVELS, MAX_PASS_ROWS, KV_PAGE = 8, 64, 64
 
 
 class ModelDesc(C.Structure):
     _fields_ = [("n_layers", C.c_int), ("d", C.c_int), ("n_q", C.c_int), ("n_kv", C.c_int), ("hd", C.c_int),
                 ("ffn", C.c_int), ("vocab", C.c_int), ("dtype", C.c_int), ("rope_base", C.c_float), ("eps", C.c_float),
-                ("max_seq", C.c_int), ("max_rows", C.c_int)]
+                ("max_seq", C.c_int), ("max_rows", C.c_int), ("rows_copy_layers", C.c_int)]
 
 
 class LayerWeights(C.Structure):
@@ -67,8 +68,10 @@ _SIGS = {
     "hsd_sampler_scratch_bytes": (_sz, [_i]),
     "hsd_accept_resample": (_i, [_vp, _vp, _vp, _i, _i, C.c_uint64, C.c_uint32, C.c_uint32, _vp, _vp, _vp]),
     "hsd_packed_bytes": (_sz, [_i, _i, _i]),
-    "hsd_pack_weight": (_i, [_vp, _vp, _i, _i, _i, _vp]),
-    "hsd_gemm": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp]),
+    "hsd_gemm_workspace_bytes": (_sz, [_i, _i, _i]),
+    "hsd_pack_weight": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
+    "hsd_gemm": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp]),
+    "hsd_tune": (_i, [_i, _i, _i, _i]),
     "hsd_hier_workspace_bytes": (_sz, [_i, C.POINTER(Level), _ip]),
     "hsd_hier_create": (_i, [_i, C.POINTER(Level), _ip, _f, C.c_uint64, _vp, _sz, _vp, C.POINTER(_vp)]),
     "hsd_hier_destroy": (None, [_vp]),
@@ -132,9 +135,9 @@ def _rows_view(ptr, rows, vocab, keepalive):
 
 # ---- model -----------------------------------------------------------------------------------
 class Model:
-    def __init__(self, shape, dtype, max_seq, max_rows, rope_base=10000.0, eps=1e-5):
+    def __init__(self, shape, dtype, max_seq, max_rows, rope_base=10000.0, eps=1e-5, rows_copy_layers=0):
         self.desc = ModelDesc(shape["n_layers"], shape["d"], shape["n_q"], shape["n_kv"], shape["hd"], shape["ffn"],
-                              shape["vocab"], dtype, rope_base, eps, max_seq, max_rows)
+                              shape["vocab"], dtype, rope_base, eps, max_seq, max_rows, rows_copy_layers)
         self.dtype = dtype
         self.tdtype = torch.bfloat16 if dtype == BF16 else torch.float32
         self.stream = _stream()
@@ -220,18 +223,21 @@ def accept_resample(p, q, x, seed, level, call):
     return n, m
 
 
-def pack_weight(w, dtype):
+def pack_weight(w, dtype, layout=LAYOUT_TILES):
     """w: cuda tensor [n, k] of the dtype's element type; returns the packed buffer."""
     n, k = w.shape
     out = _buf(lib.hsd_packed_bytes(n, k, dtype))
-    _check(lib.hsd_pack_weight(w.contiguous().data_ptr(), out.data_ptr(), n, k, dtype, _stream()))
+    _check(lib.hsd_pack_weight(w.contiguous().data_ptr(), out.data_ptr(), n, k, dtype, layout, _stream()))
     return out
 
 
-def gemm(x, packed, n, dtype):
+def gemm(x, packed, n, dtype, ws=None, layout=LAYOUT_TILES):
     m, k = x.shape
     y = torch.empty((m, n), dtype=torch.float32, device="cuda")
-    _check(lib.hsd_gemm(x.contiguous().data_ptr(), packed.data_ptr(), y.data_ptr(), m, n, k, dtype, _stream()))
+    if ws is None:
+        ws = _buf(lib.hsd_gemm_workspace_bytes(m, n, k))
+    _check(lib.hsd_gemm(x.contiguous().data_ptr(), packed.data_ptr(), y.data_ptr(), m, n, k, dtype, layout, ws.data_ptr(),
+                        _stream()))
     return y
 
 

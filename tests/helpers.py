@@ -14,9 +14,9 @@ def oracle_decoder(shape, weights, max_len):
     return decoder.Decoder(oracle_spec(shape), weights, max_len)
 
 
-def gpu_model(shape, weights, bf16, max_seq, max_rows):
+def gpu_model(shape, weights, bf16, max_seq, max_rows, rows_copy_layers=0):
     from paper_2510_19705_amd import hsd
-    m = hsd.Model(shape, hsd.BF16 if bf16 else hsd.F32, max_seq, max_rows, inputs.ROPE_BASE, inputs.EPS)
+    m = hsd.Model(shape, hsd.BF16 if bf16 else hsd.F32, max_seq, max_rows, inputs.ROPE_BASE, inputs.EPS, rows_copy_layers)
     m.load(weights)
     return m
 

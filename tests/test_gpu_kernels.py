@@ -108,10 +108,10 @@ def test_accept_resample_rejects_bad_arguments(hsd):
 # ---- small-M GEMM ----------------------------------------------------------------------------
 @pytest.mark.parametrize("m,n,k", [(1, 48, 64), (5, 5000, 256), (16, 3072, 2048), (17, 2048, 8192), (33, 1000, 512),
                                    (64, 4096, 1024), (6, 32000, 2048)])
-@pytest.mark.parametrize("bf16", [True, False])
-def test_gemm(hsd, m, n, k, bf16):
+@pytest.mark.parametrize("bf16,layout", [(True, 0), (True, 1), (False, 0)], ids=["bf16_tiles", "bf16_rows", "f32"])
+def test_gemm(hsd, m, n, k, bf16, layout):
     import torch
-    say("gemm", m, n, k, "bf16" if bf16 else "f32")
+    say("gemm", m, n, k, "bf16" if bf16 else "f32", "layout", layout)
     rng = np.random.default_rng(m * 1000 + n + k)
     x = rng.standard_normal((m, k)).astype(np.float32)
     w = (rng.standard_normal((n, k)) / np.sqrt(k)).astype(np.float32)
@@ -120,8 +120,25 @@ def test_gemm(hsd, m, n, k, bf16):
     ref = x.astype(np.float64) @ w.astype(np.float64).T
     dt = hsd.BF16 if bf16 else hsd.F32
     td = torch.bfloat16 if bf16 else torch.float32
-    packed = hsd.pack_weight(_cuda(w, td), dt)
-    got = hsd.gemm(_cuda(x, td), packed, n, dt).cpu().numpy()
+    packed = hsd.pack_weight(_cuda(w, td), dt, layout)
+    got = hsd.gemm(_cuda(x, td), packed, n, dt, None, layout).cpu().numpy()
     # exact products, fp32 accumulation over k terms in a few partial sums
     tol = 4e-6 * np.sqrt(k) * np.abs(ref).max() + 1e-6
     assert np.abs(got - ref).max() < tol, (np.abs(got - ref).max(), tol)
+
+
+def test_gemm_split_k_exchange_repeated(hsd):
+    """The split-K partial tiles travel through one reused workspace: 60 launches with fresh
+    activations each must all match (a stale or early read of a partial would show up here)."""
+    import torch
+    m, n, k = 6, 2048, 2048                     # 128 column groups x 8 K slices
+    rng = np.random.default_rng(5)
+    w = inputs.bf16_round((rng.standard_normal((n, k)) / np.sqrt(k)).astype(np.float32))
+    packed = hsd.pack_weight(_cuda(w, torch.bfloat16), hsd.BF16)
+    ws = torch.zeros(hsd.lib.hsd_gemm_workspace_bytes(m, n, k), dtype=torch.uint8, device="cuda")
+    w64 = w.astype(np.float64).T
+    xs = [inputs.bf16_round(rng.standard_normal((m, k)).astype(np.float32) * (1 + i % 5)) for i in range(60)]
+    outs = [hsd.gemm(_cuda(x, torch.bfloat16), packed, n, hsd.BF16, ws) for x in xs]      # queued back to back
+    for i, (x, y) in enumerate(zip(xs, outs)):
+        ref = x.astype(np.float64) @ w64
+        assert np.abs(y.cpu().numpy() - ref).max() < 4e-6 * np.sqrt(k) * np.abs(ref).max() + 1e-6, i

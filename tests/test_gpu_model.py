@@ -48,18 +48,21 @@ def test_pass_fp32_logits_rel_1e4():
     model.close()
 
 
-@pytest.mark.parametrize("shape", [SMALL_BF16, SMALL_BF16_MHA], ids=["gqa_hd64", "mha_hd128"])
-def test_pass_bf16_logits_abs_2e2(shape):
-    """bf16 storage (MFMA GEMMs, MFMA attention over the tiled cache): logits within 2e-2 absolute."""
+@pytest.mark.parametrize("shape,rows_copy", [(SMALL_BF16, 2), (SMALL_BF16, 0), (SMALL_BF16_MHA, 2)],
+                         ids=["gqa_hd64_rowcopies", "gqa_hd64", "mha_hd128_rowcopies"])
+def test_pass_bf16_logits_abs_2e2(shape, rows_copy):
+    """bf16 storage (MFMA GEMMs, MFMA attention over the tiled cache; with row copies the one-token passes
+    go through the row kernel in the first layers): logits within 2e-2 absolute."""
     w = inputs.make_weights(shape, seed=21, bf16=True)
     toks = inputs.make_prompt(shape["vocab"], 330, seed=22)
-    model = gpu_model(shape, w, True, max_seq=384, max_rows=64)
+    model = gpu_model(shape, w, True, max_seq=384, max_rows=64, rows_copy_layers=rows_copy)
     model.set_pages([5, 1, 4, 0, 3, 2])
     oracle = oracle_decoder(shape, w, 384)
     L = shape["n_layers"]
     exits = (1, L // 2, L)
     schedule = [(0, 64, 2, 0), (64, 64, 2, 2), (128, 33, 2, 33), (161, 1, 0, 1), (161, 1, 2, 1), (162, 6, 1, 6),
-                (162, 9, 2, 9), (171, 64, 2, 0), (235, 64, 2, 5), (299, 17, 2, 17), (316, 4, 2, 4)]
+                (162, 9, 2, 9), (171, 64, 2, 0), (235, 64, 2, 5), (299, 17, 2, 17), (316, 2, 0, 2), (316, 2, 2, 2),
+                (318, 1, 1, 1), (318, 4, 2, 4)]
     worst = 0.0
     for tag, got, ref in _run_passes(model, oracle, toks, schedule, exits):
         if got.shape[0] == 0:
