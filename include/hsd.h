@@ -90,12 +90,14 @@ int hsd_model_pass(hsd_model*, const int32_t* tokens_dev, int pos0, int m, int e
  * launch at the sites below is bracketed by two events on the model's stream (up to max_launches
  * launches, later ones are not timed; the brackets add a little host and device overhead, so throughput
  * is measured without them).  end synchronises the stream and returns launches and total
- * milliseconds per site. */
+ * milliseconds per site (raw: subtract launches * empty_bracket_ms for the kernels alone). */
 enum { HSD_SITE_QKV = 0, HSD_SITE_ATTN = 1, HSD_SITE_O = 2, HSD_SITE_GATEUP = 3, HSD_SITE_DOWN = 4, HSD_SITE_HEAD = 5,
        HSD_N_SITES = 6 };
 typedef struct {
     int64_t launches[HSD_N_SITES];
     double ms[HSD_N_SITES];
+    double empty_bracket_ms; /* mean time between the two events of a bracket with nothing inside, measured by
+                                hsd_profile_end on the same stream: what a bracket adds to the launch it times */
 } hsd_site_times;
 int hsd_profile_begin(hsd_model*, int max_launches);
 int hsd_profile_end(hsd_model*, hsd_site_times* out);
@@ -126,6 +128,23 @@ size_t hsd_sampler_scratch_bytes(int vocab);
 int hsd_accept_resample(const float* p_dev, const float* q_dev, int32_t* x_dev, int t, int vocab,
                         uint64_t seed, uint32_t level, uint32_t call, int32_t* result_dev,
                         void* scratch_dev, void* stream);
+
+/* k-query attention over a paged KV cache, for a batch of sequences (the pass uses it with batch 1).
+ * One layer's cache: hsd_kv_layer_bytes(n_pages, ...) bytes; pages_dev [batch, max_pages] int32 gives the physical
+ * page (HSD_KV_PAGE positions) of each logical page of each sequence.  hsd_kv_write stores logical K/V
+ * [batch, n, n_kv, hd] (dtype) at positions pos0_dev[b] .. pos0_dev[b] + n - 1 in the cache's internal layout.
+ * hsd_attention: q_dev [batch, m, n_q, hd] are the queries of the m newest tokens of every sequence, whose K/V
+ * must already be in the cache at positions pos0_dev[b] .. pos0_dev[b] + m - 1; query i attends to positions
+ * 0 .. pos0_dev[b] + i (causal among the new tokens), scores scaled by 1/sqrt(hd).  att_dev [batch, m, n_q, hd]
+ * (dtype).  max_len >= every pos0_dev[b] + m bounds the launch.  workspace_dev:
+ * hsd_attention_workspace_bytes(batch, m, n_q, n_kv, hd, max_len). */
+size_t hsd_kv_layer_bytes(int n_pages, int n_kv, int hd, int dtype);
+size_t hsd_attention_workspace_bytes(int batch, int m, int n_q, int n_kv, int hd, int max_len);
+int hsd_kv_write(void* kv_layer_dev, const int32_t* pages_dev, int max_pages, const int32_t* pos0_dev, int batch, int n,
+                 int n_kv, int hd, int dtype, const void* k_dev, const void* v_dev, void* stream);
+int hsd_attention(const void* q_dev, const void* kv_layer_dev, const int32_t* pages_dev, int max_pages,
+                  const int32_t* pos0_dev, int batch, int m, int max_len, int n_q, int n_kv, int hd, int dtype,
+                  void* att_dev, void* workspace_dev, void* stream);
 
 /* Small-M weight-streaming GEMM y = x W^T, y_dev [m, n] fp32 = x_dev [m, k] (dtype) times W [n, k].
  * hsd_pack_weight copies W (row-major, dtype) into the streaming format (packed_dev:

@@ -19,30 +19,34 @@
 // online-softmax states through LDS.  With nsplit == 1 the normalised output is written directly;
 // otherwise one partial per workgroup goes to the merge kernel.
 // ------------------------------------------------------------------------------------------------
-template <int HD>
+// One step = SP blocks of 32 positions (SP = 2, a whole page, for hd 64; SP = 1 for hd 128, where the tiles of a
+// page would not fit the registers twice).
+template <int HD, int SP>
 struct KvTiles {
-    bf16x8 k[2][HD / 32];
-    bf16x8 v[HD / 16];
+    bf16x8 k[2 * SP][HD / 32];     // 16-position tiles x 32-dim chunks
+    bf16x8 v[SP][HD / 16];         // 32-position blocks x 16-dim tiles
 };
 
-template <int HD>
-__device__ __forceinline__ void load_kv(KvTiles<HD>& t, const bf16_t* __restrict__ kv_layer, const int32_t* __restrict__ pages,
+template <int HD, int SP>
+__device__ __forceinline__ void load_kv(KvTiles<HD, SP>& t, const bf16_t* __restrict__ kv_layer, const int32_t* __restrict__ pages,
                                         size_t page_base, int step, int n_kv, int g, int lane) {
     constexpr int KC = HD / 32, DT = HD / 16;
-    const int p0 = step << 5;
+    const int p0 = step * 32 * SP;
     const int page = pages[page_base + p0 / HSD_KV_PAGE];
     const int inpage = p0 % HSD_KV_PAGE;
     const size_t blk = kv_block_elems(HD);
     const bf16_t* kblk = kv_layer + ((size_t)page * n_kv + g) * 2 * blk;
     const bf16_t* vblk = kblk + blk;
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int h = 0; h < 2 * SP; ++h)
 #pragma unroll
         for (int c = 0; c < KC; ++c)
             t.k[h][c] = *reinterpret_cast<const bf16x8*>(kblk + (size_t)(((inpage >> 4) + h) * KC + c) * 512 + lane * 8);
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-        t.v[dt] = *reinterpret_cast<const bf16x8*>(vblk + (size_t)((inpage >> 5) * DT + dt) * 512 + lane * 8);
+    for (int sb = 0; sb < SP; ++sb)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+            t.v[sb][dt] = *reinterpret_cast<const bf16x8*>(vblk + (size_t)(((inpage >> 5) + sb) * DT + dt) * 512 + lane * 8);
 }
 
 template <int HD, int QT>
@@ -53,9 +57,11 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const bf16_t* __restrict
                                                         float* __restrict__ part_o, float* __restrict__ part_ml, int rpad,
                                                         bf16_t* __restrict__ att) {
     extern __shared__ float lds[];                 // [NW][QT*16][HD + 2]: o, then running max and sum
+    constexpr int SP = HD == 64 ? 2 : 1;
     constexpr int KC = HD / 32;   // K chunks of 32 dims per 16-position tile
     constexpr int DT = HD / 16;   // 16-dim tiles of the output
     constexpr int RS = HD + 2;
+    constexpr int NV = 8 * SP;    // scores per lane and query tile in one step
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
     const int j = lane & 15, grp = lane >> 4;
     const int split = blockIdx.x, nsplit = gridDim.x, g = blockIdx.y;
@@ -64,13 +70,22 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const bf16_t* __restrict
     const int R = M * group;
     const int pos0 = pos0_arr ? pos0_arr[b] : pos0_all;
     const int S = pos0 + M;
-    const int total_steps = (S + 31) >> 5;
+    const int total_steps = (S + 32 * SP - 1) / (32 * SP);
     const int step0 = split * steps_per_split;
     const int step1 = min(total_steps, step0 + steps_per_split);
 
+    // K/V of this wave's first two steps are requested before anything else
+    const size_t page_base = (size_t)b * max_pages;
+    KvTiles<HD, SP> buf[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int st = step0 + wave + i * NW;
+        if (st < step1) load_kv<HD, SP>(buf[i], kv_layer, pages, page_base, st, n_kv, g, lane);
+    }
+
     bf16x8 qreg[QT][KC];
     int limit[QT];
-    float m_run[QT], l_run[QT];
+    float m_run[QT], l_run[QT];    // l_run: this lane's share of the row sum (its own positions), reduced at the end
     f32x4 o[QT][DT];
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
@@ -88,56 +103,73 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const bf16_t* __restrict
         for (int dt = 0; dt < DT; ++dt) o[qt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    const size_t page_base = (size_t)b * max_pages;
-    KvTiles<HD> cur, nxt;
-    int step = step0 + wave;
-    if (step < step1) load_kv<HD>(cur, kv_layer, pages, page_base, step, n_kv, g, lane);
-    for (; step < step1; step += NW) {
-        const bool more = step + NW < step1;
-        if (more) load_kv<HD>(nxt, kv_layer, pages, page_base, step + NW, n_kv, g, lane);   // in flight during the math
-        const int p0 = step << 5;
+    for (int base = step0 + wave; base < step1; base += 2 * NW) {
 #pragma unroll
-        for (int qt = 0; qt < QT; ++qt) {
-            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < 2; ++i) {
+            const int step = base + i * NW;
+            if (step < step1) {
+                const KvTiles<HD, SP>& cur = buf[i];
+                const int p0 = step * 32 * SP;
+                // scores of all query tiles first, then their maxima, then the exponentials: independent chains
+                // next to each other so that MFMA and cross-lane latencies overlap
+                float v[QT][NV], mx[QT];
 #pragma unroll
-            for (int c = 0; c < KC; ++c) {
-                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[0][c], qreg[qt][c], s0, 0, 0, 0);
-                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[1][c], qreg[qt][c], s1, 0, 0, 0);
-            }
-            // lane (j, grp): s0[r] is position p0 + 4 grp + r, s1[r] is p0 + 16 + 4 grp + r, query row j
-            float v[8];
-            float mx = -INFINITY;
+                for (int qt = 0; qt < QT; ++qt) {
+                    mx[qt] = -INFINITY;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int pa = p0 + 4 * grp + r;
-                v[r] = pa < limit[qt] ? s0[r] * scale_log2 : -INFINITY;
-                v[4 + r] = pa + 16 < limit[qt] ? s1[r] * scale_log2 : -INFINITY;
-                mx = fmaxf(mx, fmaxf(v[r], v[4 + r]));
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run[qt], mx);
-            const float m_use = m_new == -INFINITY ? 0.f : m_new;      // row fully masked so far: all p = 0
-            const float alpha = exp2f(m_run[qt] - m_use);
-            float sum = 0.f;
-            bf16x8 pb;
+                    for (int h = 0; h < 2 * SP; ++h) {
+                        f32x4 sc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float pe = exp2f(v[e] - m_use);
-                sum += pe;
-                pb[e] = (bf16_t)pe;
-            }
-            sum += __shfl_xor(sum, 16, 64);
-            sum += __shfl_xor(sum, 32, 64);
-            l_run[qt] = l_run[qt] * alpha + sum;
-            m_run[qt] = m_new;
+                        for (int c = 0; c < KC; ++c) sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[h][c], qreg[qt][c], sc, 0, 0, 0);
+                        // lane (j, grp): sc[r] is position p0 + 16 h + 4 grp + r of query row j
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                o[qt][dt] *= alpha;
-                o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.v[dt], pb, o[qt][dt], 0, 0, 0);
+                        for (int r = 0; r < 4; ++r) {
+                            const int pa = p0 + 16 * h + 4 * grp + r;
+                            const float val = pa < limit[qt] ? sc[r] * scale_log2 : -INFINITY;
+                            v[qt][4 * h + r] = val;
+                            mx[qt] = fmaxf(mx[qt], val);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt) mx[qt] = fmaxf(mx[qt], __shfl_xor(mx[qt], 16, 64));
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt) mx[qt] = fmaxf(mx[qt], __shfl_xor(mx[qt], 32, 64));
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt) {
+                    const float m_new = fmaxf(m_run[qt], mx[qt]);
+                    const float m_use = m_new == -INFINITY ? 0.f : m_new;      // row fully masked so far: all p = 0
+                    const float alpha = exp2f(m_run[qt] - m_use);
+                    m_run[qt] = m_new;
+                    float sum = 0.f;
+                    bf16x8 pb[SP];
+#pragma unroll
+                    for (int sb = 0; sb < SP; ++sb)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            // B-operand element e of block sb: position 32 sb + 16 (e / 4) + 4 grp + e % 4
+                            const float pe = exp2f(v[qt][8 * sb + e] - m_use);
+                            sum += pe;
+                            pb[sb][e] = (bf16_t)pe;
+                        }
+                    l_run[qt] = l_run[qt] * alpha + sum;
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt) {
+                        o[qt][dt] *= alpha;
+#pragma unroll
+                        for (int sb = 0; sb < SP; ++sb)
+                            o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.v[sb][dt], pb[sb], o[qt][dt], 0, 0, 0);
+                    }
+                }
+                const int nxt = step + 2 * NW;
+                if (nxt < step1) load_kv<HD, SP>(buf[i], kv_layer, pages, page_base, nxt, n_kv, g, lane);
             }
         }
-        if (more) cur = nxt;
+    }
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {          // row sums: the four lane groups hold disjoint positions
+        l_run[qt] += __shfl_xor(l_run[qt], 16, 64);
+        l_run[qt] += __shfl_xor(l_run[qt], 32, 64);
     }
 
     // this wave's state to LDS: o^T accumulators hold d = 16 dt + 4 grp + r for query row j
@@ -312,15 +344,16 @@ AttnPlan attn_plan(int batch, int m, int n_q, int n_kv, int hd, int max_len, boo
     p.qt = R <= 16 ? 1 : (R <= 32 ? 2 : 4);
     p.qgroups = ceil_div(R, 16 * p.qt);
     p.rpad = p.qgroups * p.qt * 16;
-    const int total_steps = ceil_div(max_len, 32);
+    int total_steps = ceil_div(max_len, 32);
     if (mfma) {
+        total_steps = ceil_div(max_len, hd == 64 ? 64 : 32);     // the MFMA kernel steps over a whole page for hd 64
         const int per_wave = p.qt * 16 * (hd + 2) * 4;               // LDS bytes of one wave's state
         p.nw = 65536 / per_wave;
         if (p.nw > 8) p.nw = 8;
         if (p.nw < 1) p.nw = 1;
         // one workgroup per (head, query group) while its waves get at most ~6 steps each; beyond that
         // split the sequence over workgroups (at most 64) and merge
-        int want = ceil_div(total_steps, p.nw * 6);
+        int want = ceil_div(total_steps, p.nw * (hd == 64 ? 3 : 6));
         const int cap = 2048 / (batch * n_kv * p.qgroups) > 0 ? 2048 / (batch * n_kv * p.qgroups) : 1;
         if (want > cap) want = cap;
         if (want > 64) want = 64;
@@ -387,4 +420,72 @@ int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, 
         attn_merge_kernel<float><<<mg, 64, 0, s>>>(part_o, part_ml, p.nsplit, p.rpad, m, n_q, n_kv, hd, (float*)att);
     HSD_LAUNCH_CHECK();
     return HSD_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// stand-alone entry points: cache fill from logical K/V, attention over a batch of sequences
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void kv_write_kernel(T* __restrict__ kv_layer, const int32_t* __restrict__ pages, int max_pages,
+                                const int32_t* __restrict__ pos0_arr, int n, int n_kv, int hd, const T* __restrict__ k,
+                                const T* __restrict__ v) {
+    const int b = blockIdx.z, i = blockIdx.x, kvh = blockIdx.y;
+    const int pos = pos0_arr[b] + i;
+    const int page = pages[(size_t)b * max_pages + pos / HSD_KV_PAGE], ip = pos % HSD_KV_PAGE;
+    T* kblk = kv_layer + ((size_t)page * n_kv + kvh) * 2 * kv_block_elems(hd);
+    T* vblk = kblk + kv_block_elems(hd);
+    const size_t src = (((size_t)b * n + i) * n_kv + kvh) * hd;
+    for (int d = threadIdx.x; d < hd; d += blockDim.x) {
+        if constexpr (sizeof(T) == 4) {
+            kblk[(size_t)ip * hd + d] = k[src + d];
+            vblk[(size_t)ip * hd + d] = v[src + d];
+        } else {
+            kblk[kv_k_index(ip, d, hd)] = k[src + d];
+            vblk[kv_v_index(ip, d, hd)] = v[src + d];
+        }
+    }
+}
+
+extern "C" size_t hsd_kv_layer_bytes(int n_pages, int n_kv, int hd, int dtype) {
+    if (n_pages < 1 || n_kv < 1 || hd < 32 || hd % 32 != 0) return 0;
+    return (size_t)n_pages * kv_page_elems(n_kv, hd) * dtype_size(dtype);
+}
+
+extern "C" size_t hsd_attention_workspace_bytes(int batch, int m, int n_q, int n_kv, int hd, int max_len) {
+    if (batch < 1 || m < 1 || n_q < 1 || n_kv < 1 || n_q % n_kv != 0 || max_len < 1) return 0;
+    return attn_workspace_bytes(batch, m, n_q, n_kv, hd, max_len);
+}
+
+static int check_attn_args(int batch, int m, int n_q, int n_kv, int hd, int dtype) {
+    if (batch < 1 || m < 1 || m > HSD_MAX_PASS_ROWS) HSD_FAIL(HSD_EINVAL, "attention: batch=%d m=%d (m within 1..%d)", batch, m, HSD_MAX_PASS_ROWS);
+    if (n_kv < 1 || n_q < 1 || n_q % n_kv != 0) HSD_FAIL(HSD_EINVAL, "attention: n_q=%d n_kv=%d", n_q, n_kv);
+    if (hd % 32 != 0 || hd < 32 || hd > 256) HSD_FAIL(HSD_EINVAL, "attention: head dim %d", hd);
+    if (dtype != HSD_F32 && dtype != HSD_BF16) HSD_FAIL(HSD_EINVAL, "attention: dtype %d", dtype);
+    return HSD_OK;
+}
+
+extern "C" int hsd_kv_write(void* kv_layer_dev, const int32_t* pages_dev, int max_pages, const int32_t* pos0_dev, int batch, int n,
+                            int n_kv, int hd, int dtype, const void* k_dev, const void* v_dev, void* stream) {
+    if (!kv_layer_dev || !pages_dev || !pos0_dev || !k_dev || !v_dev) HSD_FAIL(HSD_EINVAL, "hsd_kv_write: null pointer");
+    if (int rc = check_attn_args(batch, 1, n_kv, n_kv, hd, dtype)) return rc;
+    if (n < 1 || max_pages < 1) HSD_FAIL(HSD_EINVAL, "hsd_kv_write: n=%d max_pages=%d", n, max_pages);
+    dim3 grid(n, n_kv, batch);
+    if (dtype == HSD_BF16)
+        kv_write_kernel<bf16_t><<<grid, 64, 0, (hipStream_t)stream>>>((bf16_t*)kv_layer_dev, pages_dev, max_pages, pos0_dev, n, n_kv, hd,
+                                                                      (const bf16_t*)k_dev, (const bf16_t*)v_dev);
+    else
+        kv_write_kernel<float><<<grid, 64, 0, (hipStream_t)stream>>>((float*)kv_layer_dev, pages_dev, max_pages, pos0_dev, n, n_kv, hd,
+                                                                     (const float*)k_dev, (const float*)v_dev);
+    HSD_LAUNCH_CHECK();
+    return HSD_OK;
+}
+
+extern "C" int hsd_attention(const void* q_dev, const void* kv_layer_dev, const int32_t* pages_dev, int max_pages,
+                             const int32_t* pos0_dev, int batch, int m, int max_len, int n_q, int n_kv, int hd, int dtype,
+                             void* att_dev, void* workspace_dev, void* stream) {
+    if (!q_dev || !kv_layer_dev || !pages_dev || !pos0_dev || !att_dev || !workspace_dev) HSD_FAIL(HSD_EINVAL, "hsd_attention: null pointer");
+    if (int rc = check_attn_args(batch, m, n_q, n_kv, hd, dtype)) return rc;
+    if (max_len < m || max_len > max_pages * HSD_KV_PAGE) HSD_FAIL(HSD_EINVAL, "hsd_attention: max_len=%d outside %d..%d", max_len, m, max_pages * HSD_KV_PAGE);
+    return launch_attention(q_dev, kv_layer_dev, pages_dev, max_pages, pos0_dev, 0, batch, m, max_len, n_q, n_kv, hd, dtype, att_dev,
+                            (float*)workspace_dev, 0, (hipStream_t)stream);
 }

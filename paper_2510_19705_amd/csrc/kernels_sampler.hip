@@ -178,6 +178,130 @@ __global__ __launch_bounds__(THREADS) void accept_resample_kernel(const float* _
     }
 }
 
+// Same rule in ONE workgroup for vocabularies up to 32768: no exchange between workgroups, no fences.
+// The row is cut in 8 chunks of 4096 tokens; in chunk k thread i owns tokens 4096 k + 4 i .. + 3 (so a
+// wave reads 1 KiB contiguous).  Per chunk an exclusive scan of the threads' integer sums, chunk totals
+// chained in order: together the prefix sums in token order, which locate the one (chunk, thread) whose
+// four tokens hold the threshold.
+constexpr int SMALL_THREADS = 1024, SMALL_CHUNKS = 8, SMALL_MAX_V = SMALL_THREADS * 4 * SMALL_CHUNKS;
+
+__global__ __launch_bounds__(SMALL_THREADS) void accept_resample_small_kernel(const float* __restrict__ p, const float* __restrict__ q,
+                                                                              int32_t* __restrict__ x, int t, int V, uint32_t k0,
+                                                                              uint32_t k1, uint32_t level, uint32_t call,
+                                                                              int32_t* __restrict__ result) {
+    constexpr int NWAVE = SMALL_THREADS / 64;
+    __shared__ int sh_n;
+    __shared__ uint64_t sh_a[NWAVE], sh_b[NWAVE];
+    __shared__ uint64_t sh_tot[NWAVE][SMALL_CHUNKS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (wave == 0) {
+        bool reject = false;
+        if (lane < t) {
+            const int xi = min(max(x[lane], 0), V - 1);
+            const Philox4 rnd = philox4x32_10((uint32_t)lane, call, level, 0u, k0, k1);
+            const float u = (float)(rnd.w[0] >> 8) * 5.9604644775390625e-8f;
+            const float px = p[(size_t)lane * V + xi], qx = q[(size_t)lane * V + xi];
+            reject = !(__fmul_rn(u, qx) < px);
+        }
+        const unsigned long long mask = __ballot(reject);
+        if (lane == 0) sh_n = mask ? (int)__ffsll((long long)mask) - 1 : t;
+    }
+    __syncthreads();
+    const int n = sh_n;
+    const float* prow = p + (size_t)n * V;
+    const float* qrow = n < t ? q + (size_t)n * V : nullptr;
+    const bool vec = (V & 3) == 0 && ((uintptr_t)prow & 15) == 0 && (!qrow || ((uintptr_t)qrow & 15) == 0);
+    float pv[SMALL_CHUNKS][4], rv[SMALL_CHUNKS][4];
+    uint64_t a = 0, b = 0;
+#pragma unroll
+    for (int k = 0; k < SMALL_CHUNKS; ++k) {
+        const int i = (k * SMALL_THREADS + tid) * 4;
+        float4 pp = {0.f, 0.f, 0.f, 0.f}, qq = {0.f, 0.f, 0.f, 0.f};
+        if (vec) {
+            if (i < V) {
+                pp = *reinterpret_cast<const float4*>(prow + i);
+                if (qrow) qq = *reinterpret_cast<const float4*>(qrow + i);
+            }
+        } else {
+            if (i < V) { pp.x = prow[i]; if (qrow) qq.x = qrow[i]; }
+            if (i + 1 < V) { pp.y = prow[i + 1]; if (qrow) qq.y = qrow[i + 1]; }
+            if (i + 2 < V) { pp.z = prow[i + 2]; if (qrow) qq.z = qrow[i + 2]; }
+            if (i + 3 < V) { pp.w = prow[i + 3]; if (qrow) qq.w = qrow[i + 3]; }
+        }
+        pv[k][0] = pp.x; pv[k][1] = pp.y; pv[k][2] = pp.z; pv[k][3] = pp.w;
+        rv[k][0] = qrow ? fmaxf(0.f, __fsub_rn(pp.x, qq.x)) : 0.f;
+        rv[k][1] = qrow ? fmaxf(0.f, __fsub_rn(pp.y, qq.y)) : 0.f;
+        rv[k][2] = qrow ? fmaxf(0.f, __fsub_rn(pp.z, qq.z)) : 0.f;
+        rv[k][3] = qrow ? fmaxf(0.f, __fsub_rn(pp.w, qq.w)) : 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            b += fixed_weight(pv[k][e]);
+            a += fixed_weight(rv[k][e]);
+        }
+    }
+    uint64_t ta = a, tb = b;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        ta += __shfl_xor(ta, o, 64);
+        tb += __shfl_xor(tb, o, 64);
+    }
+    if (lane == 0) { sh_a[wave] = ta; sh_b[wave] = tb; }
+    __syncthreads();
+    ta = tb = 0;
+    for (int w = 0; w < NWAVE; ++w) { ta += sh_a[w]; tb += sh_b[w]; }
+    const bool use_resid = qrow != nullptr && ta != 0;     // residual identically zero: fall back to p
+    const uint64_t S = use_resid ? ta : tb;
+    const Philox4 rnd = philox4x32_10((uint32_t)t, call, level, 0u, k0, k1);
+    const uint64_t thr = __umul64hi(S, (uint64_t)rnd.w[1] << 32);
+    // per chunk: this thread's sum and its inclusive scan inside the wave
+    uint64_t mine[SMALL_CHUNKS], inc[SMALL_CHUNKS];
+#pragma unroll
+    for (int k = 0; k < SMALL_CHUNKS; ++k) {
+        uint64_t m4 = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) m4 += fixed_weight(use_resid ? rv[k][e] : pv[k][e]);
+        mine[k] = m4;
+        uint64_t v = m4;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint64_t up = __shfl_up(v, o, 64);
+            if (lane >= o) v += up;
+        }
+        inc[k] = v;
+        if (lane == 63) sh_tot[wave][k] = v;
+    }
+    __syncthreads();
+    uint64_t chunk_base = 0;                               // tokens before chunk k
+#pragma unroll
+    for (int k = 0; k < SMALL_CHUNKS; ++k) {
+        uint64_t before = chunk_base + inc[k] - mine[k];
+        uint64_t chunk_total = 0;
+        for (int w = 0; w < NWAVE; ++w) {
+            const uint64_t v = sh_tot[w][k];
+            if (w < wave) before += v;
+            chunk_total += v;
+        }
+        if (mine[k] != 0 && before <= thr && thr < before + mine[k]) {      // exactly one (chunk, thread)
+            uint64_t run = before;
+            int m = (k * SMALL_THREADS + tid) * 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                run += fixed_weight(use_resid ? rv[k][e] : pv[k][e]);
+                if (run > thr) { m += e; break; }
+            }
+            result[0] = n;
+            result[1] = m;
+            x[n] = m;
+        }
+        chunk_base += chunk_total;
+    }
+    if (S == 0 && tid == 0) {                              // unreachable for a distribution row
+        result[0] = n;
+        result[1] = V - 1;
+        x[n] = V - 1;
+    }
+}
+
 }  // namespace
 
 extern "C" size_t hsd_sampler_scratch_bytes(int vocab) {
@@ -187,6 +311,12 @@ extern "C" size_t hsd_sampler_scratch_bytes(int vocab) {
 
 int launch_accept_resample(const float* p, const float* q, int32_t* x, int t, int vocab, uint64_t seed, uint32_t level,
                            uint32_t call, int32_t* result, void* scratch, hipStream_t s) {
+    if (vocab <= SMALL_MAX_V) {
+        accept_resample_small_kernel<<<1, SMALL_THREADS, 0, s>>>(p, q, x, t, vocab, (uint32_t)seed, (uint32_t)(seed >> 32), level,
+                                                              call, result);
+        HSD_LAUNCH_CHECK();
+        return HSD_OK;
+    }
     const int nslices = ceil_div(vocab, SLICE);
     accept_resample_kernel<<<nslices, THREADS, 0, s>>>(p, q, x, t, vocab, (uint32_t)seed, (uint32_t)(seed >> 32), level, call,
                                                        result, (uint32_t*)scratch, (uint64_t*)((char*)scratch + 16));

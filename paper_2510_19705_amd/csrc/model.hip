@@ -210,6 +210,20 @@ extern "C" int hsd_profile_end(hsd_model* m, hsd_site_times* out) {
         out->launches[m->prof_site[i]]++;
         out->ms[m->prof_site[i]] += ms;
     }
+    // what a bracket costs by itself: pairs of events with nothing between them
+    const int pairs = (int)(m->prof_events.size() / 2) < 64 ? (int)(m->prof_events.size() / 2) : 64;
+    for (int i = 0; i < pairs; ++i) {
+        HSD_HIP(hipEventRecord(m->prof_events[2 * i], m->stream));
+        HSD_HIP(hipEventRecord(m->prof_events[2 * i + 1], m->stream));
+    }
+    HSD_HIP(hipStreamSynchronize(m->stream));
+    double sum = 0.0;
+    for (int i = 0; i < pairs; ++i) {
+        float ms = 0.f;
+        HSD_HIP(hipEventElapsedTime(&ms, m->prof_events[2 * i], m->prof_events[2 * i + 1]));
+        sum += ms;
+    }
+    out->empty_bracket_ms = pairs ? sum / pairs : 0.0;
     return HSD_OK;
 }
 

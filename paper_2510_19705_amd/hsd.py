@@ -41,7 +41,7 @@ SITE_NAMES = ("qkv", "attn", "o", "gateup", "down", "head")
 
 
 class SiteTimes(C.Structure):
-    _fields_ = [("launches", C.c_int64 * N_SITES), ("ms", C.c_double * N_SITES)]
+    _fields_ = [("launches", C.c_int64 * N_SITES), ("ms", C.c_double * N_SITES), ("empty_bracket_ms", C.c_double)]
 
 
 class Stats(C.Structure):
@@ -67,6 +67,10 @@ _SIGS = {
     "hsd_softmax": (_i, [_vp, _vp, _i, _i, _f, _vp]),
     "hsd_sampler_scratch_bytes": (_sz, [_i]),
     "hsd_accept_resample": (_i, [_vp, _vp, _vp, _i, _i, C.c_uint64, C.c_uint32, C.c_uint32, _vp, _vp, _vp]),
+    "hsd_kv_layer_bytes": (_sz, [_i, _i, _i, _i]),
+    "hsd_attention_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
+    "hsd_kv_write": (_i, [_vp, _vp, _i, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp]),
+    "hsd_attention": (_i, [_vp, _vp, _vp, _i, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp]),
     "hsd_packed_bytes": (_sz, [_i, _i, _i]),
     "hsd_gemm_workspace_bytes": (_sz, [_i, _i, _i]),
     "hsd_pack_weight": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
@@ -183,7 +187,9 @@ class Model:
     def profile_end(self):
         st = SiteTimes()
         _check(lib.hsd_profile_end(self.handle, C.byref(st)))
-        return {SITE_NAMES[i]: (st.launches[i], st.ms[i]) for i in range(N_SITES)}
+        out = {SITE_NAMES[i]: (st.launches[i], st.ms[i]) for i in range(N_SITES)}
+        out["empty_bracket_ms"] = st.empty_bracket_ms
+        return out
 
     def set_pages(self, table):
         a, p = _i32(table)
@@ -221,6 +227,35 @@ def accept_resample(p, q, x, seed, level, call):
                                    res.data_ptr(), _sampler_scratch[key].data_ptr(), _stream()))
     n, m = res.cpu().tolist()
     return n, m
+
+
+class KvLayer:
+    """One layer's paged KV cache for a batch of sequences (stand-alone attention tests and micro-benchmarks)."""
+
+    def __init__(self, batch, max_len, n_kv, hd, dtype, page_perm=None):
+        self.batch, self.n_kv, self.hd, self.dtype = batch, n_kv, hd, dtype
+        self.max_pages = (max_len + KV_PAGE - 1) // KV_PAGE
+        n_pages = batch * self.max_pages
+        self.buf = torch.zeros(lib.hsd_kv_layer_bytes(n_pages, n_kv, hd, dtype), dtype=torch.uint8, device="cuda")
+        table = np.arange(n_pages, dtype=np.int32) if page_perm is None else np.asarray(page_perm, dtype=np.int32)
+        self.pages = torch.from_numpy(table.reshape(batch, self.max_pages).copy()).cuda()
+
+    def write(self, pos0, k, v):
+        """k, v: cuda tensors [batch, n, n_kv, hd] of the cache's element type; pos0: int32 cuda tensor [batch]."""
+        _check(lib.hsd_kv_write(self.buf.data_ptr(), self.pages.data_ptr(), self.max_pages, pos0.data_ptr(), self.batch,
+                                k.shape[1], self.n_kv, self.hd, self.dtype, k.contiguous().data_ptr(),
+                                v.contiguous().data_ptr(), _stream()))
+
+    def attention(self, q, pos0, max_len, ws=None):
+        """q: [batch, m, n_q, hd]; returns att of the same shape and type."""
+        b, m, n_q, hd = q.shape
+        if ws is None:
+            ws = _buf(lib.hsd_attention_workspace_bytes(b, m, n_q, self.n_kv, hd, max_len))
+        out = torch.empty_like(q)
+        _check(lib.hsd_attention(q.contiguous().data_ptr(), self.buf.data_ptr(), self.pages.data_ptr(), self.max_pages,
+                                 pos0.data_ptr(), b, m, max_len, n_q, self.n_kv, hd, self.dtype, out.data_ptr(),
+                                 ws.data_ptr(), _stream()))
+        return out
 
 
 def pack_weight(w, dtype, layout=LAYOUT_TILES):

@@ -65,6 +65,17 @@ def test_accept_resample_bit_exact(hsd, V, t):
         assert (n_hist > 0).sum() >= 2                     # both rejections and acceptances were exercised
 
 
+@pytest.mark.parametrize("V", [32000, 32768, 32769, 40000])
+def test_accept_resample_kernel_boundary(hsd, V):
+    """Vocabularies around the switch between the one-workgroup and the multi-workgroup kernel."""
+    seed = 99
+    for call in range(10):
+        p, q, x = inputs.make_prob_rows(V, 5, seed=V + call, sigma=3.0, noise=0.6)
+        ref = specsample.verify(list(p), list(q), list(x), specsample.PhiloxChooser(seed), 2, call)
+        xd = _cuda(np.concatenate([x, [0]]).astype(np.int32))
+        assert hsd.accept_resample(_cuda(p), _cuda(q), xd, seed, 2, call) == ref, (V, call)
+
+
 def test_accept_resample_degenerate_rows(hsd):
     import torch
     V, seed = 3000, 77
@@ -142,3 +153,59 @@ def test_gemm_split_k_exchange_repeated(hsd):
     for i, (x, y) in enumerate(zip(xs, outs)):
         ref = x.astype(np.float64) @ w64
         assert np.abs(y.cpu().numpy() - ref).max() < 4e-6 * np.sqrt(k) * np.abs(ref).max() + 1e-6, i
+
+
+# ---- k-query attention over the paged cache ------------------------------------------------------
+def _attention_ref(q, k, v, pos0):
+    """Textbook attention in fp64: q [B, m, n_q, hd], k / v [B, S, n_kv, hd] (S >= pos0 + m), causal among the
+    m new tokens at positions pos0[b] + i."""
+    B, m, n_q, hd = q.shape
+    n_kv = k.shape[2]
+    out = np.zeros(q.shape)
+    for b in range(B):
+        for i in range(m):
+            L = int(pos0[b]) + i + 1
+            for h in range(n_q):
+                g = h // (n_q // n_kv)
+                sc = k[b, :L, g].astype(np.float64) @ q[b, i, h].astype(np.float64) / np.sqrt(hd)
+                w = np.exp(sc - sc.max())
+                out[b, i, h] = (w / w.sum()) @ v[b, :L, g].astype(np.float64)
+    return out
+
+
+@pytest.mark.parametrize("B,S,m,n_q,n_kv,hd,bf16", [
+    (1, 100, 1, 4, 4, 64, False), (2, 333, 5, 6, 2, 32, False),
+    (1, 70, 1, 8, 8, 64, True), (1, 777, 6, 32, 8, 64, True), (3, 1500, 4, 8, 8, 128, True), (2, 4200, 16, 16, 2, 128, True),
+    (1, 9000, 8, 8, 1, 64, True), (8, 300, 2, 4, 4, 128, True), (1, 640, 16, 32, 8, 64, True),
+])
+def test_attention(hsd, B, S, m, n_q, n_kv, hd, bf16):
+    """Per-sequence lengths differ (ragged batch), pages are permuted; bf16: 2e-2 absolute on outputs of unit scale."""
+    import torch
+    say("attention", B, S, m, n_q, n_kv, hd, "bf16" if bf16 else "f32")
+    rng = np.random.default_rng(S + m)
+    rnd = (lambda sh: inputs.bf16_round(rng.standard_normal(sh).astype(np.float32))) if bf16 else (lambda sh: rng.standard_normal(sh).astype(np.float32))
+    lens = [S - (b * 37) % max(1, S // 3) for b in range(B)]           # total positions per sequence, new tokens included
+    pos0 = np.array([l - m for l in lens], dtype=np.int32)
+    k, v, q = rnd((B, S, n_kv, hd)), rnd((B, S, n_kv, hd)), rnd((B, m, n_q, hd))
+    dt, td = (hsd.BF16, torch.bfloat16) if bf16 else (hsd.F32, torch.float32)
+    max_pages = (S + 63) // 64
+    perm = np.random.default_rng(1).permutation(B * max_pages)
+    cache = hsd.KvLayer(B, S, n_kv, hd, dt, perm)
+    zero = torch.zeros(B, dtype=torch.int32, device="cuda")
+    # fill every sequence up to its own length (rows beyond stay zero), in two writes to exercise offsets
+    n1 = min(lens) // 2
+    cache.write(zero, _cuda(k[:, :n1], td), _cuda(v[:, :n1], td))
+    for b in range(B):
+        kb = np.zeros((B, lens[b] - n1, n_kv, hd), dtype=np.float32)
+        vb = np.zeros_like(kb)
+        kb[b], vb[b] = k[b, n1:lens[b]], v[b, n1:lens[b]]
+        one = hsd.KvLayer.__new__(hsd.KvLayer)
+        one.__dict__.update(cache.__dict__)
+        one.batch = 1
+        one.pages = cache.pages[b:b + 1].contiguous()
+        one.write(torch.tensor([n1], dtype=torch.int32, device="cuda"), _cuda(kb[b:b + 1], td), _cuda(vb[b:b + 1], td))
+    got = cache.attention(_cuda(q, td), _cuda(pos0), max(lens)).float().cpu().numpy()
+    ref = _attention_ref(q, k, v, pos0)
+    err = np.abs(got - ref).max()
+    say("  max abs err %.2e" % err)
+    assert err < (2e-2 if bf16 else 2e-5)
