@@ -176,10 +176,14 @@ def main():
     raw_us = total_ms / launches * 1e3
     avg_us = raw_us - bracket_us                          # the two events of a bracket cost bracket_us by themselves
     achieved = bytes_per_launch / (avg_us * 1e-6) / 1e9
+    # HBM bytes per launch measured with hardware counters (two rocprofv3 --pmc runs, see profiles/): not measurable
+    # from inside this process, so the committed summary is quoted
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % dom)
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_1b_layer_kernels_pmc.txt")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch_%s:" % dom):
+                traffic = int(line.split(":")[1])
     roofline = {"bound": "hbm", "kernel": "gemm_bf16_kernel (%s projection)" % dom, "achieved": achieved,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                 "avg_launch_us": avg_us, "avg_launch_us_with_event_bracket": raw_us, "event_bracket_us": bracket_us,

@@ -1,0 +1,49 @@
+"""Full-size check of the bench workload's shape (1B-shaped bf16 model, exits 2 / 6 / 16, prompt 512) in the launch
+configuration bench.py times: draft-step and verify-pass logits against the fp64 oracle, all 32000 entries per row."""
+import numpy as np
+import pytest
+
+from paper_2510_19705_amd import inputs
+from helpers import gpu_model, oracle_decoder, say
+
+pytestmark = pytest.mark.gpu
+
+
+def test_1b_shape_passes_match_oracle():
+    import torch
+    shape = inputs.SHAPES["1b"]
+    say("generating 1B-shaped weights")
+    w = inputs.make_weights(shape, seed=77, bf16=True)
+    toks = inputs.make_prompt(shape["vocab"], 530, seed=78)
+    model = gpu_model(shape, w, True, max_seq=1024, max_rows=64, rows_copy_layers=2)
+    say("oracle: 16 layers over 519 tokens in fp64")
+    oracle = oracle_decoder(shape, w, 640)
+    ref_all = oracle.forward([int(t) for t in toks[:519]], 0, 16)          # fills the oracle cache for every layer
+    td = torch.from_numpy(toks).cuda()
+    for p0 in range(0, 512, 64):
+        model.model_pass(td[p0:p0 + 64], p0, 16, 0)
+    # verify pass of the target: 7 rows (pending token + 6 drafts)
+    got = model.model_pass(td[512:519], 512, 16, 7).cpu().numpy()
+    err = np.abs(got - ref_all[512:519]).max()
+    say("target verify pass, 7 rows: max abs err %.3e (|z| max %.2f)" % (err, np.abs(ref_all[512:519]).max()))
+    assert err < 2e-2
+    # verify pass of the middle level (exit 6), 5 rows, and a one-token draft step of exit 2 (row kernel)
+    ref6 = oracle.forward([int(t) for t in toks[519:524]], 519, 6)
+    got6 = model.model_pass(td[519:524], 519, 6, 5).cpu().numpy()
+    err6 = np.abs(got6 - ref6).max()
+    say("exit-6 verify pass, 5 rows: max abs err %.3e" % err6)
+    assert err6 < 2e-2
+    ref2 = oracle.forward([int(toks[524])], 524, 2)
+    got2 = model.model_pass(td[524:525], 524, 2, 1).cpu().numpy()
+    err2 = np.abs(got2 - ref2).max()
+    say("exit-2 draft step: max abs err %.3e" % err2)
+    assert err2 < 2e-2
+    # the distributions the sampler sees: softmax rows within 1e-3 of the oracle's in total variation
+    from oracle import decoder
+    from paper_2510_19705_amd import hsd
+    p_gpu = hsd.softmax(torch.from_numpy(got).cuda(), 1.0).cpu().numpy().astype(np.float64)
+    p_ref = decoder.distributions(ref_all[512:519], 1.0).astype(np.float64)
+    tv = 0.5 * np.abs(p_gpu - p_ref).sum(axis=1).max()
+    say("largest total-variation distance of a row: %.3e" % tv)
+    assert tv < 5e-3
+    model.close()
