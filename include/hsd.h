@@ -101,6 +101,12 @@ typedef struct {
 } hsd_site_times;
 int hsd_profile_begin(hsd_model*, int max_launches);
 int hsd_profile_end(hsd_model*, hsd_site_times* out);
+/* Mean duration, in microseconds, of one launch of a layer site (bf16 models; HSD_SITE_QKV .. HSD_SITE_DOWN) in the
+ * configuration a pass of `rows` tokens at position pos0 uses: `iters` launches
+ * back to back between two events on the model's stream, cycling through the layers so that every launch streams
+ * different weights.  Inputs are whatever the last pass left in the activation buffers; the residual stream and the KV
+ * rows at pos0.. are overwritten, so run a pass before trusting the model's state again. */
+int hsd_measure_site(hsd_model*, int site, int rows, int pos0, int iters, double* us_out);
 
 /* ---------------------------------------------------------------------------------------------
  * Stand-alone kernels of the path (each is what the pass / the driver launches internally).

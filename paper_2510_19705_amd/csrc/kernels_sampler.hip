@@ -33,7 +33,17 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
     return Philox4{{c0, c1, c2, c3}};
 }
 
-__device__ __forceinline__ uint64_t fixed_weight(float r) { return (uint64_t)((double)r * 4611686018427387904.0); }   // r * 2^62
+// floor(r * 2^62) for an fp32 r in [0, 1], exactly, with integer operations only (a double multiply and a
+// double -> uint64 conversion cost several times more): r = mant * 2^(exp - 150), so the weight is mant shifted by
+// exp - 88 (at most 39 to the left for r = 1).  Values below 2^-62, subnormals included, give 0.
+__device__ __forceinline__ uint64_t fixed_weight(float r) {
+    const uint32_t bits = __float_as_uint(r);
+    const int exp = (int)(bits >> 23) & 0xFF;
+    const uint64_t mant = (uint64_t)((bits & 0x7FFFFFu) | 0x800000u);
+    const int shift = exp - 88;
+    if (exp == 0 || shift <= -24) return 0;
+    return shift >= 0 ? mant << shift : mant >> -shift;
+}
 
 // scratch layout: [0] ticket counter (uint32), then slice totals: resid[nslices], plain[nslices] (uint64)
 __global__ __launch_bounds__(THREADS) void accept_resample_kernel(const float* __restrict__ p, const float* __restrict__ q,

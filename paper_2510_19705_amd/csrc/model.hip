@@ -354,66 +354,98 @@ static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, int ex
 // RMSNorm: they store bf16(x * w_norm) into m->xn and add the rows' sums of squares into m->ss[1]
 // (second norm of the layer) or m->ss[0] (first norm of the next layer, or the final norm at the exit);
 // the GEMM that consumes m->xn multiplies by 1/rms in its epilogue.
-static int pass_bf16(hsd_model* m, const int32_t* tok, int pos0, int rows, int exit_layer, int n_logit_rows, float* logits) {
+static int launch_site_bf16(hsd_model* m, int site, int l, int pos0, int rows, const float* next_norm_w) {
     const hsd_model_desc& d = m->desc;
     hipStream_t s = m->stream;
     const int nq = d.n_q * d.hd, nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
-    int rc;
-    if ((rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, m->ss[0], m->ss[1], m->layers[0].norm1, m->xn, s))) return rc;
-    GemmArgs base = {};
-    base.M = rows; base.part = m->part; base.tickets = m->tickets; base.eps = d.eps;
-    for (int l = 0; l < exit_layer; ++l) {
-        const LayerWeights& L = m->layers[l];
-        bf16_t* kv_layer = (bf16_t*)(m->kv + m->kv_layer_bytes * l);
-        const bool rowk = L.wqkv_rows && rows <= g_gemv_max_m;     // one or two tokens: stream the row-major copies
-        {
-            GemmArgs g = base;
+    const LayerWeights& L = m->layers[l];
+    bf16_t* kv_layer = (bf16_t*)(m->kv + m->kv_layer_bytes * l);
+    const bool rowk = L.wqkv_rows && rows <= g_gemv_max_m;     // one or two tokens: stream the row-major copies
+    GemmArgs g = {};
+    g.M = rows; g.part = m->part; g.tickets = m->tickets; g.eps = d.eps;
+    switch (site) {
+        case HSD_SITE_QKV:
             g.a = (const bf16_t*)m->xn; g.ss_in = m->ss[0]; g.ss_zero = m->ss[1];
             g.wp = (const bf16x8*)(rowk ? L.wqkv_rows : L.wqkv); g.N = nqkv; g.K = d.d;
             g.out_bf16 = (bf16_t*)m->q; g.kv_layer = kv_layer; g.pages = m->pages_dev;
             g.pos0 = pos0; g.n_q = d.n_q; g.n_kv = d.n_kv; g.hd = d.hd; g.rope_base = d.rope_base;
-            SiteTimer t(m, HSD_SITE_QKV);
-            if ((rc = rowk ? launch_gemv_bf16(g, EPI_ROPE, s) : launch_gemm_bf16(g, EPI_ROPE, gemm_plan(rows, nqkv, d.d, EPI_ROPE), s))) return rc;
-        }
-        {
-            SiteTimer t(m, HSD_SITE_ATTN);
-            if ((rc = launch_attention(m->q, kv_layer, m->pages_dev, m->max_pages, nullptr, pos0, 1, rows, pos0 + rows, d.n_q, d.n_kv,
-                                       d.hd, d.dtype, m->att, m->attn_ws, 0, s))) return rc;
-        }
-        {
-            GemmArgs g = base;
+            return rowk ? launch_gemv_bf16(g, EPI_ROPE, s) : launch_gemm_bf16(g, EPI_ROPE, gemm_plan(rows, nqkv, d.d, EPI_ROPE), s);
+        case HSD_SITE_ATTN:
+            return launch_attention(m->q, kv_layer, m->pages_dev, m->max_pages, nullptr, pos0, 1, rows, pos0 + rows, d.n_q, d.n_kv,
+                                    d.hd, d.dtype, m->att, m->attn_ws, 0, s);
+        case HSD_SITE_O:
             g.a = (const bf16_t*)m->att; g.wp = (const bf16x8*)(rowk ? L.wo_rows : L.wo); g.N = d.d; g.K = nq;
             g.out_f32 = m->x; g.ss_out = m->ss[1]; g.norm_w = L.norm2; g.out_bf16 = (bf16_t*)m->xn;
-            SiteTimer t(m, HSD_SITE_O);
-            if ((rc = rowk ? launch_gemv_bf16(g, EPI_RESID, s) : launch_gemm_bf16(g, EPI_RESID, gemm_plan(rows, d.d, nq, EPI_RESID), s))) return rc;
-        }
-        {
-            GemmArgs g = base;
+            return rowk ? launch_gemv_bf16(g, EPI_RESID, s) : launch_gemm_bf16(g, EPI_RESID, gemm_plan(rows, d.d, nq, EPI_RESID), s);
+        case HSD_SITE_GATEUP:
             g.a = (const bf16_t*)m->xn; g.ss_in = m->ss[1]; g.ss_zero = m->ss[0];
             g.wp = (const bf16x8*)L.wgu; g.N = 2 * d.ffn; g.K = d.d;
             g.out_bf16 = (bf16_t*)m->h;
-            SiteTimer t(m, HSD_SITE_GATEUP);
-            if ((rc = launch_gemm_bf16(g, EPI_SWIGLU, gemm_plan(rows, 2 * d.ffn, d.d, EPI_SWIGLU), s))) return rc;
-        }
-        {
-            GemmArgs g = base;
+            return launch_gemm_bf16(g, EPI_SWIGLU, gemm_plan(rows, 2 * d.ffn, d.d, EPI_SWIGLU), s);
+        case HSD_SITE_DOWN:
             g.a = (const bf16_t*)m->h; g.wp = (const bf16x8*)(rowk ? L.wd_rows : L.wd); g.N = d.d; g.K = d.ffn;
-            g.out_f32 = m->x; g.ss_out = m->ss[0];
-            g.norm_w = l + 1 == exit_layer ? m->norm_f : m->layers[l + 1].norm1;
-            g.out_bf16 = (bf16_t*)m->xn;
-            SiteTimer t(m, HSD_SITE_DOWN);
-            if ((rc = rowk ? launch_gemv_bf16(g, EPI_RESID, s) : launch_gemm_bf16(g, EPI_RESID, gemm_plan(rows, d.d, d.ffn, EPI_RESID), s))) return rc;
-        }
+            g.out_f32 = m->x; g.ss_out = m->ss[0]; g.norm_w = next_norm_w; g.out_bf16 = (bf16_t*)m->xn;
+            return rowk ? launch_gemv_bf16(g, EPI_RESID, s) : launch_gemm_bf16(g, EPI_RESID, gemm_plan(rows, d.d, d.ffn, EPI_RESID), s);
+        default:
+            HSD_FAIL(HSD_EINVAL, "unknown site %d", site);
     }
-    if (n_logit_rows == 0) return HSD_OK;
+}
+
+static int launch_head_bf16(hsd_model* m, int rows, int n_logit_rows, float* logits) {
+    const hsd_model_desc& d = m->desc;
     const int row0 = rows - n_logit_rows;
-    GemmArgs g = base;
+    GemmArgs g = {};
+    g.part = m->part; g.tickets = m->tickets; g.eps = d.eps;
     g.M = n_logit_rows;
     g.a = (const bf16_t*)m->xn + (size_t)row0 * d.d; g.ss_in = m->ss[0] + row0;
     g.wp = (const bf16x8*)m->head; g.N = d.vocab; g.K = d.d;
     g.out_f32 = logits;
+    return launch_gemm_bf16(g, EPI_STORE, gemm_plan(n_logit_rows, d.vocab, d.d, EPI_STORE), m->stream);
+}
+
+static int pass_bf16(hsd_model* m, const int32_t* tok, int pos0, int rows, int exit_layer, int n_logit_rows, float* logits) {
+    const hsd_model_desc& d = m->desc;
+    int rc;
+    if ((rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, m->ss[0], m->ss[1], m->layers[0].norm1, m->xn, m->stream))) return rc;
+    for (int l = 0; l < exit_layer; ++l) {
+        const float* next_norm = l + 1 == exit_layer ? m->norm_f : m->layers[l + 1].norm1;
+        for (int site = HSD_SITE_QKV; site <= HSD_SITE_DOWN; ++site) {
+            SiteTimer t(m, site);
+            if ((rc = launch_site_bf16(m, site, l, pos0, rows, next_norm))) return rc;
+        }
+    }
+    if (n_logit_rows == 0) return HSD_OK;
     SiteTimer t(m, HSD_SITE_HEAD);
-    return launch_gemm_bf16(g, EPI_STORE, gemm_plan(n_logit_rows, d.vocab, d.d, EPI_STORE), s);
+    return launch_head_bf16(m, rows, n_logit_rows, logits);
+}
+
+extern "C" int hsd_measure_site(hsd_model* m, int site, int rows, int pos0, int iters, double* us_out) {
+    if (!m || !us_out) HSD_FAIL(HSD_EINVAL, "hsd_measure_site: null pointer");
+    const hsd_model_desc& d = m->desc;
+    if (d.dtype != HSD_BF16) HSD_FAIL(HSD_EINVAL, "hsd_measure_site: bf16 models only");
+    if (site < HSD_SITE_QKV || site > HSD_SITE_DOWN || rows < 1 || rows > d.max_rows || iters < 1 || pos0 < 0 || pos0 + rows > d.max_seq)
+        HSD_FAIL(HSD_EINVAL, "hsd_measure_site: bad arguments (sites: q/k/v, attention, o, gate/up, down)");
+    for (int l = 0; l < d.n_layers; ++l)
+        if (!m->layer_loaded[l]) HSD_FAIL(HSD_ESTATE, "hsd_measure_site: layer %d not loaded", l);
+    hipEvent_t e0, e1;
+    HSD_HIP(hipEventCreate(&e0));
+    HSD_HIP(hipEventCreate(&e1));
+    int rc = HSD_OK;
+    auto one = [&](int i) { return launch_site_bf16(m, site, i % d.n_layers, pos0, rows, m->norm_f); };
+    for (int i = 0; i < d.n_layers && !rc; ++i) rc = one(i);                 // warm-up, one launch per layer
+    if (!rc && hipEventRecord(e0, m->stream) != hipSuccess) rc = HSD_EHIP;
+    for (int i = 0; i < iters && !rc; ++i) rc = one(i);
+    float ms = 0.f;
+    if (!rc && (hipEventRecord(e1, m->stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                hipEventElapsedTime(&ms, e0, e1) != hipSuccess)) {
+        hsd_set_error("hsd_measure_site: event timing failed");
+        rc = HSD_EHIP;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc) return rc;
+    *us_out = (double)ms * 1e3 / iters;
+    return HSD_OK;
 }
 
 // One pass: rows tokens at positions pos0.., layers [0, exit_layer), logits of the last n_logit_rows rows.

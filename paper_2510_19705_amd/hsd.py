@@ -64,6 +64,7 @@ _SIGS = {
     "hsd_model_pass": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
     "hsd_profile_begin": (_i, [_vp, _i]),
     "hsd_profile_end": (_i, [_vp, C.POINTER(SiteTimes)]),
+    "hsd_measure_site": (_i, [_vp, _i, _i, _i, _i, _dp]),
     "hsd_softmax": (_i, [_vp, _vp, _i, _i, _f, _vp]),
     "hsd_sampler_scratch_bytes": (_sz, [_i]),
     "hsd_accept_resample": (_i, [_vp, _vp, _vp, _i, _i, C.c_uint64, C.c_uint32, C.c_uint32, _vp, _vp, _vp]),
@@ -171,6 +172,17 @@ class Model:
         torch.cuda.current_stream().synchronize()
         _check(lib.hsd_model_load_layer(self.handle, layer, C.byref(lw)))
 
+    def load_layer_dev(self, layer, t):
+        """hsd_model_load_layer with cuda tensors already in the model's element type (norms fp32)."""
+        order = ("norm1", "wq", "wk", "wv", "wo", "norm2", "wg", "wu", "wd")
+        lw = LayerWeights(*[t[k].contiguous().data_ptr() for k in order])
+        torch.cuda.current_stream().synchronize()
+        _check(lib.hsd_model_load_layer(self.handle, layer, C.byref(lw)))
+
+    def load_head_dev(self, embed, head, norm_f):
+        torch.cuda.current_stream().synchronize()
+        _check(lib.hsd_model_load_head(self.handle, embed.data_ptr(), head.data_ptr(), norm_f.data_ptr()))
+
     def load_head(self, embed, head, norm_f):
         e, h, n = self._dev(embed), self._dev(head), self._dev(norm_f, norm=True)
         torch.cuda.current_stream().synchronize()
@@ -190,6 +202,11 @@ class Model:
         out = {SITE_NAMES[i]: (st.launches[i], st.ms[i]) for i in range(N_SITES)}
         out["empty_bracket_ms"] = st.empty_bracket_ms
         return out
+
+    def measure_site(self, site, rows, pos0, iters):
+        us = C.c_double()
+        _check(lib.hsd_measure_site(self.handle, SITE_NAMES.index(site), rows, pos0, iters, C.byref(us)))
+        return us.value
 
     def set_pages(self, table):
         a, p = _i32(table)
