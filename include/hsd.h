@@ -135,6 +135,18 @@ int hsd_accept_resample(const float* p_dev, const float* q_dev, int32_t* x_dev, 
                         uint64_t seed, uint32_t level, uint32_t call, int32_t* result_dev,
                         void* scratch_dev, void* stream);
 
+/* hsd_softmax over the verifier's t+1 logit rows followed by hsd_accept_resample, in ONE launch (what the driver
+ * runs after a verifier pass, and after a base-level drafting pass with t == 0; Alg. 1 and Alg. 2): one workgroup
+ * per row keeps the row in registers from the logits to the drawn token.  Same arguments and the same results, bit
+ * for bit, as the two calls in sequence: logits_dev [t+1, vocab] fp32; probs_dev [t+1, vocab] receives the rows
+ * p_1..p_{t+1} (may be null when they are not needed afterwards).  Vocabularies up to 32768 only (HSD_ECAPACITY
+ * beyond; use the two calls).  host_mailbox, if not null, is device-accessible pinned host memory of at least
+ * (t + 3) int32 that receives n, m, then the n accepted draft ids followed by m, readable after the stream has
+ * been synchronised.  scratch_dev as for hsd_accept_resample. */
+int hsd_softmax_verify(const float* logits_dev, const float* q_dev, int32_t* x_dev, int t, int vocab,
+                       float temperature, uint64_t seed, uint32_t level, uint32_t call, float* probs_dev,
+                       int32_t* result_dev, void* scratch_dev, int32_t* host_mailbox, void* stream);
+
 /* k-query attention over a paged KV cache, for a batch of sequences (the pass uses it with batch 1).
  * One layer's cache: hsd_kv_layer_bytes(n_pages, ...) bytes; pages_dev [batch, max_pages] int32 gives the physical
  * page (HSD_KV_PAGE positions) of each logical page of each sequence.  hsd_kv_write stores logical K/V

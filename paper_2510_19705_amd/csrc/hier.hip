@@ -46,6 +46,7 @@ struct hsd_hier {
     int32_t* result_dev;
     void* sampler_scratch;
     int32_t* mailbox;   // pinned host memory: n, m, then up to 65 token ids
+    int32_t* mailbox_dev;   // the same memory as the device addresses it
     hsd_stats stats;
 };
 
@@ -152,10 +153,16 @@ int draft_step(hsd_hier* h, int row) {
     const int start = std::min(effective_cached(h, 0), h->len - 1);
     if (int rc = level_pass(h, 0, start, 1)) return rc;
     float* p = L.rows + (size_t)row * h->V;
-    if (int rc = launch_softmax(h->logits, p, 1, h->V, h->temperature, h->stream)) return rc;
-    if (int rc = launch_accept_resample(p, nullptr, h->tok_dev + h->len, 0, h->V, h->seed, 0u, L.call++, h->result_dev,
-                                        h->sampler_scratch, h->stream))
-        return rc;
+    if (softmax_verify_supported(h->V)) {
+        if (int rc = launch_softmax_verify(h->logits, nullptr, h->tok_dev + h->len, 0, h->V, h->temperature, h->seed, 0u, L.call++, p,
+                                           h->result_dev, h->sampler_scratch, nullptr, h->stream))
+            return rc;
+    } else {
+        if (int rc = launch_softmax(h->logits, p, 1, h->V, h->temperature, h->stream)) return rc;
+        if (int rc = launch_accept_resample(p, nullptr, h->tok_dev + h->len, 0, h->V, h->seed, 0u, L.call++, h->result_dev,
+                                            h->sampler_scratch, h->stream))
+            return rc;
+    }
     L.cached_len = h->len;
     h->len += 1;
     return HSD_OK;
@@ -173,12 +180,19 @@ int verify_step(hsd_hier* h, int idx, int t, const float* q_dev, int* n_out) {
     const int start = std::min(effective_cached(h, idx), ctx_end - 1);
     if (int rc = level_pass(h, idx, start, t + 1)) return rc;
     float* p = L.rows + (size_t)L.count * h->V;
-    if (int rc = launch_softmax(h->logits, p, t + 1, h->V, h->temperature, h->stream)) return rc;
-    if (int rc = launch_accept_resample(p, q_dev, h->tok_dev + ctx_end, t, h->V, h->seed, (uint32_t)idx, L.call++, h->result_dev,
-                                        h->sampler_scratch, h->stream))
-        return rc;
-    HSD_HIP(hipMemcpyAsync(h->mailbox, h->result_dev, 8, hipMemcpyDeviceToHost, h->stream));
-    HSD_HIP(hipMemcpyAsync(h->mailbox + 2, h->tok_dev + ctx_end, (size_t)(t + 1) * 4, hipMemcpyDeviceToHost, h->stream));
+    if (softmax_verify_supported(h->V)) {
+        // one launch; the kernel writes n, m and the surviving tokens straight into the pinned mailbox
+        if (int rc = launch_softmax_verify(h->logits, q_dev, h->tok_dev + ctx_end, t, h->V, h->temperature, h->seed, (uint32_t)idx,
+                                           L.call++, p, h->result_dev, h->sampler_scratch, h->mailbox_dev, h->stream))
+            return rc;
+    } else {
+        if (int rc = launch_softmax(h->logits, p, t + 1, h->V, h->temperature, h->stream)) return rc;
+        if (int rc = launch_accept_resample(p, q_dev, h->tok_dev + ctx_end, t, h->V, h->seed, (uint32_t)idx, L.call++, h->result_dev,
+                                            h->sampler_scratch, h->stream))
+            return rc;
+        HSD_HIP(hipMemcpyAsync(h->mailbox, h->result_dev, 8, hipMemcpyDeviceToHost, h->stream));
+        HSD_HIP(hipMemcpyAsync(h->mailbox + 2, h->tok_dev + ctx_end, (size_t)(t + 1) * 4, hipMemcpyDeviceToHost, h->stream));
+    }
     HSD_HIP(hipStreamSynchronize(h->stream));
     const int n = h->mailbox[0];
     if (n < 0 || n > t) HSD_FAIL(HSD_EHIP, "verify: device returned n=%d for t=%d", n, t);
@@ -280,8 +294,10 @@ extern "C" int hsd_hier_create(int n_levels, const hsd_level* levels, const int*
     h->tok_host.assign(h->max_seq, 0);
     h->len = 0;
     h->mailbox = nullptr;
+    h->mailbox_dev = nullptr;
     reset_counters(h);
-    hipError_t e = hipHostMalloc((void**)&h->mailbox, 68 * sizeof(int32_t), hipHostMallocDefault);
+    hipError_t e = hipHostMalloc((void**)&h->mailbox, 68 * sizeof(int32_t), hipHostMallocMapped);
+    if (e == hipSuccess) e = hipHostGetDevicePointer((void**)&h->mailbox_dev, h->mailbox, 0);
     if (e == hipSuccess) e = hipMemsetAsync(h->sampler_scratch, 0, hsd_sampler_scratch_bytes(h->V), h->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
     if (e != hipSuccess) {

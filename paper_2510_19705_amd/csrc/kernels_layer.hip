@@ -2,6 +2,7 @@
 // RMSNorm, rotary embedding + KV append, vocabulary softmax.  None of them is bandwidth-relevant
 // next to the weight and KV streams; they exist to keep every step of the pass on the device.
 #include "common.h"
+#include "softmax_row.h"
 
 __device__ __forceinline__ float block_sum_256(float v, float* sh) {
     v = wave_sum(v);
@@ -116,98 +117,55 @@ __global__ void rope_kv_kernel(const float* __restrict__ part, int ksplit, int M
 }
 
 // p = softmax(z / temperature) per row (grid.x rows, 1024 threads); temperature 0: one-hot at the
-// lowest-index maximum.  CACHED: the row fits the workgroup's registers (vocab <= 1024 * 4 * CH), so it is
-// read once; otherwise it is re-read from L2 for the sum and the final pass.
+// lowest-index maximum.  CH > 0: the row fits the workgroup's registers (vocab <= 1024 * 4 * CH), so it is
+// read once; CH == 0: it is re-read from L2 for the sum and the final pass.
 template <int CH>
-__global__ __launch_bounds__(1024) void softmax_kernel(const float* __restrict__ z, float* __restrict__ p, int V,
-                                                       float temperature) {
+__global__ __launch_bounds__(SOFTMAX_THREADS) void softmax_kernel(const float* __restrict__ z, float* __restrict__ p, int V,
+                                                                  float temperature) {
     __shared__ float shv[16];
     __shared__ int shi[16];
     const float* zr = z + (size_t)blockIdx.x * V;
     float* pr = p + (size_t)blockIdx.x * V;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
-    constexpr bool CACHED = CH > 0;
-    constexpr int NC = CACHED ? CH : 1;
-    const bool vec = CACHED && (V & 3) == 0 && ((uintptr_t)zr & 15) == 0 && ((uintptr_t)pr & 15) == 0;
-    float4 c[NC];
-    float mx = -INFINITY;
-    int arg = 0x7fffffff;
-    if constexpr (CACHED) {
-#pragma unroll
-        for (int k = 0; k < NC; ++k) {
-            const int i = (k * 1024 + tid) * 4;          // elements i .. i+3, ascending in k for a fixed thread
-            float4 v = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-            if (vec) {
-                if (i < V) v = *reinterpret_cast<const float4*>(zr + i);
-            } else {
-                if (i < V) v.x = zr[i];
-                if (i + 1 < V) v.y = zr[i + 1];
-                if (i + 2 < V) v.z = zr[i + 2];
-                if (i + 3 < V) v.w = zr[i + 3];
-            }
-            c[k] = v;
-            if (v.x > mx) { mx = v.x; arg = i; }
-            if (v.y > mx) { mx = v.y; arg = i + 1; }
-            if (v.z > mx) { mx = v.z; arg = i + 2; }
-            if (v.w > mx) { mx = v.w; arg = i + 3; }
-        }
+    if constexpr (CH > 0) {
+        const bool vec = (V & 3) == 0 && ((uintptr_t)zr & 15) == 0 && ((uintptr_t)pr & 15) == 0;
+        float4 c[CH];
+        softmax_row_cached<CH>(zr, V, temperature, vec, c, shv, shi);
+        store_row_cached<CH>(pr, V, vec, c);
     } else {
+        const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+        float mx = -INFINITY;
+        int arg = 0x7fffffff;
         for (int i = tid; i < V; i += blockDim.x) {
             const float v = zr[i];
             if (v > mx) { mx = v; arg = i; }
         }
-    }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const float om = __shfl_xor(mx, o, 64);
-        const int oa = __shfl_xor(arg, o, 64);
-        if (om > mx || (om == mx && oa < arg)) { mx = om; arg = oa; }
-    }
-    if (lane == 0) { shv[wave] = mx; shi[wave] = arg; }
-    __syncthreads();
-    mx = shv[0];
-    arg = shi[0];
-    for (int w = 1; w < nw; ++w)
-        if (shv[w] > mx || (shv[w] == mx && shi[w] < arg)) { mx = shv[w]; arg = shi[w]; }
-    __syncthreads();
-    if (temperature == 0.f) {
-        for (int i = tid; i < V; i += blockDim.x) pr[i] = i == arg ? 1.f : 0.f;
-        return;
-    }
-    const float it = 1.0f / temperature;
-    float sum = 0.f;
-    if constexpr (CACHED) {
-#pragma unroll
-        for (int k = 0; k < NC; ++k) {                   // exp(-inf) = 0 for the padding
-            c[k].x = expf((c[k].x - mx) * it); c[k].y = expf((c[k].y - mx) * it);
-            c[k].z = expf((c[k].z - mx) * it); c[k].w = expf((c[k].w - mx) * it);
-            sum += (c[k].x + c[k].y) + (c[k].z + c[k].w);
+        for (int o = 32; o > 0; o >>= 1) {
+            const float om = __shfl_xor(mx, o, 64);
+            const int oa = __shfl_xor(arg, o, 64);
+            if (om > mx || (om == mx && oa < arg)) { mx = om; arg = oa; }
         }
-    } else {
-        for (int i = tid; i < V; i += blockDim.x) sum += expf((zr[i] - mx) * it);
-    }
-    sum = wave_sum(sum);
-    if (lane == 0) shv[wave] = sum;
-    __syncthreads();
-    sum = 0.f;
-    for (int w = 0; w < nw; ++w) sum += shv[w];
-    const float inv = 1.0f / sum;
-    if constexpr (CACHED) {
-#pragma unroll
-        for (int k = 0; k < NC; ++k) {
-            const int i = (k * 1024 + tid) * 4;
-            const float4 v = {c[k].x * inv, c[k].y * inv, c[k].z * inv, c[k].w * inv};
-            if (vec) {
-                if (i < V) *reinterpret_cast<float4*>(pr + i) = v;
-            } else {
-                if (i < V) pr[i] = v.x;
-                if (i + 1 < V) pr[i + 1] = v.y;
-                if (i + 2 < V) pr[i + 2] = v.z;
-                if (i + 3 < V) pr[i + 3] = v.w;
-            }
+        if (lane == 0) { shv[wave] = mx; shi[wave] = arg; }
+        __syncthreads();
+        mx = shv[0];
+        arg = shi[0];
+        for (int w = 1; w < nw; ++w)
+            if (shv[w] > mx || (shv[w] == mx && shi[w] < arg)) { mx = shv[w]; arg = shi[w]; }
+        __syncthreads();
+        if (temperature == 0.f) {
+            for (int i = tid; i < V; i += blockDim.x) pr[i] = i == arg ? 1.f : 0.f;
+            return;
         }
-    } else {
-        for (int i = tid; i < V; i += blockDim.x) pr[i] = expf((zr[i] - mx) * it) * inv;
+        const float it = 1.0f / temperature;
+        float sum = 0.f;
+        for (int i = tid; i < V; i += blockDim.x) sum += expf(__fmul_rn(__fsub_rn(zr[i], mx), it));
+        sum = wave_sum(sum);
+        if (lane == 0) shv[wave] = sum;
+        __syncthreads();
+        sum = 0.f;
+        for (int w = 0; w < nw; ++w) sum += shv[w];
+        const float inv = 1.0f / sum;
+        for (int i = tid; i < V; i += blockDim.x) pr[i] = __fmul_rn(expf(__fmul_rn(__fsub_rn(zr[i], mx), it)), inv);
     }
 }
 
@@ -246,12 +204,12 @@ int launch_rope_kv(const float* part, int ksplit, int m, void* q, void* kv_layer
 }
 
 int launch_softmax(const float* z, float* p, int rows, int vocab, float temperature, hipStream_t s) {
-    if (vocab <= 1024 * 4 * 2)
-        softmax_kernel<2><<<rows, 1024, 0, s>>>(z, p, vocab, temperature);
-    else if (vocab <= 1024 * 4 * 8)
-        softmax_kernel<8><<<rows, 1024, 0, s>>>(z, p, vocab, temperature);
+    if (vocab <= SOFTMAX_THREADS * 4 * 2)
+        softmax_kernel<2><<<rows, SOFTMAX_THREADS, 0, s>>>(z, p, vocab, temperature);
+    else if (vocab <= SOFTMAX_THREADS * 4 * 8)
+        softmax_kernel<8><<<rows, SOFTMAX_THREADS, 0, s>>>(z, p, vocab, temperature);
     else
-        softmax_kernel<0><<<rows, 1024, 0, s>>>(z, p, vocab, temperature);
+        softmax_kernel<0><<<rows, SOFTMAX_THREADS, 0, s>>>(z, p, vocab, temperature);
     HSD_LAUNCH_CHECK();
     return HSD_OK;
 }

@@ -7,6 +7,7 @@
 // threshold and scans inside it.  Random numbers are Philox4x32-10 blocks addressed by
 // (seed; slot, call, level), so nothing depends on launch geometry.
 #include "common.h"
+#include "softmax_row.h"
 
 namespace {
 
@@ -188,21 +189,146 @@ __global__ __launch_bounds__(THREADS) void accept_resample_kernel(const float* _
     }
 }
 
-// Same rule in ONE workgroup for vocabularies up to 32768: no exchange between workgroups, no fences.
-// The row is cut in 8 chunks of 4096 tokens; in chunk k thread i owns tokens 4096 k + 4 i .. + 3 (so a
-// wave reads 1 KiB contiguous).  Per chunk an exclusive scan of the threads' integer sums, chunk totals
-// chained in order: together the prefix sums in token order, which locate the one (chunk, thread) whose
-// four tokens hold the threshold.
-constexpr int SMALL_THREADS = 1024, SMALL_CHUNKS = 8, SMALL_MAX_V = SMALL_THREADS * 4 * SMALL_CHUNKS;
+// ---- one-workgroup search -------------------------------------------------------------------------
+// Rows of up to 32768 tokens are held by one workgroup of 1024 threads in 8 chunks of 4096 tokens; in chunk k
+// thread i owns tokens 4096 k + 4 i .. + 3 (a wave reads 1 KiB contiguous).  Token order is therefore
+// (chunk, wave, lane, element).
+constexpr int SMALL_THREADS = SOFTMAX_THREADS, SMALL_CHUNKS = 8, SMALL_MAX_V = SMALL_THREADS * 4 * SMALL_CHUNKS;
+constexpr int SMALL_WAVES = SMALL_THREADS / 64;
 
+struct SearchShared {
+    uint64_t tot[SMALL_CHUNKS * SMALL_WAVES];     // [chunk][wave] sums, i.e. in token order
+    int token;
+};
+
+// Sums of 8 values over the 64 lanes with 10 exchanges instead of 48: each step halves the values a lane
+// carries.  Afterwards every lane holds the wave's sum of value number lane >> 3.
+__device__ __forceinline__ uint64_t wave_sum8(const uint64_t (&v)[8], int lane) {
+    uint64_t a[4], b[2];
+    const bool h5 = lane & 32, h4 = lane & 16, h3 = lane & 8;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) a[j] = (h5 ? v[j + 4] : v[j]) + __shfl_xor(h5 ? v[j] : v[j + 4], 32, 64);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) b[j] = (h4 ? a[j + 2] : a[j]) + __shfl_xor(h4 ? a[j] : a[j + 2], 16, 64);
+    uint64_t c = (h3 ? b[1] : b[0]) + __shfl_xor(h3 ? b[0] : b[1], 8, 64);
+    c += __shfl_xor(c, 4, 64);
+    c += __shfl_xor(c, 2, 64);
+    c += __shfl_xor(c, 1, 64);
+    return c;
+}
+
+__device__ __forceinline__ uint64_t wave_inclusive_scan(uint64_t v, int lane) {
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint64_t up = __shfl_up(v, o, 64);
+        if (lane >= o) v += up;
+    }
+    return v;
+}
+
+// Inverse-CDF draw over the integer weights of this thread's tokens, which weights4(k, w) yields for chunk k
+// (recomputed where needed rather than kept: 32 64-bit weights would not fit the register budget): with S their total over the
+// workgroup and thr = floor(S * U32 / 2^32), the smallest token whose inclusive prefix exceeds thr goes to
+// sh.token (one thread writes it; the caller puts a barrier before reading).  Returns S to every thread; for
+// S == 0 nothing is written.  One barrier inside; sh.tot must not be in use by slower waves on entry.
+template <typename F>
+__device__ __forceinline__ uint64_t search_token(F&& weights4, uint32_t U32, SearchShared& sh) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint64_t cs[SMALL_CHUNKS];
+#pragma unroll
+    for (int k = 0; k < SMALL_CHUNKS; ++k) {
+        uint64_t w4[4];
+        weights4(k, w4);
+        cs[k] = (w4[0] + w4[1]) + (w4[2] + w4[3]);
+    }
+    const uint64_t wsum = wave_sum8(cs, lane);
+    if ((lane & 7) == 0) sh.tot[(lane >> 3) * SMALL_WAVES + wave] = wsum;
+    __syncthreads();
+    // every wave scans the 128 (chunk, wave) totals, two per lane
+    const uint64_t e0 = sh.tot[2 * lane], e1 = sh.tot[2 * lane + 1];
+    const uint64_t inc = wave_inclusive_scan(e0 + e1, lane);
+    const uint64_t S = __shfl(inc, 63, 64);
+    if (S == 0) return 0;
+    const uint64_t thr = __umul64hi(S, (uint64_t)U32 << 32);                  // floor(S * U / 2^32) < S
+    const uint64_t exc = inc - (e0 + e1);
+    const bool here = exc <= thr && thr < inc;                               // exactly one lane
+    const bool second = thr >= exc + e0;
+    const unsigned long long mask = __ballot(here);
+    const int src = (int)__ffsll((long long)mask) - 1;
+    const int entry = __shfl(2 * lane + (second ? 1 : 0), src, 64);
+    const uint64_t before = __shfl(second ? exc + e0 : exc, src, 64);
+    if (wave != (entry & (SMALL_WAVES - 1))) return S;
+    const int kk = entry / SMALL_WAVES;
+    uint64_t mine = 0;
+#pragma unroll
+    for (int k = 0; k < SMALL_CHUNKS; ++k)
+        if (k == kk) mine = cs[k];
+    const uint64_t linc = wave_inclusive_scan(mine, lane);
+    const uint64_t lexc = before + linc - mine;
+    if (mine != 0 && lexc <= thr && thr < lexc + mine) {                     // exactly one lane
+        uint64_t w4[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int k = 0; k < SMALL_CHUNKS; ++k)
+            if (k == kk) weights4(k, w4);
+        const uint64_t r0 = lexc + w4[0], r1 = r0 + w4[1], r2 = r1 + w4[2];
+        const int e = r0 > thr ? 0 : r1 > thr ? 1 : r2 > thr ? 2 : 3;
+        sh.token = (kk * SMALL_THREADS + tid) * 4 + e;
+    }
+    return S;
+}
+
+// Loads this thread's 32 values of a row (0 beyond V).
+__device__ __forceinline__ void load_row_chunks(const float* __restrict__ row, int V, bool vec, float4 (&c)[SMALL_CHUNKS]) {
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int k = 0; k < SMALL_CHUNKS; ++k) {
+        const int i = (k * SMALL_THREADS + tid) * 4;
+        float4 v = {0.f, 0.f, 0.f, 0.f};
+        if (vec) {
+            if (i < V) v = *reinterpret_cast<const float4*>(row + i);
+        } else {
+            if (i < V) v.x = row[i];
+            if (i + 1 < V) v.y = row[i + 1];
+            if (i + 2 < V) v.z = row[i + 2];
+            if (i + 3 < V) v.w = row[i + 3];
+        }
+        c[k] = v;
+    }
+}
+
+// Token drawn from the normalised max(0, p - q) (q != null and the residual not identically zero) or from p,
+// per Alg. 2; p and q are this thread's chunks.  The token lands in sh.token (barrier included).
+__device__ __forceinline__ void draw_corrected(const float4 (&pc)[SMALL_CHUNKS], const float4 (&qc)[SMALL_CHUNKS], bool have_q,
+                                               uint32_t U32, int V, SearchShared& sh) {
+    uint64_t S = 0;
+    if (have_q) {
+        S = search_token([&](int k, uint64_t (&w)[4]) {
+            w[0] = fixed_weight(fmaxf(0.f, __fsub_rn(pc[k].x, qc[k].x)));
+            w[1] = fixed_weight(fmaxf(0.f, __fsub_rn(pc[k].y, qc[k].y)));
+            w[2] = fixed_weight(fmaxf(0.f, __fsub_rn(pc[k].z, qc[k].z)));
+            w[3] = fixed_weight(fmaxf(0.f, __fsub_rn(pc[k].w, qc[k].w)));
+        }, U32, sh);
+        if (S == 0) __syncthreads();                       // all waves are past the totals before they are rewritten
+    }
+    if (S == 0) {                                          // bonus row, or residual identically zero: draw from p
+        S = search_token([&](int k, uint64_t (&w)[4]) {
+            w[0] = fixed_weight(pc[k].x);
+            w[1] = fixed_weight(pc[k].y);
+            w[2] = fixed_weight(pc[k].z);
+            w[3] = fixed_weight(pc[k].w);
+        }, U32, sh);
+    }
+    if (S == 0 && threadIdx.x == 0) sh.token = V - 1;      // unreachable for a distribution row
+    __syncthreads();
+}
+
+// Alg. 2 in ONE workgroup for vocabularies up to 32768: no exchange between workgroups, no fences.
 __global__ __launch_bounds__(SMALL_THREADS) void accept_resample_small_kernel(const float* __restrict__ p, const float* __restrict__ q,
                                                                               int32_t* __restrict__ x, int t, int V, uint32_t k0,
                                                                               uint32_t k1, uint32_t level, uint32_t call,
                                                                               int32_t* __restrict__ result) {
-    constexpr int NWAVE = SMALL_THREADS / 64;
     __shared__ int sh_n;
-    __shared__ uint64_t sh_a[NWAVE], sh_b[NWAVE];
-    __shared__ uint64_t sh_tot[NWAVE][SMALL_CHUNKS];
+    __shared__ SearchShared sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (wave == 0) {
         bool reject = false;
@@ -221,94 +347,97 @@ __global__ __launch_bounds__(SMALL_THREADS) void accept_resample_small_kernel(co
     const float* prow = p + (size_t)n * V;
     const float* qrow = n < t ? q + (size_t)n * V : nullptr;
     const bool vec = (V & 3) == 0 && ((uintptr_t)prow & 15) == 0 && (!qrow || ((uintptr_t)qrow & 15) == 0);
-    float pv[SMALL_CHUNKS][4], rv[SMALL_CHUNKS][4];
-    uint64_t a = 0, b = 0;
-#pragma unroll
-    for (int k = 0; k < SMALL_CHUNKS; ++k) {
-        const int i = (k * SMALL_THREADS + tid) * 4;
-        float4 pp = {0.f, 0.f, 0.f, 0.f}, qq = {0.f, 0.f, 0.f, 0.f};
-        if (vec) {
-            if (i < V) {
-                pp = *reinterpret_cast<const float4*>(prow + i);
-                if (qrow) qq = *reinterpret_cast<const float4*>(qrow + i);
-            }
-        } else {
-            if (i < V) { pp.x = prow[i]; if (qrow) qq.x = qrow[i]; }
-            if (i + 1 < V) { pp.y = prow[i + 1]; if (qrow) qq.y = qrow[i + 1]; }
-            if (i + 2 < V) { pp.z = prow[i + 2]; if (qrow) qq.z = qrow[i + 2]; }
-            if (i + 3 < V) { pp.w = prow[i + 3]; if (qrow) qq.w = qrow[i + 3]; }
-        }
-        pv[k][0] = pp.x; pv[k][1] = pp.y; pv[k][2] = pp.z; pv[k][3] = pp.w;
-        rv[k][0] = qrow ? fmaxf(0.f, __fsub_rn(pp.x, qq.x)) : 0.f;
-        rv[k][1] = qrow ? fmaxf(0.f, __fsub_rn(pp.y, qq.y)) : 0.f;
-        rv[k][2] = qrow ? fmaxf(0.f, __fsub_rn(pp.z, qq.z)) : 0.f;
-        rv[k][3] = qrow ? fmaxf(0.f, __fsub_rn(pp.w, qq.w)) : 0.f;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            b += fixed_weight(pv[k][e]);
-            a += fixed_weight(rv[k][e]);
-        }
-    }
-    uint64_t ta = a, tb = b;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        ta += __shfl_xor(ta, o, 64);
-        tb += __shfl_xor(tb, o, 64);
-    }
-    if (lane == 0) { sh_a[wave] = ta; sh_b[wave] = tb; }
-    __syncthreads();
-    ta = tb = 0;
-    for (int w = 0; w < NWAVE; ++w) { ta += sh_a[w]; tb += sh_b[w]; }
-    const bool use_resid = qrow != nullptr && ta != 0;     // residual identically zero: fall back to p
-    const uint64_t S = use_resid ? ta : tb;
+    float4 pc[SMALL_CHUNKS], qc[SMALL_CHUNKS];
+    load_row_chunks(prow, V, vec, pc);
+    if (qrow) load_row_chunks(qrow, V, vec, qc);
     const Philox4 rnd = philox4x32_10((uint32_t)t, call, level, 0u, k0, k1);
-    const uint64_t thr = __umul64hi(S, (uint64_t)rnd.w[1] << 32);
-    // per chunk: this thread's sum and its inclusive scan inside the wave
-    uint64_t mine[SMALL_CHUNKS], inc[SMALL_CHUNKS];
-#pragma unroll
-    for (int k = 0; k < SMALL_CHUNKS; ++k) {
-        uint64_t m4 = 0;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) m4 += fixed_weight(use_resid ? rv[k][e] : pv[k][e]);
-        mine[k] = m4;
-        uint64_t v = m4;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint64_t up = __shfl_up(v, o, 64);
-            if (lane >= o) v += up;
-        }
-        inc[k] = v;
-        if (lane == 63) sh_tot[wave][k] = v;
-    }
-    __syncthreads();
-    uint64_t chunk_base = 0;                               // tokens before chunk k
-#pragma unroll
-    for (int k = 0; k < SMALL_CHUNKS; ++k) {
-        uint64_t before = chunk_base + inc[k] - mine[k];
-        uint64_t chunk_total = 0;
-        for (int w = 0; w < NWAVE; ++w) {
-            const uint64_t v = sh_tot[w][k];
-            if (w < wave) before += v;
-            chunk_total += v;
-        }
-        if (mine[k] != 0 && before <= thr && thr < before + mine[k]) {      // exactly one (chunk, thread)
-            uint64_t run = before;
-            int m = (k * SMALL_THREADS + tid) * 4;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                run += fixed_weight(use_resid ? rv[k][e] : pv[k][e]);
-                if (run > thr) { m += e; break; }
-            }
-            result[0] = n;
-            result[1] = m;
-            x[n] = m;
-        }
-        chunk_base += chunk_total;
-    }
-    if (S == 0 && tid == 0) {                              // unreachable for a distribution row
+    draw_corrected(pc, qc, qrow != nullptr, rnd.w[1], V, sh);
+    if (tid == 0) {
+        const int m = sh.token;
         result[0] = n;
-        result[1] = V - 1;
-        x[n] = V - 1;
+        result[1] = m;
+        x[n] = m;
+    }
+}
+
+// Softmax of the verifier's t+1 logit rows, the t accept tests and the corrected / bonus token in ONE launch:
+// workgroup i turns logit row i into p_i in registers (same bits as the softmax kernel), stores it, tests
+// draft i (i < t) and draws the token Alg. 2 would emit IF the first rejection were at i (i = t: the bonus
+// token), all with the call's one sampling draw, as only one row's token is used.  Rejecting rows and row t
+// then race an atomic max of ~(i << 32 | token): the largest is the smallest i, i.e. n and its token.  The
+// last workgroup to take a ticket publishes them (result, x[n], and a pinned host mailbox if given) and
+// resets key and ticket.  The ticket increment depends on the returned value of the max, so the max is
+// performed before the ticket is taken.
+__global__ __launch_bounds__(SMALL_THREADS) void softmax_verify_kernel(const float* __restrict__ z, const float* __restrict__ q,
+                                                                       int32_t* __restrict__ x, int t, int V, float temperature,
+                                                                       uint32_t k0, uint32_t k1, uint32_t level, uint32_t call,
+                                                                       float* __restrict__ p_out, int32_t* __restrict__ result,
+                                                                       uint32_t* ticket, unsigned long long* key,
+                                                                       int32_t* __restrict__ mailbox) {
+    __shared__ float shv[16];
+    __shared__ int shi[16];
+    __shared__ SearchShared sh;
+    __shared__ int sh_reject;
+    const int row = blockIdx.x, tid = threadIdx.x;
+    const float* zr = z + (size_t)row * V;
+    const float* qr = row < t ? q + (size_t)row * V : nullptr;
+    float* pr = p_out ? p_out + (size_t)row * V : nullptr;
+    const bool vec = (V & 3) == 0 && ((uintptr_t)zr & 15) == 0 && (!qr || ((uintptr_t)qr & 15) == 0) && (!pr || ((uintptr_t)pr & 15) == 0);
+    const int xi = row < t ? min(max(x[row], 0), V - 1) : -1;
+    float4 pc[SMALL_CHUNKS], qc[SMALL_CHUNKS];
+    if (qr) load_row_chunks(qr, V, vec, qc);
+    softmax_row_cached<SMALL_CHUNKS>(zr, V, temperature, vec, pc, shv, shi);
+    if (pr) store_row_cached<SMALL_CHUNKS>(pr, V, vec, pc);
+    if (row < t) {
+        // the thread that owns the drafted token tests it: accept iff fl32(u * q(x)) < p(x)
+        if (((xi >> 2) & (SMALL_THREADS - 1)) == tid) {
+            const int kk = xi >> 12, e = xi & 3;
+            float px = 0.f, qx = 0.f;
+#pragma unroll
+            for (int k = 0; k < SMALL_CHUNKS; ++k)
+                if (k == kk) {
+                    px = e == 0 ? pc[k].x : e == 1 ? pc[k].y : e == 2 ? pc[k].z : pc[k].w;
+                    qx = e == 0 ? qc[k].x : e == 1 ? qc[k].y : e == 2 ? qc[k].z : qc[k].w;
+                }
+            const Philox4 rnd = philox4x32_10((uint32_t)row, call, level, 0u, k0, k1);
+            const float u = (float)(rnd.w[0] >> 8) * 5.9604644775390625e-8f;
+            sh_reject = !(__fmul_rn(u, qx) < px);
+        }
+    } else if (tid == 0) {
+        sh_reject = 1;                                     // the bonus row always takes part
+    }
+    const Philox4 rnd = philox4x32_10((uint32_t)t, call, level, 0u, k0, k1);
+    draw_corrected(pc, qc, qr != nullptr, rnd.w[1], V, sh);           // ends with a barrier: sh_reject and sh.token are visible
+    if (tid >= 64) return;
+    int last = 0;
+    unsigned long long best = 0;
+    if (tid == 0) {
+        unsigned long long old = 0;
+        if (sh_reject) {
+            const unsigned long long mine = ~(((unsigned long long)row << 32) | (unsigned long long)(uint32_t)sh.token);
+            old = __hip_atomic_fetch_max(key, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        const uint32_t step = 1u + (uint32_t)(old == 1ull);           // old is 0 or has bit 63 set: always 1, but data-dependent
+        const uint32_t done = __hip_atomic_fetch_add(ticket, step, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (done == (uint32_t)t) {
+            last = 1;
+            best = ~__hip_atomic_exchange(key, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    last = __shfl(last, 0, 64);
+    if (!last) return;
+    best = __shfl(best, 0, 64);
+    const int n = (int)(best >> 32), m = (int)(uint32_t)best;
+    if (tid == 0) {
+        result[0] = n;
+        result[1] = m;
+        x[n] = m;
+        if (mailbox) { mailbox[0] = n; mailbox[1] = m; }
+    }
+    if (mailbox) {                                         // the accepted drafts and the new token, for the host
+        if (tid < n) mailbox[2 + tid] = x[tid];
+        if (tid == 0) mailbox[2 + n] = m;
     }
 }
 
@@ -334,6 +463,21 @@ int launch_accept_resample(const float* p, const float* q, int32_t* x, int t, in
     return HSD_OK;
 }
 
+// Fused softmax + Alg. 2 (vocabularies up to 32768 only); scratch as for launch_accept_resample (ticket in word 0,
+// the key in bytes 8..15, both zero between launches).
+bool softmax_verify_supported(int vocab) { return vocab <= SMALL_MAX_V; }
+
+int launch_softmax_verify(const float* z, const float* q, int32_t* x, int t, int vocab, float temperature, uint64_t seed,
+                          uint32_t level, uint32_t call, float* p_out, int32_t* result, void* scratch, int32_t* mailbox,
+                          hipStream_t s) {
+    if (vocab > SMALL_MAX_V) HSD_FAIL(HSD_ECAPACITY, "fused softmax + verify: vocabulary %d above %d", vocab, SMALL_MAX_V);
+    softmax_verify_kernel<<<t + 1, SMALL_THREADS, 0, s>>>(z, q, x, t, vocab, temperature, (uint32_t)seed, (uint32_t)(seed >> 32), level,
+                                                          call, p_out, result, (uint32_t*)scratch,
+                                                          (unsigned long long*)((char*)scratch + 8), mailbox);
+    HSD_LAUNCH_CHECK();
+    return HSD_OK;
+}
+
 extern "C" int hsd_accept_resample(const float* p_dev, const float* q_dev, int32_t* x_dev, int t, int vocab, uint64_t seed,
                                    uint32_t level, uint32_t call, int32_t* result_dev, void* scratch_dev, void* stream) {
     if (!p_dev || !x_dev || !result_dev || !scratch_dev) HSD_FAIL(HSD_EINVAL, "hsd_accept_resample: null pointer");
@@ -342,4 +486,15 @@ extern "C" int hsd_accept_resample(const float* p_dev, const float* q_dev, int32
     if (vocab < 1) HSD_FAIL(HSD_EINVAL, "hsd_accept_resample: vocab=%d", vocab);
     return launch_accept_resample(p_dev, q_dev, x_dev, t, vocab, seed, level, call, result_dev, scratch_dev,
                                   (hipStream_t)stream);
+}
+
+extern "C" int hsd_softmax_verify(const float* logits_dev, const float* q_dev, int32_t* x_dev, int t, int vocab, float temperature,
+                                  uint64_t seed, uint32_t level, uint32_t call, float* probs_dev, int32_t* result_dev,
+                                  void* scratch_dev, int32_t* host_mailbox, void* stream) {
+    if (!logits_dev || !x_dev || !result_dev || !scratch_dev) HSD_FAIL(HSD_EINVAL, "hsd_softmax_verify: null pointer");
+    if (t < 0 || t > 64) HSD_FAIL(HSD_EINVAL, "hsd_softmax_verify: t=%d outside 0..64", t);
+    if (t > 0 && !q_dev) HSD_FAIL(HSD_EINVAL, "hsd_softmax_verify: draft rows missing for t=%d", t);
+    if (vocab < 1 || !(temperature >= 0.f)) HSD_FAIL(HSD_EINVAL, "hsd_softmax_verify: vocab=%d temperature=%g", vocab, temperature);
+    return launch_softmax_verify(logits_dev, q_dev, x_dev, t, vocab, temperature, seed, level, call, probs_dev, result_dev,
+                                 scratch_dev, host_mailbox, (hipStream_t)stream);
 }

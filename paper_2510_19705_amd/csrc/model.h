@@ -67,3 +67,7 @@ int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, 
 // kernels_sampler.hip
 int launch_accept_resample(const float* p, const float* q, int32_t* x, int t, int vocab, uint64_t seed, uint32_t level,
                            uint32_t call, int32_t* result, void* scratch, hipStream_t s);
+bool softmax_verify_supported(int vocab);
+int launch_softmax_verify(const float* z, const float* q, int32_t* x, int t, int vocab, float temperature, uint64_t seed,
+                          uint32_t level, uint32_t call, float* p_out, int32_t* result, void* scratch, int32_t* mailbox,
+                          hipStream_t s);

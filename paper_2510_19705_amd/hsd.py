@@ -68,6 +68,7 @@ _SIGS = {
     "hsd_softmax": (_i, [_vp, _vp, _i, _i, _f, _vp]),
     "hsd_sampler_scratch_bytes": (_sz, [_i]),
     "hsd_accept_resample": (_i, [_vp, _vp, _vp, _i, _i, C.c_uint64, C.c_uint32, C.c_uint32, _vp, _vp, _vp]),
+    "hsd_softmax_verify": (_i, [_vp, _vp, _vp, _i, _i, C.c_float, C.c_uint64, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp, _vp]),
     "hsd_kv_layer_bytes": (_sz, [_i, _i, _i, _i]),
     "hsd_attention_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
     "hsd_kv_write": (_i, [_vp, _vp, _i, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp]),
@@ -244,6 +245,23 @@ def accept_resample(p, q, x, seed, level, call):
                                    res.data_ptr(), _sampler_scratch[key].data_ptr(), _stream()))
     n, m = res.cpu().tolist()
     return n, m
+
+
+def softmax_verify(z, q, x, temperature, seed, level, call, want_probs=True, mailbox=None):
+    """hsd_softmax + hsd_accept_resample in one launch.  z [t+1, V] fp32 logits, q [t, V] fp32, x int32 [t+1] (cuda).
+    mailbox: optional pinned int32 host tensor (t + 3 entries).  Returns (n, m, probs or None) after synchronising."""
+    t, V = z.shape[0] - 1, z.shape[1]
+    key = (V, torch.cuda.current_device())
+    if key not in _sampler_scratch:
+        _sampler_scratch[key] = torch.zeros(lib.hsd_sampler_scratch_bytes(V), dtype=torch.uint8, device="cuda")
+    res = torch.empty(2, dtype=torch.int32, device="cuda")
+    probs = torch.empty_like(z) if want_probs else None
+    _check(lib.hsd_softmax_verify(z.data_ptr(), q.data_ptr() if t > 0 else None, x.data_ptr(), t, V, temperature, seed, level,
+                                  call, probs.data_ptr() if want_probs else None, res.data_ptr(),
+                                  _sampler_scratch[key].data_ptr(), mailbox.data_ptr() if mailbox is not None else None,
+                                  _stream()))
+    n, m = res.cpu().tolist()
+    return n, m, probs
 
 
 class KvLayer:

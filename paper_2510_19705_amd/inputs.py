@@ -99,3 +99,16 @@ def make_prob_rows(vocab, t, seed, sigma=2.0, noise=1.0, one_hot=False):
     x = np.array([rng.choice(vocab, p=q[i].astype(np.float64) / q[i].astype(np.float64).sum())
                   for i in range(t)], dtype=np.int32)
     return p, q, x
+
+
+def make_logit_rows(vocab, t, seed, sigma=2.0, noise=1.0):
+    """Verifier logits z [t+1, V] (fp32), draft rows q [t, V] (fp32 probabilities of perturbed logits) and draft
+    tokens x_i ~ q_i: the inputs of the fused softmax + Verify launch."""
+    rng = np.random.default_rng(seed)
+    z = (rng.standard_normal((t + 1, vocab)) * sigma).astype(np.float32)
+    zq = z[:t].astype(np.float64) + rng.standard_normal((t, vocab)) * noise
+    e = np.exp(zq - zq.max(axis=-1, keepdims=True)) if t else zq
+    q = (e / e.sum(axis=-1, keepdims=True)).astype(np.float32) if t else zq.astype(np.float32)
+    x = np.array([rng.choice(vocab, p=q[i].astype(np.float64) / q[i].astype(np.float64).sum())
+                  for i in range(t)], dtype=np.int32)
+    return z, q, x

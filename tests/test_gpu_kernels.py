@@ -104,6 +104,77 @@ def test_accept_resample_degenerate_rows(hsd):
     assert got == ref and got[0] == 0 and got[1] != x[0]
 
 
+# ---- softmax + Verify in one launch ----------------------------------------------------------------
+@pytest.mark.parametrize("V", [50, 2050, 5000, 32000, 32768])
+@pytest.mark.parametrize("t", [0, 1, 5, 16])
+@pytest.mark.parametrize("temperature", [1.0, 0.6])
+def test_softmax_verify_fused(hsd, V, t, temperature):
+    """The fused launch against the oracle (softmax in fp64 rounded to fp32, then Alg. 2 on the Philox stream):
+    equal (n, m) whenever the oracle's decisions keep a margin above the fp32 softmax error (nearly always;
+    counted), probabilities to fp32 accuracy; and bit-identical to the two stand-alone launches always."""
+    import torch
+    say("softmax_verify", V, t, temperature)
+    seed = 0xC0FFEE1234
+    checked = 0
+    n_calls = 16
+    n_hist = np.zeros(t + 2, dtype=int)
+    for call in range(n_calls):
+        z, q, x = inputs.make_logit_rows(V, t, seed=77 * V + 13 * t + call, sigma=2.0 + (call % 3), noise=0.3 + 0.4 * (call % 4))
+        p_ref = decoder.distributions(z.astype(np.float64), temperature).astype(np.float32)
+        ch = specsample.PhiloxChooser(seed)
+        n_ref, m_ref = specsample.verify(list(p_ref), list(q), list(x), ch, level=2, call=call)
+        zd, qd = _cuda(z), _cuda(q) if t else _cuda(z[:0])
+        xd = _cuda(np.concatenate([x, [0]]).astype(np.int32))
+        mailbox = torch.zeros(t + 3, dtype=torch.int32).pin_memory()
+        n, m, probs = hsd.softmax_verify(zd, qd, xd, temperature, seed, 2, call, mailbox=mailbox)
+        got_p = probs.cpu().numpy()
+        assert np.abs(got_p - p_ref).max() <= 2e-6 * p_ref.max() + 1e-9
+        robust = min(ch.accept_margins + [1.0]) > 1e-4 and min(ch.sample_margins + [1.0]) > 3e-6
+        if robust:
+            checked += 1
+            assert (n, m) == (n_ref, m_ref), (V, t, call)
+            n_hist[n] += 1
+        # the two stand-alone launches on the same inputs: identical bits
+        p2 = hsd.softmax(zd, temperature)
+        assert torch.equal(p2, probs)
+        xd2 = _cuda(np.concatenate([x, [0]]).astype(np.int32))
+        assert hsd.accept_resample(p2, qd, xd2, seed, 2, call) == (n, m)
+        assert torch.equal(xd, xd2)
+        assert mailbox[:2].tolist() == [n, m]
+        assert mailbox[2:3 + n].tolist() == list(x[:n]) + [m]
+        # without the probability rows the decision is the same
+        xd3 = _cuda(np.concatenate([x, [0]]).astype(np.int32))
+        assert hsd.softmax_verify(zd, qd, xd3, temperature, seed, 2, call, want_probs=False)[:2] == (n, m)
+    say("  checked against the oracle:", checked, "of", n_calls, "accepted-count histogram", n_hist.tolist())
+    assert checked >= n_calls - 3
+
+
+def test_softmax_verify_greedy_and_limits(hsd):
+    """Temperature 0: one-hot rows, drafts accepted iff they equal the verifier's argmax; vocabularies beyond the
+    one-workgroup limit and bad arguments are refused."""
+    import torch
+    V, t = 4000, 4
+    z, q, x = inputs.make_logit_rows(V, t, seed=3)
+    q = np.zeros_like(q)
+    arg = z.argmax(axis=1)
+    x = arg[:t].astype(np.int32).copy()
+    x[2] = (x[2] + 1) % V                                    # third draft disagrees
+    q[np.arange(t), x] = 1.0
+    xd = _cuda(np.concatenate([x, [0]]).astype(np.int32))
+    n, m, probs = hsd.softmax_verify(_cuda(z), _cuda(q), xd, 0.0, 5, 1, 0)
+    p_ref = decoder.distributions(z.astype(np.float64), 0.0).astype(np.float32)
+    assert (probs.cpu().numpy() == p_ref).all()
+    ref = specsample.verify(list(p_ref), list(q), list(x), specsample.PhiloxChooser(5), 1, 0)
+    assert (n, m) == ref == (2, int(arg[2]))
+    f = hsd.lib.hsd_softmax_verify
+    zz = torch.zeros((2, 40000), device="cuda")
+    xx = torch.zeros(70, dtype=torch.int32, device="cuda")
+    assert f(zz.data_ptr(), zz.data_ptr(), xx.data_ptr(), 1, 40000, 1.0, 0, 0, 0, None, xx.data_ptr(), xx.data_ptr(), None, None) == -2
+    assert f(zz.data_ptr(), None, xx.data_ptr(), 1, 8, 1.0, 0, 0, 0, None, xx.data_ptr(), xx.data_ptr(), None, None) == -1
+    assert f(zz.data_ptr(), zz.data_ptr(), xx.data_ptr(), 65, 8, 1.0, 0, 0, 0, None, xx.data_ptr(), xx.data_ptr(), None, None) == -1
+    assert f(zz.data_ptr(), zz.data_ptr(), xx.data_ptr(), 1, 8, -1.0, 0, 0, 0, None, xx.data_ptr(), xx.data_ptr(), None, None) == -1
+
+
 def test_accept_resample_rejects_bad_arguments(hsd):
     import torch
     p = torch.zeros((2, 8), device="cuda")
