@@ -338,10 +338,16 @@ struct AttnPlan {
     int nsplit, steps_per_split, rpad, qt, qgroups, nw;
 };
 
+// Up to this many query rows per KV head, one 16-row tile per workgroup (more workgroups, each re-reading the
+// head's K/V from L2, instead of more tiles per workgroup): measured faster at every pass size up to 64 tokens and
+// contexts up to 4096 (two tiles per workgroup double the registers and halve what is in flight).  Beyond it two
+// tiles per workgroup; a tuning knob (hsd_tune key 101).
+int g_attn_qt1_rows = 1 << 30;
+
 AttnPlan attn_plan(int batch, int m, int n_q, int n_kv, int hd, int max_len, bool mfma) {
     AttnPlan p;
     const int R = m * (n_q / n_kv);
-    p.qt = R <= 16 ? 1 : (R <= 32 ? 2 : 4);
+    p.qt = R <= 16 || R <= g_attn_qt1_rows ? 1 : 2;
     p.qgroups = ceil_div(R, 16 * p.qt);
     p.rpad = p.qgroups * p.qt * 16;
     int total_steps = ceil_div(max_len, 32);
@@ -398,7 +404,7 @@ int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, 
         attn_mfma_kernel<HD_, QT_><<<grid, p.nw * 64, (size_t)p.nw * QT_ * 16 * (HD_ + 2) * 4, s>>>(                    \
             (const bf16_t*)q, (const bf16_t*)kv_layer, pages, max_pages, pos0_dev, pos0_all, m, n_q, n_kv, scale_log2, \
             p.steps_per_split, p.qgroups, part_o, part_ml, p.rpad, (bf16_t*)att);
-        HSD_ATT(64, 1) HSD_ATT(64, 2) HSD_ATT(64, 4) HSD_ATT(128, 1) HSD_ATT(128, 2) HSD_ATT(128, 4)
+        HSD_ATT(64, 1) HSD_ATT(64, 2) HSD_ATT(128, 1) HSD_ATT(128, 2)
 #undef HSD_ATT
     } else {
         dim3 grid(p.nsplit, n_q, batch * m);

@@ -280,3 +280,11 @@ def test_attention(hsd, B, S, m, n_q, n_kv, hd, bf16):
     err = np.abs(got - ref).max()
     say("  max abs err %.2e" % err)
     assert err < (2e-2 if bf16 else 2e-5)
+    if bf16 and m * (n_q // n_kv) > 16:
+        # the two-tiles-per-workgroup variant (a tuning alternative) on the same inputs
+        hsd.lib.hsd_tune(101, 16, 0, 0)
+        try:
+            got2 = cache.attention(_cuda(q, td), _cuda(pos0), max(lens)).float().cpu().numpy()
+        finally:
+            hsd.lib.hsd_tune(101, 1 << 30, 0, 0)
+        assert np.abs(got2 - ref).max() < 2e-2
