@@ -180,7 +180,7 @@ int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int
 
 /* Overrides of the GEMM launch heuristics, for tuning sweeps (process-wide; 0 restores the heuristic).
  * key 0..3 = epilogue kind (store, residual, SwiGLU, RoPE) of the tiled kernel: nt column tiles per
- * workgroup, ksplit workgroups along K, waves per workgroup.  key 100: nt = most tokens the row kernel
+ * workgroup, ksplit workgroups along K (waves is ignored: workgroups have 8 waves).  key 100: nt = most tokens the row kernel
  * serves before the MFMA kernel takes over on row-major weights.  key 101: nt = most query rows per KV head
  * (tokens x query heads per KV head) for which the MFMA attention gives each workgroup one 16-row tile; above
  * it, two. */

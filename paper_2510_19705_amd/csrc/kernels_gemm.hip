@@ -106,18 +106,33 @@ __device__ __forceinline__ void ss_add(unsigned long long* ss, int m, float sum_
 }
 
 // RoPE on one (dim j, dim j + hd/2) pair of token row ml of `head` (q heads, then k heads, then v heads, which are
-// not rotated), then the q store or the KV-cache append through the page table.  Angle in fp64.
-__device__ __forceinline__ void rope_store(const GemmArgs& g, int head, int j, int ml, float a, float b) {
+// not rotated), then the q store or the KV-cache append through the page table.  Angle in fp64.  In two parts:
+// rope_prepare needs only the element's coordinates (the rotation and the page-table entry), so the kernels run it
+// before their weight stream, whose latency hides the fp64 sincos and the page lookup; rope_finish needs the sums.
+struct RopePre {
+    double cs, sn;
+    int page;
+};
+
+__device__ __forceinline__ RopePre rope_prepare(const GemmArgs& g, int head, int j, int ml) {
+    RopePre r{1.0, 0.0, 0};
+    const int pos = g.pos0 + ml;
+    if (head < g.n_q + g.n_kv) {
+        const double ang = (double)pos * exp2(-2.0 * (double)j / (double)g.hd * log2((double)g.rope_base));
+        sincos(ang, &r.sn, &r.cs);
+    }
+    if (head >= g.n_q) r.page = g.pages[pos / HSD_KV_PAGE];
+    return r;
+}
+
+__device__ __forceinline__ void rope_finish(const GemmArgs& g, int head, int j, int ml, float a, float b, const RopePre& pre) {
     const int hd = g.hd, half = hd >> 1;
     const int pos = g.pos0 + ml;
     const bool is_q = head < g.n_q, is_v = head >= g.n_q + g.n_kv;
     float ra = a, rb = b;
     if (!is_v) {
-        const double ang = (double)pos * exp2(-2.0 * (double)j / (double)hd * log2((double)g.rope_base));
-        double sn, cs;
-        sincos(ang, &sn, &cs);
-        ra = (float)((double)a * cs - (double)b * sn);
-        rb = (float)((double)b * cs + (double)a * sn);
+        ra = (float)((double)a * pre.cs - (double)b * pre.sn);
+        rb = (float)((double)b * pre.cs + (double)a * pre.sn);
     }
     if (is_q) {
         bf16_t* dst = g.out_bf16 + ((size_t)ml * g.n_q + head) * hd;
@@ -126,8 +141,8 @@ __device__ __forceinline__ void rope_store(const GemmArgs& g, int head, int j, i
         return;
     }
     const int kvh = is_v ? head - g.n_q - g.n_kv : head - g.n_q;
-    const int page = g.pages[pos / HSD_KV_PAGE], ip = pos % HSD_KV_PAGE;
-    bf16_t* blk = g.kv_layer + (size_t)page * kv_page_elems(g.n_kv, hd) + (size_t)kvh * 2 * kv_block_elems(hd) +
+    const int ip = pos % HSD_KV_PAGE;
+    bf16_t* blk = g.kv_layer + (size_t)pre.page * kv_page_elems(g.n_kv, hd) + (size_t)kvh * 2 * kv_block_elems(hd) +
                   (is_v ? kv_block_elems(hd) : 0);
     if (is_v) {
         blk[kv_v_index(ip, j, hd)] = (bf16_t)ra;
@@ -181,6 +196,49 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
     }
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
     if (g.ss_zero && blockIdx.x == 0 && blockIdx.y == 0) ss_clear(g.ss_zero, tid, blockDim.x);   // for the next producer
+
+    // ---- operands of this thread's epilogue elements: requested, and the rotary angles evaluated, before the
+    // weight stream, whose latency covers them (workgroups are 512 threads; element i of thread tid is
+    // tid + 512 i in the epilogue's order) ----
+    constexpr int OUTS = (EPI == EPI_STORE || EPI == EPI_RESID) ? TOTAL : MT * (NT / 2) * 256;
+    constexpr int EPT = (OUTS + 511) / 512;
+    float pre_inv[EPT], pre_x[EPT], pre_nw[EPT];
+    RopePre pre_rope[EPT];
+#pragma unroll
+    for (int i = 0; i < EPT; ++i) {
+        const int idx = tid + 512 * i;
+        pre_inv[i] = 1.f;
+        pre_x[i] = 0.f;
+        pre_nw[i] = 0.f;
+        pre_rope[i] = RopePre{1.0, 0.0, 0};
+        if (idx >= OUTS) continue;
+        const int tile = idx >> 8, rem = idx & 255, r = rem >> 6, l = rem & 63;
+        if constexpr (EPI == EPI_STORE || EPI == EPI_RESID) {
+            const int mt = tile / NT, nt = tile % NT;
+            const int ml = mt * 16 + 4 * (l >> 4) + r;
+            const int n = (ntile0 + nt) * 16 + (l & 15);
+            if (ml < M && n < N) {
+                if constexpr (EPI == EPI_RESID) {
+                    pre_x[i] = g.out_f32[(size_t)ml * N + n];
+                    if (g.out_bf16) pre_nw[i] = g.norm_w[n];
+                } else if (g.ss_in) {
+                    pre_inv[i] = row_inv_rms(g.ss_in, ml, K, g.eps);
+                }
+            }
+        } else {
+            const int mt = tile / (NT / 2), jp = tile % (NT / 2);
+            const int ml = mt * 16 + 4 * (l >> 4) + r;
+            if (ml < M) {
+                pre_inv[i] = row_inv_rms(g.ss_in, ml, K, g.eps);
+                if constexpr (EPI == EPI_ROPE) {
+                    const int pairs_per_head = g.hd >> 5;
+                    const int gp = (ntile0 >> 1) + jp;
+                    const int head = gp / pairs_per_head, j = (gp % pairs_per_head) * 16 + (l & 15);
+                    if (head < g.n_q + 2 * g.n_kv) pre_rope[i] = rope_prepare(g, head, j, ml);
+                }
+            }
+        }
+    }
 
     int kt = kb;
     for (; kt + U <= ke; kt += U) {
@@ -262,7 +320,10 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
     // ---- epilogue on the final sums red[tile][r][lane] ----
     if constexpr (EPI == EPI_STORE || EPI == EPI_RESID) {
         float* sq = red + nwaves * TOTAL;                  // [MT*16][NT*16] squares of the new residual values
-        for (int idx = tid; idx < TOTAL; idx += blockDim.x) {
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+            const int idx = tid + 512 * i;
+            if (idx >= TOTAL) continue;
             const float s = red[idx];
             const int tile = idx >> 8, rem = idx & 255, r = rem >> 6, l = rem & 63;
             const int mt = tile / NT, nt = tile % NT;
@@ -272,10 +333,10 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
             if (ml < M && n < N) {
                 float* dst = g.out_f32 + (size_t)ml * N + n;
                 if constexpr (EPI == EPI_RESID) {
-                    v = *dst + s;
-                    if (g.out_bf16) g.out_bf16[(size_t)ml * N + n] = (bf16_t)(v * g.norm_w[n]);
+                    v = pre_x[i] + s;
+                    if (g.out_bf16) g.out_bf16[(size_t)ml * N + n] = (bf16_t)(v * pre_nw[i]);
                 } else {
-                    v = g.ss_in ? s * row_inv_rms(g.ss_in, ml, K, g.eps) : s;
+                    v = s * pre_inv[i];
                 }
                 *dst = v;
             }
@@ -292,34 +353,36 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
     } else if constexpr (EPI == EPI_SWIGLU) {
         // tiles alternate gate / up; N is the fused width 2F
         const int F = N >> 1;
-        constexpr int HALF = MT * (NT / 2) * 256;
-        for (int idx = tid; idx < HALF; idx += blockDim.x) {
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+            const int idx = tid + 512 * i;
+            if (idx >= OUTS) continue;
             const int pair = idx >> 8, rem = idx & 255, r = rem >> 6, l = rem & 63;
             const int mt = pair / (NT / 2), j = pair % (NT / 2);
             const int ml = mt * 16 + 4 * (l >> 4) + r;
             const int f = ((ntile0 >> 1) + j) * 16 + (l & 15);
             if (ml < M && f < F) {
-                const float inv = row_inv_rms(g.ss_in, ml, K, g.eps);
-                const float gt = red[(mt * NT + 2 * j) * 256 + rem] * inv;
-                const float up = red[(mt * NT + 2 * j + 1) * 256 + rem] * inv;
+                const float gt = red[(mt * NT + 2 * j) * 256 + rem] * pre_inv[i];
+                const float up = red[(mt * NT + 2 * j + 1) * 256 + rem] * pre_inv[i];
                 g.out_bf16[(size_t)ml * F + f] = (bf16_t)(gt / (1.f + __expf(-gt)) * up);
             }
         }
     } else {
         // EPI_ROPE: tile pairs hold dims [16 jb, 16 jb + 16) and their partners hd/2 further of one head
-        const int hd = g.hd, pairs_per_head = hd >> 5;
-        constexpr int HALF = MT * (NT / 2) * 256;
-        for (int idx = tid; idx < HALF; idx += blockDim.x) {
+        const int pairs_per_head = g.hd >> 5;
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+            const int idx = tid + 512 * i;
+            if (idx >= OUTS) continue;
             const int pair = idx >> 8, rem = idx & 255, r = rem >> 6, l = rem & 63;
             const int mt = pair / (NT / 2), jp = pair % (NT / 2);
             const int ml = mt * 16 + 4 * (l >> 4) + r;
             const int gp = (ntile0 >> 1) + jp;                      // global pair index
             const int head = gp / pairs_per_head, j = (gp % pairs_per_head) * 16 + (l & 15);
             if (ml >= M || head >= g.n_q + 2 * g.n_kv) continue;
-            const float inv = row_inv_rms(g.ss_in, ml, K, g.eps);
-            const float a = red[(mt * NT + 2 * jp) * 256 + rem] * inv;
-            const float b = red[(mt * NT + 2 * jp + 1) * 256 + rem] * inv;
-            rope_store(g, head, j, ml, a, b);
+            const float a = red[(mt * NT + 2 * jp) * 256 + rem] * pre_inv[i];
+            const float b = red[(mt * NT + 2 * jp + 1) * 256 + rem] * pre_inv[i];
+            rope_finish(g, head, j, ml, a, b, pre_rope[i]);
         }
     }
 }
@@ -346,6 +409,27 @@ __global__ __launch_bounds__(512) void gemv_bf16_kernel(const GemmArgs g) {
     const int per = (KC + nwaves - 1) / nwaves;
     const int c0 = wave * per, c1 = min(KC, c0 + per);
     if (g.ss_zero && blockIdx.x == 0) ss_clear(g.ss_zero, tid, blockDim.x);
+
+    // epilogue operands first: their latency (and the rotary sincos) hides behind the weight stream
+    const int er = tid / MB, em = tid % MB;            // epilogue element of this thread: row er, token em
+    const bool active = tid < R * MB && em < M && n0 + er < N;
+    float pre_inv = 1.f, pre_x = 0.f, pre_nw = 0.f;
+    RopePre pre_rope{1.0, 0.0, 0};
+    if constexpr (EPI == EPI_STORE) {
+        if (active && g.ss_in) pre_inv = row_inv_rms(g.ss_in, em, K, g.eps);
+    } else if constexpr (EPI == EPI_RESID) {
+        if (active) {
+            pre_x = g.out_f32[(size_t)em * N + n0 + er];
+            if (g.out_bf16) pre_nw = g.norm_w[n0 + er];
+        }
+    } else {
+        const int half = g.hd >> 1;
+        const int head = blockIdx.x / half, j = blockIdx.x % half;
+        if (tid < M && head < g.n_q + 2 * g.n_kv) {
+            pre_inv = row_inv_rms(g.ss_in, tid, K, g.eps);
+            pre_rope = rope_prepare(g, head, j, tid);
+        }
+    }
 
     float acc[MB];
 #pragma unroll
@@ -374,21 +458,19 @@ __global__ __launch_bounds__(512) void gemv_bf16_kernel(const GemmArgs g) {
         if (cl == 0) red[wave][r][m] = acc[m];
     }
     __syncthreads();
-    const int er = tid / MB, em = tid % MB;            // epilogue element of this thread: row er, token em
-    const bool active = tid < R * MB && em < M && n0 + er < N;
     float s = 0.f;
     if (tid < R * MB)
         for (int w = 0; w < nwaves; ++w) s += red[w][er][em];
 
     if constexpr (EPI == EPI_STORE) {
-        if (active) g.out_f32[(size_t)em * N + n0 + er] = g.ss_in ? s * row_inv_rms(g.ss_in, em, K, g.eps) : s;
+        if (active) g.out_f32[(size_t)em * N + n0 + er] = s * pre_inv;
     } else if constexpr (EPI == EPI_RESID) {
         float v = 0.f;
         if (active) {
             const size_t at = (size_t)em * N + n0 + er;
-            v = g.out_f32[at] + s;
+            v = pre_x + s;
             g.out_f32[at] = v;
-            if (g.out_bf16) g.out_bf16[at] = (bf16_t)(v * g.norm_w[n0 + er]);
+            if (g.out_bf16) g.out_bf16[at] = (bf16_t)(v * pre_nw);
         }
         if (tid < R * MB) sq[er][em] = v * v;
         __syncthreads();
@@ -404,10 +486,7 @@ __global__ __launch_bounds__(512) void gemv_bf16_kernel(const GemmArgs g) {
         __syncthreads();
         const int half = g.hd >> 1;
         const int head = blockIdx.x / half, j = blockIdx.x % half;
-        if (tid < M && head < g.n_q + 2 * g.n_kv) {
-            const float inv = row_inv_rms(g.ss_in, tid, K, g.eps);
-            rope_store(g, head, j, tid, sq[0][tid] * inv, sq[1][tid] * inv);
-        }
+        if (tid < M && head < g.n_q + 2 * g.n_kv) rope_finish(g, head, j, tid, sq[0][tid] * pre_inv, sq[1][tid] * pre_inv, pre_rope);
     }
 }
 
@@ -459,7 +538,6 @@ __global__ void gemm_f32_kernel(const float* __restrict__ x, const float* __rest
 // ------------------------------------------------------------------------------------------------
 static int g_tune_nt[4] = {0, 0, 0, 0};      // optional overrides per epilogue kind (0 = heuristic)
 static int g_tune_ksplit[4] = {0, 0, 0, 0};
-static int g_tune_waves = 0;
 int g_gemv_max_m = 2;            // most tokens of a pass served from the row-major copies
 
 void gemm_tune(int epilogue, int nt, int ksplit, int waves) {
@@ -469,7 +547,7 @@ void gemm_tune(int epilogue, int nt, int ksplit, int waves) {
         g_tune_nt[epilogue] = nt;
         g_tune_ksplit[epilogue] = ksplit;
     }
-    g_tune_waves = waves;
+    (void)waves;
 }
 
 GemmPlan gemm_plan(int m, int n, int k, int epi) {
@@ -493,9 +571,7 @@ GemmPlan gemm_plan(int m, int n, int k, int epi) {
     if (p.ksplit > 8) p.ksplit = 8;
     if (p.ksplit > KT) p.ksplit = KT;
     if (p.ksplit < 1) p.ksplit = 1;
-    const int per_wg = ceil_div(KT, p.ksplit);
-    p.waves = g_tune_waves ? g_tune_waves : 8;
-    if (p.waves > per_wg) p.waves = per_wg;
+    p.waves = 8;                 // always 512 threads: the epilogue addresses its elements by that stride
     return p;
 }
 
