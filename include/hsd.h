@@ -183,7 +183,8 @@ int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int
  * workgroup, ksplit workgroups along K (waves is ignored: workgroups have 8 waves).  key 100: nt = most tokens the row kernel
  * serves before the MFMA kernel takes over on row-major weights.  key 101: nt = most query rows per KV head
  * (tokens x query heads per KV head) for which the MFMA attention gives each workgroup one 16-row tile; above
- * it, two. */
+ * it, two.  key 102: nt = K/V steps per wave the attention plans for when it splits a sequence over workgroups
+ * (0: default, which also caps the split at about 160 workgroups). */
 int hsd_tune(int key, int nt, int ksplit, int waves);
 
 /* ---------------------------------------------------------------------------------------------

@@ -28,11 +28,10 @@ struct KvTiles {
 };
 
 template <int HD, int SP>
-__device__ __forceinline__ void load_kv(KvTiles<HD, SP>& t, const bf16_t* __restrict__ kv_layer, const int32_t* __restrict__ pages,
-                                        size_t page_base, int step, int n_kv, int g, int lane) {
+__device__ __forceinline__ void load_kv(KvTiles<HD, SP>& t, const bf16_t* __restrict__ kv_layer, int page, int step, int n_kv,
+                                        int g, int lane) {
     constexpr int KC = HD / 32, DT = HD / 16;
     const int p0 = step * 32 * SP;
-    const int page = pages[page_base + p0 / HSD_KV_PAGE];
     const int inpage = p0 % HSD_KV_PAGE;
     const size_t blk = kv_block_elems(HD);
     const bf16_t* kblk = kv_layer + ((size_t)page * n_kv + g) * 2 * blk;
@@ -74,13 +73,20 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const bf16_t* __restrict
     const int step0 = split * steps_per_split;
     const int step1 = min(total_steps, step0 + steps_per_split);
 
-    // K/V of this wave's first two steps are requested before anything else
-    const size_t page_base = (size_t)b * max_pages;
+    // K/V of this wave's first two steps are requested before anything else.  The page-table entry a load needs
+    // is fetched one round earlier (pg[i]: the page of the step buffer i loads next), so that no K/V request waits
+    // behind a page lookup.
+    const int32_t* ptab = pages + (size_t)b * max_pages;
+    auto page_of = [&](int st) -> int { return st < step1 ? ptab[st * (32 * SP) / HSD_KV_PAGE] : 0; };
     KvTiles<HD, SP> buf[2];
+    int pg[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) pg[i] = page_of(step0 + wave + i * NW);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int st = step0 + wave + i * NW;
-        if (st < step1) load_kv<HD, SP>(buf[i], kv_layer, pages, page_base, st, n_kv, g, lane);
+        if (st < step1) load_kv<HD, SP>(buf[i], kv_layer, pg[i], st, n_kv, g, lane);
+        pg[i] = page_of(st + 2 * NW);
     }
 
     bf16x8 qreg[QT][KC];
@@ -162,7 +168,10 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const bf16_t* __restrict
                     }
                 }
                 const int nxt = step + 2 * NW;
-                if (nxt < step1) load_kv<HD, SP>(buf[i], kv_layer, pages, page_base, nxt, n_kv, g, lane);
+                if (nxt < step1) {
+                    load_kv<HD, SP>(buf[i], kv_layer, pg[i], nxt, n_kv, g, lane);
+                    pg[i] = page_of(nxt + 2 * NW);
+                }
             }
         }
     }
@@ -343,6 +352,7 @@ struct AttnPlan {
 // contexts up to 4096 (two tiles per workgroup double the registers and halve what is in flight).  Beyond it two
 // tiles per workgroup; a tuning knob (hsd_tune key 101).
 int g_attn_qt1_rows = 1 << 30;
+int g_attn_steps_per_wave = 0;      // tuning override (hsd_tune key 102); 0: the default below
 
 AttnPlan attn_plan(int batch, int m, int n_q, int n_kv, int hd, int max_len, bool mfma) {
     AttnPlan p;
@@ -357,10 +367,14 @@ AttnPlan attn_plan(int batch, int m, int n_q, int n_kv, int hd, int max_len, boo
         p.nw = 65536 / per_wave;
         if (p.nw > 8) p.nw = 8;
         if (p.nw < 1) p.nw = 1;
-        // one workgroup per (head, query group) while its waves get at most ~6 steps each; beyond that
-        // split the sequence over workgroups (at most 64) and merge
-        int want = ceil_div(total_steps, p.nw * (hd == 64 ? 3 : 6));
-        const int cap = 2048 / (batch * n_kv * p.qgroups) > 0 ? 2048 / (batch * n_kv * p.qgroups) : 1;
+        // one workgroup per (head, query group) while its waves get at most ~6 steps each; beyond that split the
+        // sequence over workgroups and merge, but only up to about 160 workgroups in all: measured on sequences of
+        // 4096 to 32768 positions, 100-250 fat workgroups stream K/V faster than a thousand thin ones (the partial
+        // states and their merge cost more than the extra parallelism gives)
+        const int spw = g_attn_steps_per_wave > 0 ? g_attn_steps_per_wave : (hd == 64 ? 3 : 6);
+        int want = ceil_div(total_steps, p.nw * spw);
+        const int heads = batch * n_kv * p.qgroups;
+        const int cap = g_attn_steps_per_wave > 0 ? 64 : (160 / heads > 0 ? 160 / heads : 1);
         if (want > cap) want = cap;
         if (want > 64) want = 64;
         if (want < 1) want = 1;
