@@ -247,6 +247,37 @@ def main():
                      "best_single_draft_predicted": {"exit": EXITS[sdr] if sdr >= 0 else None, "T": sT, "tokens_per_s": 1e3 / slat},
                      "hsd_T_best_predicted_tokens_per_s": 1e3 / hsd.expected_latency(cost, [a01, a12], list(T_best), True)}
 
+    # ---- calibration pass (Sec. 5.1) over the prompt + the tokens just generated: all-pairs acceptance rates of eight
+    # candidate exits and their pass costs, the selection of Sec. 4 on them, and the selected hierarchy measured -------
+    calibration = None
+    if not args.no_sweep:
+        h.rewind(PROMPT)
+        gen_tokens, _ = h.generate(GEN)
+        seq = torch.from_numpy(np.concatenate([prompt[:PROMPT], np.asarray(gen_tokens)]).astype(np.int32)).cuda()
+        cand = [1, 2, 3, 4, 6, 8, 12, 16]
+        alpha, cost = model.calibrate(cand, seq, PROMPT, TEMPERATURE, cost_rows=4)
+        lat, sigma, Tsel = hsd.select_hierarchy(list(cost), alpha, 15)
+        slat, sdr, sT = hsd.best_single_draft(list(cost), alpha, 15)
+        tri = max(alpha[i, j] + alpha[j, k] - alpha[i, k] - 1 for i in range(len(cand)) for j in range(len(cand))
+                  for k in range(len(cand)) if len({i, j, k}) == 3)
+        calibration = {"exits": cand, "positions": GEN, "alpha": [[round(float(v), 4) for v in row] for row in alpha],
+                       "cost_ms": [round(float(c), 4) for c in cost], "triangle_violation": float(tri),
+                       "selected_levels": [cand[i] for i in sigma], "selected_T": list(Tsel),
+                       "predicted_tokens_per_s": 1e3 / lat,
+                       "best_single_draft_predicted": {"exit": cand[sdr] if sdr >= 0 else None, "T": sT, "tokens_per_s": 1e3 / slat}}
+        try:
+            if len(sigma) > 1:
+                r = measure("calibrated_selection", [cand[i] for i in sigma], list(Tsel))
+                calibration["measured_tokens_per_s"] = r["tokens_per_s"]
+                calibration["measured_acceptance"] = r["acceptance"]
+                log("calibrated selection %s T %s: predicted %.1f, measured %.1f tok/s" % (calibration["selected_levels"], Tsel,
+                                                                                          1e3 / lat, r["tokens_per_s"]))
+            if sdr >= 0 and [cand[sdr], 16] != calibration["selected_levels"]:
+                r = measure("calibrated_single_draft", [cand[sdr], 16], [sT])
+                calibration["best_single_draft_measured_tokens_per_s"] = r["tokens_per_s"]
+        except hsd.HsdError as e:                 # e.g. a selection whose batches exceed the 64 rows of a pass
+            calibration["error"] = str(e)
+
     # ---- verify passes of a larger shape: four layers of the 7B-shaped stack (32 x 128 heads, FFN 11008) ------------
     big = None if args.no_sweep else layer_stack_microbench(hsd, inputs, torch, "7b", 4, 4096, (1, 4, 8, 16))
 
@@ -291,6 +322,7 @@ def main():
         "sweep": {k: round(v["tokens_per_s"], 1) for k, v in results.items()},
         "verify_pass": passes,
         "latency_model": selection,
+        "calibration": calibration,
         "verify_pass_7b_shaped_4_layers_ctx4096": big,
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -86,6 +86,13 @@ int hsd_model_set_pages(hsd_model*, const int32_t* page_table, int n_pages);
 int hsd_model_pass(hsd_model*, const int32_t* tokens_dev, int pos0, int m, int exit_layer,
                    int n_logit_rows, float* logits_dev);
 
+/* The same pass through the deepest of several exits, emitting every listed exit's logits on the way (Sec. 5.1:
+ * the output distributions of all candidate layers are recorded during one forward pass): exits = n_exits ascending
+ * layer counts; logits_dev [n_exits, n_logit_rows, vocab].  Each exit's rows equal, bit for bit, what
+ * hsd_model_pass gives for that exit alone.  bf16 models need ffn >= d (HSD_ECAPACITY otherwise). */
+int hsd_model_pass_exits(hsd_model*, const int32_t* tokens_dev, int pos0, int m, const int* exits, int n_exits,
+                         int n_logit_rows, float* logits_dev);
+
 /* Per-site device timing of a model's passes, for roofline accounting.  Between begin and end every
  * launch at the sites below is bracketed by two events on the model's stream (up to max_launches
  * launches, later ones are not timed; the brackets add a little host and device overhead, so throughput
@@ -146,6 +153,24 @@ int hsd_accept_resample(const float* p_dev, const float* q_dev, int32_t* x_dev, 
 int hsd_softmax_verify(const float* logits_dev, const float* q_dev, int32_t* x_dev, int t, int vocab,
                        float temperature, uint64_t seed, uint32_t level, uint32_t call, float* probs_dev,
                        int32_t* result_dev, void* scratch_dev, int32_t* host_mailbox, void* stream);
+
+/* Acceptance rate of one context between every pair of n_dists distributions (Sec. 2: sum_x min(p(x), q(x)) =
+ * 1 - TV(p, q)): rows_dev [n_dists, n_rows, vocab] fp32; out_dev [n_dists (n_dists - 1) / 2, n_rows] fp64, pairs
+ * (i < j) in the order (0,1), (0,2), .., (1,2), ..; sums in fp64 in a fixed order.  2 <= n_dists <= 64. */
+int hsd_overlap(const float* rows_dev, int n_dists, int n_rows, int vocab, double* out_dev, void* stream);
+
+/* Calibration pass of Sec. 5.1: teacher-forced run of the model over tokens_dev [n_tokens] (device int32); the first
+ * n_ctx positions are context only, every later position contributes the distributions of all listed exits
+ * (hsd_model_pass_exits, softmax at `temperature`) to alpha_out [n_exits, n_exits] (host, row-major, symmetric, unit
+ * diagonal) = mean over those positions of hsd_overlap: the empirical pairwise acceptance rates, which satisfy
+ * alpha_ij + alpha_jk <= alpha_ik + 1.  If cost_ms_out (host, [n_exits]) is not null it receives the mean time of
+ * a pass of cost_rows tokens at the end of the sequence through each exit (the costs c_i of Sec. 3.2).  Overwrites
+ * the model's KV cache for positions 0..n_tokens-1; synchronises the model's stream.  Workspace from
+ * hsd_calibrate_workspace_bytes (0 on bad arguments). */
+size_t hsd_calibrate_workspace_bytes(const hsd_model*, int n_exits, int n_tokens, int n_ctx);
+int hsd_calibrate(hsd_model*, const int* exits, int n_exits, const int32_t* tokens_dev, int n_tokens, int n_ctx,
+                  float temperature, int cost_rows, void* workspace_dev, size_t workspace_bytes, double* alpha_out,
+                  double* cost_ms_out);
 
 /* k-query attention over a paged KV cache, for a batch of sequences (the pass uses it with batch 1).
  * One layer's cache: hsd_kv_layer_bytes(n_pages, ...) bytes; pages_dev [batch, max_pages] int32 gives the physical

@@ -67,6 +67,14 @@ __global__ void resid_rmsnorm_kernel(float* __restrict__ x, const float* __restr
     for (int i = threadIdx.x; i < d; i += blockDim.x) o[i] = from_f32<T>(xr[i] * w[i] * inv);
 }
 
+// out[r, :] = bf16(x[r, :] * w): the rows an exit's head GEMM reads when the pass goes on to deeper layers (the
+// producing GEMM has stored x * w of the NEXT layer's norm; the rows' sums of squares are the same for both).
+__global__ void scale_rows_bf16_kernel(const float* __restrict__ x, const float* __restrict__ w, bf16_t* __restrict__ out, int d) {
+    const float* xr = x + (size_t)blockIdx.x * d;
+    bf16_t* o = out + (size_t)blockIdx.x * d;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) o[i] = (bf16_t)(xr[i] * w[i]);
+}
+
 // qkv = sum of the QKV GEMM partials [ksplit][m][(n_q + 2 n_kv) hd]; rotates q and k (pairs j, j+hd/2 by
 // angle pos * base^(-2j/hd), computed in fp64), writes q [m][n_q][hd] and appends k, v at pos0 + m
 // through the page table.  grid (m, n_q + 2 n_kv), 64 threads.
@@ -186,6 +194,12 @@ int launch_resid_rmsnorm(float* x, const float* part, int ksplit, int part_rows,
         resid_rmsnorm_kernel<bf16_t><<<rows, 256, 0, s>>>(x, part, ksplit, part_rows, part_row0, w, (bf16_t*)xn, d, eps, row0);
     else
         resid_rmsnorm_kernel<float><<<rows, 256, 0, s>>>(x, part, ksplit, part_rows, part_row0, w, (float*)xn, d, eps, row0);
+    HSD_LAUNCH_CHECK();
+    return HSD_OK;
+}
+
+int launch_scale_rows_bf16(const float* x, const float* w, void* out, int rows, int d, hipStream_t s) {
+    scale_rows_bf16_kernel<<<rows, 256, 0, s>>>(x, w, (bf16_t*)out, d);
     HSD_LAUNCH_CHECK();
     return HSD_OK;
 }

@@ -50,6 +50,10 @@ struct hsd_model {
 
 int model_pass(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows, int exit_layer, int n_logit_rows,
                float* logits_dev);
+// The same pass through the deepest of `exits` (ascending layer counts), with the last n_logit_rows rows' logits of
+// every listed exit: logits_dev [n_exits][n_logit_rows][vocab].
+int model_pass_exits(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows, const int* exits, int n_exits,
+                     int n_logit_rows, float* logits_dev);
 
 // kernels_layer.hip
 int launch_embed(const int32_t* tok, const void* E, float* x, int m, int d, int vocab, int dtype, unsigned long long* ss,
@@ -59,6 +63,7 @@ int launch_resid_rmsnorm(float* x, const float* part, int ksplit, int part_rows,
 int launch_rope_kv(const float* part, int ksplit, int m, void* q, void* kv_layer, const int32_t* pages, int pos0, int n_q,
                    int n_kv, int hd, float rope_base, int dtype, hipStream_t s);
 int launch_softmax(const float* z, float* p, int rows, int vocab, float temperature, hipStream_t s);
+int launch_scale_rows_bf16(const float* x, const float* w, void* out, int rows, int d, hipStream_t s);
 // kernels_attn.hip
 size_t attn_workspace_bytes(int batch, int m, int n_q, int n_kv, int hd, int max_len);
 int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, int max_pages, const int32_t* pos0_dev,

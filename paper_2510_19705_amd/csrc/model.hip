@@ -306,10 +306,14 @@ extern "C" int hsd_model_load_head(hsd_model* m, const void* embed_dev, const vo
 }
 
 // fp32 storage: plain kernels, one per step (the small correctness configuration).
-static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, int exit_layer, int n_logit_rows, float* logits) {
+static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
+                    float* logits) {
     const hsd_model_desc& d = m->desc;
     hipStream_t s = m->stream;
     const int nq = d.n_q * d.hd, nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
+    const int exit_layer = exits[n_exits - 1];
+    const size_t logit_stride = (size_t)n_logit_rows * d.vocab;
+    int ei = 0;
     int rc;
     if ((rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, nullptr, nullptr, nullptr, nullptr, s))) return rc;
     const float* pending = nullptr;     // output of the previous down projection, not yet added to x
@@ -341,12 +345,24 @@ static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, int ex
             if ((rc = launch_gemm_f32((const float*)m->h, (const float*)L.wd, m->part, rows, d.d, d.ffn, false, s))) return rc;
         }
         pending = m->part;
+        if (l + 1 == exits[ei] && l + 1 < exit_layer) {
+            // an exit on the way: the pending projection goes into x for every row (the deeper layers need them
+            // all), the final norm of all rows into xn, the head reads the logit rows
+            if (n_logit_rows > 0) {
+                if ((rc = launch_resid_rmsnorm(m->x, pending, 1, rows, 0, m->norm_f, m->xn, rows, 0, d.d, d.eps, d.dtype, s))) return rc;
+                pending = nullptr;
+                SiteTimer t(m, HSD_SITE_HEAD);
+                if ((rc = launch_gemm_f32((const float*)m->xn + (size_t)(rows - n_logit_rows) * d.d, (const float*)m->head,
+                                          logits + ei * logit_stride, n_logit_rows, d.vocab, d.d, false, s))) return rc;
+            }
+            ++ei;
+        }
     }
     if (n_logit_rows == 0) return HSD_OK;
     const int row0 = rows - n_logit_rows;
     if ((rc = launch_resid_rmsnorm(m->x, pending, 1, rows, row0, m->norm_f, m->xn, n_logit_rows, row0, d.d, d.eps, d.dtype, s))) return rc;
     SiteTimer t(m, HSD_SITE_HEAD);
-    return launch_gemm_f32((const float*)m->xn, (const float*)m->head, logits, n_logit_rows, d.vocab, d.d, false, s);
+    return launch_gemm_f32((const float*)m->xn, (const float*)m->head, logits + ei * logit_stride, n_logit_rows, d.vocab, d.d, false, s);
 }
 
 // bf16 storage: five launches per layer.  RoPE and the KV append live in the QKV epilogue, SwiGLU in the
@@ -391,20 +407,24 @@ static int launch_site_bf16(hsd_model* m, int site, int l, int pos0, int rows, c
     }
 }
 
-static int launch_head_bf16(hsd_model* m, int rows, int n_logit_rows, float* logits) {
+static int launch_head_bf16(hsd_model* m, const void* xn, int rows, int n_logit_rows, float* logits) {
     const hsd_model_desc& d = m->desc;
     const int row0 = rows - n_logit_rows;
     GemmArgs g = {};
     g.part = m->part; g.tickets = m->tickets; g.eps = d.eps;
     g.M = n_logit_rows;
-    g.a = (const bf16_t*)m->xn + (size_t)row0 * d.d; g.ss_in = m->ss[0] + row0;
+    g.a = (const bf16_t*)xn + (size_t)row0 * d.d; g.ss_in = m->ss[0] + row0;
     g.wp = (const bf16x8*)m->head; g.N = d.vocab; g.K = d.d;
     g.out_f32 = logits;
     return launch_gemm_bf16(g, EPI_STORE, gemm_plan(n_logit_rows, d.vocab, d.d, EPI_STORE), m->stream);
 }
 
-static int pass_bf16(hsd_model* m, const int32_t* tok, int pos0, int rows, int exit_layer, int n_logit_rows, float* logits) {
+static int pass_bf16(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
+                     float* logits) {
     const hsd_model_desc& d = m->desc;
+    const int exit_layer = exits[n_exits - 1];
+    const size_t logit_stride = (size_t)n_logit_rows * d.vocab;
+    int ei = 0;
     int rc;
     if ((rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, m->ss[0], m->ss[1], m->layers[0].norm1, m->xn, m->stream))) return rc;
     for (int l = 0; l < exit_layer; ++l) {
@@ -413,10 +433,20 @@ static int pass_bf16(hsd_model* m, const int32_t* tok, int pos0, int rows, int e
             SiteTimer t(m, site);
             if ((rc = launch_site_bf16(m, site, l, pos0, rows, next_norm))) return rc;
         }
+        if (l + 1 == exits[ei] && l + 1 < exit_layer) {
+            // an exit on the way: m->xn holds x scaled by the next layer's norm weights, the head needs the final
+            // norm's (same sums of squares); m->h is free between the down projection and the next gate/up
+            if (n_logit_rows > 0) {
+                if ((rc = launch_scale_rows_bf16(m->x, m->norm_f, m->h, rows, d.d, m->stream))) return rc;
+                SiteTimer t(m, HSD_SITE_HEAD);
+                if ((rc = launch_head_bf16(m, m->h, rows, n_logit_rows, logits + ei * logit_stride))) return rc;
+            }
+            ++ei;
+        }
     }
     if (n_logit_rows == 0) return HSD_OK;
     SiteTimer t(m, HSD_SITE_HEAD);
-    return launch_head_bf16(m, rows, n_logit_rows, logits);
+    return launch_head_bf16(m, m->xn, rows, n_logit_rows, logits + ei * logit_stride);
 }
 
 extern "C" int hsd_measure_site(hsd_model* m, int site, int rows, int pos0, int iters, double* us_out) {
@@ -450,21 +480,38 @@ extern "C" int hsd_measure_site(hsd_model* m, int site, int rows, int pos0, int 
 
 // One pass: rows tokens at positions pos0.., layers [0, exit_layer), logits of the last n_logit_rows rows.
 int model_pass(hsd_model* m, const int32_t* tok, int pos0, int rows, int exit_layer, int n_logit_rows, float* logits) {
+    return model_pass_exits(m, tok, pos0, rows, &exit_layer, 1, n_logit_rows, logits);
+}
+
+int model_pass_exits(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
+                     float* logits) {
     const hsd_model_desc& d = m->desc;
+    if (!exits || n_exits < 1 || n_exits > d.n_layers) HSD_FAIL(HSD_EINVAL, "pass: %d exits", n_exits);
+    for (int i = 0; i < n_exits; ++i)
+        if (exits[i] < 1 || exits[i] > d.n_layers || (i > 0 && exits[i] <= exits[i - 1]))
+            HSD_FAIL(HSD_EINVAL, "pass: exit layer %d (entry %d) outside 1..%d or not ascending", exits[i], i, d.n_layers);
+    const int exit_layer = exits[n_exits - 1];
+    if (n_exits > 1 && d.dtype == HSD_BF16 && d.ffn < d.d)
+        HSD_FAIL(HSD_ECAPACITY, "pass: several exits need ffn >= d for the exit rows (ffn=%d d=%d)", d.ffn, d.d);
     if (rows < 1 || rows > d.max_rows) HSD_FAIL(HSD_ECAPACITY, "pass: %d rows, model allows 1..%d", rows, d.max_rows);
     if (pos0 < 0 || pos0 + rows > d.max_seq) HSD_FAIL(HSD_ECAPACITY, "pass: positions %d..%d exceed the KV capacity %d", pos0, pos0 + rows - 1, d.max_seq);
-    if (exit_layer < 1 || exit_layer > d.n_layers) HSD_FAIL(HSD_EINVAL, "pass: exit layer %d outside 1..%d", exit_layer, d.n_layers);
     if (n_logit_rows < 0 || n_logit_rows > rows) HSD_FAIL(HSD_EINVAL, "pass: %d logit rows of %d", n_logit_rows, rows);
     if (n_logit_rows > 0 && !logits) HSD_FAIL(HSD_EINVAL, "pass: logits buffer missing");
     if (!m->head_loaded) HSD_FAIL(HSD_ESTATE, "pass: embedding / head not loaded");
     for (int l = 0; l < exit_layer; ++l)
         if (!m->layer_loaded[l]) HSD_FAIL(HSD_ESTATE, "pass: layer %d not loaded", l);
-    return d.dtype == HSD_BF16 ? pass_bf16(m, tok, pos0, rows, exit_layer, n_logit_rows, logits)
-                               : pass_f32(m, tok, pos0, rows, exit_layer, n_logit_rows, logits);
+    return d.dtype == HSD_BF16 ? pass_bf16(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits)
+                               : pass_f32(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits);
 }
 
 extern "C" int hsd_model_pass(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows, int exit_layer, int n_logit_rows,
                               float* logits_dev) {
     if (!m || !tokens_dev) HSD_FAIL(HSD_EINVAL, "hsd_model_pass: null pointer");
     return model_pass(m, tokens_dev, pos0, rows, exit_layer, n_logit_rows, logits_dev);
+}
+
+extern "C" int hsd_model_pass_exits(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows, const int* exits, int n_exits,
+                                    int n_logit_rows, float* logits_dev) {
+    if (!m || !tokens_dev) HSD_FAIL(HSD_EINVAL, "hsd_model_pass_exits: null pointer");
+    return model_pass_exits(m, tokens_dev, pos0, rows, exits, n_exits, n_logit_rows, logits_dev);
 }

@@ -62,6 +62,11 @@ _SIGS = {
     "hsd_model_load_head": (_i, [_vp, _vp, _vp, _vp]),
     "hsd_model_set_pages": (_i, [_vp, C.POINTER(C.c_int32), _i]),
     "hsd_model_pass": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
+    "hsd_model_pass_exits": (_i, [_vp, _vp, _i, _i, C.POINTER(C.c_int), _i, _i, _vp]),
+    "hsd_overlap": (_i, [_vp, _i, _i, _i, _vp, _vp]),
+    "hsd_calibrate_workspace_bytes": (C.c_size_t, [_vp, _i, _i, _i]),
+    "hsd_calibrate": (_i, [_vp, C.POINTER(C.c_int), _i, _vp, _i, _i, C.c_float, _i, _vp, C.c_size_t, C.POINTER(C.c_double),
+                           C.POINTER(C.c_double)]),
     "hsd_profile_begin": (_i, [_vp, _i]),
     "hsd_profile_end": (_i, [_vp, C.POINTER(SiteTimes)]),
     "hsd_measure_site": (_i, [_vp, _i, _i, _i, _i, _dp]),
@@ -219,6 +224,35 @@ class Model:
         _check(lib.hsd_model_pass(self.handle, tokens_dev.data_ptr(), pos0, tokens_dev.numel(), exit_layer, n_logit_rows,
                                   logits.data_ptr()))
         return logits[:n_logit_rows]
+
+    def model_pass_exits(self, tokens_dev, pos0, exits, n_logit_rows):
+        """hsd_model_pass_exits.  Returns fp32 logits [len(exits), n_logit_rows, vocab]."""
+        logits = torch.empty((len(exits), max(n_logit_rows, 1), self.desc.vocab), dtype=torch.float32, device="cuda")
+        arr = (C.c_int * len(exits))(*exits)
+        _check(lib.hsd_model_pass_exits(self.handle, tokens_dev.data_ptr(), pos0, tokens_dev.numel(), arr, len(exits),
+                                        n_logit_rows, logits.data_ptr()))
+        return logits[:, :n_logit_rows]
+
+    def calibrate(self, exits, tokens_dev, n_ctx, temperature, cost_rows=0):
+        """hsd_calibrate.  Returns (alpha [n, n] numpy fp64, costs in ms [n] or None)."""
+        n, n_tokens = len(exits), tokens_dev.numel()
+        nbytes = lib.hsd_calibrate_workspace_bytes(self.handle, n, n_tokens, n_ctx)
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+        arr = (C.c_int * n)(*exits)
+        alpha = (C.c_double * (n * n))()
+        cost = (C.c_double * n)() if cost_rows > 0 else None
+        _check(lib.hsd_calibrate(self.handle, arr, n, tokens_dev.data_ptr(), n_tokens, n_ctx, float(temperature), cost_rows,
+                                 ws.data_ptr(), nbytes, alpha, cost))
+        return np.array(alpha[:]).reshape(n, n), (np.array(cost[:]) if cost is not None else None)
+
+
+def overlap(rows):
+    """hsd_overlap.  rows: fp32 cuda tensor [n_dists, n_rows, vocab].  Returns fp64 cuda tensor [n_pairs, n_rows]."""
+    rows = rows.contiguous()
+    n, r, v = rows.shape
+    out = torch.empty((n * (n - 1) // 2, r), dtype=torch.float64, device="cuda")
+    _check(lib.hsd_overlap(rows.data_ptr(), n, r, v, out.data_ptr(), _stream()))
+    return out
 
 
 # ---- stand-alone kernels ----------------------------------------------------------------------
