@@ -181,3 +181,46 @@ def test_driver_error_paths(tiny):
         big.generate(32)
     assert e.value.code == -2
     big.close()
+
+
+def test_independent_models_in_one_hierarchy():
+    """Levels that are different networks (Sec. 3.2: models sharing only the vocabulary): a small independent
+    drafter under an early exit and the full stack of the second network.  Separate KV caches, separate validity
+    bookkeeping.  Temperature 0 and 1 streams, pass and acceptance counts against the oracle (prompt / seed chosen
+    with the oracle alone for the asserted margins)."""
+    from paper_2510_19705_amd import hsd
+    small = dict(n_layers=2, d=128, n_q=2, n_kv=1, hd=64, ffn=384, vocab=TINY["vocab"])
+    wa = inputs.make_weights(small, seed=51, bf16=False)
+    wb = inputs.make_weights(TINY, seed=1, bf16=False)
+    ma = gpu_model(small, wa, False, max_seq=256, max_rows=16)
+    mb = gpu_model(TINY, wb, False, max_seq=256, max_rows=16)
+    da, db = oracle_decoder(small, wa, 256), oracle_decoder(TINY, wb, 256)
+    T = (3, 2)
+    for temperature, pseed, seed in [(0.0, 73, 1), (1.0, 2, 305)]:
+        prompt = inputs.make_prompt(TINY["vocab"], 32, seed=pseed)
+        da.reset()
+        db.reset()
+        levels = [decoder.Level(da, 2, temperature), decoder.Level(db, 4, temperature), decoder.Level(db, 8, temperature)]
+        ch = specsample.PhiloxChooser(seed)
+        o = ohsd.HSD(levels, T, ch)
+        ref = o.generate([int(t) for t in prompt], 48)
+        if temperature == 0:
+            assert min(l.min_top2_gap for l in levels) > 1.5e-3
+        else:
+            assert min(ch.accept_margins) > 3e-4 and min(ch.sample_margins) > 3e-6
+        h = hsd.Hierarchy([(ma, 2), (mb, 4), (mb, 8)], T, temperature, seed)
+        h.prefill(prompt)
+        got, st = h.generate(48)
+        assert got.tolist() == ref, temperature
+        assert [st.passes[i] for i in range(3)] == o.passes
+        assert [st.drafted[i] for i in range(3)] == o.drafted and [st.accepted[i] for i in range(3)] == o.accepted
+        say("independent models, temperature", temperature, "accepted", o.accepted, "of", o.drafted)
+        h.close()
+    # different vocabularies are refused
+    other = dict(small, vocab=1000)
+    mc = gpu_model(other, inputs.make_weights(other, seed=3, bf16=False), False, max_seq=64, max_rows=8)
+    with pytest.raises(hsd.HsdError) as e:
+        hsd.Hierarchy([(mc, 2), (mb, 8)], (2,), 1.0, 1)
+    assert e.value.code == -1
+    for m in (ma, mb, mc):
+        m.close()
