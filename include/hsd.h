@@ -209,7 +209,9 @@ int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int
  * serves before the MFMA kernel takes over on row-major weights.  key 101: nt = most query rows per KV head
  * (tokens x query heads per KV head) for which the MFMA attention gives each workgroup one 16-row tile; above
  * it, two.  key 102: nt = K/V steps per wave the attention plans for when it splits a sequence over workgroups
- * (0: default, which also caps the split at about 160 workgroups). */
+ * (0: default, which also caps the split at about 160 workgroups).  key 103: nt = largest vocabulary the driver
+ * hands to the fused softmax + verify launch (default 32768, its limit); smaller values exercise the two-launch
+ * path hsd_softmax + hsd_accept_resample on small vocabularies. */
 int hsd_tune(int key, int nt, int ksplit, int waves);
 
 /* ---------------------------------------------------------------------------------------------

@@ -1,0 +1,200 @@
+"""Large-shape workloads of the HSD path on one MI355X, beyond what bench.py times: hierarchies of independent
+networks, up to a 70B-shaped target (140 GB of bf16 weights resident in HBM).
+
+    python -m paper_2510_19705_amd.workloads --config independent     # 125M / 1B / 7B-shaped, vocab 32000
+    python -m paper_2510_19705_amd.workloads --config 70b             # 1B / 8B exit 8 / 8B / 70B-shaped, vocab 128256
+
+Weights are drawn on the device (seeded normal, residual-writing matrices scaled by 0.1); prompts are uniform-random
+ids.  For each workload: pass time and HBM fraction of every candidate (algorithmic bytes / time / 8 TB/s), pairwise
+acceptance rates measured by teacher-forcing all candidates on the same positions (sum of min of the two
+distributions, Sec. 2 / Sec. 5.1), the latency-optimal hierarchy for them (Sec. 4), and generated tokens per second
+of that hierarchy, of the full hierarchy, of every single draft and of plain decoding of the target.  Prints one
+JSON object.
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+
+CONFIGS = {
+    # candidates (model name, exit layer) in ascending cost, the target last
+    "independent": dict(models=["125m", "1b", "7b"], levels=[("125m", 12), ("1b", 16), ("7b", 32)], prompt=1024, gen=512),
+    "70b": dict(models=["1b_v128k", "8b", "70b"], levels=[("1b_v128k", 16), ("8b", 8), ("8b", 32), ("70b", 80)], prompt=8192,
+                gen=256),
+    # a small stand-in with the same structure, for a quick check of this script
+    "smoke": dict(models=["tiny_a", "tiny"], levels=[("tiny_a", 2), ("tiny", 4), ("tiny", 8)], prompt=64, gen=32),
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def pass_bytes(shape, exit_layer, m, s_total, n_logit_rows):
+    """Algorithmic bytes of one pass: weights of the layers run + head once, KV read and written, logits and
+    probability rows."""
+    d, F, V = shape["d"], shape["ffn"], shape["vocab"]
+    nq, nkv = shape["n_q"] * shape["hd"], shape["n_kv"] * shape["hd"]
+    layer_w = (d * (nq + 2 * nkv) + nq * d + 3 * d * F) * 2
+    kv = exit_layer * (2 * s_total * nkv * 2 + 2 * m * nkv * 2)
+    return exit_layer * layer_w + V * d * 2 + kv + n_logit_rows * V * 8
+
+
+def shapes(inputs):
+    s = dict(inputs.SHAPES)
+    s["1b_v128k"] = dict(s["1b"], vocab=128256)
+    s["tiny_a"] = dict(n_layers=2, d=128, n_q=2, n_kv=1, hd=64, ffn=384, vocab=s["tiny"]["vocab"])
+    return s
+
+
+def random_model(hsd, inputs, torch, shape, seed, max_seq, max_rows=64):
+    """A bf16 model of `shape` with weights drawn on the device."""
+    d, F, V = shape["d"], shape["ffn"], shape["vocab"]
+    nq, nkv = shape["n_q"] * shape["hd"], shape["n_kv"] * shape["hd"]
+    model = hsd.Model(shape, hsd.BF16, max_seq, max_rows, inputs.ROPE_BASE, inputs.EPS)
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    rnd = lambda r, c, std: (torch.randn((r, c), device="cuda", generator=g) * std).to(torch.bfloat16)
+    norm = lambda: 1 + 0.1 * torch.randn(d, device="cuda", generator=g)
+    for l in range(shape["n_layers"]):
+        model.load_layer_dev(l, {"norm1": norm(), "norm2": norm(), "wq": rnd(nq, d, d ** -0.5), "wk": rnd(nkv, d, d ** -0.5),
+                                 "wv": rnd(nkv, d, d ** -0.5), "wo": rnd(d, nq, 0.1 * nq ** -0.5), "wg": rnd(F, d, d ** -0.5),
+                                 "wu": rnd(F, d, d ** -0.5), "wd": rnd(d, F, 0.1 * F ** -0.5)})
+        torch.cuda.synchronize()
+    model.load_head_dev(rnd(V, d, 1.0), rnd(V, d, d ** -0.5), norm())
+    torch.cuda.synchronize()
+    return model
+
+
+def measure_acceptance(hsd, torch, levels, tokens, n_ctx, chunk=16):
+    """Teacher-forces every candidate over `tokens` (which also fills all KV caches) and returns alpha [n, n]: the
+    mean over positions n_ctx.. of the overlap of the candidates' next-token distributions (temperature 1)."""
+    n, n_tokens = len(levels), tokens.numel()
+    sums = torch.zeros(n * (n - 1) // 2, dtype=torch.float64, device="cuda")
+    deepest = {}
+    for model, e in levels:
+        deepest[id(model)] = (model, max(e, deepest.get(id(model), (model, 0))[1]))
+    for pos in range(0, n_ctx, 64):                              # context-only positions: deepest exit of each network
+        c = min(64, n_ctx - pos)
+        for model, e in deepest.values():
+            model.model_pass(tokens[pos:pos + c], pos, e, 0)
+    for pos in range(n_ctx, n_tokens, chunk):
+        c = min(chunk, n_tokens - pos)
+        rows = []
+        for model, e in levels:
+            rows.append(hsd.softmax(model.model_pass(tokens[pos:pos + c], pos, e, c), 1.0))
+        sums += hsd.overlap(torch.stack(rows)).sum(dim=1)
+    alpha = np.ones((n, n))
+    s = (sums / (n_tokens - n_ctx)).cpu().numpy()
+    k = 0
+    for i in range(n):
+        for j in range(i + 1, n):
+            alpha[i, j] = alpha[j, i] = s[k]
+            k += 1
+    return alpha
+
+
+def run(config, seed=20251019, temperature=1.0):
+    import torch
+    assert torch.cuda.is_available(), "needs the GPU"
+    from . import hsd, inputs
+    cfg = CONFIGS[config]
+    shp = shapes(inputs)
+    prompt_len, gen = cfg["prompt"], cfg["gen"]
+    max_seq = (prompt_len + gen + 128 + 63) // 64 * 64
+    t0 = time.time()
+    models = {}
+    for i, name in enumerate(cfg["models"]):
+        models[name] = random_model(hsd, inputs, torch, shp[name], seed + i, max_seq)
+        log("%s loaded (%.1f GB of weights) at %.0f s" % (name, models[name].weights.numel() / 1e9, time.time() - t0))
+    levels = [(models[name], e) for name, e in cfg["levels"]]
+    names = ["%s/exit%d" % ne for ne in cfg["levels"]]
+    V = shp[cfg["models"][0]]["vocab"]
+    prompt = inputs.make_prompt(V, prompt_len, seed=seed + 100)
+    tokens = torch.from_numpy(prompt.astype(np.int32)).cuda()
+
+    n_score = min(128, prompt_len // 2)
+    alpha = measure_acceptance(hsd, torch, levels, tokens, prompt_len - n_score)
+    log("alpha\n", np.round(alpha, 3))
+
+    # cost of a 4-token pass of every candidate at the end of the prompt, and its HBM fraction
+    cost, passes = [], {}
+    for (model, e), (name, _), label in zip(levels, cfg["levels"], names):
+        m = 4
+        tk = tokens[prompt_len - m:]
+        model.model_pass(tk, prompt_len - m, e, m)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        iters = 5
+        e0.record()
+        for _ in range(iters):
+            model.model_pass(tk, prompt_len - m, e, m)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        b = pass_bytes(shp[name], e, m, prompt_len, m)
+        cost.append(ms)
+        passes[label] = {"rows": m, "ms": ms, "algorithmic_GB": b / 1e9, "hbm_frac": b / ms / 1e6 / HBM_PEAK_GBS}
+        log("%s: %.3f ms, %.1f%% of peak" % (label, ms, 100 * passes[label]["hbm_frac"]))
+
+    lat, sigma, Tsel = hsd.select_hierarchy(cost, alpha, 15)
+    results = {}
+
+    def measure(label, idx, T):
+        try:
+            h = hsd.Hierarchy([levels[i] for i in idx], T, temperature, seed)
+        except hsd.HsdError as err:
+            results[label] = {"error": str(err)}
+            return None
+        h.prefill(prompt)
+        h.generate(min(gen, 32))                                 # warm-up
+        h.rewind(prompt_len)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        _, st = h.generate(gen)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t1
+        n = len(idx)
+        results[label] = {"levels": [names[i] for i in idx], "T": list(T), "tokens_per_s": gen / dt,
+                          "acceptance": [st.accepted[i] / max(1, st.drafted[i]) for i in range(1, n)],
+                          "passes": [st.passes[i] for i in range(n)]}
+        log(label, results[label])
+        h.close()
+        return results[label]
+
+    K = len(levels) - 1
+    measure("autoregressive", [K], [])
+    measure("selected", list(sigma), list(Tsel))
+    for i in range(K):
+        slat, _, sT = hsd.best_single_draft([cost[i], cost[K]], [[1, alpha[i, K]], [alpha[i, K], 1]], 15)
+        measure("single_draft_%s" % names[i], [i, K], [sT])
+    if list(sigma) != list(range(K + 1)):
+        # the full hierarchy with the T the model picks when every level is forced in: search T in 1..8 by the formula
+        best = None
+        import itertools
+        for T in itertools.product(range(1, 9), repeat=K):
+            l = hsd.expected_latency(cost, [alpha[i, i + 1] for i in range(K)], list(T), True)
+            if best is None or l < best[0]:
+                best = (l, T)
+        measure("full_hierarchy", list(range(K + 1)), list(best[1]))
+    out = {"config": config, "candidates": names, "prompt": prompt_len, "generate": gen, "temperature": temperature,
+           "alpha": [[round(float(v), 4) for v in row] for row in alpha], "cost_ms": cost, "verify_pass": passes,
+           "selected": {"levels": [names[i] for i in sigma], "T": list(Tsel), "predicted_tokens_per_s": 1e3 / lat},
+           "measured": results}
+    for m in models.values():
+        m.close()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", choices=sorted(CONFIGS), default="independent")
+    args = ap.parse_args()
+    print(json.dumps(run(args.config)), flush=True)
+
+
+if __name__ == "__main__":
+    main()

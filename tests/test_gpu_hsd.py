@@ -61,8 +61,19 @@ def test_tiny_temperature0_stream_bit_exact(tiny, T):
     ar.close()
 
 
+@pytest.fixture(params=["fused_sampler", "two_launch_sampler"])
+def sampler_path(request):
+    """The driver's two ways from logits to (n, token): the fused launch (vocabularies up to 32768) and softmax +
+    accept/resample as two launches (larger vocabularies), the latter forced here on the small vocabulary."""
+    from paper_2510_19705_amd import hsd
+    if request.param == "two_launch_sampler":
+        hsd.lib.hsd_tune(103, 0, 0, 0)
+    yield request.param
+    hsd.lib.hsd_tune(103, 32768, 0, 0)
+
+
 @pytest.mark.parametrize("T,seed", [((4, 2), 104), ((3, 5), 100)])
-def test_tiny_temperature1_stream(tiny, T, seed):
+def test_tiny_temperature1_stream(tiny, T, seed, sampler_path):
     """Temperature 1: same Philox stream on both sides.  Every accept test and every draw of the oracle
     run keeps a margin (asserted) far above the fp32 differences between the two softmaxes, so the
     streams, the accepted counts and the pass counts must be identical.  (A rounding-level change of a row
