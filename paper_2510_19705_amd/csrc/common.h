@@ -95,6 +95,7 @@ struct GemmArgs {
     const bf16x8* wp;                   // W [N, K]: MFMA tiles (launch_gemm_bf16) or row-major (launch_gemv_bf16)
     int M, N, K;
     float* part;                        // split-K partial tiles (ksplit > 1)
+    size_t part_bytes;                  // capacity of `part`: a plan that needs more runs unsplit
     int* tickets;                       // one arrival counter per column group, zero between launches
     // consumers of a normalised input: rows of `a` are x * w_norm, the 1/rms factor is applied in the epilogue
     const unsigned long long* ss_in;    // [SS_SLOTS][HSD_MAX_PASS_ROWS]: per row, sum of squares of x times 2^24, spread over the

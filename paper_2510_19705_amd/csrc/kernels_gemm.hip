@@ -567,8 +567,13 @@ GemmPlan gemm_plan(int m, int n, int k, int epi) {
     // about a thousand workgroups: every CU must be pulling for the HBM stream to reach its peak
     // Splitting K across workgroups costs a round trip through memory for the partial tiles, which only pays for
     // plain stores of narrow matrices; the fused epilogues keep K inside the workgroup.
+    // Two measured exceptions: a RoPE matrix of 128 MB or more in at most 384 groups (1.25-1.5 workgroups per CU:
+    // the uneven second round costs a third of the bandwidth; 4 slices even it out), and a residual matrix with at
+    // most 128 groups and K >= 8192 (half the CUs idle; 2 slices).
     const int groups = ceil_div(ntiles, p.nt);
     p.ksplit = epi == EPI_STORE ? (1024 + groups / 2) / groups : 1;
+    if (epi == EPI_ROPE && groups <= 384 && (size_t)n * k * 2 >= ((size_t)128 << 20)) p.ksplit = 4;
+    if (epi == EPI_RESID && groups <= 128 && k >= 8192) p.ksplit = 2;
     if (g_tune_ksplit[epi]) p.ksplit = g_tune_ksplit[epi];
     if (p.ksplit > 8) p.ksplit = 8;
     if (p.ksplit > KT) p.ksplit = KT;
@@ -603,10 +608,16 @@ static int check_gemm(int m, int n, int k) {
     return HSD_OK;
 }
 
-int launch_gemm_bf16(const GemmArgs& g, int epi, const GemmPlan& p, hipStream_t s) {
+int launch_gemm_bf16(const GemmArgs& g, int epi, const GemmPlan& plan, hipStream_t s) {
     if (int rc = check_gemm(g.M, g.N, g.K)) return rc;
-    if (p.ksplit > 1 && (!g.part || !g.tickets)) HSD_FAIL(HSD_EINVAL, "gemm: split-K launch without partial / ticket buffers");
+    GemmPlan p = plan;
     const int mt = g.M <= 16 ? 1 : (g.M <= 32 ? 2 : 4);
+    if (p.ksplit > 1) {
+        if (!g.part || !g.tickets) HSD_FAIL(HSD_EINVAL, "gemm: split-K launch without partial / ticket buffers");
+        // the partial tiles must fit the caller's buffer (plans can change after it was sized: tuning overrides)
+        const size_t need = (size_t)ceil_div(ceil_div(g.N, 16), p.nt) * p.ksplit * mt * p.nt * 256 * sizeof(float);
+        if (need > g.part_bytes) p.ksplit = 1;
+    }
 #define HSD_CASE(NT_, MT_, E_)                                  \
     if (p.nt == NT_ && mt == MT_ && epi == E_) {                \
         launch_inst<NT_, MT_, E_>(g, p, s);                     \
@@ -726,6 +737,7 @@ extern "C" int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev,
     g.M = m; g.N = n; g.K = k;
     g.out_f32 = y_dev;
     g.part = (float*)workspace_dev;
+    g.part_bytes = part_bytes;
     g.tickets = (int*)((char*)workspace_dev + part_bytes);
     HSD_HIP(hipMemsetAsync(g.tickets, 0, (size_t)ceil_div(n, 16) * sizeof(int), s));
     return launch_gemm_bf16(g, EPI_STORE, gemm_plan(m, n, k, EPI_STORE), s);

@@ -70,8 +70,10 @@ size_t part_elems_needed(const hsd_model_desc& d) {
     const int ms[3] = {16, 32, 64};
     for (int i = 0; i < 3; ++i) {
         const int m = ms[i] < d.max_rows ? ms[i] : d.max_rows;
-        const size_t b[2] = {gemm_part_bytes(m, 2 * d.ffn, d.d, EPI_SWIGLU), gemm_part_bytes(m, d.vocab, d.d, EPI_STORE)};
-        for (int j = 0; j < 2; ++j)
+        const size_t b[5] = {gemm_part_bytes(m, 2 * d.ffn, d.d, EPI_SWIGLU), gemm_part_bytes(m, d.vocab, d.d, EPI_STORE),
+                             gemm_part_bytes(m, nqkv, d.d, EPI_ROPE), gemm_part_bytes(m, d.d, d.n_q * d.hd, EPI_RESID),
+                             gemm_part_bytes(m, d.d, d.ffn, EPI_RESID)};
+        for (int j = 0; j < 5; ++j)
             if (b[j] / 4 > need) need = b[j] / 4;
     }
     return need;
@@ -378,7 +380,7 @@ static int launch_site_bf16(hsd_model* m, int site, int l, int pos0, int rows, c
     bf16_t* kv_layer = (bf16_t*)(m->kv + m->kv_layer_bytes * l);
     const bool rowk = L.wqkv_rows && rows <= g_gemv_max_m;     // one or two tokens: stream the row-major copies
     GemmArgs g = {};
-    g.M = rows; g.part = m->part; g.tickets = m->tickets; g.eps = d.eps;
+    g.M = rows; g.part = m->part; g.part_bytes = m->part_elems * sizeof(float); g.tickets = m->tickets; g.eps = d.eps;
     switch (site) {
         case HSD_SITE_QKV:
             g.a = (const bf16_t*)m->xn; g.ss_in = m->ss[0]; g.ss_zero = m->ss[1];
@@ -411,7 +413,7 @@ static int launch_head_bf16(hsd_model* m, const void* xn, int rows, int n_logit_
     const hsd_model_desc& d = m->desc;
     const int row0 = rows - n_logit_rows;
     GemmArgs g = {};
-    g.part = m->part; g.tickets = m->tickets; g.eps = d.eps;
+    g.part = m->part; g.part_bytes = m->part_elems * sizeof(float); g.tickets = m->tickets; g.eps = d.eps;
     g.M = n_logit_rows;
     g.a = (const bf16_t*)xn + (size_t)row0 * d.d; g.ss_in = m->ss[0] + row0;
     g.wp = (const bf16x8*)m->head; g.N = d.vocab; g.K = d.d;
