@@ -47,6 +47,11 @@ struct hsd_hier {
     void* sampler_scratch;
     int32_t* mailbox;   // pinned host memory: n, m, then up to 65 token ids
     int32_t* mailbox_dev;   // the same memory as the device addresses it
+    // The fused sampler leaves the token it emits embedded in level 0's model (EmbedNext): valid for a one-token pass
+    // of that model at position pre_pos while the model's pass counter still reads pre_serial.
+    hsd_model* pre_model;
+    unsigned long long pre_serial;
+    int pre_pos;
     hsd_stats stats;
 };
 
@@ -133,7 +138,8 @@ int level_pass(hsd_hier* h, int idx, int start, int n_logit_rows) {
         h->stats.pass_rows[idx] += chunk;
         pos += chunk;
     }
-    if (int rc = model_pass(L.model, h->tok_dev + pos, pos, h->len - pos, L.exit_layer, n_logit_rows, h->logits)) return rc;
+    const bool embedded = h->pre_model == L.model && h->pre_serial == L.model->pass_serial && h->pre_pos == pos && h->len - pos == 1;
+    if (int rc = model_pass(L.model, h->tok_dev + pos, pos, h->len - pos, L.exit_layer, n_logit_rows, h->logits, embedded)) return rc;
     h->stats.passes[idx]++;
     h->stats.pass_rows[idx] += h->len - pos;
     return HSD_OK;
@@ -153,10 +159,18 @@ int draft_step(hsd_hier* h, int row) {
     const int start = std::min(effective_cached(h, 0), h->len - 1);
     if (int rc = level_pass(h, 0, start, 1)) return rc;
     float* p = L.rows + (size_t)row * h->V;
+    h->pre_model = nullptr;
     if (softmax_verify_supported(h->V)) {
+        const bool pre = g_preembed != 0;
         if (int rc = launch_softmax_verify(h->logits, nullptr, h->tok_dev + h->len, 0, h->V, h->temperature, h->seed, 0u, L.call++, p,
-                                           h->result_dev, h->sampler_scratch, nullptr, h->stream))
+                                           h->result_dev, h->sampler_scratch, nullptr, pre ? embed_next_of(L.model) : EmbedNext{},
+                                           h->stream))
             return rc;
+        if (pre) {
+            h->pre_model = L.model;
+            h->pre_serial = L.model->pass_serial;
+            h->pre_pos = h->len;
+        }
     } else {
         if (int rc = launch_softmax(h->logits, p, 1, h->V, h->temperature, h->stream)) return rc;
         if (int rc = launch_accept_resample(p, nullptr, h->tok_dev + h->len, 0, h->V, h->seed, 0u, L.call++, h->result_dev,
@@ -180,10 +194,16 @@ int verify_step(hsd_hier* h, int idx, int t, const float* q_dev, int* n_out) {
     const int start = std::min(effective_cached(h, idx), ctx_end - 1);
     if (int rc = level_pass(h, idx, start, t + 1)) return rc;
     float* p = L.rows + (size_t)L.count * h->V;
+    h->pre_model = nullptr;
+    hsd_model* m0 = h->lv[0].model;
+    bool pre = false;
     if (softmax_verify_supported(h->V)) {
-        // one launch; the kernel writes n, m and the surviving tokens straight into the pinned mailbox
+        // one launch; the kernel writes n, m and the surviving tokens straight into the pinned mailbox, and leaves m
+        // embedded in level 0's model, whose next draft pass is that one token
+        pre = g_preembed != 0;
         if (int rc = launch_softmax_verify(h->logits, q_dev, h->tok_dev + ctx_end, t, h->V, h->temperature, h->seed, (uint32_t)idx,
-                                           L.call++, p, h->result_dev, h->sampler_scratch, h->mailbox_dev, h->stream))
+                                           L.call++, p, h->result_dev, h->sampler_scratch, h->mailbox_dev,
+                                           pre ? embed_next_of(m0) : EmbedNext{}, h->stream))
             return rc;
     } else {
         if (int rc = launch_softmax(h->logits, p, t + 1, h->V, h->temperature, h->stream)) return rc;
@@ -198,6 +218,11 @@ int verify_step(hsd_hier* h, int idx, int t, const float* q_dev, int* n_out) {
     if (n < 0 || n > t) HSD_FAIL(HSD_EHIP, "verify: device returned n=%d for t=%d", n, t);
     for (int i = 0; i <= n; ++i) h->tok_host[ctx_end + i] = h->mailbox[2 + i];
     h->len = ctx_end + n + 1;
+    if (pre) {
+        h->pre_model = m0;
+        h->pre_serial = m0->pass_serial;
+        h->pre_pos = ctx_end + n;
+    }
     const int valid = ctx_end + n;                 // accepted prefix: K/V beyond it belongs to rejected drafts
     L.cached_len = valid;
     for (int j = 0; j < idx; ++j) {
@@ -295,6 +320,7 @@ extern "C" int hsd_hier_create(int n_levels, const hsd_level* levels, const int*
     h->len = 0;
     h->mailbox = nullptr;
     h->mailbox_dev = nullptr;
+    h->pre_model = nullptr;
     reset_counters(h);
     hipError_t e = hipHostMalloc((void**)&h->mailbox, 68 * sizeof(int32_t), hipHostMallocMapped);
     if (e == hipSuccess) e = hipHostGetDevicePointer((void**)&h->mailbox_dev, h->mailbox, 0);
@@ -340,6 +366,7 @@ extern "C" int hsd_prefill(hsd_hier* h, const int32_t* prompt, int n) {
     }
     HSD_HIP(hipStreamSynchronize(h->stream));
     h->len = n;
+    h->pre_model = nullptr;
     for (int i = 0; i <= h->K; ++i) h->lv[i].cached_len = n - 1;
     return HSD_OK;
 }
@@ -351,6 +378,7 @@ extern "C" int hsd_rewind(hsd_hier* h, int n) {
     HSD_HIP(hipMemcpyAsync(h->tok_dev, h->tok_host.data(), (size_t)n * 4, hipMemcpyHostToDevice, h->stream));
     HSD_HIP(hipStreamSynchronize(h->stream));
     h->len = n;
+    h->pre_model = nullptr;
     for (int i = 0; i <= h->K; ++i) h->lv[i].cached_len = std::min(h->lv[i].cached_len, n - 1);
     reset_counters(h);
     return HSD_OK;

@@ -8,6 +8,7 @@
 // (seed; slot, call, level), so nothing depends on launch geometry.
 #include "common.h"
 #include "softmax_row.h"
+#include "model.h"
 
 namespace {
 
@@ -373,11 +374,12 @@ __global__ __launch_bounds__(SMALL_THREADS) void softmax_verify_kernel(const flo
                                                                        uint32_t k0, uint32_t k1, uint32_t level, uint32_t call,
                                                                        float* __restrict__ p_out, int32_t* __restrict__ result,
                                                                        uint32_t* ticket, unsigned long long* key,
-                                                                       int32_t* __restrict__ mailbox) {
+                                                                       int32_t* __restrict__ mailbox, const EmbedNext next) {
     __shared__ float shv[16];
     __shared__ int shi[16];
     __shared__ SearchShared sh;
     __shared__ int sh_reject;
+    __shared__ int sh_last, sh_emit;
     const int row = blockIdx.x, tid = threadIdx.x;
     const float* zr = z + (size_t)row * V;
     const float* qr = row < t ? q + (size_t)row * V : nullptr;
@@ -408,36 +410,71 @@ __global__ __launch_bounds__(SMALL_THREADS) void softmax_verify_kernel(const flo
     }
     const Philox4 rnd = philox4x32_10((uint32_t)t, call, level, 0u, k0, k1);
     draw_corrected(pc, qc, qr != nullptr, rnd.w[1], V, sh);           // ends with a barrier: sh_reject and sh.token are visible
-    if (tid >= 64) return;
-    int last = 0;
-    unsigned long long best = 0;
-    if (tid == 0) {
-        unsigned long long old = 0;
-        if (sh_reject) {
-            const unsigned long long mine = ~(((unsigned long long)row << 32) | (unsigned long long)(uint32_t)sh.token);
-            old = __hip_atomic_fetch_max(key, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        const uint32_t step = 1u + (uint32_t)(old == 1ull);           // old is 0 or has bit 63 set: always 1, but data-dependent
-        const uint32_t done = __hip_atomic_fetch_add(ticket, step, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (done == (uint32_t)t) {
+    if (tid < 64) {
+        int last = 0;
+        unsigned long long best = 0;
+        if (t == 0) {                                          // one row (a draft step): nothing to agree on
             last = 1;
-            best = ~__hip_atomic_exchange(key, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            best = (unsigned long long)(uint32_t)sh.token;
+        } else if (tid == 0) {
+            unsigned long long old = 0;
+            if (sh_reject) {
+                const unsigned long long mine = ~(((unsigned long long)row << 32) | (unsigned long long)(uint32_t)sh.token);
+                old = __hip_atomic_fetch_max(key, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            const uint32_t step = 1u + (uint32_t)(old == 1ull);           // old is 0 or has bit 63 set: always 1, but data-dependent
+            const uint32_t done = __hip_atomic_fetch_add(ticket, step, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (done == (uint32_t)t) {
+                last = 1;
+                best = ~__hip_atomic_exchange(key, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
+        if (t != 0) {
+            last = __shfl(last, 0, 64);
+            best = __shfl(best, 0, 64);
+        }
+        if (last) {
+            const int n = (int)(best >> 32), m = (int)(uint32_t)best;
+            if (tid == 0) {
+                result[0] = n;
+                result[1] = m;
+                x[n] = m;
+                if (mailbox) { mailbox[0] = n; mailbox[1] = m; }
+                sh_emit = m;
+            }
+            if (mailbox) {                                     // the accepted drafts and the new token, for the host
+                if (tid < n) mailbox[2 + tid] = x[tid];
+                if (tid == 0) mailbox[2 + n] = m;
+            }
+        }
+        if (tid == 0) sh_last = last;
     }
-    last = __shfl(last, 0, 64);
-    if (!last) return;
-    best = __shfl(best, 0, 64);
-    const int n = (int)(best >> 32), m = (int)(uint32_t)best;
-    if (tid == 0) {
-        result[0] = n;
-        result[1] = m;
-        x[n] = m;
-        if (mailbox) { mailbox[0] = n; mailbox[1] = m; }
+    if (!next.E) return;
+    __syncthreads();
+    if (!sh_last) return;
+    // The emitted token, embedded for a one-token pass that may follow: the arithmetic (256 strided partial sums, four
+    // wave sums, their sum in wave order) is the embedding kernel's, so the pass sees the same bits either way.
+    int tk = sh_emit;
+    tk = tk < 0 ? 0 : (tk >= next.vocab ? next.vocab - 1 : tk);
+    float acc = 0.f;
+    if (tid < 256) {
+        for (int i = tid; i < next.d; i += 256) {
+            const float v = next.dtype == HSD_BF16 ? (float)((const bf16_t*)next.E)[(size_t)tk * next.d + i]
+                                                   : ((const float*)next.E)[(size_t)tk * next.d + i];
+            next.x[i] = v;
+            if (next.xn) ((bf16_t*)next.xn)[i] = (bf16_t)(v * next.norm_w[i]);
+            acc += v * v;
+        }
+        acc = wave_sum(acc);
+        if ((tid & 63) == 0) shv[tid >> 6] = acc;
     }
-    if (mailbox) {                                         // the accepted drafts and the new token, for the host
-        if (tid < n) mailbox[2 + tid] = x[tid];
-        if (tid == 0) mailbox[2 + n] = m;
+    __syncthreads();
+    if (next.ss && tid < SS_SLOTS) {
+        float s4 = 0.f;
+        for (int w = 0; w < 4; ++w) s4 += shv[w];
+        next.ss[tid * HSD_MAX_PASS_ROWS] = tid == 0 ? (unsigned long long)((double)s4 * 16777216.0 + 0.5) : 0ull;
+        next.ss_other[tid * HSD_MAX_PASS_ROWS] = 0ull;
     }
 }
 
@@ -465,16 +502,17 @@ int launch_accept_resample(const float* p, const float* q, int32_t* x, int t, in
 
 // Fused softmax + Alg. 2 (vocabularies up to 32768 only); scratch as for launch_accept_resample (ticket in word 0,
 // the key in bytes 8..15, both zero between launches).
+int g_preembed = 1;                           // hsd_tune key 104: 0 keeps the embedding of the emitted token in the next pass
 int g_fused_sampler_max_v = SMALL_MAX_V;       // hsd_tune key 103: lower it to send smaller vocabularies down the two-launch path
 bool softmax_verify_supported(int vocab) { return vocab <= SMALL_MAX_V && vocab <= g_fused_sampler_max_v; }
 
 int launch_softmax_verify(const float* z, const float* q, int32_t* x, int t, int vocab, float temperature, uint64_t seed,
                           uint32_t level, uint32_t call, float* p_out, int32_t* result, void* scratch, int32_t* mailbox,
-                          hipStream_t s) {
+                          const EmbedNext& next, hipStream_t s) {
     if (!softmax_verify_supported(vocab)) HSD_FAIL(HSD_ECAPACITY, "fused softmax + verify: vocabulary %d above %d", vocab, SMALL_MAX_V < g_fused_sampler_max_v ? SMALL_MAX_V : g_fused_sampler_max_v);
     softmax_verify_kernel<<<t + 1, SMALL_THREADS, 0, s>>>(z, q, x, t, vocab, temperature, (uint32_t)seed, (uint32_t)(seed >> 32), level,
                                                           call, p_out, result, (uint32_t*)scratch,
-                                                          (unsigned long long*)((char*)scratch + 8), mailbox);
+                                                          (unsigned long long*)((char*)scratch + 8), mailbox, next);
     HSD_LAUNCH_CHECK();
     return HSD_OK;
 }
@@ -497,5 +535,5 @@ extern "C" int hsd_softmax_verify(const float* logits_dev, const float* q_dev, i
     if (t > 0 && !q_dev) HSD_FAIL(HSD_EINVAL, "hsd_softmax_verify: draft rows missing for t=%d", t);
     if (vocab < 1 || !(temperature >= 0.f)) HSD_FAIL(HSD_EINVAL, "hsd_softmax_verify: vocab=%d temperature=%g", vocab, temperature);
     return launch_softmax_verify(logits_dev, q_dev, x_dev, t, vocab, temperature, seed, level, call, probs_dev, result_dev,
-                                 scratch_dev, host_mailbox, (hipStream_t)stream);
+                                 scratch_dev, host_mailbox, EmbedNext{}, (hipStream_t)stream);
 }

@@ -41,6 +41,7 @@ struct hsd_model {
     size_t part_elems;
     std::vector<bool> layer_loaded;
     bool head_loaded;
+    unsigned long long pass_serial;   // counts passes: whoever left something in the activation buffers can tell if it is still there
     // optional per-site event timing (hsd_profile_begin / hsd_profile_end)
     bool prof_on;
     size_t prof_used;
@@ -49,7 +50,7 @@ struct hsd_model {
 };
 
 int model_pass(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows, int exit_layer, int n_logit_rows,
-               float* logits_dev);
+               float* logits_dev, bool embedded = false);
 // The same pass through the deepest of `exits` (ascending layer counts), with the last n_logit_rows rows' logits of
 // every listed exit: logits_dev [n_exits][n_logit_rows][vocab].
 int model_pass_exits(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows, const int* exits, int n_exits,
@@ -73,6 +74,18 @@ int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, 
 int launch_accept_resample(const float* p, const float* q, int32_t* x, int t, int vocab, uint64_t seed, uint32_t level,
                            uint32_t call, int32_t* result, void* scratch, hipStream_t s);
 bool softmax_verify_supported(int vocab);
+// What the fused sampler needs to leave the emitted token embedded for a following one-token pass of `model`
+// (row 0 of its residual stream, normalised input and sums of squares, exactly as the embedding kernel would):
+// E == nullptr switches it off.
+struct EmbedNext {
+    const void* E;
+    int dtype, d, vocab;
+    float* x;
+    void* xn;
+    const float* norm_w;
+    unsigned long long *ss, *ss_other;
+};
+EmbedNext embed_next_of(const hsd_model* m);
 int launch_softmax_verify(const float* z, const float* q, int32_t* x, int t, int vocab, float temperature, uint64_t seed,
                           uint32_t level, uint32_t call, float* p_out, int32_t* result, void* scratch, int32_t* mailbox,
-                          hipStream_t s);
+                          const EmbedNext& next, hipStream_t s);

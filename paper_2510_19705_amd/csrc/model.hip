@@ -162,6 +162,7 @@ extern "C" int hsd_model_create(const hsd_model_desc* desc, void* weights_dev, v
     m->part_elems = part_elems_needed(*desc);
     m->layer_loaded.assign(desc->n_layers, false);
     m->head_loaded = false;
+    m->pass_serial = 0;
     m->prof_on = false;
     m->prof_used = 0;
     // Cache rows beyond the valid length are read (and masked) by the attention kernels: keep them finite.
@@ -309,7 +310,7 @@ extern "C" int hsd_model_load_head(hsd_model* m, const void* embed_dev, const vo
 
 // fp32 storage: plain kernels, one per step (the small correctness configuration).
 static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
-                    float* logits) {
+                    float* logits, bool embedded) {
     const hsd_model_desc& d = m->desc;
     hipStream_t s = m->stream;
     const int nq = d.n_q * d.hd, nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
@@ -317,7 +318,7 @@ static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, const 
     const size_t logit_stride = (size_t)n_logit_rows * d.vocab;
     int ei = 0;
     int rc;
-    if ((rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, nullptr, nullptr, nullptr, nullptr, s))) return rc;
+    if (!embedded && (rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, nullptr, nullptr, nullptr, nullptr, s))) return rc;
     const float* pending = nullptr;     // output of the previous down projection, not yet added to x
     for (int l = 0; l < exit_layer; ++l) {
         const LayerWeights& L = m->layers[l];
@@ -422,13 +423,15 @@ static int launch_head_bf16(hsd_model* m, const void* xn, int rows, int n_logit_
 }
 
 static int pass_bf16(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
-                     float* logits) {
+                     float* logits, bool embedded) {
     const hsd_model_desc& d = m->desc;
     const int exit_layer = exits[n_exits - 1];
     const size_t logit_stride = (size_t)n_logit_rows * d.vocab;
     int ei = 0;
     int rc;
-    if ((rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, m->ss[0], m->ss[1], m->layers[0].norm1, m->xn, m->stream))) return rc;
+    if (!embedded &&
+        (rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, m->ss[0], m->ss[1], m->layers[0].norm1, m->xn, m->stream)))
+        return rc;
     for (int l = 0; l < exit_layer; ++l) {
         const float* next_norm = l + 1 == exit_layer ? m->norm_f : m->layers[l + 1].norm1;
         for (int site = HSD_SITE_QKV; site <= HSD_SITE_DOWN; ++site) {
@@ -463,6 +466,7 @@ extern "C" int hsd_measure_site(hsd_model* m, int site, int rows, int pos0, int 
     HSD_HIP(hipEventCreate(&e0));
     HSD_HIP(hipEventCreate(&e1));
     int rc = HSD_OK;
+    ++m->pass_serial;                                    // the activation buffers are overwritten
     auto one = [&](int i) { return launch_site_bf16(m, site, i % d.n_layers, pos0, rows, m->norm_f); };
     for (int i = 0; i < d.n_layers && !rc; ++i) rc = one(i);                 // warm-up, one launch per layer
     if (!rc && hipEventRecord(e0, m->stream) != hipSuccess) rc = HSD_EHIP;
@@ -481,12 +485,29 @@ extern "C" int hsd_measure_site(hsd_model* m, int site, int rows, int pos0, int 
 }
 
 // One pass: rows tokens at positions pos0.., layers [0, exit_layer), logits of the last n_logit_rows rows.
-int model_pass(hsd_model* m, const int32_t* tok, int pos0, int rows, int exit_layer, int n_logit_rows, float* logits) {
-    return model_pass_exits(m, tok, pos0, rows, &exit_layer, 1, n_logit_rows, logits);
+static int pass_checked(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
+                        float* logits, bool embedded);
+
+// embedded: row 0 of the residual stream (and, bf16, of the normalised input and the sums of squares) already holds
+// the one token of this pass, left there by the fused sampler (EmbedNext); only for rows == 1.
+int model_pass(hsd_model* m, const int32_t* tok, int pos0, int rows, int exit_layer, int n_logit_rows, float* logits, bool embedded) {
+    return pass_checked(m, tok, pos0, rows, &exit_layer, 1, n_logit_rows, logits, embedded && rows == 1);
 }
 
 int model_pass_exits(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
                      float* logits) {
+    return pass_checked(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits, false);
+}
+
+EmbedNext embed_next_of(const hsd_model* m) {
+    const hsd_model_desc& d = m->desc;
+    const bool bf = d.dtype == HSD_BF16;
+    return EmbedNext{m->embed, d.dtype, d.d, d.vocab, m->x, bf ? m->xn : nullptr, bf ? m->layers[0].norm1 : nullptr,
+                     bf ? m->ss[0] : nullptr, bf ? m->ss[1] : nullptr};
+}
+
+static int pass_checked(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
+                        float* logits, bool embedded) {
     const hsd_model_desc& d = m->desc;
     if (!exits || n_exits < 1 || n_exits > d.n_layers) HSD_FAIL(HSD_EINVAL, "pass: %d exits", n_exits);
     for (int i = 0; i < n_exits; ++i)
@@ -502,8 +523,9 @@ int model_pass_exits(hsd_model* m, const int32_t* tok, int pos0, int rows, const
     if (!m->head_loaded) HSD_FAIL(HSD_ESTATE, "pass: embedding / head not loaded");
     for (int l = 0; l < exit_layer; ++l)
         if (!m->layer_loaded[l]) HSD_FAIL(HSD_ESTATE, "pass: layer %d not loaded", l);
-    return d.dtype == HSD_BF16 ? pass_bf16(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits)
-                               : pass_f32(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits);
+    ++m->pass_serial;
+    return d.dtype == HSD_BF16 ? pass_bf16(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits, embedded)
+                               : pass_f32(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits, embedded);
 }
 
 extern "C" int hsd_model_pass(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows, int exit_layer, int n_logit_rows,

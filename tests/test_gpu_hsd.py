@@ -235,3 +235,29 @@ def test_independent_models_in_one_hierarchy():
     assert e.value.code == -1
     for m in (ma, mb, mc):
         m.close()
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+def test_token_embedded_by_the_sampler_changes_nothing(bf16):
+    """The fused sampler leaves the token it emits embedded for the one-token pass that follows; with that switched
+    off the embedding kernel does it.  Same tokens, same counters (bf16: the row's sum of squares is accumulated in
+    the same order on both routes, so even the bits agree)."""
+    from paper_2510_19705_amd import hsd
+    shape = dict(n_layers=4, d=256, n_q=8, n_kv=2, hd=64, ffn=608, vocab=5000)
+    w = inputs.make_weights(shape, seed=61, bf16=bf16)
+    prompt = inputs.make_prompt(shape["vocab"], 40, seed=62)
+    model = gpu_model(shape, w, bf16, max_seq=192, max_rows=16, rows_copy_layers=2 if bf16 else 0)
+    runs = []
+    for pre in (1, 0):
+        hsd.lib.hsd_tune(104, pre, 0, 0)
+        try:
+            h = hsd.Hierarchy([(model, 1), (model, 2), (model, 4)], (3, 2), 1.0, 77)
+            h.prefill(prompt)
+            toks, st = h.generate(60)
+            d = h.draft(2)                                  # explicit draft calls go the same way
+            runs.append((toks.tolist(), [st.passes[i] for i in range(3)], [st.accepted[i] for i in range(3)], d[0].tolist()))
+            h.close()
+        finally:
+            hsd.lib.hsd_tune(104, 1, 0, 0)
+    assert runs[0] == runs[1]
+    model.close()
