@@ -149,6 +149,34 @@ def test_softmax_verify_fused(hsd, V, t, temperature):
     assert checked >= n_calls - 3
 
 
+@pytest.mark.parametrize("V,t", [(1, 0), (1, 3), (2, 5), (7, 64), (4097, 64), (32768, 64)])
+def test_sampler_extreme_shapes(hsd, V, t):
+    """The largest draft count (64), the smallest vocabularies (1 and 2 tokens: every draw is forced or a coin), and
+    chunk-boundary vocabularies, through both the two-launch and the fused entry points, bit-exact on the oracle."""
+    import torch
+    seed = 4242
+    for call in range(4):
+        p, q, x = inputs.make_prob_rows(V, t, seed=9 * V + t + call, sigma=1.5, noise=0.7)
+        ref = specsample.verify(list(p), list(q), list(x), specsample.PhiloxChooser(seed), 1, call)
+        xd = _cuda(np.concatenate([x, [0]]).astype(np.int32))
+        assert hsd.accept_resample(_cuda(p), _cuda(q) if t else _cuda(p[:0]), xd, seed, 1, call) == ref, (V, t, call)
+        if V == 1:
+            assert ref == (t, 0)                              # one token: always accepted, always emitted
+        # fused: logits whose softmax is exactly representable are hard to come by, so compare with its own two-launch twin
+        z, q2, x2 = inputs.make_logit_rows(V, t, seed=5 * V + t + call)
+        zd, qd = _cuda(z), _cuda(q2) if t else _cuda(z[:0])
+        xa = _cuda(np.concatenate([x2, [0]]).astype(np.int32))
+        xb = xa.clone()
+        n, m, probs = hsd.softmax_verify(zd, qd, xa, 1.0, seed, 1, call)
+        assert hsd.accept_resample(hsd.softmax(zd, 1.0), qd, xb, seed, 1, call) == (n, m)
+        assert torch.equal(xa, xb)
+        p_ref = decoder.distributions(z.astype(np.float64), 1.0).astype(np.float32)
+        ch = specsample.PhiloxChooser(seed)
+        ref2 = specsample.verify(list(p_ref), list(q2), list(x2), ch, 1, call)
+        if min(ch.accept_margins + [1.0]) > 1e-4 and min(ch.sample_margins + [1.0]) > 3e-6:
+            assert (n, m) == ref2, (V, t, call)
+
+
 def test_softmax_verify_greedy_and_limits(hsd):
     """Temperature 0: one-hot rows, drafts accepted iff they equal the verifier's argmax; vocabularies beyond the
     one-workgroup limit and bad arguments are refused."""
