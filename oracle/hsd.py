@@ -17,13 +17,19 @@ p(. | context[:len-n_rows+1+r]) for r = 0..n_rows-1.  Random decisions go
 through a chooser (specsample.PhiloxChooser, or exact.ScriptedChooser for
 exact enumeration): `call` counts a level's Verify calls, or draft steps at
 level 0.
+
+`truncate=True` is the variant the latency formula of Thm 3.2 describes literally: an intermediate level hands up
+exactly T_idx tokens (what it collected beyond that is dropped), so every Verify sees exactly T drafts.  The
+counter `tested` (accept tests evaluated: up to and including the first rejection) gives the per-test acceptance
+frequency accepted / tested that the IID ablation of the appendix plugs into its coin.
 """
 from . import specsample
 
 
 class HSD:
-    def __init__(self, levels, T, chooser):
+    def __init__(self, levels, T, chooser, truncate=False):
         assert len(T) == len(levels) - 1 and all(t >= 1 for t in T)
+        self.truncate = truncate
         self.levels = levels
         self.K = len(levels) - 1
         self.T = list(T)
@@ -34,6 +40,7 @@ class HSD:
         self.drafted = [0] * len(levels)       # draft tokens offered to level idx's Verify
         self.accepted = [0] * len(levels)      # of those, accepted
         self.pass_rows = [0] * len(levels)
+        self.tested = [0] * len(levels)        # accept tests evaluated at level idx
 
     def _verify(self, idx, draft_tokens, draft_probs, context):
         t = len(draft_tokens)
@@ -44,6 +51,7 @@ class HSD:
         n, m = specsample.verify(p_rows, draft_probs, draft_tokens, self.chooser, idx, call)
         self.drafted[idx] += t
         self.accepted[idx] += n
+        self.tested[idx] += n + (1 if n < t else 0)
         return list(draft_tokens[:n]) + [m], [p_rows[i] for i in range(n + 1)]
 
     def run(self, idx, context):
@@ -69,6 +77,8 @@ class HSD:
                 tokens.extend(vt)
                 probs.extend(vp)
                 count += len(vt)
+            if self.truncate:
+                tokens, probs = tokens[:self.T[idx]], probs[:self.T[idx]]
         return tokens, probs
 
     def generate(self, prompt, n_tokens):

@@ -92,6 +92,20 @@ class PhiloxChooser:
         return sample_row(p, q, int(w[1]), self.sample_margins)
 
 
+class IIDChooser(PhiloxChooser):
+    """The ablation of the appendix "Examining the assumptions of HSD": Alg. 2's test on each draft is replaced by a
+    biased coin, P[accept] = alpha[level] whatever p and q are (the coin uses the same Philox word as the real test
+    would; the corrected / bonus token is drawn as before).  alpha is indexed by the verifying level."""
+
+    def __init__(self, seed, alpha):
+        super().__init__(seed)
+        self.alpha = [np.float32(a) for a in alpha]
+
+    def accept(self, level, call, i, p_x, q_x):
+        w = philox.draw(self.seed, level, call, i)
+        return bool(np.float32(philox.uniform24(w[0])) < self.alpha[level])
+
+
 def verify(p_rows, q_rows, x, chooser, level, call):
     """Alg. 2 after the verifier pass: p_rows = (p_1..p_{t+1}), q_rows = (q_1..q_t),
     x = (x_1..x_t).  Returns (n, m): number of accepted draft tokens and the
