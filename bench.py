@@ -247,6 +247,23 @@ def main():
                      "best_single_draft_predicted": {"exit": EXITS[sdr] if sdr >= 0 else None, "T": sT, "tokens_per_s": 1e3 / slat},
                      "hsd_T_best_predicted_tokens_per_s": 1e3 / hsd.expected_latency(cost, [a01, a12], list(T_best), True)}
 
+    # ---- the four settings of the appendix on HSD's assumptions: real / coin-flip acceptances x measured / fixed costs ----
+    cost_ms = [passes["exit%d" % e]["ms"] for e in EXITS]
+    st_real = h.stats()                                         # of the profiled generation above (real rule)
+    coin = [0.0] + [st_real.accepted[i] / max(1, st_real.tested[i]) for i in (1, 2)]
+    h.set_ablation(coin, False)
+    h.rewind(PROMPT)
+    h.generate(GEN)                                             # warm-up
+    dt_iid, st_iid = timed_generation(h, torch, PROMPT, GEN, 3)
+    h.set_ablation(None, False)
+    ablation = {"per_test_acceptance": coin[1:], "cost_ms_per_pass": cost_ms, "T": list(T_best),
+                "ms_per_token": {"real_acceptance_real_cost": elapsed / args.steps / GEN * 1e3,
+                                 "iid_acceptance_real_cost": dt_iid / GEN * 1e3,
+                                 "real_acceptance_artificial_cost": hsd.stats_cost(st_real, cost_ms) / st_real.tokens,
+                                 "iid_acceptance_artificial_cost": hsd.stats_cost(st_iid, cost_ms) / st_iid.tokens,
+                                 "formula_exact_expectation": hsd.expected_latency(cost_ms, coin[1:], list(T_best), True),
+                                 "formula_as_printed": hsd.expected_latency(cost_ms, coin[1:], list(T_best), False)}}
+
     # ---- calibration pass (Sec. 5.1) over the prompt + the tokens just generated: all-pairs acceptance rates of eight
     # candidate exits and their pass costs, the selection of Sec. 4 on them, and the selected hierarchy measured -------
     calibration = None
@@ -323,6 +340,7 @@ def main():
         "verify_pass": passes,
         "latency_model": selection,
         "calibration": calibration,
+        "ablation": ablation,
         "verify_pass_7b_shaped_4_layers_ctx4096": big,
         "roofline": roofline,
         "cpu_baseline": cpu,

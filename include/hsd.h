@@ -269,6 +269,8 @@ typedef struct {
     int64_t pass_rows[HSD_MAX_LEVELS]; /* tokens fed, summed over passes */
     int64_t drafted[HSD_MAX_LEVELS];   /* draft tokens offered to the level's Verify */
     int64_t accepted[HSD_MAX_LEVELS];  /* of those, accepted */
+    int64_t tested[HSD_MAX_LEVELS];    /* accept tests evaluated (up to and including the first rejection of a call):
+                                          accepted / tested is the per-test acceptance frequency */
     int64_t rounds;                    /* HSD(K, .) calls */
     int64_t tokens;                    /* tokens emitted by the target level */
 } hsd_stats;
@@ -276,6 +278,18 @@ typedef struct {
 /* Calls HSD(K, .) until n_tokens are produced; the last round is cut at n_tokens (the sequence keeps
  * the surplus).  out: cap n_tokens.  stats may be NULL. */
 int hsd_generate(hsd_hier*, int n_tokens, int32_t* out, hsd_stats* stats);
+
+/* The two simplifications the latency analysis makes, as switches (appendix "Examining the assumptions of HSD";
+ * Thm 3.2).  coin: NULL restores Alg. 2's accept test; otherwise [n_levels] floats, entry i in [0, 1] makes level
+ * i's Verify accept every draft with that fixed probability (u_i < coin[i], same Philox word; the corrected / bonus
+ * token is drawn as before), a negative entry keeps the real test at that level, entry 0 is ignored.
+ * exactly_T != 0: an intermediate level hands up exactly T_idx tokens and drops what it collected beyond (the
+ * variant Thm 3.2's formula describes literally).  Takes effect from the next hsd_run / hsd_generate. */
+int hsd_hier_set_ablation(hsd_hier*, const float* coin, int exactly_T);
+
+/* sum_i passes[i] * cost[i] over the first n_levels levels: the "artificial cost" accounting of the same appendix
+ * (a fixed cost per forward pass instead of measured time). */
+double hsd_stats_cost(const hsd_stats*, int n_levels, const double* cost);
 int hsd_get_stats(const hsd_hier*, hsd_stats*);
 int hsd_sequence_length(const hsd_hier*);
 

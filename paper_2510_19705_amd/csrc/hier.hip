@@ -52,6 +52,8 @@ struct hsd_hier {
     hsd_model* pre_model;
     unsigned long long pre_serial;
     int pre_pos;
+    float coin[HSD_MAX_LEVELS];   // >= 0: fixed acceptance probability at that level's Verify (ablation), < 0: Alg. 2
+    bool exactly_T;               // intermediate levels hand up exactly T tokens (ablation)
     hsd_stats stats;
 };
 
@@ -163,7 +165,7 @@ int draft_step(hsd_hier* h, int row) {
     if (softmax_verify_supported(h->V)) {
         const bool pre = g_preembed != 0;
         if (int rc = launch_softmax_verify(h->logits, nullptr, h->tok_dev + h->len, 0, h->V, h->temperature, h->seed, 0u, L.call++, p,
-                                           h->result_dev, h->sampler_scratch, nullptr, pre ? embed_next_of(L.model) : EmbedNext{},
+                                           h->result_dev, h->sampler_scratch, nullptr, pre ? embed_next_of(L.model) : EmbedNext{}, -1.f,
                                            h->stream))
             return rc;
         if (pre) {
@@ -174,7 +176,7 @@ int draft_step(hsd_hier* h, int row) {
     } else {
         if (int rc = launch_softmax(h->logits, p, 1, h->V, h->temperature, h->stream)) return rc;
         if (int rc = launch_accept_resample(p, nullptr, h->tok_dev + h->len, 0, h->V, h->seed, 0u, L.call++, h->result_dev,
-                                            h->sampler_scratch, h->stream))
+                                            h->sampler_scratch, -1.f, h->stream))
             return rc;
     }
     L.cached_len = h->len;
@@ -203,12 +205,12 @@ int verify_step(hsd_hier* h, int idx, int t, const float* q_dev, int* n_out) {
         pre = g_preembed != 0;
         if (int rc = launch_softmax_verify(h->logits, q_dev, h->tok_dev + ctx_end, t, h->V, h->temperature, h->seed, (uint32_t)idx,
                                            L.call++, p, h->result_dev, h->sampler_scratch, h->mailbox_dev,
-                                           pre ? embed_next_of(m0) : EmbedNext{}, h->stream))
+                                           pre ? embed_next_of(m0) : EmbedNext{}, h->coin[idx], h->stream))
             return rc;
     } else {
         if (int rc = launch_softmax(h->logits, p, t + 1, h->V, h->temperature, h->stream)) return rc;
         if (int rc = launch_accept_resample(p, q_dev, h->tok_dev + ctx_end, t, h->V, h->seed, (uint32_t)idx, L.call++, h->result_dev,
-                                            h->sampler_scratch, h->stream))
+                                            h->sampler_scratch, h->coin[idx], h->stream))
             return rc;
         HSD_HIP(hipMemcpyAsync(h->mailbox, h->result_dev, 8, hipMemcpyDeviceToHost, h->stream));
         HSD_HIP(hipMemcpyAsync(h->mailbox + 2, h->tok_dev + ctx_end, (size_t)(t + 1) * 4, hipMemcpyDeviceToHost, h->stream));
@@ -233,6 +235,7 @@ int verify_step(hsd_hier* h, int idx, int t, const float* q_dev, int* n_out) {
     L.count += n + 1;
     h->stats.drafted[idx] += t;
     h->stats.accepted[idx] += n;
+    h->stats.tested[idx] += n + (n < t ? 1 : 0);
     *n_out = n + 1;
     return HSD_OK;
 }
@@ -255,6 +258,14 @@ int run_level(hsd_hier* h, int idx, int* count_out) {
             int t = 0, n1 = 0;
             if (int rc = run_level(h, idx - 1, &t)) return rc;
             if (int rc = verify_step(h, idx, t, h->lv[idx - 1].rows, &n1)) return rc;
+        }
+        if (h->exactly_T && L.count > h->T[idx]) {
+            // drop what was collected beyond T: the sequence ends earlier, and no level may count the dropped
+            // positions as cached (their tokens are gone); the level's first T rows stay where they are
+            h->len -= L.count - h->T[idx];
+            L.count = h->T[idx];
+            for (int j = 0; j <= h->K; ++j) h->lv[j].cached_len = std::min(h->lv[j].cached_len, h->len);
+            h->pre_model = nullptr;
         }
     }
     *count_out = L.count;
@@ -321,6 +332,8 @@ extern "C" int hsd_hier_create(int n_levels, const hsd_level* levels, const int*
     h->mailbox = nullptr;
     h->mailbox_dev = nullptr;
     h->pre_model = nullptr;
+    h->exactly_T = false;
+    for (int i = 0; i < HSD_MAX_LEVELS; ++i) h->coin[i] = -1.f;
     reset_counters(h);
     hipError_t e = hipHostMalloc((void**)&h->mailbox, 68 * sizeof(int32_t), hipHostMallocMapped);
     if (e == hipSuccess) e = hipHostGetDevicePointer((void**)&h->mailbox_dev, h->mailbox, 0);
@@ -339,6 +352,23 @@ extern "C" void hsd_hier_destroy(hsd_hier* h) {
     if (!h) return;
     if (h->mailbox) (void)hipHostFree(h->mailbox);
     delete h;
+}
+
+extern "C" int hsd_hier_set_ablation(hsd_hier* h, const float* coin, int exactly_T) {
+    if (!h) HSD_FAIL(HSD_EINVAL, "hsd_hier_set_ablation: null pointer");
+    if (coin)
+        for (int i = 1; i <= h->K; ++i)
+            if (!(coin[i] <= 1.f)) HSD_FAIL(HSD_EINVAL, "hsd_hier_set_ablation: coin[%d] = %g above 1 (negative = real test)", i, coin[i]);
+    for (int i = 0; i < HSD_MAX_LEVELS; ++i) h->coin[i] = coin && i >= 1 && i <= h->K ? coin[i] : -1.f;
+    h->exactly_T = exactly_T != 0;
+    return HSD_OK;
+}
+
+extern "C" double hsd_stats_cost(const hsd_stats* st, int n_levels, const double* cost) {
+    if (!st || !cost || n_levels < 1 || n_levels > HSD_MAX_LEVELS) return -1.0;
+    double c = 0.0;
+    for (int i = 0; i < n_levels; ++i) c += (double)st->passes[i] * cost[i];
+    return c;
 }
 
 extern "C" int hsd_prefill(hsd_hier* h, const int32_t* prompt, int n) {

@@ -16,6 +16,8 @@ constexpr int SLICE = 2048;          // elements per workgroup
 constexpr int THREADS = 256;
 constexpr int PER_THREAD = SLICE / THREADS;
 
+// `coin` in the kernels below: negative = Alg. 2's test; in [0, 1] = the ablation of the appendix on the assumptions
+// of HSD, where every draft is accepted with that fixed probability (u < coin, same Philox word).
 struct Philox4 { uint32_t w[4]; };
 
 __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
@@ -52,7 +54,7 @@ __global__ __launch_bounds__(THREADS) void accept_resample_kernel(const float* _
                                                                   int32_t* __restrict__ x, int t, int V, uint32_t k0,
                                                                   uint32_t k1, uint32_t level, uint32_t call,
                                                                   int32_t* __restrict__ result, uint32_t* ticket,
-                                                                  uint64_t* totals) {
+                                                                  uint64_t* totals, float coin) {
     __shared__ int sh_n;
     __shared__ uint64_t sh_a[THREADS / 64], sh_b[THREADS / 64];
     __shared__ bool sh_last;
@@ -70,7 +72,7 @@ __global__ __launch_bounds__(THREADS) void accept_resample_kernel(const float* _
             const Philox4 rnd = philox4x32_10((uint32_t)lane, call, level, 0u, k0, k1);
             const float u = (float)(rnd.w[0] >> 8) * 5.9604644775390625e-8f;          // 2^-24 grid in [0,1)
             const float px = p[(size_t)lane * V + xi], qx = q[(size_t)lane * V + xi];
-            reject = !(__fmul_rn(u, qx) < px);
+            reject = coin >= 0.f ? !(u < coin) : !(__fmul_rn(u, qx) < px);
         }
         const unsigned long long mask = __ballot(reject);
         if (lane == 0) sh_n = mask ? (int)__ffsll((long long)mask) - 1 : t;
@@ -327,7 +329,7 @@ __device__ __forceinline__ void draw_corrected(const float4 (&pc)[SMALL_CHUNKS],
 __global__ __launch_bounds__(SMALL_THREADS) void accept_resample_small_kernel(const float* __restrict__ p, const float* __restrict__ q,
                                                                               int32_t* __restrict__ x, int t, int V, uint32_t k0,
                                                                               uint32_t k1, uint32_t level, uint32_t call,
-                                                                              int32_t* __restrict__ result) {
+                                                                              int32_t* __restrict__ result, float coin) {
     __shared__ int sh_n;
     __shared__ SearchShared sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -338,7 +340,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void accept_resample_small_kernel(co
             const Philox4 rnd = philox4x32_10((uint32_t)lane, call, level, 0u, k0, k1);
             const float u = (float)(rnd.w[0] >> 8) * 5.9604644775390625e-8f;
             const float px = p[(size_t)lane * V + xi], qx = q[(size_t)lane * V + xi];
-            reject = !(__fmul_rn(u, qx) < px);
+            reject = coin >= 0.f ? !(u < coin) : !(__fmul_rn(u, qx) < px);
         }
         const unsigned long long mask = __ballot(reject);
         if (lane == 0) sh_n = mask ? (int)__ffsll((long long)mask) - 1 : t;
@@ -374,7 +376,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void softmax_verify_kernel(const flo
                                                                        uint32_t k0, uint32_t k1, uint32_t level, uint32_t call,
                                                                        float* __restrict__ p_out, int32_t* __restrict__ result,
                                                                        uint32_t* ticket, unsigned long long* key,
-                                                                       int32_t* __restrict__ mailbox, const EmbedNext next) {
+                                                                       int32_t* __restrict__ mailbox, const EmbedNext next, float coin) {
     __shared__ float shv[16];
     __shared__ int shi[16];
     __shared__ SearchShared sh;
@@ -403,7 +405,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void softmax_verify_kernel(const flo
                 }
             const Philox4 rnd = philox4x32_10((uint32_t)row, call, level, 0u, k0, k1);
             const float u = (float)(rnd.w[0] >> 8) * 5.9604644775390625e-8f;
-            sh_reject = !(__fmul_rn(u, qx) < px);
+            sh_reject = coin >= 0.f ? !(u < coin) : !(__fmul_rn(u, qx) < px);
         }
     } else if (tid == 0) {
         sh_reject = 1;                                     // the bonus row always takes part
@@ -486,16 +488,16 @@ extern "C" size_t hsd_sampler_scratch_bytes(int vocab) {
 }
 
 int launch_accept_resample(const float* p, const float* q, int32_t* x, int t, int vocab, uint64_t seed, uint32_t level,
-                           uint32_t call, int32_t* result, void* scratch, hipStream_t s) {
+                           uint32_t call, int32_t* result, void* scratch, float coin, hipStream_t s) {
     if (vocab <= SMALL_MAX_V) {
         accept_resample_small_kernel<<<1, SMALL_THREADS, 0, s>>>(p, q, x, t, vocab, (uint32_t)seed, (uint32_t)(seed >> 32), level,
-                                                              call, result);
+                                                              call, result, coin);
         HSD_LAUNCH_CHECK();
         return HSD_OK;
     }
     const int nslices = ceil_div(vocab, SLICE);
     accept_resample_kernel<<<nslices, THREADS, 0, s>>>(p, q, x, t, vocab, (uint32_t)seed, (uint32_t)(seed >> 32), level, call,
-                                                       result, (uint32_t*)scratch, (uint64_t*)((char*)scratch + 16));
+                                                       result, (uint32_t*)scratch, (uint64_t*)((char*)scratch + 16), coin);
     HSD_LAUNCH_CHECK();
     return HSD_OK;
 }
@@ -508,11 +510,11 @@ bool softmax_verify_supported(int vocab) { return vocab <= SMALL_MAX_V && vocab 
 
 int launch_softmax_verify(const float* z, const float* q, int32_t* x, int t, int vocab, float temperature, uint64_t seed,
                           uint32_t level, uint32_t call, float* p_out, int32_t* result, void* scratch, int32_t* mailbox,
-                          const EmbedNext& next, hipStream_t s) {
+                          const EmbedNext& next, float coin, hipStream_t s) {
     if (!softmax_verify_supported(vocab)) HSD_FAIL(HSD_ECAPACITY, "fused softmax + verify: vocabulary %d above %d", vocab, SMALL_MAX_V < g_fused_sampler_max_v ? SMALL_MAX_V : g_fused_sampler_max_v);
     softmax_verify_kernel<<<t + 1, SMALL_THREADS, 0, s>>>(z, q, x, t, vocab, temperature, (uint32_t)seed, (uint32_t)(seed >> 32), level,
                                                           call, p_out, result, (uint32_t*)scratch,
-                                                          (unsigned long long*)((char*)scratch + 8), mailbox, next);
+                                                          (unsigned long long*)((char*)scratch + 8), mailbox, next, coin);
     HSD_LAUNCH_CHECK();
     return HSD_OK;
 }
@@ -523,7 +525,7 @@ extern "C" int hsd_accept_resample(const float* p_dev, const float* q_dev, int32
     if (t < 0 || t > 64) HSD_FAIL(HSD_EINVAL, "hsd_accept_resample: t=%d outside 0..64", t);
     if (t > 0 && !q_dev) HSD_FAIL(HSD_EINVAL, "hsd_accept_resample: draft rows missing for t=%d", t);
     if (vocab < 1) HSD_FAIL(HSD_EINVAL, "hsd_accept_resample: vocab=%d", vocab);
-    return launch_accept_resample(p_dev, q_dev, x_dev, t, vocab, seed, level, call, result_dev, scratch_dev,
+    return launch_accept_resample(p_dev, q_dev, x_dev, t, vocab, seed, level, call, result_dev, scratch_dev, -1.f,
                                   (hipStream_t)stream);
 }
 
@@ -535,5 +537,5 @@ extern "C" int hsd_softmax_verify(const float* logits_dev, const float* q_dev, i
     if (t > 0 && !q_dev) HSD_FAIL(HSD_EINVAL, "hsd_softmax_verify: draft rows missing for t=%d", t);
     if (vocab < 1 || !(temperature >= 0.f)) HSD_FAIL(HSD_EINVAL, "hsd_softmax_verify: vocab=%d temperature=%g", vocab, temperature);
     return launch_softmax_verify(logits_dev, q_dev, x_dev, t, vocab, temperature, seed, level, call, probs_dev, result_dev,
-                                 scratch_dev, host_mailbox, EmbedNext{}, (hipStream_t)stream);
+                                 scratch_dev, host_mailbox, EmbedNext{}, -1.f, (hipStream_t)stream);
 }

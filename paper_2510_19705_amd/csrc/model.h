@@ -72,7 +72,7 @@ int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, 
                      float* workspace, int force_simple, hipStream_t s);
 // kernels_sampler.hip
 int launch_accept_resample(const float* p, const float* q, int32_t* x, int t, int vocab, uint64_t seed, uint32_t level,
-                           uint32_t call, int32_t* result, void* scratch, hipStream_t s);
+                           uint32_t call, int32_t* result, void* scratch, float coin, hipStream_t s);
 bool softmax_verify_supported(int vocab);
 // What the fused sampler needs to leave the emitted token embedded for a following one-token pass of `model`
 // (row 0 of its residual stream, normalised input and sums of squares, exactly as the embedding kernel would):
@@ -88,4 +88,4 @@ struct EmbedNext {
 EmbedNext embed_next_of(const hsd_model* m);
 int launch_softmax_verify(const float* z, const float* q, int32_t* x, int t, int vocab, float temperature, uint64_t seed,
                           uint32_t level, uint32_t call, float* p_out, int32_t* result, void* scratch, int32_t* mailbox,
-                          const EmbedNext& next, hipStream_t s);
+                          const EmbedNext& next, float coin, hipStream_t s);

@@ -47,7 +47,7 @@ class SiteTimes(C.Structure):
 class Stats(C.Structure):
     _fields_ = [("passes", C.c_int64 * MAX_LEVELS), ("pass_rows", C.c_int64 * MAX_LEVELS),
                 ("drafted", C.c_int64 * MAX_LEVELS), ("accepted", C.c_int64 * MAX_LEVELS),
-                ("rounds", C.c_int64), ("tokens", C.c_int64)]
+                ("tested", C.c_int64 * MAX_LEVELS), ("rounds", C.c_int64), ("tokens", C.c_int64)]
 
 
 _vp, _i, _sz, _f, _d = C.c_void_p, C.c_int, C.c_size_t, C.c_float, C.c_double
@@ -62,6 +62,8 @@ _SIGS = {
     "hsd_model_load_head": (_i, [_vp, _vp, _vp, _vp]),
     "hsd_model_set_pages": (_i, [_vp, C.POINTER(C.c_int32), _i]),
     "hsd_model_pass": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
+    "hsd_hier_set_ablation": (_i, [_vp, C.POINTER(C.c_float), _i]),
+    "hsd_stats_cost": (C.c_double, [C.POINTER(Stats), _i, C.POINTER(C.c_double)]),
     "hsd_model_pass_exits": (_i, [_vp, _vp, _i, _i, C.POINTER(C.c_int), _i, _i, _vp]),
     "hsd_overlap": (_i, [_vp, _i, _i, _i, _vp, _vp]),
     "hsd_calibrate_workspace_bytes": (C.c_size_t, [_vp, _i, _i, _i]),
@@ -408,6 +410,13 @@ class Hierarchy:
         _check(lib.hsd_generate(self.handle, n_tokens, out.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(st)))
         return out, st
 
+    def set_ablation(self, coin=None, exactly_T=False):
+        """hsd_hier_set_ablation: coin = per-level fixed acceptance probabilities (entry 0 ignored, negative = real)."""
+        arr = None
+        if coin is not None:
+            arr = (C.c_float * MAX_LEVELS)(*([float(c) for c in coin] + [-1.0] * (MAX_LEVELS - len(coin))))
+        _check(lib.hsd_hier_set_ablation(self.handle, arr, int(exactly_T)))
+
     def stats(self):
         st = Stats()
         _check(lib.hsd_get_stats(self.handle, C.byref(st)))
@@ -423,6 +432,12 @@ class Hierarchy:
 
 
 # ---- host-side latency model ------------------------------------------------------------------
+def stats_cost(st, cost):
+    """hsd_stats_cost: sum of passes[i] * cost[i]."""
+    c, cp = _f64(cost)
+    return lib.hsd_stats_cost(C.byref(st), len(c), cp)
+
+
 def gamma(alpha, Ti, Tj):
     return lib.hsd_gamma(alpha, Ti, Tj)
 

@@ -261,3 +261,41 @@ def test_token_embedded_by_the_sampler_changes_nothing(bf16):
             hsd.lib.hsd_tune(104, 1, 0, 0)
     assert runs[0] == runs[1]
     model.close()
+
+
+@pytest.mark.parametrize("mode,seed", [("truncate", 502), ("coin", 501), ("both", 500)])
+def test_ablation_modes_follow_the_oracle(tiny, mode, seed):
+    """The switches of the appendix on HSD's assumptions: coin-flip acceptances (same Philox words, fixed
+    probability per level) and the exactly-T variant of Alg. 1.  Streams, pass counts, accepted / tested counters
+    equal the oracle's (seeds chosen with the oracle alone for the asserted margins)."""
+    from paper_2510_19705_amd import hsd
+    w, prompt, model = tiny
+    T, coin = (3, 2), [0.0, 0.8, 0.6]
+    levels = _oracle_levels(w, TINY, TINY_EXITS, 1.0)
+    ch = specsample.IIDChooser(seed, coin) if mode != "truncate" else specsample.PhiloxChooser(seed)
+    o = ohsd.HSD(levels, T, ch, truncate=(mode != "coin"))
+    ref = o.generate([int(t) for t in prompt], 64)
+    assert min(ch.accept_margins + [1.0]) > 3e-4 and min(ch.sample_margins) > 3e-6
+    h = _gpu_hier(model, TINY_EXITS, T, 1.0, seed=seed)
+    h.set_ablation(coin if mode != "truncate" else None, exactly_T=(mode != "coin"))
+    h.prefill(prompt)
+    got, st = h.generate(64)
+    assert got.tolist() == ref
+    assert [st.passes[i] for i in range(3)] == o.passes
+    assert [st.accepted[i] for i in range(3)] == o.accepted and [st.tested[i] for i in range(3)] == o.tested
+    assert [st.drafted[i] for i in range(3)] == o.drafted
+    if mode != "coin":
+        assert st.drafted[2] == 2 * st.passes[2]                 # the top level always sees exactly T_1 drafts
+    cost = [1.0, 2.5, 7.0]
+    assert hsd.stats_cost(st, cost) == sum(p * c for p, c in zip(o.passes, cost))
+    # back to the real rule: the plain stream of this seed again
+    h.set_ablation(None, False)
+    h.rewind(len(prompt))
+    levels = _oracle_levels(w, TINY, TINY_EXITS, 1.0)
+    ch2 = specsample.PhiloxChooser(seed)
+    ref2 = ohsd.HSD(levels, T, ch2).generate([int(t) for t in prompt], 24)
+    if min(ch2.accept_margins) > 3e-4 and min(ch2.sample_margins) > 3e-6:
+        assert h.generate(24)[0].tolist() == ref2
+    with pytest.raises(hsd.HsdError):
+        h.set_ablation([0.0, 1.5, 0.5])
+    h.close()
