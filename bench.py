@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Bench of the HSD hot path on one MI355X.
 
-Workload (benchmark configs[1]): 1B-shaped early-exit hierarchy, bf16, batch 1 - 16 layers,
+Workload: 1B-shaped early-exit hierarchy, bf16, batch 1 - 16 layers,
 d 2048, 32 query / 8 KV heads x 64, FFN 8192, vocab 32000, drafters = exits after layers 2 and 6
 sharing the final norm and head; prompt of 512 uniform-random ids, 256 generated tokens,
 temperature 1.  Random-init weights (the paper's checkpoints and prompts are not available offline).
@@ -111,7 +111,7 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the sweeps; run HSD at T=(4,2) only")
     args = ap.parse_args()
     if args.gpus != 1:
-        log("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, 'How the path would shard').")
+        log("bench.py measures one GPU: this build has no multi-GPU path; run it with --gpus 1.")
         sys.exit(2)
 
     import torch
