@@ -212,7 +212,9 @@ int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int
  * (0: default, which also caps the split at about 160 workgroups).  key 103: nt = largest vocabulary the driver
  * hands to the fused softmax + verify launch (default 32768, its limit); smaller values exercise the two-launch
  * path hsd_softmax + hsd_accept_resample on small vocabularies.  key 104: nt = 0 stops the driver's fused sampler
- * from embedding the token it emits for the one-token pass that follows (default 1; same results either way). */
+ * from embedding the token it emits for the one-token pass that follows (default 1; same results either way).
+ * key 105: nt = 0 makes the driver synchronise the stream after each Verify instead of polling the sampler's
+ * sequence number in pinned host memory (default 1; same results either way). */
 int hsd_tune(int key, int nt, int ksplit, int waves);
 
 /* ---------------------------------------------------------------------------------------------

@@ -128,6 +128,7 @@ extern int g_attn_qt1_rows;
 extern int g_attn_steps_per_wave;
 extern int g_fused_sampler_max_v;
 extern int g_preembed;
+extern int g_poll_mailbox;
 int launch_gemv_bf16(const GemmArgs& g, int epi, hipStream_t s);   // row-major W: EPI_STORE, EPI_RESID, EPI_ROPE
 int launch_gemm_f32(const float* x, const float* w, float* out, int m, int n, int k, bool swiglu, hipStream_t s);
 // interleave: 0 plain rows at row_offset, 1 / 2 gate / up of a fused SwiGLU matrix, 3 attention heads of hd rows

@@ -16,6 +16,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <chrono>
 #include <vector>
 
 #include "model.h"
@@ -47,6 +48,7 @@ struct hsd_hier {
     void* sampler_scratch;
     int32_t* mailbox;   // pinned host memory: n, m, then up to 65 token ids
     int32_t* mailbox_dev;   // the same memory as the device addresses it
+    int mailbox_seq;        // last sequence number handed to a sampler launch (the kernel stores it after its results)
     // The fused sampler leaves the token it emits embedded in level 0's model (EmbedNext): valid for a one-token pass
     // of that model at position pre_pos while the model's pass counter still reads pre_serial.
     hsd_model* pre_model;
@@ -166,7 +168,7 @@ int draft_step(hsd_hier* h, int row) {
         const bool pre = g_preembed != 0;
         if (int rc = launch_softmax_verify(h->logits, nullptr, h->tok_dev + h->len, 0, h->V, h->temperature, h->seed, 0u, L.call++, p,
                                            h->result_dev, h->sampler_scratch, nullptr, pre ? embed_next_of(L.model) : EmbedNext{}, -1.f,
-                                           h->stream))
+                                           0, h->stream))
             return rc;
         if (pre) {
             h->pre_model = L.model;
@@ -184,6 +186,19 @@ int draft_step(hsd_hier* h, int row) {
     return HSD_OK;
 }
 
+// Waits for the sampler kernel's sequence number in the pinned mailbox by polling it: the host learns n a few
+// microseconds after the kernel wrote it, without the wake-up latency of a stream synchronisation, and queues the
+// next pass while the kernel finishes.  Gives up after a while (returns false: the caller synchronises the stream).
+bool wait_mailbox(hsd_hier* h) {
+    if (!g_poll_mailbox) return false;
+    volatile int32_t* slot = h->mailbox + MAILBOX_SEQ_SLOT;
+    const auto t0 = std::chrono::steady_clock::now();
+    for (unsigned spins = 0;; ++spins) {
+        if (__atomic_load_n(slot, __ATOMIC_ACQUIRE) == h->mailbox_seq) return true;
+        if ((spins & 1023) == 1023 && std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(200)) return false;
+    }
+}
+
 // Verify (Alg. 2): the last t sequence tokens are drafts with rows q_dev.  Returns n+1 in *n_out.
 int verify_step(hsd_hier* h, int idx, int t, const float* q_dev, int* n_out) {
     LevelState& L = h->lv[idx];
@@ -198,15 +213,16 @@ int verify_step(hsd_hier* h, int idx, int t, const float* q_dev, int* n_out) {
     float* p = L.rows + (size_t)L.count * h->V;
     h->pre_model = nullptr;
     hsd_model* m0 = h->lv[0].model;
-    bool pre = false;
+    bool pre = false, polled = false;
     if (softmax_verify_supported(h->V)) {
         // one launch; the kernel writes n, m and the surviving tokens straight into the pinned mailbox, and leaves m
         // embedded in level 0's model, whose next draft pass is that one token
         pre = g_preembed != 0;
         if (int rc = launch_softmax_verify(h->logits, q_dev, h->tok_dev + ctx_end, t, h->V, h->temperature, h->seed, (uint32_t)idx,
                                            L.call++, p, h->result_dev, h->sampler_scratch, h->mailbox_dev,
-                                           pre ? embed_next_of(m0) : EmbedNext{}, h->coin[idx], h->stream))
+                                           pre ? embed_next_of(m0) : EmbedNext{}, h->coin[idx], ++h->mailbox_seq, h->stream))
             return rc;
+        polled = wait_mailbox(h);
     } else {
         if (int rc = launch_softmax(h->logits, p, t + 1, h->V, h->temperature, h->stream)) return rc;
         if (int rc = launch_accept_resample(p, q_dev, h->tok_dev + ctx_end, t, h->V, h->seed, (uint32_t)idx, L.call++, h->result_dev,
@@ -215,7 +231,7 @@ int verify_step(hsd_hier* h, int idx, int t, const float* q_dev, int* n_out) {
         HSD_HIP(hipMemcpyAsync(h->mailbox, h->result_dev, 8, hipMemcpyDeviceToHost, h->stream));
         HSD_HIP(hipMemcpyAsync(h->mailbox + 2, h->tok_dev + ctx_end, (size_t)(t + 1) * 4, hipMemcpyDeviceToHost, h->stream));
     }
-    HSD_HIP(hipStreamSynchronize(h->stream));
+    if (!polled) HSD_HIP(hipStreamSynchronize(h->stream));
     const int n = h->mailbox[0];
     if (n < 0 || n > t) HSD_FAIL(HSD_EHIP, "verify: device returned n=%d for t=%d", n, t);
     for (int i = 0; i <= n; ++i) h->tok_host[ctx_end + i] = h->mailbox[2 + i];
@@ -331,11 +347,13 @@ extern "C" int hsd_hier_create(int n_levels, const hsd_level* levels, const int*
     h->len = 0;
     h->mailbox = nullptr;
     h->mailbox_dev = nullptr;
+    h->mailbox_seq = 0;
     h->pre_model = nullptr;
     h->exactly_T = false;
     for (int i = 0; i < HSD_MAX_LEVELS; ++i) h->coin[i] = -1.f;
     reset_counters(h);
     hipError_t e = hipHostMalloc((void**)&h->mailbox, 68 * sizeof(int32_t), hipHostMallocMapped);
+    if (e == hipSuccess) memset(h->mailbox, 0, 68 * sizeof(int32_t));
     if (e == hipSuccess) e = hipHostGetDevicePointer((void**)&h->mailbox_dev, h->mailbox, 0);
     if (e == hipSuccess) e = hipMemsetAsync(h->sampler_scratch, 0, hsd_sampler_scratch_bytes(h->V), h->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
@@ -448,6 +466,7 @@ extern "C" int hsd_verify(hsd_hier* h, int level, const int32_t* draft_tokens, c
     const int ctx_end = h->len - t;
     int n1 = 0;
     if (int rc = verify_step(h, level, t, draft_probs_dev, &n1)) return rc;
+    HSD_HIP(hipStreamSynchronize(h->stream));          // the driver itself only polls for n; a caller gets a finished stream
     if (tokens_out) std::copy(h->tok_host.begin() + ctx_end, h->tok_host.begin() + ctx_end + n1, tokens_out);
     *n_out = n1;
     if (probs_dev_out) *probs_dev_out = L.rows + (size_t)row0 * h->V;
@@ -461,8 +480,11 @@ extern "C" int hsd_run(hsd_hier* h, int level, int32_t* tokens_out, int cap, int
     const int base = h->len;
     int count = 0;
     if (int rc = run_level(h, level, &count)) return rc;
-    if (level == 0 || h->K == 0)
+    if (level == 0 || h->K == 0) {
         if (int rc = fetch_tokens(h, base)) return rc;
+    } else {
+        HSD_HIP(hipStreamSynchronize(h->stream));
+    }
     if (level == h->K) {
         h->stats.rounds++;
         h->stats.tokens += count;
@@ -490,6 +512,7 @@ extern "C" int hsd_generate(hsd_hier* h, int n_tokens, int32_t* out, hsd_stats* 
         h->stats.rounds++;
         h->stats.tokens += count;
     }
+    HSD_HIP(hipStreamSynchronize(h->stream));          // the rounds only polled for each Verify's result
     std::copy(h->tok_host.begin() + base, h->tok_host.begin() + base + n_tokens, out);
     if (stats) *stats = h->stats;
     return HSD_OK;

@@ -550,6 +550,7 @@ void gemm_tune(int epilogue, int nt, int ksplit, int waves) {
     if (epilogue == 102) { g_attn_steps_per_wave = nt; return; }
     if (epilogue == 103) { g_fused_sampler_max_v = nt; return; }
     if (epilogue == 104) { g_preembed = nt; return; }
+    if (epilogue == 105) { g_poll_mailbox = nt; return; }
     if (epilogue >= 0 && epilogue < 4) {
         g_tune_nt[epilogue] = nt;
         g_tune_ksplit[epilogue] = ksplit;

@@ -376,7 +376,8 @@ __global__ __launch_bounds__(SMALL_THREADS) void softmax_verify_kernel(const flo
                                                                        uint32_t k0, uint32_t k1, uint32_t level, uint32_t call,
                                                                        float* __restrict__ p_out, int32_t* __restrict__ result,
                                                                        uint32_t* ticket, unsigned long long* key,
-                                                                       int32_t* __restrict__ mailbox, const EmbedNext next, float coin) {
+                                                                       int32_t* __restrict__ mailbox, const EmbedNext next, float coin,
+                                                                       int mailbox_seq) {
     __shared__ float shv[16];
     __shared__ int shi[16];
     __shared__ SearchShared sh;
@@ -448,6 +449,13 @@ __global__ __launch_bounds__(SMALL_THREADS) void softmax_verify_kernel(const flo
             if (mailbox) {                                     // the accepted drafts and the new token, for the host
                 if (tid < n) mailbox[2 + tid] = x[tid];
                 if (tid == 0) mailbox[2 + n] = m;
+                if (mailbox_seq) {
+                    // a host that polls instead of waiting for the stream: the payload above is made visible system-wide
+                    // by every lane that wrote it, then the sequence number follows
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");
+                    if (tid == 0)
+                        __hip_atomic_store(mailbox + MAILBOX_SEQ_SLOT, mailbox_seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                }
             }
         }
         if (tid == 0) sh_last = last;
@@ -504,17 +512,18 @@ int launch_accept_resample(const float* p, const float* q, int32_t* x, int t, in
 
 // Fused softmax + Alg. 2 (vocabularies up to 32768 only); scratch as for launch_accept_resample (ticket in word 0,
 // the key in bytes 8..15, both zero between launches).
+int g_poll_mailbox = 1;                       // hsd_tune key 105: 0 makes the driver wait for the stream after each Verify instead
 int g_preembed = 1;                           // hsd_tune key 104: 0 keeps the embedding of the emitted token in the next pass
 int g_fused_sampler_max_v = SMALL_MAX_V;       // hsd_tune key 103: lower it to send smaller vocabularies down the two-launch path
 bool softmax_verify_supported(int vocab) { return vocab <= SMALL_MAX_V && vocab <= g_fused_sampler_max_v; }
 
 int launch_softmax_verify(const float* z, const float* q, int32_t* x, int t, int vocab, float temperature, uint64_t seed,
                           uint32_t level, uint32_t call, float* p_out, int32_t* result, void* scratch, int32_t* mailbox,
-                          const EmbedNext& next, float coin, hipStream_t s) {
+                          const EmbedNext& next, float coin, int mailbox_seq, hipStream_t s) {
     if (!softmax_verify_supported(vocab)) HSD_FAIL(HSD_ECAPACITY, "fused softmax + verify: vocabulary %d above %d", vocab, SMALL_MAX_V < g_fused_sampler_max_v ? SMALL_MAX_V : g_fused_sampler_max_v);
     softmax_verify_kernel<<<t + 1, SMALL_THREADS, 0, s>>>(z, q, x, t, vocab, temperature, (uint32_t)seed, (uint32_t)(seed >> 32), level,
                                                           call, p_out, result, (uint32_t*)scratch,
-                                                          (unsigned long long*)((char*)scratch + 8), mailbox, next, coin);
+                                                          (unsigned long long*)((char*)scratch + 8), mailbox, next, coin, mailbox_seq);
     HSD_LAUNCH_CHECK();
     return HSD_OK;
 }
@@ -537,5 +546,5 @@ extern "C" int hsd_softmax_verify(const float* logits_dev, const float* q_dev, i
     if (t > 0 && !q_dev) HSD_FAIL(HSD_EINVAL, "hsd_softmax_verify: draft rows missing for t=%d", t);
     if (vocab < 1 || !(temperature >= 0.f)) HSD_FAIL(HSD_EINVAL, "hsd_softmax_verify: vocab=%d temperature=%g", vocab, temperature);
     return launch_softmax_verify(logits_dev, q_dev, x_dev, t, vocab, temperature, seed, level, call, probs_dev, result_dev,
-                                 scratch_dev, host_mailbox, EmbedNext{}, -1.f, (hipStream_t)stream);
+                                 scratch_dev, host_mailbox, EmbedNext{}, -1.f, 0, (hipStream_t)stream);
 }

@@ -88,4 +88,7 @@ struct EmbedNext {
 EmbedNext embed_next_of(const hsd_model* m);
 int launch_softmax_verify(const float* z, const float* q, int32_t* x, int t, int vocab, float temperature, uint64_t seed,
                           uint32_t level, uint32_t call, float* p_out, int32_t* result, void* scratch, int32_t* mailbox,
-                          const EmbedNext& next, float coin, hipStream_t s);
+                          const EmbedNext& next, float coin, int mailbox_seq, hipStream_t s);
+// With mailbox_seq != 0 the kernel ends its mailbox writes by storing mailbox_seq into this slot of the mailbox
+// (which then must have MAILBOX_SEQ_SLOT + 1 entries), after a system-scope release: a host may poll it.
+constexpr int MAILBOX_SEQ_SLOT = 67;

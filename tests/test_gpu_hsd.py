@@ -299,3 +299,22 @@ def test_ablation_modes_follow_the_oracle(tiny, mode, seed):
     with pytest.raises(hsd.HsdError):
         h.set_ablation([0.0, 1.5, 0.5])
     h.close()
+
+
+def test_polling_and_stream_wait_agree(tiny):
+    """The driver learns each Verify's result by polling the sampler's sequence number in pinned memory; with that
+    switched off it waits for the stream.  Same stream of tokens and counters, over many verifies in a row."""
+    from paper_2510_19705_amd import hsd
+    _, prompt, model = tiny
+    runs = []
+    for poll in (1, 0, 1):
+        hsd.lib.hsd_tune(105, poll, 0, 0)
+        try:
+            h = _gpu_hier(model, TINY_EXITS, (2, 1), 1.0, seed=9)
+            h.prefill(prompt)
+            toks, st = h.generate(150)
+            runs.append((toks.tolist(), [st.passes[i] for i in range(3)], [st.accepted[i] for i in range(3)]))
+            h.close()
+        finally:
+            hsd.lib.hsd_tune(105, 1, 0, 0)
+    assert runs[0] == runs[1] == runs[2]
