@@ -120,9 +120,12 @@ int hsd_measure_site(hsd_model*, int site, int rows, int pos0, int iters, double
  * ------------------------------------------------------------------------------------------- */
 
 /* p = softmax(z / temperature) row-wise, fp32 [rows, vocab]; temperature == 0 writes the one-hot
- * row at the lowest-index maximum.  logits_dev and probs_dev must not overlap. */
+ * row at the lowest-index maximum.  logits_dev and probs_dev must not overlap.  Vocabularies above 32768 are cut in
+ * slices over several workgroups and need scratch_dev of hsd_softmax_scratch_bytes(rows, vocab) bytes (16-byte
+ * aligned; 0 bytes and NULL allowed for smaller vocabularies). */
+size_t hsd_softmax_scratch_bytes(int rows, int vocab);
 int hsd_softmax(const float* logits_dev, float* probs_dev, int rows, int vocab, float temperature,
-                void* stream);
+                void* scratch_dev, void* stream);
 
 /* Bytes of device scratch hsd_accept_resample needs for a vocabulary size. */
 size_t hsd_sampler_scratch_bytes(int vocab);

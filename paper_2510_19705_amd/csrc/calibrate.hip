@@ -44,7 +44,7 @@ int launch_overlap(const float* P, int n, int R, int V, double* out, size_t stri
 }
 
 struct CalibLayout {
-    size_t logits, probs, overlaps, total;
+    size_t logits, probs, overlaps, softmax, total;
     int chunk, npairs, n_scored;
 };
 
@@ -61,6 +61,7 @@ int calib_layout(const hsd_model* m, int n_exits, int n_tokens, int n_ctx, Calib
     L->logits = o;   o += align_up(rows, 256);
     L->probs = o;    o += align_up(rows, 256);
     L->overlaps = o; o += align_up((size_t)(L->npairs > 0 ? L->npairs : 1) * L->n_scored * sizeof(double), 256);
+    L->softmax = o;  o += softmax_scratch_bytes(n_exits * L->chunk, m->desc.vocab);
     L->total = o;
     return HSD_OK;
 }
@@ -106,7 +107,7 @@ extern "C" int hsd_calibrate(hsd_model* m, const int* exits, int n_exits, const 
     for (int pos = n_ctx; pos < n_tokens;) {
         const int c = std::min(L.chunk, n_tokens - pos);
         if (int rc = model_pass_exits(m, tokens_dev + pos, pos, c, exits, n_exits, c, logits)) return rc;
-        if (int rc = launch_softmax(logits, probs, n_exits * c, d.vocab, temperature, s)) return rc;
+        if (int rc = launch_softmax(logits, probs, n_exits * c, d.vocab, temperature, (float*)(wb + L.softmax), s)) return rc;
         if (int rc = launch_overlap(probs, n_exits, c, d.vocab, overlaps + (pos - n_ctx), (size_t)L.n_scored, s)) return rc;
         pos += c;
     }

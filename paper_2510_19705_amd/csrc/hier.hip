@@ -46,6 +46,7 @@ struct hsd_hier {
     int logit_rows_cap;
     int32_t* result_dev;
     void* sampler_scratch;
+    float* softmax_scratch;
     int32_t* mailbox;   // pinned host memory: n, m, then up to 65 token ids
     int32_t* mailbox_dev;   // the same memory as the device addresses it
     int mailbox_seq;        // last sequence number handed to a sampler launch (the kernel stores it after its results)
@@ -76,7 +77,7 @@ int rows_cap_of(int n_levels, const int* T, int level) {
 }
 
 struct HierLayout {
-    size_t tok, logits, rows[HSD_MAX_LEVELS], result, sampler, total;
+    size_t tok, logits, rows[HSD_MAX_LEVELS], result, sampler, softmax, total;
     int logit_rows, max_seq, V;
 };
 
@@ -117,6 +118,7 @@ int hier_layout(int n_levels, const hsd_level* levels, const int* T, HierLayout*
     }
     L->result = o;  o += 256;
     L->sampler = o; o += hsd_sampler_scratch_bytes(L->V);
+    L->softmax = o; o += softmax_scratch_bytes(L->logit_rows, L->V);
     L->total = o;
     return HSD_OK;
 }
@@ -176,7 +178,7 @@ int draft_step(hsd_hier* h, int row) {
             h->pre_pos = h->len;
         }
     } else {
-        if (int rc = launch_softmax(h->logits, p, 1, h->V, h->temperature, h->stream)) return rc;
+        if (int rc = launch_softmax(h->logits, p, 1, h->V, h->temperature, h->softmax_scratch, h->stream)) return rc;
         if (int rc = launch_accept_resample(p, nullptr, h->tok_dev + h->len, 0, h->V, h->seed, 0u, L.call++, h->result_dev,
                                             h->sampler_scratch, -1.f, h->stream))
             return rc;
@@ -224,7 +226,7 @@ int verify_step(hsd_hier* h, int idx, int t, const float* q_dev, int* n_out) {
             return rc;
         polled = wait_mailbox(h);
     } else {
-        if (int rc = launch_softmax(h->logits, p, t + 1, h->V, h->temperature, h->stream)) return rc;
+        if (int rc = launch_softmax(h->logits, p, t + 1, h->V, h->temperature, h->softmax_scratch, h->stream)) return rc;
         if (int rc = launch_accept_resample(p, q_dev, h->tok_dev + ctx_end, t, h->V, h->seed, (uint32_t)idx, L.call++, h->result_dev,
                                             h->sampler_scratch, h->coin[idx], h->stream))
             return rc;
@@ -339,6 +341,7 @@ extern "C" int hsd_hier_create(int n_levels, const hsd_level* levels, const int*
     h->logit_rows_cap = L.logit_rows;
     h->result_dev = (int32_t*)(wb + L.result);
     h->sampler_scratch = wb + L.sampler;
+    h->softmax_scratch = (float*)(wb + L.softmax);
     for (int i = 0; i < n_levels; ++i) {
         h->lv[i] = LevelState{levels[i].model, levels[i].exit_layer, 0, (float*)(wb + L.rows[i]), rows_cap_of(n_levels, T, i), 0, 0u};
         if (i < h->K) h->T[i] = T[i];

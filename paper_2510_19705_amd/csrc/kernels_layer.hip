@@ -125,8 +125,7 @@ __global__ void rope_kv_kernel(const float* __restrict__ part, int ksplit, int M
 }
 
 // p = softmax(z / temperature) per row (grid.x rows, 1024 threads); temperature 0: one-hot at the
-// lowest-index maximum.  CH > 0: the row fits the workgroup's registers (vocab <= 1024 * 4 * CH), so it is
-// read once; CH == 0: it is re-read from L2 for the sum and the final pass.
+// lowest-index maximum.  The row fits the workgroup's registers (vocab <= 1024 * 4 * CH), so it is read once.
 template <int CH>
 __global__ __launch_bounds__(SOFTMAX_THREADS) void softmax_kernel(const float* __restrict__ z, float* __restrict__ p, int V,
                                                                   float temperature) {
@@ -134,47 +133,89 @@ __global__ __launch_bounds__(SOFTMAX_THREADS) void softmax_kernel(const float* _
     __shared__ int shi[16];
     const float* zr = z + (size_t)blockIdx.x * V;
     float* pr = p + (size_t)blockIdx.x * V;
-    if constexpr (CH > 0) {
-        const bool vec = (V & 3) == 0 && ((uintptr_t)zr & 15) == 0 && ((uintptr_t)pr & 15) == 0;
-        float4 c[CH];
-        softmax_row_cached<CH>(zr, V, temperature, vec, c, shv, shi);
-        store_row_cached<CH>(pr, V, vec, c);
-    } else {
-        const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
-        float mx = -INFINITY;
-        int arg = 0x7fffffff;
-        for (int i = tid; i < V; i += blockDim.x) {
-            const float v = zr[i];
-            if (v > mx) { mx = v; arg = i; }
-        }
+    const bool vec = (V & 3) == 0 && ((uintptr_t)zr & 15) == 0 && ((uintptr_t)pr & 15) == 0;
+    float4 c[CH];
+    softmax_row_cached<CH>(zr, V, temperature, vec, c, shv, shi);
+    store_row_cached<CH>(pr, V, vec, c);
+}
+
+// Larger vocabularies: a row is cut in slices of SLICE_V tokens, one workgroup each (a single workgroup streams a
+// row at one CU's ~40 GB/s, which for 128256 tokens costs tens of microseconds).  First launch: every slice's
+// maximum (lowest index on ties) and sum of exp((z - slice max) / temperature); second launch: the row's maximum and
+// the sum of the slice sums rescaled to it, in slice order, then p = exp((z - max) / temperature) / sum for the slice.
+constexpr int SLICE_V = SOFTMAX_THREADS * 8;
+
+__global__ __launch_bounds__(SOFTMAX_THREADS) void softmax_slice_stats_kernel(const float* __restrict__ z, int V, float temperature,
+                                                                              float* __restrict__ stats, int nslices) {
+    __shared__ float shv[16];
+    __shared__ int shi[16];
+    const int row = blockIdx.x, sl = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float* zr = z + (size_t)row * V;
+    const int lo = sl * SLICE_V, hi = min(V, lo + SLICE_V);
+    float v[8];
+    float mx = -INFINITY;
+    int arg = 0x7fffffff;
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const float om = __shfl_xor(mx, o, 64);
-            const int oa = __shfl_xor(arg, o, 64);
-            if (om > mx || (om == mx && oa < arg)) { mx = om; arg = oa; }
-        }
-        if (lane == 0) { shv[wave] = mx; shi[wave] = arg; }
-        __syncthreads();
-        mx = shv[0];
-        arg = shi[0];
-        for (int w = 1; w < nw; ++w)
-            if (shv[w] > mx || (shv[w] == mx && shi[w] < arg)) { mx = shv[w]; arg = shi[w]; }
-        __syncthreads();
-        if (temperature == 0.f) {
-            for (int i = tid; i < V; i += blockDim.x) pr[i] = i == arg ? 1.f : 0.f;
-            return;
-        }
+    for (int k = 0; k < 8; ++k) {
+        const int i = lo + k * SOFTMAX_THREADS + tid;
+        v[k] = i < hi ? zr[i] : -INFINITY;
+        if (v[k] > mx) { mx = v[k]; arg = i; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float om = __shfl_xor(mx, o, 64);
+        const int oa = __shfl_xor(arg, o, 64);
+        if (om > mx || (om == mx && oa < arg)) { mx = om; arg = oa; }
+    }
+    if (lane == 0) { shv[wave] = mx; shi[wave] = arg; }
+    __syncthreads();
+    mx = shv[0];
+    arg = shi[0];
+    for (int w = 1; w < 16; ++w)
+        if (shv[w] > mx || (shv[w] == mx && shi[w] < arg)) { mx = shv[w]; arg = shi[w]; }
+    __syncthreads();
+    float sum = 0.f;
+    if (temperature != 0.f) {
         const float it = 1.0f / temperature;
-        float sum = 0.f;
-        for (int i = tid; i < V; i += blockDim.x) sum += expf(__fmul_rn(__fsub_rn(zr[i], mx), it));
+#pragma unroll
+        for (int k = 0; k < 8; ++k) sum = __fadd_rn(sum, expf(__fmul_rn(__fsub_rn(v[k], mx), it)));     // exp(-inf) = 0 for the padding
         sum = wave_sum(sum);
         if (lane == 0) shv[wave] = sum;
         __syncthreads();
         sum = 0.f;
-        for (int w = 0; w < nw; ++w) sum += shv[w];
-        const float inv = 1.0f / sum;
-        for (int i = tid; i < V; i += blockDim.x) pr[i] = __fmul_rn(expf(__fmul_rn(__fsub_rn(zr[i], mx), it)), inv);
+        for (int w = 0; w < 16; ++w) sum += shv[w];
     }
+    if (tid == 0) {
+        float* st = stats + ((size_t)row * nslices + sl) * 4;
+        st[0] = mx;
+        st[1] = sum;
+        st[2] = __int_as_float(arg);
+    }
+}
+
+__global__ __launch_bounds__(SOFTMAX_THREADS) void softmax_slice_write_kernel(const float* __restrict__ z, float* __restrict__ p, int V,
+                                                                              float temperature, const float* __restrict__ stats,
+                                                                              int nslices) {
+    const int row = blockIdx.x, sl = blockIdx.y, tid = threadIdx.x;
+    const float* st = stats + (size_t)row * nslices * 4;
+    float mx = st[0];
+    int arg = __float_as_int(st[2]);
+    for (int s = 1; s < nslices; ++s) {                    // slices ascend in index, so ties keep the earlier one
+        const float m = st[s * 4];
+        if (m > mx) { mx = m; arg = __float_as_int(st[s * 4 + 2]); }
+    }
+    const float* zr = z + (size_t)row * V;
+    float* pr = p + (size_t)row * V;
+    const int lo = sl * SLICE_V, hi = min(V, lo + SLICE_V);
+    if (temperature == 0.f) {
+        for (int i = lo + tid; i < hi; i += SOFTMAX_THREADS) pr[i] = i == arg ? 1.f : 0.f;
+        return;
+    }
+    const float it = 1.0f / temperature;
+    float sum = 0.f;
+    for (int s = 0; s < nslices; ++s) sum = __fadd_rn(sum, __fmul_rn(st[s * 4 + 1], expf(__fmul_rn(__fsub_rn(st[s * 4], mx), it))));
+    const float inv = 1.0f / sum;
+    for (int i = lo + tid; i < hi; i += SOFTMAX_THREADS) pr[i] = __fmul_rn(expf(__fmul_rn(__fsub_rn(zr[i], mx), it)), inv);
 }
 
 // ---- launchers --------------------------------------------------------------------------------
@@ -217,20 +258,38 @@ int launch_rope_kv(const float* part, int ksplit, int m, void* q, void* kv_layer
     return HSD_OK;
 }
 
-int launch_softmax(const float* z, float* p, int rows, int vocab, float temperature, hipStream_t s) {
-    if (vocab <= SOFTMAX_THREADS * 4 * 2)
+// Bytes of device scratch launch_softmax needs beyond the rows (slice statistics of the large-vocabulary path).
+size_t softmax_scratch_bytes(int rows, int vocab) {
+    if (vocab <= SOFTMAX_THREADS * 4 * 8) return 0;
+    return align_up((size_t)rows * ceil_div(vocab, SLICE_V) * 4 * sizeof(float), 256);
+}
+
+int launch_softmax(const float* z, float* p, int rows, int vocab, float temperature, float* scratch, hipStream_t s) {
+    if (vocab <= SOFTMAX_THREADS * 4 * 2) {
         softmax_kernel<2><<<rows, SOFTMAX_THREADS, 0, s>>>(z, p, vocab, temperature);
-    else if (vocab <= SOFTMAX_THREADS * 4 * 8)
+    } else if (vocab <= SOFTMAX_THREADS * 4 * 8) {
         softmax_kernel<8><<<rows, SOFTMAX_THREADS, 0, s>>>(z, p, vocab, temperature);
-    else
-        softmax_kernel<0><<<rows, SOFTMAX_THREADS, 0, s>>>(z, p, vocab, temperature);
+    } else {
+        if (!scratch) HSD_FAIL(HSD_EINVAL, "softmax: vocabulary %d needs the slice scratch", vocab);
+        const int nslices = ceil_div(vocab, SLICE_V);
+        softmax_slice_stats_kernel<<<dim3(rows, nslices), SOFTMAX_THREADS, 0, s>>>(z, vocab, temperature, scratch, nslices);
+        HSD_LAUNCH_CHECK();
+        softmax_slice_write_kernel<<<dim3(rows, nslices), SOFTMAX_THREADS, 0, s>>>(z, p, vocab, temperature, scratch, nslices);
+    }
     HSD_LAUNCH_CHECK();
     return HSD_OK;
 }
 
-extern "C" int hsd_softmax(const float* logits_dev, float* probs_dev, int rows, int vocab, float temperature, void* stream) {
+extern "C" size_t hsd_softmax_scratch_bytes(int rows, int vocab) {
+    return rows < 1 || vocab < 1 ? 0 : softmax_scratch_bytes(rows, vocab);
+}
+
+extern "C" int hsd_softmax(const float* logits_dev, float* probs_dev, int rows, int vocab, float temperature, void* scratch_dev,
+                           void* stream) {
     if (!logits_dev || !probs_dev || rows < 0 || vocab < 1 || !(temperature >= 0.f))
         HSD_FAIL(HSD_EINVAL, "hsd_softmax: bad arguments (rows=%d vocab=%d temperature=%g)", rows, vocab, temperature);
     if (rows == 0) return HSD_OK;
-    return launch_softmax(logits_dev, probs_dev, rows, vocab, temperature, (hipStream_t)stream);
+    if (softmax_scratch_bytes(rows, vocab) > 0 && (!scratch_dev || ((uintptr_t)scratch_dev & 15)))
+        HSD_FAIL(HSD_EINVAL, "hsd_softmax: vocabulary %d needs 16-byte aligned scratch of hsd_softmax_scratch_bytes()", vocab);
+    return launch_softmax(logits_dev, probs_dev, rows, vocab, temperature, (float*)scratch_dev, (hipStream_t)stream);
 }

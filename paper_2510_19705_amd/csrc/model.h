@@ -63,7 +63,8 @@ int launch_resid_rmsnorm(float* x, const float* part, int ksplit, int part_rows,
                          int rows, int row0, int d, float eps, int dtype, hipStream_t s);
 int launch_rope_kv(const float* part, int ksplit, int m, void* q, void* kv_layer, const int32_t* pages, int pos0, int n_q,
                    int n_kv, int hd, float rope_base, int dtype, hipStream_t s);
-int launch_softmax(const float* z, float* p, int rows, int vocab, float temperature, hipStream_t s);
+size_t softmax_scratch_bytes(int rows, int vocab);
+int launch_softmax(const float* z, float* p, int rows, int vocab, float temperature, float* scratch, hipStream_t s);
 int launch_scale_rows_bf16(const float* x, const float* w, void* out, int rows, int d, hipStream_t s);
 // kernels_attn.hip
 size_t attn_workspace_bytes(int batch, int m, int n_q, int n_kv, int hd, int max_len);

@@ -72,7 +72,8 @@ _SIGS = {
     "hsd_profile_begin": (_i, [_vp, _i]),
     "hsd_profile_end": (_i, [_vp, C.POINTER(SiteTimes)]),
     "hsd_measure_site": (_i, [_vp, _i, _i, _i, _i, _dp]),
-    "hsd_softmax": (_i, [_vp, _vp, _i, _i, _f, _vp]),
+    "hsd_softmax_scratch_bytes": (_sz, [_i, _i]),
+    "hsd_softmax": (_i, [_vp, _vp, _i, _i, _f, _vp, _vp]),
     "hsd_sampler_scratch_bytes": (_sz, [_i]),
     "hsd_accept_resample": (_i, [_vp, _vp, _vp, _i, _i, C.c_uint64, C.c_uint32, C.c_uint32, _vp, _vp, _vp]),
     "hsd_softmax_verify": (_i, [_vp, _vp, _vp, _i, _i, C.c_float, C.c_uint64, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp, _vp]),
@@ -261,8 +262,10 @@ def overlap(rows):
 def softmax(logits, temperature):
     logits = logits.contiguous()
     out = torch.empty_like(logits)
+    nb = lib.hsd_softmax_scratch_bytes(logits.shape[0], logits.shape[1])
+    scratch = torch.empty(nb, dtype=torch.uint8, device="cuda") if nb else None
     _check(lib.hsd_softmax(logits.data_ptr(), out.data_ptr(), logits.shape[0], logits.shape[1], float(temperature),
-                           _stream()))
+                           scratch.data_ptr() if nb else None, _stream()))
     return out
 
 

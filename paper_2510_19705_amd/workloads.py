@@ -3,6 +3,7 @@ networks, up to a 70B-shaped target (140 GB of bf16 weights resident in HBM).
 
     python -m paper_2510_19705_amd.workloads --config independent     # 125M / 1B / 7B-shaped, vocab 32000
     python -m paper_2510_19705_amd.workloads --config 70b             # 1B / 8B exit 8 / 8B / 70B-shaped, vocab 128256
+    python -m paper_2510_19705_amd.workloads --config microbench      # one 7B-shaped layer: KV length x query tokens x batch
 
 Weights are drawn on the device (seeded normal, residual-writing matrices scaled by 0.1); prompts are uniform-random
 ids.  For each workload: pass time and HBM fraction of every candidate (algorithmic bytes / time / 8 TB/s), pairwise
@@ -189,11 +190,96 @@ def run(config, seed=20251019, temperature=1.0):
     return out
 
 
+def _time(torch, fn, iters):
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / iters                     # microseconds
+
+
+def microbench():
+    """Isolated verify pass of ONE 7B-shaped layer (32 x 128 heads, MHA, d 4096, FFN 11008), bf16, random K/V and
+    activations: k query tokens per sequence, cached length S, batch B.  Attention per layer at every cell whose K/V
+    fits (one layer's K/V is B * S * 16 KiB); the four projections at B * k rows, up to the 64 rows one pass of this
+    library takes (cells beyond are left out).  Also the sampler at vocab 128256 on random distributions."""
+    import torch
+    assert torch.cuda.is_available(), "needs the GPU"
+    from . import hsd, inputs
+    shape = dict(inputs.SHAPES["7b"], n_layers=4)
+    d, F = shape["d"], shape["ffn"]
+    n_q, n_kv, hd = shape["n_q"], shape["n_kv"], shape["hd"]
+    model = random_model(hsd, inputs, torch, shape, 1, 256)
+    tok = torch.randint(0, shape["vocab"], (128,), device="cuda", dtype=torch.int32)
+    model.model_pass(tok[:64], 0, 4, 0)
+    site_mb = {"qkv": (n_q + 2 * n_kv) * hd * d * 2 / 1e6, "o": n_q * hd * d * 2 / 1e6, "gateup": 2 * F * d * 2 / 1e6,
+               "down": F * d * 2 / 1e6}
+    gemm = {}
+    for rows in (1, 2, 4, 8, 16, 32, 64):
+        model.model_pass(tok[64:64 + rows], 64, 4, rows)
+        us = {k: model.measure_site(k, rows, 64, 100) for k in site_mb}
+        gemm[rows] = us
+        log("rows %2d: " % rows + "  ".join("%s %.1f us (%.2f TB/s)" % (k, v, site_mb[k] / v) for k, v in us.items()))
+    model.close()
+    cells = []
+    for B in (1, 8, 64):
+        for S in (4096, 16384, 32768):
+            kv_bytes = 2 * S * n_kv * hd * 2 * B
+            cache = hsd.KvLayer(B, S, n_kv, hd, hsd.BF16)
+            cache.buf.view(torch.int16).random_(-16000, 16000)   # finite bf16 patterns
+            ws = None
+            for k in (1, 2, 4, 8, 16):
+                q = torch.randn(B, k, n_q, hd, device="cuda").to(torch.bfloat16)
+                pos0 = torch.full((B,), S - k, dtype=torch.int32, device="cuda")
+                nb = hsd.lib.hsd_attention_workspace_bytes(B, k, n_q, n_kv, hd, S)
+                if ws is None or ws.numel() < nb:
+                    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+                att_us = _time(torch, lambda: cache.attention(q, pos0, S, ws), 5 if kv_bytes > 4e9 else 20)
+                rows = B * k
+                cell = {"batch": B, "kv_len": S, "k": k, "kv_GB": kv_bytes / 1e9, "attention_us": att_us,
+                        "attention_TBps": kv_bytes / att_us / 1e6}
+                if rows in gemm:
+                    g = sum(gemm[rows].values())
+                    w_bytes = sum(site_mb.values()) * 1e6
+                    cell.update({"projections_us": g, "layer_us": g + att_us,
+                                 "layer_hbm_frac": (w_bytes + kv_bytes) / (g + att_us) / 1e3 / HBM_PEAK_GBS})
+                cells.append(cell)
+                log(cell)
+            del cache
+            torch.cuda.empty_cache()
+    # sampler at the largest vocabulary (two launches: softmax, then accept / resample)
+    sampler = []
+    V = 128256
+    for sigma in (1.0, 4.0):
+        for t in (1, 4, 16):
+            z = torch.randn(t + 1, V, device="cuda") * sigma
+            p = hsd.softmax(z, 1.0)
+            qd = hsd.softmax(z[:t] + torch.randn(t, V, device="cuda"), 1.0)
+            x = torch.multinomial(qd, 1).to(torch.int32).flatten()
+            xd = torch.cat([x, torch.zeros(1, dtype=torch.int32, device="cuda")])
+            scratch = torch.zeros(hsd.lib.hsd_sampler_scratch_bytes(V), dtype=torch.uint8, device="cuda")
+            res = torch.empty(2, dtype=torch.int32, device="cuda")
+            pbuf = torch.empty_like(z)
+            sm = torch.empty(max(256, hsd.lib.hsd_softmax_scratch_bytes(t + 1, V)), dtype=torch.uint8, device="cuda")
+
+            def both():
+                hsd._check(hsd.lib.hsd_softmax(z.data_ptr(), pbuf.data_ptr(), t + 1, V, 1.0, sm.data_ptr(), hsd._stream()))
+                hsd._check(hsd.lib.hsd_accept_resample(pbuf.data_ptr(), qd.data_ptr(), xd.data_ptr(), t, V, 7, 1, 0, res.data_ptr(),
+                                                       scratch.data_ptr(), hsd._stream()))
+            sampler.append({"vocab": V, "sigma": sigma, "t": t, "softmax_plus_accept_us": _time(torch, both, 50)})
+            log(sampler[-1])
+    return {"config": "microbench", "projections_us_by_rows": gemm, "weight_MB": site_mb, "cells": cells, "sampler": sampler}
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", choices=sorted(CONFIGS), default="independent")
+    ap.add_argument("--config", choices=sorted(CONFIGS) + ["microbench"], default="independent")
     args = ap.parse_args()
-    print(json.dumps(run(args.config)), flush=True)
+    print(json.dumps(microbench() if args.config == "microbench" else run(args.config)), flush=True)
 
 
 if __name__ == "__main__":

@@ -24,7 +24,7 @@ def _cuda(a, dtype=None):
 
 
 # ---- softmax ---------------------------------------------------------------------------------
-@pytest.mark.parametrize("rows,V", [(1, 50), (3, 2048), (5, 5000), (17, 128256)])
+@pytest.mark.parametrize("rows,V", [(1, 50), (3, 2048), (5, 5000), (2, 32769), (3, 40961), (17, 128256)])
 @pytest.mark.parametrize("temperature", [1.0, 0.7, 0.0])
 def test_softmax(hsd, rows, V, temperature):
     say("softmax", rows, V, temperature)
