@@ -96,9 +96,9 @@ extern "C" int hsd_calibrate(hsd_model* m, const int* exits, int n_exits, const 
     float* logits = (float*)(wb + L.logits);
     float* probs = (float*)(wb + L.probs);
     double* overlaps = (double*)(wb + L.overlaps);
-    const int deepest = exits[n_exits - 1];            // model_pass_exits validates the list
 
-    // context-only positions through the deepest exit, then the scored positions with every exit's rows
+    // context-only positions through the deepest exit (model_pass_exits validates the list), then the scored positions
+    // with every exit's rows
     for (int pos = 0; pos < n_ctx;) {
         const int c = std::min(d.max_rows, n_ctx - pos);
         if (int rc = model_pass_exits(m, tokens_dev + pos, pos, c, exits, n_exits, 0, nullptr)) return rc;
@@ -111,7 +111,6 @@ extern "C" int hsd_calibrate(hsd_model* m, const int* exits, int n_exits, const 
         if (int rc = launch_overlap(probs, n_exits, c, d.vocab, overlaps + (pos - n_ctx), (size_t)L.n_scored, s)) return rc;
         pos += c;
     }
-    (void)deepest;
     std::vector<double> host((size_t)L.npairs * L.n_scored);
     if (L.npairs > 0) {
         HSD_HIP(hipMemcpyAsync(host.data(), overlaps, host.size() * sizeof(double), hipMemcpyDeviceToHost, s));
