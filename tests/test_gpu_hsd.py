@@ -318,3 +318,55 @@ def test_polling_and_stream_wait_agree(tiny):
         finally:
             hsd.lib.hsd_tune(105, 1, 0, 0)
     assert runs[0] == runs[1] == runs[2]
+
+
+@pytest.mark.parametrize("name,exits,T,n,t0_prompt,t1_seed", [
+    ("eight_levels", (1, 2, 3, 4, 5, 6, 7, 8), (2, 1, 1, 1, 1, 1, 1), 40, 11, 801),
+    ("forty_drafts", (2, 8), (40,), 90, 12, 811)])
+def test_largest_hierarchies(name, exits, T, n, t0_prompt, t1_seed):
+    """The most levels the library takes (8) and verify passes of 41 rows (40 drafts + bonus row), against the oracle
+    at temperature 0 and 1; prompts / seeds chosen with the oracle alone for the asserted margins."""
+    w = inputs.make_weights(TINY, seed=1, bf16=False)
+    model = gpu_model(TINY, w, False, max_seq=256, max_rows=64)
+    for temperature, pseed, seed in ((0.0, t0_prompt, 1), (1.0, 2, t1_seed)):
+        prompt = inputs.make_prompt(TINY["vocab"], 32, seed=pseed)
+        levels = _oracle_levels(w, TINY, exits, temperature)
+        ch = specsample.PhiloxChooser(seed)
+        o = ohsd.HSD(levels, T, ch)
+        ref = o.generate([int(t) for t in prompt], n)
+        if temperature == 0:
+            assert min(l.min_top2_gap for l in levels) > 1e-3
+        else:
+            assert min(ch.accept_margins) > 3e-4 and min(ch.sample_margins) > 3e-6
+        h = _gpu_hier(model, exits, T, temperature, seed=seed)
+        h.prefill(prompt)
+        got, st = h.generate(n)
+        assert got.tolist() == ref, (name, temperature)
+        k = len(exits)
+        assert [st.passes[i] for i in range(k)] == o.passes and [st.accepted[i] for i in range(k)] == o.accepted
+        say(name, "temperature", temperature, "accepted", o.accepted, "of", o.drafted)
+        h.close()
+    model.close()
+
+
+def test_sequence_up_to_the_last_cache_position():
+    """Generation may fill the KV capacity exactly; one token more is refused with HSD_ECAPACITY and leaves the
+    hierarchy usable (rewind + generate again gives the same tokens)."""
+    from paper_2510_19705_amd import hsd
+    w = inputs.make_weights(TINY, seed=1, bf16=False)
+    model = gpu_model(TINY, w, False, max_seq=128, max_rows=16)
+    prompt = inputs.make_prompt(TINY["vocab"], 100, seed=3)
+    h = _gpu_hier(model, TINY_EXITS, (3, 2), 1.0, seed=5)
+    h.prefill(prompt)
+    with pytest.raises(hsd.HsdError) as e:
+        h.generate(200)                                      # runs into the capacity of 128 positions
+    assert e.value.code == -2
+    full = h.sequence_length()
+    assert 120 <= full <= 128
+    h.rewind(100)
+    a, _ = h.generate(16)
+    h.rewind(100)
+    b, _ = h.generate(16)
+    assert a.tolist() == b.tolist()
+    h.close()
+    model.close()
