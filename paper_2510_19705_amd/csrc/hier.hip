@@ -4,7 +4,9 @@
 // intermediate levels, current drafts).  Draft steps and the verifier's pass + rejection kernel are
 // enqueued without host round trips: the sampler writes each new token id straight into the buffer
 // that the next pass embeds from.  The host only learns n (accepted count) and the corrected token
-// once per Verify, which is the one synchronisation Alg. 1's control flow needs.
+// once per Verify, which is the one round trip Alg. 1's control flow needs: the sampler kernel writes them into
+// pinned host memory followed by a sequence number, and the host polls that number instead of waiting for the
+// stream, so the next pass is queued while the kernel is still finishing.
 //
 // KV validity (the paper does not discuss caching): level i keeps cached_len_i = number of leading
 // sequence tokens whose K/V for its layers is in the cache.  A pass of level i feeds every token

@@ -1,11 +1,13 @@
-// Fused rejection rule of Alg. 2 (App. B.1) / Sec. 2: accept tests for the t drafted tokens, then
-// the corrected token from the normalised residual max(0, p - q) or the bonus token from p_{t+1},
-// in ONE launch.  Every workgroup first evaluates the t accept tests (lane i tests draft i, the
-// first rejection is found with a ballot), so all agree on n; each then sums the fixed-point weights
-// of its slice of the chosen row (integer sums: any order gives the same bits); the last workgroup
-// to finish (device-scope ticket) scans the slice totals, locates the slice that holds the
-// threshold and scans inside it.  Random numbers are Philox4x32-10 blocks addressed by
-// (seed; slot, call, level), so nothing depends on launch geometry.
+// The rejection rule of Alg. 2 (App. B.1) / Sec. 2 on the device: accept tests for the t drafted tokens, then the
+// corrected token from the normalised residual max(0, p - q) or the bonus token from p_{t+1}.  Random numbers are
+// Philox4x32-10 blocks addressed by (seed; slot, call, level), so nothing depends on launch geometry; sums are over
+// integer fixed-point weights, so any reduction order gives the same token.  Three kernels:
+//  * accept_resample_kernel (any vocabulary): every workgroup evaluates the t accept tests (lane i tests draft i,
+//    first rejection by ballot), sums the weights of its slice of the chosen row; the last workgroup to finish
+//    (device-scope ticket) scans the slice totals, locates the slice that holds the threshold and scans inside it;
+//  * accept_resample_small_kernel (vocabulary <= 32768): the same in one workgroup that holds the row in registers;
+//  * softmax_verify_kernel (vocabulary <= 32768): softmax of the logit rows, the accept tests and the draw fused, one
+//    workgroup per row, plus what the driver needs next (results in pinned host memory, the emitted token embedded).
 #include "common.h"
 #include "softmax_row.h"
 #include "model.h"
