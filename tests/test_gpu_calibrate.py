@@ -95,6 +95,10 @@ def test_calibrate_matrix_and_selection(bf16):
     assert np.array_equal(alpha, alpha.T) and (np.diag(alpha) == 1).all()
     assert calibrate.triangle_violation(alpha) <= 1e-9
     assert (cost > 0).all() and cost[-1] > cost[0]            # deeper exits cost more
+    # no context-only positions, fewer positions than one chunk
+    a_short, _ = model.calibrate(exits, _cuda(toks[:11].astype(np.int32)), 0, 1.0)
+    r_short = calibrate.acceptance_matrix(calibrate.exit_distributions(oracle_decoder(shape, w, 128), exits, toks[:11], 0, 1.0))
+    assert np.abs(a_short - r_short).max() < (8e-3 if bf16 else 1e-5)
     # temperature 0: one-hot rows, overlap = fraction of positions where the argmaxes agree
     a0, _ = model.calibrate(exits, _cuda(toks.astype(np.int32)), 30, 0.0)
     r0 = calibrate.acceptance_matrix(calibrate.exit_distributions(oracle_decoder(shape, w, 128), exits, toks, 30, 0.0))
