@@ -59,6 +59,7 @@ struct hsd_hier {
     int pre_pos;
     float coin[HSD_MAX_LEVELS];   // >= 0: fixed acceptance probability at that level's Verify (ablation), < 0: Alg. 2
     bool exactly_T;               // intermediate levels hand up exactly T tokens (ablation)
+    bool skip_target_rows;        // set while hsd_generate runs
     hsd_stats stats;
 };
 
@@ -215,6 +216,9 @@ int verify_step(hsd_hier* h, int idx, int t, const float* q_dev, int* n_out) {
     const int start = std::min(effective_cached(h, idx), ctx_end - 1);
     if (int rc = level_pass(h, idx, start, t + 1)) return rc;
     float* p = L.rows + (size_t)L.count * h->V;
+    // Nobody verifies the target's tokens, so inside hsd_generate its rows p_1..p_{n+1} need not be stored (the
+    // fused kernel keeps each row in registers); single calls (hsd_verify, hsd_run) always return them.
+    float* p_store = h->skip_target_rows && idx == h->K && softmax_verify_supported(h->V) ? nullptr : p;
     h->pre_model = nullptr;
     hsd_model* m0 = h->lv[0].model;
     bool pre = false, polled = false;
@@ -223,7 +227,7 @@ int verify_step(hsd_hier* h, int idx, int t, const float* q_dev, int* n_out) {
         // embedded in level 0's model, whose next draft pass is that one token
         pre = g_preembed != 0;
         if (int rc = launch_softmax_verify(h->logits, q_dev, h->tok_dev + ctx_end, t, h->V, h->temperature, h->seed, (uint32_t)idx,
-                                           L.call++, p, h->result_dev, h->sampler_scratch, h->mailbox_dev,
+                                           L.call++, p_store, h->result_dev, h->sampler_scratch, h->mailbox_dev,
                                            pre ? embed_next_of(m0) : EmbedNext{}, h->coin[idx], ++h->mailbox_seq, h->stream))
             return rc;
         polled = wait_mailbox(h);
@@ -355,6 +359,7 @@ extern "C" int hsd_hier_create(int n_levels, const hsd_level* levels, const int*
     h->mailbox_seq = 0;
     h->pre_model = nullptr;
     h->exactly_T = false;
+    h->skip_target_rows = false;
     for (int i = 0; i < HSD_MAX_LEVELS; ++i) h->coin[i] = -1.f;
     reset_counters(h);
     hipError_t e = hipHostMalloc((void**)&h->mailbox, 68 * sizeof(int32_t), hipHostMallocMapped);
@@ -508,15 +513,21 @@ extern "C" int hsd_generate(hsd_hier* h, int n_tokens, int32_t* out, hsd_stats* 
     if (n_tokens < 0) HSD_FAIL(HSD_EINVAL, "hsd_generate: n_tokens=%d", n_tokens);
     if (h->len < 1) HSD_FAIL(HSD_ESTATE, "hsd_generate: empty sequence (call hsd_prefill first)");
     const int base = h->len;
+    h->skip_target_rows = h->K > 0;
     while (h->len - base < n_tokens) {
         const int before = h->len;
         int count = 0;
-        if (int rc = run_level(h, h->K, &count)) return rc;
+        const int rc0 = run_level(h, h->K, &count);
+        if (rc0) {
+            h->skip_target_rows = false;
+            return rc0;
+        }
         if (h->K == 0)
             if (int rc = fetch_tokens(h, before)) return rc;
         h->stats.rounds++;
         h->stats.tokens += count;
     }
+    h->skip_target_rows = false;
     HSD_HIP(hipStreamSynchronize(h->stream));          // the rounds only polled for each Verify's result
     std::copy(h->tok_host.begin() + base, h->tok_host.begin() + base + n_tokens, out);
     if (stats) *stats = h->stats;
