@@ -292,6 +292,16 @@ int hsd_generate(hsd_hier*, int n_tokens, int32_t* out, hsd_stats* stats);
  * variant Thm 3.2's formula describes literally).  Takes effect from the next hsd_run / hsd_generate. */
 int hsd_hier_set_ablation(hsd_hier*, const float* coin, int exactly_T);
 
+/* Synthetic drafter (workload construction for hierarchies of random-init networks, whose distributions would
+ * otherwise overlap by chance only; Sec. 5 works with drafters whose acceptance rates are 0.6-0.9): level `level`
+ * (below the target) still runs its own pass, which is what it costs and what the statistics count, but takes as
+ * its logits those of level `source_level` (above it, not synthetic itself) at the same contexts plus
+ * noise_std * n(level, position, vocabulary entry), n standard normal from Philox4x32-10 blocks with counter
+ * (entry / 4, position, level | 2^31, 0x4E4F4953) by Box-Muller.  The source's side passes are not counted, so only
+ * the fixed-cost accounting (hsd_stats_cost) is meaningful for such a run, not its wall-clock time.
+ * source_level < 0 switches it off. */
+int hsd_hier_set_distilled(hsd_hier*, int level, int source_level, float noise_std);
+
 /* sum_i passes[i] * cost[i] over the first n_levels levels: the "artificial cost" accounting of the same appendix
  * (a fixed cost per forward pass instead of measured time). */
 double hsd_stats_cost(const hsd_stats*, int n_levels, const double* cost);

@@ -31,6 +31,8 @@ struct LevelState {
     int rows_cap;
     int count;          // tokens collected by the current HSD(level, .) call
     uint32_t call;      // Philox call index: Verify calls (draft steps at level 0)
+    int distill_src;    // >= 0: this level's logits are that level's logits plus noise (synthetic drafter), else -1
+    float distill_std;
 };
 
 struct hsd_hier {
@@ -151,7 +153,21 @@ int level_pass(hsd_hier* h, int idx, int start, int n_logit_rows) {
     if (int rc = model_pass(L.model, h->tok_dev + pos, pos, h->len - pos, L.exit_layer, n_logit_rows, h->logits, embedded)) return rc;
     h->stats.passes[idx]++;
     h->stats.pass_rows[idx] += h->len - pos;
-    return HSD_OK;
+    if (L.distill_src < 0 || n_logit_rows == 0) return HSD_OK;
+    // Synthetic drafter: the pass above is what the level costs; its distribution comes from the source level's
+    // logits at the same contexts (a side pass that is not counted and does not move the source's cached length;
+    // the K/V it writes are those of the current tokens) plus the level's noise.
+    const LevelState& S = h->lv[L.distill_src];
+    const int smax = S.model->desc.max_rows;
+    int sp = std::max(0, std::min(effective_cached(h, L.distill_src), h->len - n_logit_rows));
+    while (h->len - sp > smax) {
+        const int chunk = std::min(smax, h->len - sp - n_logit_rows);
+        if (chunk < 1) HSD_FAIL(HSD_ECAPACITY, "pass: %d logit rows do not fit a pass of %d rows of the source level", n_logit_rows, smax);
+        if (int rc = model_pass(S.model, h->tok_dev + sp, sp, chunk, S.exit_layer, 0, nullptr)) return rc;
+        sp += chunk;
+    }
+    if (int rc = model_pass(S.model, h->tok_dev + sp, sp, h->len - sp, S.exit_layer, n_logit_rows, h->logits)) return rc;
+    return launch_add_noise(h->logits, n_logit_rows, h->V, h->seed, (uint32_t)idx, h->len - n_logit_rows, L.distill_std, h->stream);
 }
 
 int check_room(const hsd_hier* h, int extra) {
@@ -349,7 +365,7 @@ extern "C" int hsd_hier_create(int n_levels, const hsd_level* levels, const int*
     h->sampler_scratch = wb + L.sampler;
     h->softmax_scratch = (float*)(wb + L.softmax);
     for (int i = 0; i < n_levels; ++i) {
-        h->lv[i] = LevelState{levels[i].model, levels[i].exit_layer, 0, (float*)(wb + L.rows[i]), rows_cap_of(n_levels, T, i), 0, 0u};
+        h->lv[i] = LevelState{levels[i].model, levels[i].exit_layer, 0, (float*)(wb + L.rows[i]), rows_cap_of(n_levels, T, i), 0, 0u, -1, 0.f};
         if (i < h->K) h->T[i] = T[i];
     }
     h->tok_host.assign(h->max_seq, 0);
@@ -380,6 +396,21 @@ extern "C" void hsd_hier_destroy(hsd_hier* h) {
     if (!h) return;
     if (h->mailbox) (void)hipHostFree(h->mailbox);
     delete h;
+}
+
+extern "C" int hsd_hier_set_distilled(hsd_hier* h, int level, int source_level, float noise_std) {
+    if (!h) HSD_FAIL(HSD_EINVAL, "hsd_hier_set_distilled: null pointer");
+    if (level < 0 || level >= h->K) HSD_FAIL(HSD_EINVAL, "hsd_hier_set_distilled: level %d outside 0..%d (the target is never synthetic)", level, h->K - 1);
+    if (source_level < 0) {
+        h->lv[level].distill_src = -1;
+        return HSD_OK;
+    }
+    if (source_level <= level || source_level > h->K) HSD_FAIL(HSD_EINVAL, "hsd_hier_set_distilled: source level %d must lie in %d..%d", source_level, level + 1, h->K);
+    if (h->lv[source_level].distill_src >= 0) HSD_FAIL(HSD_EINVAL, "hsd_hier_set_distilled: source level %d is synthetic itself", source_level);
+    if (!(noise_std >= 0.f)) HSD_FAIL(HSD_EINVAL, "hsd_hier_set_distilled: noise_std %g", noise_std);
+    h->lv[level].distill_src = source_level;
+    h->lv[level].distill_std = noise_std;
+    return HSD_OK;
 }
 
 extern "C" int hsd_hier_set_ablation(hsd_hier* h, const float* coin, int exactly_T) {

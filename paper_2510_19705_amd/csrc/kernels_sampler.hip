@@ -490,7 +490,37 @@ __global__ __launch_bounds__(SMALL_THREADS) void softmax_verify_kernel(const flo
     }
 }
 
+// z[r, v] += std * n(level, pos0 + r, v): the synthetic closeness of a drafter to a deeper level (workload
+// construction, not part of the method).  n = Box-Muller on the words of the Philox block with counter
+// (v / 4, position, level | 2^31, 0x4E4F4953), two normals per word pair, evaluated in fp64.
+__global__ __launch_bounds__(256) void add_noise_kernel(float* __restrict__ z, int V, uint32_t k0, uint32_t k1, uint32_t level,
+                                                        int pos0, float std) {
+    const int blk = blockIdx.x * blockDim.x + threadIdx.x, row = blockIdx.y;
+    if (blk * 4 >= V) return;
+    const Philox4 w = philox4x32_10((uint32_t)blk, (uint32_t)(pos0 + row), level | 0x80000000u, 0x4E4F4953u, k0, k1);
+    float* zr = z + (size_t)row * V + (size_t)blk * 4;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const double u1 = ((double)w.w[2 * h] + 0.5) * 2.3283064365386963e-10;          // 2^-32
+        const double u2 = ((double)w.w[2 * h + 1] + 0.5) * 2.3283064365386963e-10;
+        const double r = sqrt(-2.0 * log(u1));
+        double sn, cs;
+        sincos(6.283185307179586 * u2, &sn, &cs);
+        const int v = blk * 4 + 2 * h;
+        if (v < V) zr[2 * h] = (float)((double)zr[2 * h] + (double)std * (r * cs));
+        if (v + 1 < V) zr[2 * h + 1] = (float)((double)zr[2 * h + 1] + (double)std * (r * sn));
+    }
+}
+
 }  // namespace
+
+int launch_add_noise(float* z, int rows, int vocab, uint64_t seed, uint32_t level, int pos0, float std, hipStream_t s) {
+    if (rows < 1) return HSD_OK;
+    add_noise_kernel<<<dim3(ceil_div(ceil_div(vocab, 4), 256), rows), 256, 0, s>>>(z, vocab, (uint32_t)seed, (uint32_t)(seed >> 32), level,
+                                                                                  pos0, std);
+    HSD_LAUNCH_CHECK();
+    return HSD_OK;
+}
 
 extern "C" size_t hsd_sampler_scratch_bytes(int vocab) {
     const int nslices = ceil_div(vocab < 1 ? 1 : vocab, SLICE);

@@ -74,6 +74,7 @@ int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, 
 // kernels_sampler.hip
 int launch_accept_resample(const float* p, const float* q, int32_t* x, int t, int vocab, uint64_t seed, uint32_t level,
                            uint32_t call, int32_t* result, void* scratch, float coin, hipStream_t s);
+int launch_add_noise(float* z, int rows, int vocab, uint64_t seed, uint32_t level, int pos0, float std, hipStream_t s);
 bool softmax_verify_supported(int vocab);
 // What the fused sampler needs to leave the emitted token embedded for a following one-token pass of `model`
 // (row 0 of its residual stream, normalised input and sums of squares, exactly as the embedding kernel would):

@@ -63,6 +63,7 @@ _SIGS = {
     "hsd_model_set_pages": (_i, [_vp, C.POINTER(C.c_int32), _i]),
     "hsd_model_pass": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
     "hsd_hier_set_ablation": (_i, [_vp, C.POINTER(C.c_float), _i]),
+    "hsd_hier_set_distilled": (_i, [_vp, _i, _i, _f]),
     "hsd_stats_cost": (C.c_double, [C.POINTER(Stats), _i, C.POINTER(C.c_double)]),
     "hsd_model_pass_exits": (_i, [_vp, _vp, _i, _i, C.POINTER(C.c_int), _i, _i, _vp]),
     "hsd_overlap": (_i, [_vp, _i, _i, _i, _vp, _vp]),
@@ -412,6 +413,10 @@ class Hierarchy:
         st = Stats()
         _check(lib.hsd_generate(self.handle, n_tokens, out.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(st)))
         return out, st
+
+    def set_distilled(self, level, source_level, noise_std):
+        """hsd_hier_set_distilled: level's logits = source level's logits + seeded Gaussian noise (synthetic drafter)."""
+        _check(lib.hsd_hier_set_distilled(self.handle, level, source_level, float(noise_std)))
 
     def set_ablation(self, coin=None, exactly_T=False):
         """hsd_hier_set_ablation: coin = per-level fixed acceptance probabilities (entry 0 ignored, negative = real)."""

@@ -398,3 +398,50 @@ def test_vocabulary_above_the_fused_sampler_limit():
         assert [st.passes[i] for i in range(3)] == o.passes and [st.accepted[i] for i in range(3)] == o.accepted
         h.close()
     model.close()
+
+
+def test_distilled_drafters_follow_the_oracle():
+    """Synthetic drafters (a foreign small network and an early exit whose logits are replaced by the target's plus
+    seeded Gaussian noise of std 1.0 / 0.5): stream, pass counts and acceptance counters against the oracle, and
+    the noise rows themselves."""
+    from oracle import distill
+    from paper_2510_19705_amd import hsd
+    small = dict(n_layers=2, d=128, n_q=2, n_kv=1, hd=64, ffn=384, vocab=TINY["vocab"])
+    wa = inputs.make_weights(small, seed=51, bf16=False)
+    wb = inputs.make_weights(TINY, seed=1, bf16=False)
+    ma = gpu_model(small, wa, False, max_seq=256, max_rows=16)
+    mb = gpu_model(TINY, wb, False, max_seq=256, max_rows=16)
+    da, db = oracle_decoder(small, wa, 256), oracle_decoder(TINY, wb, 256)
+    prompt = inputs.make_prompt(TINY["vocab"], 32, seed=2)
+    seed, T = 1301, (3, 2)
+    tgt = decoder.Level(db, 8, 1.0)
+    levels = [distill.DistilledLevel(da, 2, tgt, 0, 1.0, seed, 1.0), distill.DistilledLevel(db, 4, tgt, 1, 0.5, seed, 1.0), tgt]
+    ch = specsample.PhiloxChooser(seed)
+    o = ohsd.HSD(levels, T, ch)
+    ref = o.generate([int(t) for t in prompt], 48)
+    assert min(ch.accept_margins) > 3e-4 and min(ch.sample_margins) > 3e-6
+    h = hsd.Hierarchy([(ma, 2), (mb, 4), (mb, 8)], T, 1.0, seed)
+    h.set_distilled(0, 2, 1.0)
+    h.set_distilled(1, 2, 0.5)
+    h.prefill(prompt)
+    got, st = h.generate(48)
+    assert got.tolist() == ref
+    assert [st.passes[i] for i in range(3)] == o.passes                  # the source's side passes are not counted
+    assert [st.accepted[i] for i in range(3)] == o.accepted and [st.tested[i] for i in range(3)] == o.tested
+    say("distilled drafters: accepted", o.accepted, "tested", o.tested)
+    # the first draft row after a rewind: softmax(target logits + noise) against the oracle's row
+    h.rewind(len(prompt))
+    toks, q = h.draft(1)
+    db.reset()
+    da.reset()
+    row = levels[0].next_dists([int(t) for t in prompt], 1)[0]
+    assert np.abs(q.cpu().numpy()[0] - row).max() < 2e-6 * row.max() + 1e-9
+    with pytest.raises(hsd.HsdError):
+        h.set_distilled(2, 2, 1.0)                                       # the target is never synthetic
+    with pytest.raises(hsd.HsdError):
+        h.set_distilled(1, 0, 1.0)                                       # the source must be above
+    h.set_distilled(0, -1, 0.0)
+    h.set_distilled(1, -1, 0.0)
+    h.close()
+    ma.close()
+    mb.close()
