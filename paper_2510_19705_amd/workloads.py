@@ -4,6 +4,7 @@ networks, up to a 70B-shaped target (140 GB of bf16 weights resident in HBM).
     python -m paper_2510_19705_amd.workloads --config independent     # 125M / 1B / 7B-shaped, vocab 32000
     python -m paper_2510_19705_amd.workloads --config 70b             # 1B / 8B exit 8 / 8B / 70B-shaped, vocab 128256
     python -m paper_2510_19705_amd.workloads --config microbench      # one 7B-shaped layer: KV length x query tokens x batch
+    python -m paper_2510_19705_amd.workloads --config independent --distill   # drafters = target logits + noise (std 1.0 / 0.5)
 
 Weights are drawn on the device (seeded normal, residual-writing matrices scaled by 0.1); prompts are uniform-random
 ids.  For each workload: pass time and HBM fraction of every candidate (algorithmic bytes / time / 8 TB/s), pairwise
@@ -275,11 +276,98 @@ def microbench():
     return {"config": "microbench", "projections_us_by_rows": gemm, "weight_MB": site_mb, "cells": cells, "sampler": sampler}
 
 
+def run_distilled(config, stds, seed=20251019, temperature=1.0, gen=None):
+    """The same candidates with synthetic closeness: every drafter's logits are the target's plus Gaussian noise of
+    the given standard deviations (hsd_hier_set_distilled), which puts acceptance rates in the 0.5-0.9 range the
+    paper works in.  The target's side passes make wall-clock meaningless, so every run is priced with the fixed
+    cost per pass measured beforehand (the appendix's artificial-cost accounting): ms per token = sum of passes x
+    cost / tokens.  Acceptance rates are the per-test frequencies of the runs themselves."""
+    import itertools
+    import torch
+    assert torch.cuda.is_available(), "needs the GPU"
+    from . import hsd, inputs
+    cfg = CONFIGS[config]
+    shp = shapes(inputs)
+    prompt_len = cfg["prompt"]
+    gen = gen or cfg["gen"]
+    max_seq = (prompt_len + gen + 128 + 63) // 64 * 64
+    models = {name: random_model(hsd, inputs, torch, shp[name], seed + i, max_seq) for i, name in enumerate(cfg["models"])}
+    levels = [(models[name], e) for name, e in cfg["levels"]]
+    names = ["%s/exit%d" % ne for ne in cfg["levels"]]
+    K = len(levels) - 1
+    assert len(stds) == K
+    prompt = inputs.make_prompt(shp[cfg["models"][0]]["vocab"], prompt_len, seed=seed + 100)
+    tokens = torch.from_numpy(prompt.astype(np.int32)).cuda()
+    cost = []
+    for (model, e) in levels:                                   # fixed cost: a 4-token pass at the end of the prompt
+        for p0 in range(0, prompt_len, 64):
+            model.model_pass(tokens[p0:p0 + min(64, prompt_len - p0)], p0, e, 0)
+        tk = tokens[prompt_len - 4:]
+        cost.append(_time(torch, lambda: model.model_pass(tk, prompt_len - 4, e, 4), 5) / 1e3)
+    log("cost ms", cost)
+    results = {}
+
+    def measure(label, idx, T):
+        h = hsd.Hierarchy([levels[i] for i in idx], T, temperature, seed)
+        for j, i in enumerate(idx[:-1]):
+            h.set_distilled(j, len(idx) - 1, stds[i])
+        h.prefill(prompt)
+        _, st = h.generate(gen)
+        n = len(idx)
+        results[label] = {"levels": [names[i] for i in idx], "T": list(T),
+                          "artificial_ms_per_token": hsd.stats_cost(st, [cost[i] for i in idx]) / st.tokens,
+                          "per_test_acceptance": [st.accepted[i] / max(1, st.tested[i]) for i in range(1, n)],
+                          "passes": [st.passes[i] for i in range(n)], "tokens": st.tokens}
+        log(label, results[label])
+        h.close()
+        return results[label]
+
+    measure("autoregressive", [K], [])
+    alpha = np.eye(K + 1)
+    for i in range(K):                                          # alpha_{i,K} from a single-draft run
+        r = measure("probe_%s" % names[i], [i, K], [4])
+        alpha[i, K] = alpha[K, i] = r["per_test_acceptance"][0]
+    for i in range(K - 1):                                      # alpha_{i,i+1} from a three-level run
+        r = measure("probe_%s_%s" % (names[i], names[i + 1]), [i, i + 1, K], [3, 2])
+        alpha[i, i + 1] = alpha[i + 1, i] = r["per_test_acceptance"][0]
+    for i in range(K + 1):                                      # pairs never measured: the triangle-inequality lower bound
+        for j in range(i + 2, K):
+            alpha[i, j] = alpha[j, i] = max(0.0, alpha[i, j - 1] + alpha[j - 1, j] - 1.0)
+    log("alpha\n", np.round(alpha, 3))
+    lat, sigma, Tsel = hsd.select_hierarchy(cost, alpha, 15)
+    measure("selected", list(sigma), list(Tsel))
+    for i in range(K):
+        _, _, sT = hsd.best_single_draft([cost[i], cost[K]], [[1, alpha[i, K]], [alpha[i, K], 1]], 15)
+        measure("single_draft_%s" % names[i], [i, K], [sT])
+    if list(sigma) != list(range(K + 1)):
+        best = None
+        for T in itertools.product(range(1, 9), repeat=K):
+            l = hsd.expected_latency(cost, [alpha[i, i + 1] for i in range(K)], list(T), True)
+            if best is None or l < best[0]:
+                best = (l, T)
+        measure("full_hierarchy", list(range(K + 1)), list(best[1]))
+    for m in models.values():
+        m.close()
+    return {"config": config + " (distilled)", "noise_std": list(stds), "candidates": names, "cost_ms": cost,
+            "alpha": [[round(float(v), 4) for v in row] for row in alpha],
+            "selected": {"levels": [names[i] for i in sigma], "T": list(Tsel), "predicted_ms_per_token": lat}, "runs": results}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", choices=sorted(CONFIGS) + ["microbench"], default="independent")
+    ap.add_argument("--distill", action="store_true", help="synthetic drafters: target logits + noise, fixed-cost accounting")
+    ap.add_argument("--gen", type=int, default=0)
     args = ap.parse_args()
-    print(json.dumps(microbench() if args.config == "microbench" else run(args.config)), flush=True)
+    if args.config == "microbench":
+        out = microbench()
+    elif args.distill:
+        K = len(CONFIGS[args.config]["levels"]) - 1
+        stds = [1.0, 0.5, 0.35, 0.25][:K] if K > 1 else [0.7]
+        out = run_distilled(args.config, stds, gen=args.gen or None)
+    else:
+        out = run(args.config)
+    print(json.dumps(out), flush=True)
 
 
 if __name__ == "__main__":
