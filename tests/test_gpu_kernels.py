@@ -276,6 +276,7 @@ def _attention_ref(q, k, v, pos0):
     (1, 100, 1, 4, 4, 64, False), (2, 333, 5, 6, 2, 32, False),
     (1, 70, 1, 8, 8, 64, True), (1, 777, 6, 32, 8, 64, True), (3, 1500, 4, 8, 8, 128, True), (2, 4200, 16, 16, 2, 128, True),
     (1, 9000, 8, 8, 1, 64, True), (8, 300, 2, 4, 4, 128, True), (1, 640, 16, 32, 8, 64, True),
+    (1, 32768, 4, 16, 4, 128, True),                       # the longest context of the microbenchmark configuration
 ])
 def test_attention(hsd, B, S, m, n_q, n_kv, hd, bf16):
     """Per-sequence lengths differ (ragged batch), pages are permuted; bf16: 2e-2 absolute on outputs of unit scale."""
