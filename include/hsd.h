@@ -29,7 +29,7 @@ extern "C" {
 enum { HSD_OK = 0, HSD_EINVAL = -1, HSD_ECAPACITY = -2, HSD_ESTATE = -3, HSD_EHIP = -4 };
 enum { HSD_F32 = 0, HSD_BF16 = 1 };
 enum { HSD_LAYOUT_TILES = 0, HSD_LAYOUT_ROWS = 1 };
-enum { HSD_MAX_LEVELS = 8, HSD_MAX_PASS_ROWS = 64, HSD_KV_PAGE = 64 };
+enum { HSD_MAX_LEVELS = 8, HSD_MAX_PASS_ROWS = 64, HSD_KV_PAGE = 64, HSD_MAX_GEMM_ROWS = 4096 };
 
 typedef struct hsd_model hsd_model;
 typedef struct hsd_hier hsd_hier;
@@ -198,7 +198,12 @@ int hsd_attention(const void* q_dev, const void* kv_layer_dev, const int32_t* pa
  *   HSD_LAYOUT_TILES - MFMA operand tiles; workgroups own 16-column tiles (wide matrices: gate/up, head);
  *   HSD_LAYOUT_ROWS  - row-major; workgroups own 2-4 output features and use packed bf16 dot products
  *                      (narrow matrices: q/k/v, attention output, FFN down), m above 16 in several launches.
- * fp32 ignores the layout.  k must be a multiple of 32, 1 <= m <= HSD_MAX_PASS_ROWS.
+ * fp32 ignores the layout.  k must be a multiple of 32, 1 <= m <= HSD_MAX_GEMM_ROWS.
+ * Above HSD_MAX_PASS_ROWS rows (a batch of sequences times their drafted tokens, the batched cells of the layer
+ * microbenchmark; Sec. 3.1: each load of the weights should serve as many tokens as possible) the tiled bf16 format
+ * is served either by one weight stream per 64 rows or, from a few hundred rows on, where the matrix cores and not
+ * the stream bound the time, by a kernel tiled for them (128 x 256 per workgroup, activations through LDS); the
+ * results are the same sums of exact products in fp32, in a different order.
  * workspace_dev: hsd_gemm_workspace_bytes(m, n, k). */
 size_t hsd_packed_bytes(int n, int k, int dtype);
 size_t hsd_gemm_workspace_bytes(int m, int n, int k);
@@ -217,7 +222,9 @@ int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int
  * path hsd_softmax + hsd_accept_resample on small vocabularies.  key 104: nt = 0 stops the driver's fused sampler
  * from embedding the token it emits for the one-token pass that follows (default 1; same results either way).
  * key 105: nt = 0 makes the driver synchronise the stream after each Verify instead of polling the sampler's
- * sequence number in pinned host memory (default 1; same results either way). */
+ * sequence number in pinned host memory (default 1; same results either way).  key 106: nt = fewest rows of an
+ * hsd_gemm call (above HSD_MAX_PASS_ROWS) that the kernel tiled for the matrix cores serves; calls with fewer rows
+ * stream the weights once per 64 rows (0: default: above 128 rows, or from 32 column strips of 256 on). */
 int hsd_tune(int key, int nt, int ksplit, int waves);
 
 /* ---------------------------------------------------------------------------------------------

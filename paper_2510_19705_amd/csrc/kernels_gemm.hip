@@ -18,6 +18,8 @@
 //   epilogue  - plain store (LM head), residual add (+ the two products above), SwiGLU on interleaved
 //               gate/up tiles, or RoPE + KV-cache append + q store.
 // fp32 (small correctness configuration): one wave per output column with plain FMAs, unfused.
+#include <algorithm>
+
 #include "common.h"
 
 // ------------------------------------------------------------------------------------------------
@@ -543,6 +545,19 @@ __global__ void gemm_f32_kernel(const float* __restrict__ x, const float* __rest
 static int g_tune_nt[4] = {0, 0, 0, 0};      // optional overrides per epilogue kind (0 = heuristic)
 static int g_tune_ksplit[4] = {0, 0, 0, 0};
 int g_gemv_max_m = 2;            // most tokens of a pass served from the row-major copies
+// Fewest rows of an hsd_gemm call (above 64) served by the kernel tiled for the matrix cores; 0: the measured rule in
+// use_wide_kernel.  A tuning knob (hsd_tune key 106).
+static int g_wide_min_rows = 0;
+
+// Above 128 rows the tiled kernel always wins (one weight stream per 64 rows costs 1.8-4 x its time at 256 rows).
+// Up to 128 rows it is one row block: ahead with 32 or more column strips (q/k/v, gate/up: 55 against 110-130 us on
+// the 7B-shaped layer), level or slightly behind with 16 (attention output, FFN down), where two weight streams
+// fill the chip better than 16 workgroups.
+static bool use_wide_kernel(int m, int n) {
+    if (m <= HSD_MAX_PASS_ROWS) return false;
+    if (g_wide_min_rows > 0) return m >= g_wide_min_rows;
+    return m > 128 || gemm_wide_workgroups(m, n) >= 32;
+}
 
 void gemm_tune(int epilogue, int nt, int ksplit, int waves) {
     if (epilogue == 100) { g_gemv_max_m = nt; return; }
@@ -551,6 +566,7 @@ void gemm_tune(int epilogue, int nt, int ksplit, int waves) {
     if (epilogue == 103) { g_fused_sampler_max_v = nt; return; }
     if (epilogue == 104) { g_preembed = nt; return; }
     if (epilogue == 105) { g_poll_mailbox = nt; return; }
+    if (epilogue == 106) { g_wide_min_rows = nt > 0 ? nt : 0; return; }
     if (epilogue >= 0 && epilogue < 4) {
         g_tune_nt[epilogue] = nt;
         g_tune_ksplit[epilogue] = ksplit;
@@ -611,8 +627,8 @@ static void launch_inst(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
         gemm_bf16_kernel<NT, MT, EPI, false><<<grid, p.waves * 64, gemm_lds_bytes(p, g.M, EPI), s>>>(g);
 }
 
-static int check_gemm(int m, int n, int k) {
-    if (m < 1 || m > HSD_MAX_PASS_ROWS) HSD_FAIL(HSD_EINVAL, "gemm: m=%d outside 1..%d", m, HSD_MAX_PASS_ROWS);
+static int check_gemm(int m, int n, int k, int max_rows = HSD_MAX_PASS_ROWS) {
+    if (m < 1 || m > max_rows) HSD_FAIL(HSD_EINVAL, "gemm: m=%d outside 1..%d", m, max_rows);
     if (n < 1 || k < 32 || k % 32 != 0) HSD_FAIL(HSD_EINVAL, "gemm: n=%d k=%d (k must be a positive multiple of 32)", n, k);
     return HSD_OK;
 }
@@ -663,7 +679,7 @@ static int launch_gemv_mb(const GemmArgs& g, hipStream_t s) {
 // Row-major W: 16 tokens per launch (the pass only sends one or two tokens here; more would make the
 // per-token activation reads outweigh the weight stream, and the tiled kernel serves them).
 int launch_gemv_bf16(const GemmArgs& g0, int epi, hipStream_t s) {
-    if (int rc = check_gemm(g0.M, g0.N, g0.K)) return rc;
+    if (int rc = check_gemm(g0.M, g0.N, g0.K, HSD_MAX_GEMM_ROWS)) return rc;
     if (epi == EPI_ROPE && g0.N != (g0.n_q + 2 * g0.n_kv) * g0.hd) HSD_FAIL(HSD_EINVAL, "gemv: q/k/v width mismatch");
     for (int m0 = 0; m0 < g0.M; m0 += 16) {
         GemmArgs g = g0;
@@ -689,7 +705,7 @@ int launch_gemv_bf16(const GemmArgs& g0, int epi, hipStream_t s) {
 }
 
 int launch_gemm_f32(const float* x, const float* w, float* out, int m, int n, int k, bool swiglu, hipStream_t s) {
-    if (int rc = check_gemm(m, n, k)) return rc;
+    if (int rc = check_gemm(m, n, k, HSD_MAX_GEMM_ROWS)) return rc;
     if (swiglu)
         gemm_f32_kernel<1><<<ceil_div(n / 2, 4), 256, 0, s>>>(x, w, out, m, n, k);
     else
@@ -718,9 +734,16 @@ extern "C" int hsd_pack_weight(const void* w_dev, void* packed_dev, int n, int k
     return launch_pack(w_dev, packed_dev, n, k, dtype, 0, 0, 0, layout == HSD_LAYOUT_ROWS, s);
 }
 
+// split-K partial tiles of the widest plan any 64-row block of an m-row product may use
+static size_t gemm_store_part_bytes(int m, int n, int k) {
+    size_t b = gemm_part_bytes(std::min(m, (int)HSD_MAX_PASS_ROWS), n, k, EPI_STORE);       // the full blocks
+    if (m > HSD_MAX_PASS_ROWS && m % HSD_MAX_PASS_ROWS) b = std::max(b, gemm_part_bytes(m % HSD_MAX_PASS_ROWS, n, k, EPI_STORE));
+    return align_up(b, 256);
+}
+
 extern "C" size_t hsd_gemm_workspace_bytes(int m, int n, int k) {
-    if (m < 1 || m > HSD_MAX_PASS_ROWS || n < 1 || k < 32) return 0;
-    return align_up(gemm_part_bytes(m, n, k, EPI_STORE), 256) + align_up((size_t)ceil_div(n, 16) * sizeof(int), 256);
+    if (m < 1 || m > HSD_MAX_GEMM_ROWS || n < 1 || k < 32) return 0;
+    return gemm_store_part_bytes(m, n, k) + align_up((size_t)ceil_div(n, 16) * sizeof(int), 256);
 }
 
 extern "C" int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int n, int k, int dtype, int layout,
@@ -728,7 +751,7 @@ extern "C" int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev,
     if (!x_dev || !packed_dev || !y_dev || !workspace_dev || (dtype != HSD_F32 && dtype != HSD_BF16) ||
         (layout != HSD_LAYOUT_TILES && layout != HSD_LAYOUT_ROWS))
         HSD_FAIL(HSD_EINVAL, "hsd_gemm: bad arguments");
-    if (int rc = check_gemm(m, n, k)) return rc;
+    if (int rc = check_gemm(m, n, k, HSD_MAX_GEMM_ROWS)) return rc;
     hipStream_t s = (hipStream_t)stream;
     if (dtype == HSD_F32) return launch_gemm_f32((const float*)x_dev, (const float*)packed_dev, y_dev, m, n, k, false, s);
     if (layout == HSD_LAYOUT_ROWS) {
@@ -739,15 +762,23 @@ extern "C" int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev,
         g.out_f32 = y_dev;
         return launch_gemv_bf16(g, EPI_STORE, s);
     }
-    const size_t part_bytes = align_up(gemm_part_bytes(m, n, k, EPI_STORE), 256);
+    if (use_wide_kernel(m, n))
+        return launch_gemm_wide_bf16((const bf16_t*)x_dev, (const bf16x8*)packed_dev, y_dev, m, n, k, s);
+    const size_t part_bytes = gemm_store_part_bytes(m, n, k);
     GemmArgs g = {};
-    g.a = (const bf16_t*)x_dev;
     g.wp = (const bf16x8*)packed_dev;
-    g.M = m; g.N = n; g.K = k;
-    g.out_f32 = y_dev;
+    g.N = n; g.K = k;
     g.part = (float*)workspace_dev;
     g.part_bytes = part_bytes;
     g.tickets = (int*)((char*)workspace_dev + part_bytes);
     HSD_HIP(hipMemsetAsync(g.tickets, 0, (size_t)ceil_div(n, 16) * sizeof(int), s));
-    return launch_gemm_bf16(g, EPI_STORE, gemm_plan(m, n, k, EPI_STORE), s);
+    // one weight stream per block of 64 rows; the blocks share the workspace, in stream order (the last arriver of a
+    // column group leaves its ticket at zero for the next launch)
+    for (int m0 = 0; m0 < m; m0 += HSD_MAX_PASS_ROWS) {
+        g.M = std::min((int)HSD_MAX_PASS_ROWS, m - m0);
+        g.a = (const bf16_t*)x_dev + (size_t)m0 * k;
+        g.out_f32 = y_dev + (size_t)m0 * n;
+        if (int rc = launch_gemm_bf16(g, EPI_STORE, gemm_plan(g.M, n, k, EPI_STORE), s)) return rc;
+    }
+    return HSD_OK;
 }

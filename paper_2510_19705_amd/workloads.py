@@ -4,6 +4,7 @@ networks, up to a 70B-shaped target (140 GB of bf16 weights resident in HBM).
     python -m paper_2510_19705_amd.workloads --config independent     # 125M / 1B / 7B-shaped, vocab 32000
     python -m paper_2510_19705_amd.workloads --config 70b             # 1B / 8B exit 8 / 8B / 70B-shaped, vocab 128256
     python -m paper_2510_19705_amd.workloads --config microbench      # one 7B-shaped layer: KV length x query tokens x batch
+    python -m paper_2510_19705_amd.workloads --config projections     # its four projections alone, 1 to 1024 rows
     python -m paper_2510_19705_amd.workloads --config independent --distill   # drafters = target logits + noise (std 1.0 / 0.5)
 
 Weights are drawn on the device (seeded normal, residual-writing matrices scaled by 0.1); prompts are uniform-random
@@ -21,6 +22,7 @@ import time
 import numpy as np
 
 HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = 2500.0      # dense bf16
 
 CONFIGS = {
     # candidates (model name, exit layer) in ascending cost, the target last
@@ -203,11 +205,10 @@ def _time(torch, fn, iters):
     return e0.elapsed_time(e1) * 1e3 / iters                     # microseconds
 
 
-def microbench():
-    """Isolated verify pass of ONE 7B-shaped layer (32 x 128 heads, MHA, d 4096, FFN 11008), bf16, random K/V and
-    activations: k query tokens per sequence, cached length S, batch B.  Attention per layer at every cell whose K/V
-    fits (one layer's K/V is B * S * 16 KiB); the four projections at B * k rows, up to the 64 rows one pass of this
-    library takes (cells beyond are left out).  Also the sampler at vocab 128256 on random distributions."""
+def projections():
+    """The four projections of one 7B-shaped layer (d 4096, 32 x 128 heads, FFN 11008), bf16, by row count: up to 64
+    rows as the fused kernels of a pass (microseconds and TB/s of weights), 128 to 1024 rows as plain products through
+    hsd_gemm (microseconds, TFLOP/s, fraction of the dense bf16 MFMA peak)."""
     import torch
     assert torch.cuda.is_available(), "needs the GPU"
     from . import hsd, inputs
@@ -226,6 +227,40 @@ def microbench():
         gemm[rows] = us
         log("rows %2d: " % rows + "  ".join("%s %.1f us (%.2f TB/s)" % (k, v, site_mb[k] / v) for k, v in us.items()))
     model.close()
+    # many-row cells: plain products y = x W^T at the four projection shapes (no fused epilogue at these row counts)
+    site_nk = {"qkv": ((n_q + 2 * n_kv) * hd, d), "o": (d, n_q * hd), "gateup": (2 * F, d), "down": (d, F)}
+    packed = {k: hsd.pack_weight((torch.randn(n, kk, device="cuda") * kk ** -0.5).to(torch.bfloat16), hsd.BF16, 0)
+              for k, (n, kk) in site_nk.items()}
+    gemm_many = {}
+    for rows in (128, 256, 512, 1024):
+        us = {}
+        for k, (n, kk) in site_nk.items():
+            x = torch.randn(rows, kk, device="cuda").to(torch.bfloat16)
+            ws = torch.zeros(hsd.lib.hsd_gemm_workspace_bytes(rows, n, kk), dtype=torch.uint8, device="cuda")
+            us[k] = _time(torch, lambda: hsd.gemm(x, packed[k], n, hsd.BF16, ws), 20)
+        flop = {k: 2.0 * rows * n * kk for k, (n, kk) in site_nk.items()}
+        gemm_many[rows] = {"us": us, "tflops": {k: flop[k] / us[k] / 1e6 for k in us},
+                           "mfma_frac": sum(flop.values()) / sum(us.values()) / 1e6 / MFMA_PEAK_TFLOPS}
+        log("rows %4d: " % rows + "  ".join("%s %.1f us (%.0f TFLOP/s)" % (k, v, flop[k] / v / 1e6) for k, v in us.items()) +
+            "  | MFMA fraction of the four: %.3f" % gemm_many[rows]["mfma_frac"])
+    del packed
+    torch.cuda.empty_cache()
+    return {"shape": shape, "weight_MB": site_mb, "site_nk": site_nk, "projections_us_by_rows": gemm, "projections_many_rows": gemm_many}
+
+
+def microbench():
+    """Isolated verify pass of ONE 7B-shaped layer (32 x 128 heads, MHA, d 4096, FFN 11008), bf16, random K/V and
+    activations: k query tokens per sequence, cached length S, batch B.  Attention per layer at every cell whose K/V
+    fits (one layer's K/V is B * S * 16 KiB); the four projections at B * k rows: up to 64 rows as the fused kernels
+    of a pass, beyond (128 to 1024 rows, where the matrix cores and not the weight stream bound the time) as plain
+    products through hsd_gemm, reported against the dense bf16 MFMA peak.  Also the sampler at vocab 128256 on random
+    distributions."""
+    import torch
+    assert torch.cuda.is_available(), "needs the GPU"
+    from . import hsd, inputs
+    pr = projections()
+    shape, site_mb, site_nk, gemm, gemm_many = pr["shape"], pr["weight_MB"], pr["site_nk"], pr["projections_us_by_rows"], pr["projections_many_rows"]
+    n_q, n_kv, hd = shape["n_q"], shape["n_kv"], shape["hd"]
     cells = []
     for B in (1, 8, 64):
         for S in (4096, 16384, 32768):
@@ -248,6 +283,12 @@ def microbench():
                     w_bytes = sum(site_mb.values()) * 1e6
                     cell.update({"projections_us": g, "layer_us": g + att_us,
                                  "layer_hbm_frac": (w_bytes + kv_bytes) / (g + att_us) / 1e3 / HBM_PEAK_GBS})
+                elif rows in gemm_many:
+                    g = sum(gemm_many[rows]["us"].values())
+                    flop = 2.0 * rows * sum(n * kk for n, kk in site_nk.values()) + 4.0 * rows * S * n_q * hd
+                    cell.update({"projections_us": g, "layer_us": g + att_us, "projections_mfma_frac": gemm_many[rows]["mfma_frac"],
+                                 "layer_hbm_frac": (sum(site_mb.values()) * 1e6 + kv_bytes) / (g + att_us) / 1e3 / HBM_PEAK_GBS,
+                                 "layer_mfma_frac": flop / (g + att_us) / 1e6 / MFMA_PEAK_TFLOPS})
                 cells.append(cell)
                 log(cell)
             del cache
@@ -273,7 +314,8 @@ def microbench():
                                                        scratch.data_ptr(), hsd._stream()))
             sampler.append({"vocab": V, "sigma": sigma, "t": t, "softmax_plus_accept_us": _time(torch, both, 50)})
             log(sampler[-1])
-    return {"config": "microbench", "projections_us_by_rows": gemm, "weight_MB": site_mb, "cells": cells, "sampler": sampler}
+    return {"config": "microbench", "projections_us_by_rows": gemm, "projections_many_rows": gemm_many, "weight_MB": site_mb,
+            "cells": cells, "sampler": sampler}
 
 
 def run_distilled(config, stds, seed=20251019, temperature=1.0, gen=None):
@@ -355,12 +397,14 @@ def run_distilled(config, stds, seed=20251019, temperature=1.0, gen=None):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", choices=sorted(CONFIGS) + ["microbench"], default="independent")
+    ap.add_argument("--config", choices=sorted(CONFIGS) + ["microbench", "projections"], default="independent")
     ap.add_argument("--distill", action="store_true", help="synthetic drafters: target logits + noise, fixed-cost accounting")
     ap.add_argument("--gen", type=int, default=0)
     args = ap.parse_args()
     if args.config == "microbench":
         out = microbench()
+    elif args.config == "projections":
+        out = projections()
     elif args.distill:
         K = len(CONFIGS[args.config]["levels"]) - 1
         stds = [1.0, 0.5, 0.35, 0.25][:K] if K > 1 else [0.7]

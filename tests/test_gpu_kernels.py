@@ -237,6 +237,44 @@ def test_gemm(hsd, m, n, k, bf16, layout):
     assert np.abs(got - ref).max() < tol, (np.abs(got - ref).max(), tol)
 
 
+@pytest.mark.parametrize("m,n,k", [(65, 1000, 512), (128, 4096, 1024), (200, 520, 96), (513, 300, 2048), (1024, 2048, 4096),
+                                   (1000, 48, 32)])
+@pytest.mark.parametrize("path", ["tiled_for_mfma", "stream_per_64_rows"])
+def test_gemm_many_rows(hsd, m, n, k, path):
+    """More than 64 rows (a batch of sequences times their drafted tokens): the kernel tiled for the matrix cores
+    (ragged row / column blocks, an odd number of 32-wide k tiles, fewer columns than one workgroup's strip) and the
+    one-stream-per-64-rows path against the fp64 product of the same bf16 inputs."""
+    import torch
+    say("gemm_many_rows", m, n, k, path)
+    rng = np.random.default_rng(m * 7 + n + k)
+    x = inputs.bf16_round(rng.standard_normal((m, k)).astype(np.float32))
+    w = inputs.bf16_round((rng.standard_normal((n, k)) / np.sqrt(k)).astype(np.float32))
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    packed = hsd.pack_weight(_cuda(w, torch.bfloat16), hsd.BF16, 0)
+    hsd.lib.hsd_tune(106, 65 if path == "tiled_for_mfma" else 1 << 30, 0, 0)
+    try:
+        got = hsd.gemm(_cuda(x, torch.bfloat16), packed, n, hsd.BF16, None, 0).cpu().numpy()
+    finally:
+        hsd.lib.hsd_tune(106, 0, 0, 0)
+    tol = 4e-6 * np.sqrt(k) * np.abs(ref).max() + 1e-6
+    assert np.abs(got - ref).max() < tol, (np.abs(got - ref).max(), tol)
+
+
+@pytest.mark.parametrize("bf16,layout", [(True, 1), (False, 0)], ids=["bf16_rows", "f32"])
+def test_gemm_many_rows_other_formats(hsd, bf16, layout):
+    import torch
+    m, n, k = 130, 600, 256
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal((m, k)).astype(np.float32)
+    w = (rng.standard_normal((n, k)) / np.sqrt(k)).astype(np.float32)
+    if bf16:
+        x, w = inputs.bf16_round(x), inputs.bf16_round(w)
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    dt, td = (hsd.BF16, torch.bfloat16) if bf16 else (hsd.F32, torch.float32)
+    got = hsd.gemm(_cuda(x, td), hsd.pack_weight(_cuda(w, td), dt, layout), n, dt, None, layout).cpu().numpy()
+    assert np.abs(got - ref).max() < 4e-6 * np.sqrt(k) * np.abs(ref).max() + 1e-6
+
+
 def test_gemm_split_k_exchange_repeated(hsd):
     """The split-K partial tiles travel through one reused workspace: 60 launches with fresh
     activations each must all match (a stale or early read of a partial would show up here)."""
