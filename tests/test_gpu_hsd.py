@@ -61,6 +61,31 @@ def test_tiny_temperature0_stream_bit_exact(tiny, T):
     ar.close()
 
 
+def test_temperature0_random_hierarchies(tiny):
+    """At temperature 0 every hierarchy must emit the target's greedy continuation (Thm 3.1 with one-hot
+    distributions), whatever its exits and T: sixteen hierarchies drawn at random (two to five levels, T of 1 to 5)
+    against one greedy decode of the oracle, whose smallest top-2 gap is asserted to dwarf the fp32 error."""
+    w, _, model = tiny
+    prompt = inputs.make_prompt(TINY["vocab"], 32, seed=10)
+    target = _oracle_levels(w, TINY, (8,), 0.0)
+    ref = ohsd.HSD(target, (), specsample.PhiloxChooser(1)).generate([int(t) for t in prompt], 48)
+    assert target[0].min_top2_gap > 1.5e-3
+    rng = np.random.default_rng(4711)
+    for trial in range(16):
+        n_lower = int(rng.integers(1, 5))
+        exits = tuple(sorted(rng.choice(np.arange(1, 8), size=n_lower, replace=False).tolist())) + (8,)
+        T = tuple(int(t) for t in rng.integers(1, 6, size=n_lower))
+        while sum(T) > 12:                                        # the verifier's pass takes at most 16 rows here
+            T = tuple(max(1, t - 1) for t in T)
+        say("hierarchy", exits, T)
+        h = _gpu_hier(model, exits, T, 0.0, seed=SEED + trial)
+        h.prefill(prompt)
+        got, st = h.generate(48)
+        assert got.tolist() == ref, (exits, T)
+        assert sum(st.passes[i] for i in range(len(exits))) > 0
+        h.close()
+
+
 @pytest.fixture(params=["fused_sampler", "two_launch_sampler"])
 def sampler_path(request):
     """The driver's two ways from logits to (n, token): the fused launch (vocabularies up to 32768) and softmax +
@@ -94,6 +119,38 @@ def test_tiny_temperature1_stream(tiny, T, seed, sampler_path):
     assert [st.passes[i] for i in range(3)] == o.passes
     say("acceptance", [st.accepted[i] / max(1, st.drafted[i]) for i in (1, 2)], "rounds", st.rounds)
     h.close()
+
+
+def test_temperature1_random_hierarchies(tiny):
+    """Temperature 1, hierarchies, T and seeds drawn at random: wherever the oracle's run keeps the margins of the
+    fixed-seed test above (decided by the oracle alone), stream, counts and passes must be identical; runs with a
+    marginal decision are skipped and counted, and most runs must qualify."""
+    w, prompt, model = tiny
+    rng = np.random.default_rng(1234)
+    compared = 0
+    for trial in range(16):
+        n_lower = int(rng.integers(1, 4))
+        exits = tuple(sorted(rng.choice(np.arange(1, 8), size=n_lower, replace=False).tolist())) + (8,)
+        T = tuple(int(t) for t in rng.integers(1, 5, size=n_lower))
+        seed = 7000 + trial
+        levels = _oracle_levels(w, TINY, exits, 1.0)
+        ch = specsample.PhiloxChooser(seed)
+        o = ohsd.HSD(levels, T, ch)
+        ref = o.generate([int(t) for t in prompt], 40)
+        wide = min(ch.accept_margins, default=1.0) > 3e-4 and min(ch.sample_margins) > 3e-6
+        say("hierarchy", exits, T, "seed", seed, "margins wide" if wide else "marginal: skipped")
+        if not wide:
+            continue
+        h = _gpu_hier(model, exits, T, 1.0, seed=seed)
+        h.prefill(prompt)
+        got, st = h.generate(40)
+        n = len(exits)
+        assert got.tolist() == ref, (exits, T, seed)
+        assert [st.drafted[i] for i in range(n)] == o.drafted and [st.accepted[i] for i in range(n)] == o.accepted
+        assert [st.passes[i] for i in range(n)] == o.passes
+        h.close()
+        compared += 1
+    assert compared >= 8, compared
 
 
 def test_draft_and_verify_calls(tiny):
