@@ -355,3 +355,17 @@ def test_attention(hsd, B, S, m, n_q, n_kv, hd, bf16):
         finally:
             hsd.lib.hsd_tune(101, 1 << 30, 0, 0)
         assert np.abs(got2 - ref).max() < 2e-2
+
+
+def test_attention_random_cells(hsd):
+    """Fourteen cells drawn at random: batch 1-5, 20-3000 cached positions, 1-24 new tokens, one to eight KV heads
+    with one to eight query heads each, both head sizes, both storage types."""
+    rng = np.random.default_rng(99)
+    for _ in range(14):
+        n_kv = int(rng.choice([1, 2, 4, 8]))
+        group = int(rng.choice([1, 2, 4, 8]))
+        m = int(rng.integers(1, 25))
+        S = int(rng.integers(max(20, m + 3), 3000))
+        bf16 = bool(rng.integers(0, 4))                       # mostly the MFMA path
+        hd = int(rng.choice([64, 128])) if bf16 else int(rng.choice([32, 64, 96]))
+        test_attention(hsd, int(rng.integers(1, 6)), S, m, n_kv * group, n_kv, hd, bf16)
