@@ -201,9 +201,9 @@ int hsd_attention(const void* q_dev, const void* kv_layer_dev, const int32_t* pa
  * fp32 ignores the layout.  k must be a multiple of 32, 1 <= m <= HSD_MAX_GEMM_ROWS.
  * Above HSD_MAX_PASS_ROWS rows (a batch of sequences times their drafted tokens, the batched cells of the layer
  * microbenchmark; Sec. 3.1: each load of the weights should serve as many tokens as possible) the tiled bf16 format
- * is served either by one weight stream per 64 rows or, from a few hundred rows on, where the matrix cores and not
- * the stream bound the time, by a kernel tiled for them (128 x 256 per workgroup, activations through LDS); the
- * results are the same sums of exact products in fp32, in a different order.
+ * is served by a kernel tiled for the matrix cores, which bound the time from a few hundred rows on (128 x 256 or
+ * 128 x 128 of the output per workgroup, activations through LDS), or, as a tuning alternative, by one weight stream
+ * per 64 rows; the results are the same sums of exact products in fp32, in a different order.
  * workspace_dev: hsd_gemm_workspace_bytes(m, n, k). */
 size_t hsd_packed_bytes(int n, int k, int dtype);
 size_t hsd_gemm_workspace_bytes(int m, int n, int k);
@@ -224,7 +224,7 @@ int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int
  * key 105: nt = 0 makes the driver synchronise the stream after each Verify instead of polling the sampler's
  * sequence number in pinned host memory (default 1; same results either way).  key 106: nt = fewest rows of an
  * hsd_gemm call (above HSD_MAX_PASS_ROWS) that the kernel tiled for the matrix cores serves; calls with fewer rows
- * stream the weights once per 64 rows (0: default: above 128 rows, or from 32 column strips of 256 on). */
+ * stream the weights once per 64 rows (0: default, every call above HSD_MAX_PASS_ROWS rows). */
 int hsd_tune(int key, int nt, int ksplit, int waves);
 
 /* ---------------------------------------------------------------------------------------------

@@ -549,14 +549,12 @@ int g_gemv_max_m = 2;            // most tokens of a pass served from the row-ma
 // use_wide_kernel.  A tuning knob (hsd_tune key 106).
 static int g_wide_min_rows = 0;
 
-// Above 128 rows the tiled kernel always wins (one weight stream per 64 rows costs 1.8-4 x its time at 256 rows).
-// Up to 128 rows it is one row block: ahead with 32 or more column strips (q/k/v, gate/up: 55 against 110-130 us on
-// the 7B-shaped layer), level or slightly behind with 16 (attention output, FFN down), where two weight streams
-// fill the chip better than 16 workgroups.
+// Above 64 rows the tiled kernel wins at every shape measured (7B-shaped layer, 128 rows: 42-100 us against 48-130 us
+// for two weight streams; 256 rows: 1.8-4 x); the per-64-rows path stays as the alternative the knob selects.
 static bool use_wide_kernel(int m, int n) {
+    (void)n;
     if (m <= HSD_MAX_PASS_ROWS) return false;
-    if (g_wide_min_rows > 0) return m >= g_wide_min_rows;
-    return m > 128 || gemm_wide_workgroups(m, n) >= 32;
+    return g_wide_min_rows > 0 ? m >= g_wide_min_rows : true;
 }
 
 void gemm_tune(int epilogue, int nt, int ksplit, int waves) {

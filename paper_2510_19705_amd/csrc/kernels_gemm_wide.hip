@@ -26,18 +26,20 @@ namespace {
 
 constexpr int WIDE_ROWS = 128;                          // rows per workgroup
 constexpr int WIDE_MT = WIDE_ROWS / 16;                 // 16-row tiles per workgroup (every wave computes all)
-constexpr int WIDE_NT = 4;                              // 16-column tiles per wave
 constexpr int WIDE_WAVES = 4;
-constexpr int WIDE_COLS = WIDE_WAVES * WIDE_NT * 16;    // 256 columns per workgroup
 constexpr int WIDE_SKT = 4;                             // 32-wide k steps per LDS slab
 constexpr int WIDE_NB = 8;                              // ring of W register sets, one per k step in flight
 constexpr int WIDE_APT = WIDE_SKT * WIDE_MT * 64 / (WIDE_WAVES * 64);   // 16-byte A chunks per thread and slab: 8
 static_assert(WIDE_NB == 2 * WIDE_SKT && WIDE_APT == 2 * WIDE_SKT, "the main loop is unrolled over two slabs");
 
+// WIDE_NT: 16-column tiles per wave (4: 256 columns per workgroup; 2: 128 columns, for matrices too narrow to fill the
+// chip with 256-column strips: twice the workgroups, at the price of twice the LDS reads per MFMA, ~80 % of its rate)
+template <int WIDE_NT>
 __global__ __launch_bounds__(WIDE_WAVES * 64) void gemm_wide_bf16_kernel(const bf16_t* __restrict__ a,
                                                                          const bf16x8* __restrict__ wp,
                                                                          float* __restrict__ out, int M, int N, int K,
                                                                          int mblocks, int nblocks) {
+    constexpr int WIDE_COLS = WIDE_WAVES * WIDE_NT * 16;
     __shared__ bf16x8 lds_a[2][WIDE_SKT][WIDE_MT][64];          // 64 KiB
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -127,13 +129,13 @@ __global__ __launch_bounds__(WIDE_WAVES * 64) void gemm_wide_bf16_kernel(const b
 #pragma unroll
                     for (int nt = 0; nt < WIDE_NT; ++nt)
                         acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[j & 1][mt], bq[u][nt], acc[mt][nt], 0, 0, 0);
-                // order within the step: after every four MFMAs one LDS read, six times one global load and, in the
-                // steps that fill the other buffer, four times one LDS write
+                // order within the step: after every WIDE_NT MFMAs (one row tile) one LDS read, then the step's global
+                // loads one by one and, in the steps that fill the other buffer, four times one LDS write
 #pragma unroll
                 for (int g = 0; g < 8; ++g) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, WIDE_NT, 0);
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                    if (g < 6) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                    if (g < WIDE_NT + 2) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
                     if ((j == 1 || j == 2) && g >= 4) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
                 }
             }
@@ -159,15 +161,22 @@ __global__ __launch_bounds__(WIDE_WAVES * 64) void gemm_wide_bf16_kernel(const b
 
 }  // namespace
 
+// Column strips of 256, unless they leave at least half of the 256 CUs idle: then strips of 128 (twice the workgroups,
+// still one round).
+static int wide_nt(int m, int n) {
+    return ceil_div(m, WIDE_ROWS) * ceil_div(n, 256) <= 128 ? 2 : 4;
+}
+
 // bf16, packed tiles.  Shapes are the caller's to check (m >= 1, k a positive multiple of 32).
 int launch_gemm_wide_bf16(const bf16_t* a, const bf16x8* wp, float* out, int m, int n, int k, hipStream_t s) {
-    const int mblocks = ceil_div(m, WIDE_ROWS), nblocks = ceil_div(n, WIDE_COLS);
+    const int nt = wide_nt(m, n);
+    const int mblocks = ceil_div(m, WIDE_ROWS), nblocks = ceil_div(n, WIDE_WAVES * nt * 16);
     const long long grid = 8ll * mblocks * ceil_div(nblocks, 8);
     if (grid > 0x7fffffffll) HSD_FAIL(HSD_EINVAL, "gemm: %d x %d is too large for one launch", m, n);
-    gemm_wide_bf16_kernel<<<dim3((unsigned)grid), WIDE_WAVES * 64, 0, s>>>(a, wp, out, m, n, k, mblocks, nblocks);
+    if (nt == 2)
+        gemm_wide_bf16_kernel<2><<<dim3((unsigned)grid), WIDE_WAVES * 64, 0, s>>>(a, wp, out, m, n, k, mblocks, nblocks);
+    else
+        gemm_wide_bf16_kernel<4><<<dim3((unsigned)grid), WIDE_WAVES * 64, 0, s>>>(a, wp, out, m, n, k, mblocks, nblocks);
     HSD_LAUNCH_CHECK();
     return HSD_OK;
 }
-
-// Workgroups of one launch (the caller weighs this against streaming the weights once per 64 rows).
-int gemm_wide_workgroups(int m, int n) { return ceil_div(m, WIDE_ROWS) * ceil_div(n, WIDE_COLS); }
