@@ -224,7 +224,8 @@ int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int
  * key 105: nt = 0 makes the driver synchronise the stream after each Verify instead of polling the sampler's
  * sequence number in pinned host memory (default 1; same results either way).  key 106: nt = fewest rows of an
  * hsd_gemm call (above HSD_MAX_PASS_ROWS) that the kernel tiled for the matrix cores serves; calls with fewer rows
- * stream the weights once per 64 rows (0: default, every call above HSD_MAX_PASS_ROWS rows). */
+ * stream the weights once per 64 rows (0: default, every call above HSD_MAX_PASS_ROWS rows).  key 107: nt = 128 or 256
+ * fixes the columns per workgroup of that kernel (0: default, 256 unless that leaves half the CUs without a workgroup). */
 int hsd_tune(int key, int nt, int ksplit, int waves);
 
 /* ---------------------------------------------------------------------------------------------

@@ -132,6 +132,7 @@ extern int g_poll_mailbox;
 int launch_gemv_bf16(const GemmArgs& g, int epi, hipStream_t s);   // row-major W: EPI_STORE, EPI_RESID, EPI_ROPE
 // more than 64 rows, W in MFMA tiles, plain store (kernels_gemm_wide.hip)
 int launch_gemm_wide_bf16(const bf16_t* a, const bf16x8* wp, float* out, int m, int n, int k, hipStream_t s);
+extern int g_wide_cols;
 int launch_gemm_f32(const float* x, const float* w, float* out, int m, int n, int k, bool swiglu, hipStream_t s);
 // interleave: 0 plain rows at row_offset, 1 / 2 gate / up of a fused SwiGLU matrix, 3 attention heads of hd rows
 // with each 16-dim block followed by the block of its RoPE partners, 4 heads with each dim followed by its partner.

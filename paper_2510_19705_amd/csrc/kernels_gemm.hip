@@ -565,6 +565,7 @@ void gemm_tune(int epilogue, int nt, int ksplit, int waves) {
     if (epilogue == 104) { g_preembed = nt; return; }
     if (epilogue == 105) { g_poll_mailbox = nt; return; }
     if (epilogue == 106) { g_wide_min_rows = nt > 0 ? nt : 0; return; }
+    if (epilogue == 107) { g_wide_cols = nt; return; }
     if (epilogue >= 0 && epilogue < 4) {
         g_tune_nt[epilogue] = nt;
         g_tune_ksplit[epilogue] = ksplit;

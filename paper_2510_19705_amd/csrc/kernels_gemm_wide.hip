@@ -32,13 +32,12 @@ constexpr int WIDE_NB = 8;                              // ring of W register se
 constexpr int WIDE_APT = WIDE_SKT * WIDE_MT * 64 / (WIDE_WAVES * 64);   // 16-byte A chunks per thread and slab: 8
 static_assert(WIDE_NB == 2 * WIDE_SKT && WIDE_APT == 2 * WIDE_SKT, "the main loop is unrolled over two slabs");
 
-// WIDE_NT: 16-column tiles per wave (4: 256 columns per workgroup; 2: 128 columns, for matrices too narrow to fill the
-// chip with 256-column strips: twice the workgroups, at the price of twice the LDS reads per MFMA, ~80 % of its rate)
+// WIDE_NT: 16-column tiles per wave (4: 256 columns per workgroup; 2: 128 columns: twice the LDS reads per MFMA, ~80 %
+// of the LDS rate, but half the registers, so two workgroups share a CU and each covers the other's first loads,
+// last stores and barriers)
 template <int WIDE_NT>
-__global__ __launch_bounds__(WIDE_WAVES * 64) void gemm_wide_bf16_kernel(const bf16_t* __restrict__ a,
-                                                                         const bf16x8* __restrict__ wp,
-                                                                         float* __restrict__ out, int M, int N, int K,
-                                                                         int mblocks, int nblocks) {
+__device__ __forceinline__ void gemm_wide_body(const bf16_t* __restrict__ a, const bf16x8* __restrict__ wp, float* __restrict__ out,
+                                               int M, int N, int K, int mblocks, int nblocks) {
     constexpr int WIDE_COLS = WIDE_WAVES * WIDE_NT * 16;
     __shared__ bf16x8 lds_a[2][WIDE_SKT][WIDE_MT][64];          // 64 KiB
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -159,11 +158,27 @@ __global__ __launch_bounds__(WIDE_WAVES * 64) void gemm_wide_bf16_kernel(const b
     }
 }
 
+__global__ __launch_bounds__(WIDE_WAVES * 64) void gemm_wide_bf16_kernel_256(const bf16_t* __restrict__ a, const bf16x8* __restrict__ wp,
+                                                                             float* __restrict__ out, int M, int N, int K, int mblocks,
+                                                                             int nblocks) {
+    gemm_wide_body<4>(a, wp, out, M, N, K, mblocks, nblocks);
+}
+
+// register budget of two waves per SIMD (256): fits without spills
+__global__ __launch_bounds__(WIDE_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2))) void gemm_wide_bf16_kernel_128(
+    const bf16_t* __restrict__ a, const bf16x8* __restrict__ wp, float* __restrict__ out, int M, int N, int K, int mblocks, int nblocks) {
+    gemm_wide_body<2>(a, wp, out, M, N, K, mblocks, nblocks);
+}
+
 }  // namespace
+
+int g_wide_cols = 0;      // tuning override (hsd_tune key 107): 128 or 256 columns per workgroup, 0: the rule below
 
 // Column strips of 256, unless they leave at least half of the 256 CUs idle: then strips of 128 (twice the workgroups,
 // still one round).
 static int wide_nt(int m, int n) {
+    if (g_wide_cols == 128) return 2;
+    if (g_wide_cols == 256) return 4;
     return ceil_div(m, WIDE_ROWS) * ceil_div(n, 256) <= 128 ? 2 : 4;
 }
 
@@ -174,9 +189,9 @@ int launch_gemm_wide_bf16(const bf16_t* a, const bf16x8* wp, float* out, int m, 
     const long long grid = 8ll * mblocks * ceil_div(nblocks, 8);
     if (grid > 0x7fffffffll) HSD_FAIL(HSD_EINVAL, "gemm: %d x %d is too large for one launch", m, n);
     if (nt == 2)
-        gemm_wide_bf16_kernel<2><<<dim3((unsigned)grid), WIDE_WAVES * 64, 0, s>>>(a, wp, out, m, n, k, mblocks, nblocks);
+        gemm_wide_bf16_kernel_128<<<dim3((unsigned)grid), WIDE_WAVES * 64, 0, s>>>(a, wp, out, m, n, k, mblocks, nblocks);
     else
-        gemm_wide_bf16_kernel<4><<<dim3((unsigned)grid), WIDE_WAVES * 64, 0, s>>>(a, wp, out, m, n, k, mblocks, nblocks);
+        gemm_wide_bf16_kernel_256<<<dim3((unsigned)grid), WIDE_WAVES * 64, 0, s>>>(a, wp, out, m, n, k, mblocks, nblocks);
     HSD_LAUNCH_CHECK();
     return HSD_OK;
 }
