@@ -225,7 +225,10 @@ int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int
  * sequence number in pinned host memory (default 1; same results either way).  key 106: nt = fewest rows of an
  * hsd_gemm call (above HSD_MAX_PASS_ROWS) that the kernel tiled for the matrix cores serves; calls with fewer rows
  * stream the weights once per 64 rows (0: default, every call above HSD_MAX_PASS_ROWS rows).  key 107: nt = 128 or 256
- * fixes the columns per workgroup of that kernel (0: default, 256 unless that leaves half the CUs without a workgroup). */
+ * fixes the columns per workgroup of that kernel (0: default, 256 unless that leaves half the CUs without a workgroup).
+ * key 108: nt = most column groups of a residual or RoPE projection that still get two workgroups per group, each owning
+ * half of the columns of its tiles, for passes of few rows (default 128; 0 switches the scheme off; the results differ
+ * by the rounding of a different summation order at most). */
 int hsd_tune(int key, int nt, int ksplit, int waves);
 
 /* ---------------------------------------------------------------------------------------------

@@ -97,6 +97,7 @@ struct GemmArgs {
     float* part;                        // split-K partial tiles (ksplit > 1)
     size_t part_bytes;                  // capacity of `part`: a plan that needs more runs unsplit
     int* tickets;                       // one arrival counter per column group, zero between launches
+    int halves;                         // set by the launcher from the plan: workgroup b owns columns 8 (b & 1) .. + 8 of the tiles of group b >> 1
     // consumers of a normalised input: rows of `a` are x * w_norm, the 1/rms factor is applied in the epilogue
     const unsigned long long* ss_in;    // [SS_SLOTS][HSD_MAX_PASS_ROWS]: per row, sum of squares of x times 2^24, spread over the
                                         // slots; null: no scaling (EPI_STORE only)
@@ -118,6 +119,7 @@ struct GemmPlan {
     int nt;       // 16-column tiles per workgroup
     int ksplit;   // workgroups along K per column group
     int waves;    // waves per workgroup; they split the workgroup's K slice
+    int halves;   // 1: two workgroups per column group, each owning 8 of the 16 columns of its tiles (ksplit = 1 only)
 };
 GemmPlan gemm_plan(int m, int n, int k, int epi);
 size_t gemm_part_bytes(int m, int n, int k, int epi);

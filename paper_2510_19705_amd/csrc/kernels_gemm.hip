@@ -169,7 +169,12 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
     const int M = g.M, N = g.N, K = g.K;
     const int KT = K >> 5;
     const int ntiles = (N + 15) >> 4;
-    const int ntile0 = blockIdx.x * NT;
+    // halves: two workgroups share a column group, each loads and owns 8 of the 16 columns of every tile (in the
+    // packed tile those are every other 128-byte line; for RoPE pairs the same columns of both tiles, i.e. whole
+    // pairs); the other half of the MFMA's columns multiplies zeros
+    const bool halves = g.halves != 0;
+    const int ntile0 = (halves ? (int)(blockIdx.x >> 1) : (int)blockIdx.x) * NT;
+    const bool my_col = !halves || (int)((threadIdx.x & 15) >> 3) == (int)(blockIdx.x & 1);   // this lane's column (lane % 16) is the workgroup's
     const int ksplit = gridDim.y;
     const int per_wg = (KT + ksplit - 1) / ksplit;
     const int kt0 = blockIdx.y * per_wg, kt1 = min(KT, kt0 + per_wg);
@@ -191,7 +196,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
         const int t = min(ntile0 + nt, ntiles - 1);     // clamp: tiles past the edge are computed, never stored
         bp[nt] = g.wp + (size_t)t * KT * 64 + lane;
     }
-    auto load_b = [&](int nt, int kt) -> bf16x8 { return __builtin_nontemporal_load(bp[nt] + (size_t)kt * 64); };
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    auto load_b = [&](int nt, int kt) -> bf16x8 { return my_col ? __builtin_nontemporal_load(bp[nt] + (size_t)kt * 64) : zero; };
     const bf16_t* ap[MT];
     bool av[MT];
 #pragma unroll
@@ -200,7 +206,6 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
         av[mt] = m < M;
         ap[mt] = g.a + (size_t)(av[mt] ? m : 0) * K;
     }
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
     if (g.ss_zero && blockIdx.x == 0 && blockIdx.y == 0) ss_clear(g.ss_zero, tid, blockDim.x);   // for the next producer
 
     // ---- operands of this thread's epilogue elements: requested, and the rotary angles evaluated, before the
@@ -223,7 +228,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
             const int mt = tile / NT, nt = tile % NT;
             const int ml = mt * 16 + 4 * (l >> 4) + r;
             const int n = (ntile0 + nt) * 16 + (l & 15);
-            if (ml < M && n < N) {
+            const bool own = !halves || (int)((l & 15) >> 3) == (int)(blockIdx.x & 1);
+            if (ml < M && n < N && own) {
                 if constexpr (EPI == EPI_RESID) {
                     pre_x[i] = g.out_f32[(size_t)ml * N + n];
                     if (g.out_bf16) pre_nw[i] = g.norm_w[n];
@@ -234,7 +240,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
         } else {
             const int mt = tile / (NT / 2), jp = tile % (NT / 2);
             const int ml = mt * 16 + 4 * (l >> 4) + r;
-            if (ml < M) {
+            const bool own = !halves || (int)((l & 15) >> 3) == (int)(blockIdx.x & 1);
+            if (ml < M && own) {
                 pre_inv[i] = row_inv_rms(g.ss_in, ml, K, g.eps);
                 if constexpr (EPI == EPI_ROPE) {
                     const int pairs_per_head = g.hd >> 5;
@@ -335,8 +342,9 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
             const int mt = tile / NT, nt = tile % NT;
             const int ml = mt * 16 + 4 * (l >> 4) + r;
             const int n = (ntile0 + nt) * 16 + (l & 15);
+            const bool own = !halves || (int)((l & 15) >> 3) == (int)(blockIdx.x & 1);
             float v = 0.f;
-            if (ml < M && n < N) {
+            if (ml < M && n < N && own) {
                 float* dst = g.out_f32 + (size_t)ml * N + n;
                 if constexpr (EPI == EPI_RESID) {
                     v = pre_x[i] + s;
@@ -367,7 +375,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
             const int mt = pair / (NT / 2), j = pair % (NT / 2);
             const int ml = mt * 16 + 4 * (l >> 4) + r;
             const int f = ((ntile0 >> 1) + j) * 16 + (l & 15);
-            if (ml < M && f < F) {
+            const bool own = !halves || (int)((l & 15) >> 3) == (int)(blockIdx.x & 1);
+            if (ml < M && f < F && own) {
                 const float gt = red[(mt * NT + 2 * j) * 256 + rem] * pre_inv[i];
                 const float up = red[(mt * NT + 2 * j + 1) * 256 + rem] * pre_inv[i];
                 g.out_bf16[(size_t)ml * F + f] = (bf16_t)(gt / (1.f + __expf(-gt)) * up);
@@ -385,7 +394,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
             const int ml = mt * 16 + 4 * (l >> 4) + r;
             const int gp = (ntile0 >> 1) + jp;                      // global pair index
             const int head = gp / pairs_per_head, j = (gp % pairs_per_head) * 16 + (l & 15);
-            if (ml >= M || head >= g.n_q + 2 * g.n_kv) continue;
+            const bool own = !halves || (int)((l & 15) >> 3) == (int)(blockIdx.x & 1);
+            if (ml >= M || head >= g.n_q + 2 * g.n_kv || !own) continue;
             const float a = red[(mt * NT + 2 * jp) * 256 + rem] * pre_inv[i];
             const float b = red[(mt * NT + 2 * jp + 1) * 256 + rem] * pre_inv[i];
             rope_finish(g, head, j, ml, a, b, pre_rope[i]);
@@ -545,6 +555,7 @@ __global__ void gemm_f32_kernel(const float* __restrict__ x, const float* __rest
 static int g_tune_nt[4] = {0, 0, 0, 0};      // optional overrides per epilogue kind (0 = heuristic)
 static int g_tune_ksplit[4] = {0, 0, 0, 0};
 int g_gemv_max_m = 2;            // most tokens of a pass served from the row-major copies
+static int g_halves_max_groups = 128;   // residual / RoPE projections of at most this many column groups: two workgroups per group (hsd_tune key 108)
 // Fewest rows of an hsd_gemm call (above 64) served by the kernel tiled for the matrix cores; 0: the measured rule in
 // use_wide_kernel.  A tuning knob (hsd_tune key 106).
 static int g_wide_min_rows = 0;
@@ -565,6 +576,7 @@ void gemm_tune(int epilogue, int nt, int ksplit, int waves) {
     if (epilogue == 104) { g_preembed = nt; return; }
     if (epilogue == 105) { g_poll_mailbox = nt; return; }
     if (epilogue == 106) { g_wide_min_rows = nt > 0 ? nt : 0; return; }
+    if (epilogue == 108) { g_halves_max_groups = nt; return; }
     if (epilogue == 107) { g_wide_cols = nt; return; }
     if (epilogue >= 0 && epilogue < 4) {
         g_tune_nt[epilogue] = nt;
@@ -574,7 +586,7 @@ void gemm_tune(int epilogue, int nt, int ksplit, int waves) {
 }
 
 GemmPlan gemm_plan(int m, int n, int k, int epi) {
-    GemmPlan p{1, 1, 8};
+    GemmPlan p{1, 1, 8, 0};
     const int mt = m <= 16 ? 1 : (m <= 32 ? 2 : 4);
     const int ntiles = ceil_div(n, 16), KT = k / 32;
     switch (epi) {
@@ -595,7 +607,17 @@ GemmPlan gemm_plan(int m, int n, int k, int epi) {
     p.ksplit = epi == EPI_STORE ? (1024 + groups / 2) / groups : 1;
     if (epi == EPI_ROPE && groups <= 384 && (size_t)n * k * 2 >= ((size_t)128 << 20)) p.ksplit = 4;
     if (epi == EPI_RESID && groups <= 128 && k >= 8192) p.ksplit = 2;
-    if (g_tune_ksplit[epi]) p.ksplit = g_tune_ksplit[epi];
+    // Narrow matrices (at most 128 column groups: half the CUs would idle) with few rows: two workgroups per group,
+    // each owning 8 of the 16 columns of its tiles, instead of slices of K: twice the workgroups without an exchange
+    // (1B shape, 4-8 rows: down 10.8 -> 10.2 us, q/k/v 7.4 -> 6.9; 16 layers: -3.5 % per pass).  Each half reads all the
+    // activations, which from 16 rows on costs the residual projections more than the extra workgroups give
+    // (32 rows: down 16.6 -> 21 us), and 256-group matrices (7B shape) lose at every row count.
+    if (epi == EPI_RESID && p.nt == 1 && groups <= g_halves_max_groups && m <= 8) {
+        p.halves = 1;
+        p.ksplit = 1;
+    }
+    if (epi == EPI_ROPE && p.ksplit == 1 && groups <= g_halves_max_groups && m <= 32) p.halves = 1;
+    if (g_tune_ksplit[epi]) { p.ksplit = g_tune_ksplit[epi]; p.halves = 0; }
     if (p.ksplit > 8) p.ksplit = 8;
     if (p.ksplit > KT) p.ksplit = KT;
     if (p.ksplit < 1) p.ksplit = 1;
@@ -619,11 +641,13 @@ static size_t gemm_lds_bytes(const GemmPlan& p, int m, int epi) {
 template <int NT, int MT, int EPI>
 static void launch_inst(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     const int ntiles = ceil_div(g.N, 16);
-    dim3 grid(ceil_div(ntiles, NT), p.ksplit);
-    if (g.K / p.ksplit >= 4096 && g.K / p.ksplit < 8192)
-        gemm_bf16_kernel<NT, MT, EPI, true><<<grid, p.waves * 64, gemm_lds_bytes(p, g.M, EPI), s>>>(g);
+    GemmArgs a = g;
+    a.halves = p.halves && p.ksplit == 1;
+    dim3 grid(ceil_div(ntiles, NT) * (a.halves ? 2 : 1), p.ksplit);
+    if (a.K / p.ksplit >= 4096 && a.K / p.ksplit < 8192)
+        gemm_bf16_kernel<NT, MT, EPI, true><<<grid, p.waves * 64, gemm_lds_bytes(p, a.M, EPI), s>>>(a);
     else
-        gemm_bf16_kernel<NT, MT, EPI, false><<<grid, p.waves * 64, gemm_lds_bytes(p, g.M, EPI), s>>>(g);
+        gemm_bf16_kernel<NT, MT, EPI, false><<<grid, p.waves * 64, gemm_lds_bytes(p, a.M, EPI), s>>>(a);
 }
 
 static int check_gemm(int m, int n, int k, int max_rows = HSD_MAX_PASS_ROWS) {

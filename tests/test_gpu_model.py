@@ -107,6 +107,29 @@ def test_pass_random_shapes_bf16():
         model.close()
 
 
+@pytest.mark.parametrize("max_groups", [0, 128], ids=["whole_tiles", "half_tiles"])
+def test_pass_bf16_narrow_projection_schemes(max_groups):
+    """The narrow projections (q/k/v, attention output, FFN down) of passes of few rows run with two workgroups per
+    column group, each owning half of the columns of its tiles; switched off they keep whole tiles (FFN down then
+    splits K over two workgroups).  Both against the oracle, 1 to 9 rows (the scheme applies up to 8)."""
+    from paper_2510_19705_amd import hsd
+    shape = dict(n_layers=2, d=512, n_q=8, n_kv=2, hd=64, ffn=8192, vocab=1000)       # down: K = 8192
+    w = inputs.make_weights(shape, seed=31, bf16=True)
+    toks = inputs.make_prompt(shape["vocab"], 120, seed=32)
+    hsd.lib.hsd_tune(108, max_groups, 0, 0)
+    try:
+        model = gpu_model(shape, w, True, max_seq=128, max_rows=64)
+        oracle = oracle_decoder(shape, w, 128)
+        schedule = [(0, 50, 1, 1), (50, 1, 1, 1), (51, 3, 1, 3), (54, 8, 1, 8), (62, 9, 1, 9), (71, 5, 0, 5), (71, 5, 1, 5)]
+        for tag, got, ref in _run_passes(model, oracle, toks, schedule, (1, 2)):
+            err = np.abs(got - ref).max()
+            say("narrow projections", "half tiles" if max_groups else "whole tiles", tag, "abs err %.2e" % err)
+            assert err < 2e-2, tag
+        model.close()
+    finally:
+        hsd.lib.hsd_tune(108, 128, 0, 0)
+
+
 def test_pass_rejects_bad_arguments():
     shape = SMALL_F32
     w = inputs.make_weights(shape, seed=1, bf16=False)
