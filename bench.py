@@ -7,9 +7,10 @@ sharing the final norm and head; prompt of 512 uniform-random ids, 256 generated
 temperature 1.  Random-init weights (the paper's checkpoints and prompts are not available offline).
 
 One step = one full generation of 256 tokens by HSD from the prefilled prompt (rewind + generate:
-every draft pass, verify pass, softmax, accept/reject/resample kernel and the round driver).
+every draft pass, verify pass, softmax, accept/reject/resample kernel and the round driver), each
+step along its own sample path (sampling seed + step index).
 The (T_0, T_1) sweep {2,4,6} x {1,2,4}, the single-draft sweep and plain autoregressive decoding are
-measured first (untimed part); the timed steps run the best HSD setting.
+measured first (untimed part, eight sample paths per setting); the timed steps run the best HSD setting.
 
 Prints ONE JSON line.  `value` = generated tokens per second of HSD with everything resident in HBM.
 """
@@ -26,6 +27,7 @@ sys.path.insert(0, ROOT)
 
 PROMPT, GEN, TEMPERATURE, SEED = 512, 256, 1.0, 20251019
 EXITS = (2, 6, 16)
+SWEEP_SEEDS = tuple(SEED + 100 + i for i in range(8))      # sample paths per setting of the sweeps
 HBM_PEAK_GBS = 8000.0
 
 
@@ -102,6 +104,29 @@ def timed_generation(h, torch, n_prompt, n_gen, repeats):
     return best
 
 
+def timed_sample_paths(h, torch, n_prompt, n_gen, seeds):
+    """One generation per seed (the same prompt along different sample paths): total seconds, summed statistics.
+    The acceptances of one path of 256 tokens scatter by several per cent, and any change of a kernel's summation
+    order moves the path; the mean over paths is what a setting is worth."""
+    total, acc = 0.0, None
+    for seed in seeds:
+        h.set_seed(seed)
+        h.rewind(n_prompt)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        out, st = h.generate(n_gen)
+        torch.cuda.synchronize()
+        total += time.perf_counter() - t0
+        if acc is None:
+            acc = {"drafted": [0] * 8, "accepted": [0] * 8, "passes": [0] * 8, "rounds": 0}
+        for i in range(8):
+            acc["drafted"][i] += st.drafted[i]
+            acc["accepted"][i] += st.accepted[i]
+            acc["passes"][i] += st.passes[i]
+        acc["rounds"] += st.rounds
+    return total, acc
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -134,14 +159,14 @@ def main():
 
     results = {}
 
-    def measure(name, levels, T, repeats=2):
+    def measure(name, levels, T, seeds=SWEEP_SEEDS):
         h = make(levels, T)
         h.generate(GEN)                                   # warm-up
-        dt, st = timed_generation(h, torch, PROMPT, GEN, repeats)
+        dt, st = timed_sample_paths(h, torch, PROMPT, GEN, seeds)
         n = len(levels)
-        results[name] = {"levels": list(levels), "T": list(T), "tokens_per_s": GEN / dt,
-                         "acceptance": [st.accepted[i] / max(1, st.drafted[i]) for i in range(1, n)],
-                         "passes": [st.passes[i] for i in range(n)], "rounds": st.rounds}
+        results[name] = {"levels": list(levels), "T": list(T), "tokens_per_s": GEN * len(seeds) / dt, "sample_paths": len(seeds),
+                         "acceptance": [st["accepted"][i] / max(1, st["drafted"][i]) for i in range(1, n)],
+                         "passes": [st["passes"][i] for i in range(n)], "rounds": st["rounds"]}
         h.close()
         return results[name]
 
@@ -170,18 +195,24 @@ def main():
     T_best = tuple(best_hsd[1]["T"])
 
     # ---- timed steps: HSD at the best setting ---------------------------------------------------
+    # every step continues the prompt along its own sample path (seed + step), see timed_sample_paths
     h = make(EXITS, T_best)
-    for _ in range(args.warmup):
+    for i in range(args.warmup):
+        h.set_seed(SEED + 1000 + i)
         h.rewind(PROMPT)
         h.generate(GEN)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
+        h.set_seed(SEED + i)
         h.rewind(PROMPT)
         h.generate(GEN)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     value = GEN * args.steps / elapsed
+    h.set_seed(SEED)
+    h.rewind(PROMPT)
+    h.generate(GEN)                                            # the statistics below are those of the first path
     st = h.stats()
 
     # ---- per-pass HBM fraction (c_i of the latency model, measured at the M the level sees) --------

@@ -213,8 +213,9 @@ int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int
 
 /* Overrides of the GEMM launch heuristics, for tuning sweeps (process-wide; 0 restores the heuristic).
  * key 0..3 = epilogue kind (store, residual, SwiGLU, RoPE) of the tiled kernel: nt column tiles per
- * workgroup, ksplit workgroups along K (waves is ignored: workgroups have 8 waves).  key 100: nt = most tokens the row kernel
- * serves before the MFMA kernel takes over on row-major weights.  key 101: nt = most query rows per KV head
+ * workgroup, ksplit workgroups along K (waves is ignored: workgroups have 8 waves).  key 100: most tokens of a pass
+ * that a projection serves from its row-major copy with the row kernel before the MFMA kernel takes over: nt for the
+ * attention output (default 1), ksplit for the FFN down projection (default 2), waves for q/k/v (default 0: never).  key 101: nt = most query rows per KV head
  * (tokens x query heads per KV head) for which the MFMA attention gives each workgroup one 16-row tile; above
  * it, two.  key 102: nt = K/V steps per wave the attention plans for when it splits a sequence over workgroups
  * (0: default, which also caps the split at about 160 workgroups).  key 103: nt = largest vocabulary the driver
@@ -258,6 +259,10 @@ int hsd_prefill(hsd_hier*, const int32_t* prompt, int n);
  * counters and statistics, keeping the KV cache of the first n-1 tokens: used to repeat a
  * generation from the same prompt without repeating the prefill. */
 int hsd_rewind(hsd_hier*, int n);
+/* Replaces the seed that keys every later Philox draw of the hierarchy (Alg. 2's u_i and sampling draws, the noise of
+ * synthetic drafters); counters and sequence stay as they are.  With hsd_rewind: the same prompt continued along
+ * another sample path. */
+int hsd_hier_set_seed(hsd_hier*, uint64_t seed);
 
 /* Base case of Alg. 1: level 0 generates k tokens autoregressively after the current sequence.
  * tokens_out (cap k, may be NULL) receives them; *probs_dev_out the k distribution rows [k, vocab]

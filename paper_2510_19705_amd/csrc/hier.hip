@@ -460,6 +460,12 @@ extern "C" int hsd_prefill(hsd_hier* h, const int32_t* prompt, int n) {
     return HSD_OK;
 }
 
+extern "C" int hsd_hier_set_seed(hsd_hier* h, uint64_t seed) {
+    if (!h) HSD_FAIL(HSD_EINVAL, "hsd_hier_set_seed: null pointer");
+    h->seed = seed;
+    return HSD_OK;
+}
+
 extern "C" int hsd_rewind(hsd_hier* h, int n) {
     if (!h) HSD_FAIL(HSD_EINVAL, "hsd_rewind: null pointer");
     if (n < 1 || n > h->len) HSD_FAIL(HSD_EINVAL, "hsd_rewind: %d outside 1..%d", n, h->len);

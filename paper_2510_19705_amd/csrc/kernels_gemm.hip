@@ -554,7 +554,10 @@ __global__ void gemm_f32_kernel(const float* __restrict__ x, const float* __rest
 // ------------------------------------------------------------------------------------------------
 static int g_tune_nt[4] = {0, 0, 0, 0};      // optional overrides per epilogue kind (0 = heuristic)
 static int g_tune_ksplit[4] = {0, 0, 0, 0};
-int g_gemv_max_m = 2;            // most tokens of a pass served from the row-major copies
+// Most tokens of a pass that a projection serves from its row-major copy (1B shape, microseconds, row kernel against
+// tile kernel: q/k/v 6.9 / 6.1 at one row, 7.9 / 6.3 at two: the tile kernel with two workgroups per column group
+// always wins; attention output 4.4 / 4.9 and 5.2 / 5.0; FFN down 7.8 / 9.4 and 9.5 / 9.5).
+int g_gemv_max_m_qkv = 0, g_gemv_max_m_o = 1, g_gemv_max_m_down = 2;
 static int g_halves_max_groups = 128;   // residual / RoPE projections of at most this many column groups: two workgroups per group (hsd_tune key 108)
 // Fewest rows of an hsd_gemm call (above 64) served by the kernel tiled for the matrix cores; 0: the measured rule in
 // use_wide_kernel.  A tuning knob (hsd_tune key 106).
@@ -569,7 +572,7 @@ static bool use_wide_kernel(int m, int n) {
 }
 
 void gemm_tune(int epilogue, int nt, int ksplit, int waves) {
-    if (epilogue == 100) { g_gemv_max_m = nt; return; }
+    if (epilogue == 100) { g_gemv_max_m_o = nt; g_gemv_max_m_down = ksplit; g_gemv_max_m_qkv = waves; return; }
     if (epilogue == 101) { g_attn_qt1_rows = nt; return; }
     if (epilogue == 102) { g_attn_steps_per_wave = nt; return; }
     if (epilogue == 103) { g_fused_sampler_max_v = nt; return; }

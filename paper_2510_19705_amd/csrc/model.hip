@@ -379,7 +379,8 @@ static int launch_site_bf16(hsd_model* m, int site, int l, int pos0, int rows, c
     const int nq = d.n_q * d.hd, nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
     const LayerWeights& L = m->layers[l];
     bf16_t* kv_layer = (bf16_t*)(m->kv + m->kv_layer_bytes * l);
-    const bool rowk = L.wqkv_rows && rows <= g_gemv_max_m;     // one or two tokens: stream the row-major copies
+    // one or two tokens: some projections stream their row-major copies
+    const bool rowk = L.wqkv_rows && rows <= (site == HSD_SITE_QKV ? g_gemv_max_m_qkv : (site == HSD_SITE_O ? g_gemv_max_m_o : g_gemv_max_m_down));
     GemmArgs g = {};
     g.M = rows; g.part = m->part; g.part_bytes = m->part_elems * sizeof(float); g.tickets = m->tickets; g.eps = d.eps;
     switch (site) {

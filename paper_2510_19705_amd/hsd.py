@@ -92,6 +92,7 @@ _SIGS = {
     "hsd_hier_destroy": (None, [_vp]),
     "hsd_prefill": (_i, [_vp, C.POINTER(C.c_int32), _i]),
     "hsd_rewind": (_i, [_vp, _i]),
+    "hsd_hier_set_seed": (_i, [_vp, C.c_uint64]),
     "hsd_draft": (_i, [_vp, _i, C.POINTER(C.c_int32), C.POINTER(_vp)]),
     "hsd_verify": (_i, [_vp, _i, C.POINTER(C.c_int32), _vp, _i, _i, C.POINTER(C.c_int32), _ip, C.POINTER(_vp)]),
     "hsd_run": (_i, [_vp, _i, C.POINTER(C.c_int32), _i, _ip, C.POINTER(_vp)]),
@@ -382,6 +383,9 @@ class Hierarchy:
 
     def rewind(self, n):
         _check(lib.hsd_rewind(self.handle, n))
+
+    def set_seed(self, seed):
+        _check(lib.hsd_hier_set_seed(self.handle, seed))
 
     def draft(self, k):
         toks = np.zeros(k, dtype=np.int32)

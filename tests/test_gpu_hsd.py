@@ -502,3 +502,26 @@ def test_distilled_drafters_follow_the_oracle():
     h.close()
     ma.close()
     mb.close()
+
+
+def test_set_seed_switches_the_sample_path(tiny):
+    """hsd_hier_set_seed + rewind continue the same prompt along the sample path of another seed: equal to a
+    hierarchy created with that seed, and back to the first path with the first seed."""
+    w, prompt, model = tiny
+    T = (3, 2)
+    def fresh(seed):
+        h = _gpu_hier(model, TINY_EXITS, T, 1.0, seed=seed)
+        h.prefill(prompt)
+        out = h.generate(40)[0].tolist()
+        return h, out
+    ha, a = fresh(11)
+    hb, b = fresh(12)
+    hb.close()
+    assert a != b
+    ha.set_seed(12)
+    ha.rewind(len(prompt))
+    assert ha.generate(40)[0].tolist() == b
+    ha.set_seed(11)
+    ha.rewind(len(prompt))
+    assert ha.generate(40)[0].tolist() == a
+    ha.close()

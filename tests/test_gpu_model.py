@@ -107,6 +107,28 @@ def test_pass_random_shapes_bf16():
         model.close()
 
 
+def test_pass_bf16_row_kernel_on_every_projection():
+    """By default only the attention output (one token) and the FFN down projection (one or two tokens) take the
+    row kernel; here q/k/v (RoPE + cache append epilogue) and three-token passes are sent through it as well."""
+    from paper_2510_19705_amd import hsd
+    shape = SMALL_BF16
+    w = inputs.make_weights(shape, seed=41, bf16=True)
+    toks = inputs.make_prompt(shape["vocab"], 100, seed=42)
+    hsd.lib.hsd_tune(100, 3, 3, 3)
+    try:
+        model = gpu_model(shape, w, True, max_seq=128, max_rows=64, rows_copy_layers=shape["n_layers"])
+        oracle = oracle_decoder(shape, w, 128)
+        L = shape["n_layers"]
+        schedule = [(0, 40, L - 1, 1), (40, 1, L - 1, 1), (41, 2, L - 1, 2), (43, 3, L - 1, 3), (46, 4, L - 1, 4), (50, 1, 0, 1), (50, 1, L - 1, 1)]
+        for tag, got, ref in _run_passes(model, oracle, toks, schedule, tuple(range(1, L + 1))):
+            err = np.abs(got - ref).max()
+            say("row kernel everywhere", tag, "abs err %.2e" % err)
+            assert err < 2e-2, tag
+        model.close()
+    finally:
+        hsd.lib.hsd_tune(100, 1, 2, 0)
+
+
 @pytest.mark.parametrize("max_groups", [0, 128], ids=["whole_tiles", "half_tiles"])
 def test_pass_bf16_narrow_projection_schemes(max_groups):
     """The narrow projections (q/k/v, attention output, FFN down) of passes of few rows run with two workgroups per
