@@ -159,7 +159,8 @@ def main():
 
     results = {}
 
-    def measure(name, levels, T, seeds=SWEEP_SEEDS):
+    def measure(name, levels, T, seeds=None):
+        seeds = seeds or (SWEEP_SEEDS[:2] if args.no_sweep else SWEEP_SEEDS)     # --no-sweep: the short run for profilers
         h = make(levels, T)
         h.generate(GEN)                                   # warm-up
         dt, st = timed_sample_paths(h, torch, PROMPT, GEN, seeds)
