@@ -306,15 +306,19 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
         // Partial tile of this K slice to memory; the last slice to arrive adds them in slice order.
         // The exchange uses device-scope relaxed atomic stores and loads (performed at the level all
         // XCDs share, no cache-wide write-back or invalidate as a device-scope fence would cost on
-        // every one of ~1000 workgroups); each wave waits for its stores to be acknowledged before the
-        // workgroup takes its ticket.
+        // every one of ~1000 workgroups).  Ordering: every wave waits until the memory system has
+        // acknowledged its own write-through stores (vmcnt counts stores on this architecture, and a
+        // workgroup-scope fence alone emits no such wait), then the barrier collects all waves, and only
+        // then thread 0 takes the ticket; the last arriver's device-scope loads are issued after its own
+        // ticket returned, i.e. after every other slice's stores were acknowledged.
         float* slot = g.part + ((size_t)blockIdx.x * ksplit) * TOTAL;
         for (int idx = tid; idx < TOTAL; idx += blockDim.x) {
             float s = 0.f;
             for (int w = 0; w < nwaves; ++w) s += red[w * TOTAL + idx];
             __hip_atomic_store(slot + (size_t)blockIdx.y * TOTAL + idx, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");     // this wave's stores have completed
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // this wave's stores have been acknowledged
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
         if (tid == 0)
             sh_last = __hip_atomic_fetch_add(g.tickets + blockIdx.x, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == ksplit - 1;

@@ -49,27 +49,36 @@ def test_1b_shape_passes_match_oracle():
     model.close()
 
 
-@pytest.mark.parametrize("name,shape", [
+@pytest.mark.parametrize("name,shape,rows", [
     # one layer of the 7B shape: K = 4096 everywhere, the range where the GEMMs issue twice as many loads per batch
-    ("7b_layer", dict(inputs.SHAPES["7b"], n_layers=1, vocab=8000)),
+    ("7b_layer", dict(inputs.SHAPES["7b"], n_layers=1, vocab=8000), 6),
     # a q/k/v matrix of 138 MB in 384 column groups: the one case whose RoPE GEMM splits K over four workgroups
-    ("wide_qkv_layer", dict(n_layers=1, d=5632, n_q=64, n_kv=16, hd=128, ffn=1024, vocab=1000)),
+    ("wide_qkv_layer", dict(n_layers=1, d=5632, n_q=64, n_kv=16, hd=128, ffn=1024, vocab=1000), 6),
+    # the widths of the four-level configuration, each with its 128256-row head: the 8B shape (FFN 14336, grouped heads)
+    # and the 70B shape (d 8192, 64 query / 8 KV heads, FFN 28672: K >= 8192 plans, the residual projection split along K)
+    ("8b_layer", dict(inputs.SHAPES["8b"], n_layers=1), 4),
+    ("70b_layer", dict(inputs.SHAPES["70b"], n_layers=1), 4),
 ])
-def test_large_layer_shapes_match_oracle(name, shape):
+def test_large_layer_shapes_match_oracle(name, shape, rows):
     """Layers at the larger configurations' real widths, in the launch plans those widths select, against the fp64
-    oracle: prefill of 64 tokens in one pass, then a six-row verify pass and a one-token pass."""
+    oracle: prefill of 64 tokens in one pass, then a verify pass of `rows` rows and a one-token pass; every logit of
+    every row (up to 128256 per row) within 2e-2."""
     import torch
     say("generating", name)
     w = inputs.make_weights(shape, seed=91, bf16=True)
-    toks = inputs.make_prompt(shape["vocab"], 71, seed=92)
+    n_tok = 64 + rows + 1
+    toks = inputs.make_prompt(shape["vocab"], n_tok, seed=92)
     model = gpu_model(shape, w, True, max_seq=128, max_rows=64)
+    say("  oracle:", name)
     oracle = oracle_decoder(shape, w, 128)
     ref = oracle.forward([int(t) for t in toks], 0, 1)
+    del oracle
     td = torch.from_numpy(toks).cuda()
-    got64 = model.model_pass(td[:64], 0, 1, 3).cpu().numpy()
-    got6 = model.model_pass(td[64:70], 64, 1, 6).cpu().numpy()
-    got1 = model.model_pass(td[70:71], 70, 1, 1).cpu().numpy()
-    for tag, got, want in (("64-row pass", got64, ref[61:64]), ("6-row pass", got6, ref[64:70]), ("1-row pass", got1, ref[70:71])):
+    got64 = model.model_pass(td[:64], 0, 1, 64).cpu().numpy()
+    gotr = model.model_pass(td[64:64 + rows], 64, 1, rows).cpu().numpy()
+    got1 = model.model_pass(td[64 + rows:], 64 + rows, 1, 1).cpu().numpy()
+    for tag, got, want in (("64-row pass", got64, ref[:64]), ("%d-row pass" % rows, gotr, ref[64:64 + rows]),
+                           ("1-row pass", got1, ref[64 + rows:])):
         err = np.abs(got - want).max()
         say("  %s %s: max abs err %.3e (|z| max %.2f)" % (name, tag, err, np.abs(want).max()))
         assert err < 2e-2, (name, tag)

@@ -429,16 +429,21 @@ def test_sequence_up_to_the_last_cache_position():
     model.close()
 
 
-def test_vocabulary_above_the_fused_sampler_limit():
-    """A hierarchy whose vocabulary (33001: above 32768, not a multiple of 4) takes the sliced softmax and the
-    multi-workgroup accept / resample kernel: streams against the oracle at temperature 0 and 1.  With ~3e-5 of
-    mass per token a draw's margin is bounded by the token's own width, so the asserted margin is 1e-6 of the
-    mass, still ten times the fp32 differences between the two softmaxes."""
-    shape = dict(n_layers=4, d=128, n_q=2, n_kv=2, hd=64, ffn=256, vocab=33001)
+@pytest.mark.parametrize("vocab,wseed,cases", [
+    (33001, 71, ((0.0, 30, 1, 32), (1.0, 2, 911, 24))),
+    (128256, 72, ((0.0, 2, 1, 32), (1.0, 2, 375, 24))),           # the vocabulary of the four-level configuration
+])
+def test_vocabulary_above_the_fused_sampler_limit(vocab, wseed, cases):
+    """Hierarchies whose vocabulary (33001: above 32768, not a multiple of 4; 128256: the largest workload's) takes
+    the sliced softmax and the multi-workgroup accept / resample kernel: streams against the oracle at temperature 0
+    and 1.  With 1e-5 to 3e-5 of mass per token a draw's margin is bounded by the token's own width, so the asserted
+    margin is 1e-6 of the mass, still ten times the fp32 differences between the two softmaxes.  Prompt and sampling
+    seeds: tests/scan_stream_seeds.py."""
+    shape = dict(n_layers=4, d=128, n_q=2, n_kv=2, hd=64, ffn=256, vocab=vocab)
     exits, T = (1, 2, 4), (3, 2)
-    w = inputs.make_weights(shape, seed=71, bf16=False)
+    w = inputs.make_weights(shape, seed=wseed, bf16=False)
     model = gpu_model(shape, w, False, max_seq=128, max_rows=16)
-    for temperature, pseed, seed, n in ((0.0, 30, 1, 32), (1.0, 2, 911, 24)):
+    for temperature, pseed, seed, n in cases:
         prompt = inputs.make_prompt(shape["vocab"], 24, seed=pseed)
         levels = _oracle_levels(w, shape, exits, temperature, max_len=128)
         ch = specsample.PhiloxChooser(seed)
@@ -453,6 +458,7 @@ def test_vocabulary_above_the_fused_sampler_limit():
         got, st = h.generate(n)
         assert got.tolist() == ref, temperature
         assert [st.passes[i] for i in range(3)] == o.passes and [st.accepted[i] for i in range(3)] == o.accepted
+        say("vocabulary", vocab, "temperature", temperature, "accepted", o.accepted, "of", o.drafted)
         h.close()
     model.close()
 
