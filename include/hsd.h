@@ -30,6 +30,7 @@ enum { HSD_OK = 0, HSD_EINVAL = -1, HSD_ECAPACITY = -2, HSD_ESTATE = -3, HSD_EHI
 enum { HSD_F32 = 0, HSD_BF16 = 1 };
 enum { HSD_LAYOUT_TILES = 0, HSD_LAYOUT_ROWS = 1 };
 enum { HSD_MAX_LEVELS = 8, HSD_MAX_PASS_ROWS = 64, HSD_KV_PAGE = 64, HSD_MAX_GEMM_ROWS = 4096 };
+enum { HSD_STATIC_SAMPLER_MAX_VOCAB = 262144 };   /* largest vocabulary of hsd_accept_resample_static */
 
 typedef struct hsd_model hsd_model;
 typedef struct hsd_hier hsd_hier;
@@ -144,6 +145,19 @@ size_t hsd_sampler_scratch_bytes(int vocab);
 int hsd_accept_resample(const float* p_dev, const float* q_dev, int32_t* x_dev, int t, int vocab,
                         uint64_t seed, uint32_t level, uint32_t call, int32_t* result_dev,
                         void* scratch_dev, void* stream);
+
+/* hsd_accept_resample for callers that cannot allocate device memory or bring a workspace: code recording a HIP
+ * graph, tight serving loops, harnesses that forbid hipMalloc.  Same arguments minus scratch_dev, same results bit
+ * for bit.  The ticket and slice totals that hsd_accept_resample keeps in scratch_dev live in an array built into
+ * the library's device code (about 2 KiB per GPU, resolved on the first call on each device and held until the
+ * process ends), which bounds the vocabulary: vocab > HSD_STATIC_SAMPLER_MAX_VOCAB returns HSD_ECAPACITY.  The call
+ * allocates and frees nothing, on the device or through the runtime; it launches a small kernel that clears the
+ * ticket (no memset, so it may be recorded into a graph) and then the sampler kernel, on `stream` of the current
+ * device.  All calls on one GPU share that array: two calls whose kernels may overlap (different streams, no
+ * ordering between them) race on it and give undefined results; calls on one stream, or otherwise ordered, are
+ * safe.  Asynchronous on `stream`. */
+int hsd_accept_resample_static(const float* p_dev, const float* q_dev, int32_t* x_dev, int t, int vocab,
+                               uint64_t seed, uint32_t level, uint32_t call, int32_t* result_dev, void* stream);
 
 /* hsd_softmax over the verifier's t+1 logit rows followed by hsd_accept_resample, in ONE launch (what the driver
  * runs after a verifier pass, and after a base-level drafting pass with t == 0; Alg. 1 and Alg. 2): one workgroup

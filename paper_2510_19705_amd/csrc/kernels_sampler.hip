@@ -580,3 +580,61 @@ extern "C" int hsd_softmax_verify(const float* logits_dev, const float* q_dev, i
     return launch_softmax_verify(logits_dev, q_dev, x_dev, t, vocab, temperature, seed, level, call, probs_dev, result_dev,
                                  scratch_dev, host_mailbox, EmbedNext{}, -1.f, 0, (hipStream_t)stream);
 }
+
+// ------------------------------------------------------------------------------------------------
+// hsd_accept_resample for callers that cannot allocate device memory: the ticket and the slice totals live in a
+// file-scope device array instead of a caller's scratch buffer.
+// ------------------------------------------------------------------------------------------------
+constexpr int STATIC_MAX_V = HSD_STATIC_SAMPLER_MAX_VOCAB;
+constexpr int STATIC_SCRATCH_BYTES = 16 + 2 * (STATIC_MAX_V / 2048) * (int)sizeof(uint64_t);   // ticket + two totals per 2048-token slice
+// One copy per GPU the library runs on, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress: the kernels get the device address it resolves to, never the name.
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+namespace {
+
+static_assert(STATIC_MAX_V % SLICE == 0 && SLICE == 2048, "the static sampler's vocabulary limit must be whole slices");
+constexpr int STATIC_MAX_DEVICES = 64;
+void* g_static_scratch[STATIC_MAX_DEVICES];       // device address of `scratch` on each GPU, null until resolved
+
+// The first 16 bytes (ticket, padding) must read zero when accept_resample_kernel starts.  A kernel, not a memset:
+// callers may be recording a graph.
+__global__ void clear_ticket_kernel(uint32_t* words) {
+    if (threadIdx.x < 4) words[threadIdx.x] = 0u;
+}
+
+int static_scratch_of_current_device(void** out) {
+    int dev = -1;
+    HSD_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= STATIC_MAX_DEVICES) HSD_FAIL(HSD_ECAPACITY, "hsd_accept_resample_static: device %d beyond the %d supported", dev, STATIC_MAX_DEVICES);
+    void* ptr = __atomic_load_n(&g_static_scratch[dev], __ATOMIC_ACQUIRE);
+    if (!ptr) {
+        // resolved with this device current; two threads racing here get the same address
+        HSD_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) HSD_FAIL(HSD_EHIP, "hsd_accept_resample_static: the scratch symbol resolved to null on device %d", dev);
+        __atomic_store_n(&g_static_scratch[dev], ptr, __ATOMIC_RELEASE);
+    }
+    *out = ptr;
+    return HSD_OK;
+}
+
+}  // namespace
+
+extern "C" int hsd_accept_resample_static(const float* p_dev, const float* q_dev, int32_t* x_dev, int t, int vocab, uint64_t seed,
+                                          uint32_t level, uint32_t call, int32_t* result_dev, void* stream) {
+    if (!p_dev || !x_dev || !result_dev) HSD_FAIL(HSD_EINVAL, "hsd_accept_resample_static: null pointer");
+    if (t < 0 || t > 64) HSD_FAIL(HSD_EINVAL, "hsd_accept_resample_static: t=%d outside 0..64", t);
+    if (t > 0 && !q_dev) HSD_FAIL(HSD_EINVAL, "hsd_accept_resample_static: draft rows missing for t=%d", t);
+    if (vocab < 1) HSD_FAIL(HSD_EINVAL, "hsd_accept_resample_static: vocab=%d", vocab);
+    if (vocab > STATIC_MAX_V)
+        HSD_FAIL(HSD_ECAPACITY, "hsd_accept_resample_static: vocabulary %d above the %d the built-in scratch holds (use hsd_accept_resample)",
+                 vocab, STATIC_MAX_V);
+    void* ptr = nullptr;
+    if (int rc = static_scratch_of_current_device(&ptr)) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    if (vocab > SMALL_MAX_V) {          // the one-workgroup kernel below that size exchanges nothing through memory
+        clear_ticket_kernel<<<1, 64, 0, s>>>((uint32_t*)ptr);
+        HSD_LAUNCH_CHECK();
+    }
+    return launch_accept_resample(p_dev, q_dev, x_dev, t, vocab, seed, level, call, result_dev, ptr, -1.f, s);
+}

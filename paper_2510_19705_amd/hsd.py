@@ -77,6 +77,7 @@ _SIGS = {
     "hsd_softmax": (_i, [_vp, _vp, _i, _i, _f, _vp, _vp]),
     "hsd_sampler_scratch_bytes": (_sz, [_i]),
     "hsd_accept_resample": (_i, [_vp, _vp, _vp, _i, _i, C.c_uint64, C.c_uint32, C.c_uint32, _vp, _vp, _vp]),
+    "hsd_accept_resample_static": (_i, [_vp, _vp, _vp, _i, _i, C.c_uint64, C.c_uint32, C.c_uint32, _vp, _vp]),
     "hsd_softmax_verify": (_i, [_vp, _vp, _vp, _i, _i, C.c_float, C.c_uint64, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp, _vp]),
     "hsd_kv_layer_bytes": (_sz, [_i, _i, _i, _i]),
     "hsd_attention_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
@@ -286,6 +287,16 @@ def accept_resample(p, q, x, seed, level, call):
                                    res.data_ptr(), _sampler_scratch[key].data_ptr(), _stream()))
     n, m = res.cpu().tolist()
     return n, m
+
+
+def accept_resample_static(p, q, x, seed, level, call):
+    """hsd_accept_resample_static: as accept_resample, with the library's built-in scratch (no buffer is created here:
+    the result words are the caller's).  Returns the int32 cuda tensor [2] (n, m); x[n] = m on the device."""
+    t, V = p.shape[0] - 1, p.shape[1]
+    res = torch.empty(2, dtype=torch.int32, device="cuda")
+    _check(lib.hsd_accept_resample_static(p.data_ptr(), q.data_ptr() if t > 0 else None, x.data_ptr(), t, V, seed, level, call,
+                                          res.data_ptr(), _stream()))
+    return res
 
 
 def softmax_verify(z, q, x, temperature, seed, level, call, want_probs=True, mailbox=None):
