@@ -197,7 +197,8 @@ int hsd_calibrate(hsd_model*, const int* exits, int n_exits, const int32_t* toke
  * must already be in the cache at positions pos0_dev[b] .. pos0_dev[b] + m - 1; query i attends to positions
  * 0 .. pos0_dev[b] + i (causal among the new tokens), scores scaled by 1/sqrt(hd).  att_dev [batch, m, n_q, hd]
  * (dtype).  max_len >= every pos0_dev[b] + m bounds the launch.  workspace_dev:
- * hsd_attention_workspace_bytes(batch, m, n_q, n_kv, hd, max_len). */
+ * hsd_attention_workspace_bytes(batch, m, n_q, n_kv, hd, max_len) bytes, 256-byte aligned, zero on first use (it
+ * begins with arrival counters of the workgroups that share a sequence; the kernels leave them zeroed). */
 size_t hsd_kv_layer_bytes(int n_pages, int n_kv, int hd, int dtype);
 size_t hsd_attention_workspace_bytes(int batch, int m, int n_q, int n_kv, int hd, int max_len);
 int hsd_kv_write(void* kv_layer_dev, const int32_t* pages_dev, int max_pages, const int32_t* pos0_dev, int batch, int n,

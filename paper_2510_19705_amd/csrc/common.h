@@ -128,6 +128,8 @@ int launch_gemm_bf16(const GemmArgs& g, int epi, const GemmPlan& p, hipStream_t 
 extern int g_gemv_max_m_qkv, g_gemv_max_m_o, g_gemv_max_m_down;
 extern int g_attn_qt1_rows;
 extern int g_attn_steps_per_wave;
+extern int g_attn_target_wgs;
+extern int g_attn_fused_merge;
 extern int g_fused_sampler_max_v;
 extern int g_preembed;
 extern int g_poll_mailbox;

@@ -11,6 +11,8 @@
 // registers; row max / sum are reduced across the four 16-lane groups with wave shuffles.
 // fp32 path (small correctness configuration): lanes = positions for the scores, lanes = head
 // dims for the output, through LDS.
+#include <algorithm>
+
 #include "common.h"
 
 // ------------------------------------------------------------------------------------------------
@@ -48,13 +50,15 @@ __device__ __forceinline__ void load_kv(KvTiles<HD, SP>& t, const bf16_t* __rest
             t.v[sb][dt] = *reinterpret_cast<const bf16x8*>(vblk + (size_t)(((inpage >> 5) + sb) * DT + dt) * 512 + lane * 8);
 }
 
+constexpr int ATTN_FUSED_MAX_SPLITS = 16;     // most splits the attention kernel merges itself (last arriver)
+
 template <int HD, int QT>
 __global__ __launch_bounds__(512) void attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kv_layer,
                                                         const int32_t* __restrict__ pages, int max_pages,
                                                         const int32_t* __restrict__ pos0_arr, int pos0_all, int M, int n_q,
-                                                        int n_kv, float scale_log2, int steps_per_split, int qgroups,
-                                                        float* __restrict__ part_o, float* __restrict__ part_ml, int rpad,
-                                                        bf16_t* __restrict__ att) {
+                                                        int n_kv, float scale_log2, int steps_per_split, int nsplit, int qgroups,
+                                                        int n_units, float* __restrict__ part_o, float* __restrict__ part_ml,
+                                                        int rpad, bf16_t* __restrict__ att, int* __restrict__ tickets) {
     extern __shared__ float lds[];                 // [NW][QT*16][HD + 2]: o, then running max and sum
     constexpr int SP = HD == 64 ? 2 : 1;
     constexpr int KC = HD / 32;   // K chunks of 32 dims per 16-position tile
@@ -63,8 +67,13 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const bf16_t* __restrict
     constexpr int NV = 8 * SP;    // scores per lane and query tile in one step
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
     const int j = lane & 15, grp = lane >> 4;
-    const int split = blockIdx.x, nsplit = gridDim.x, g = blockIdx.y;
-    const int b = blockIdx.z / qgroups, qg = blockIdx.z % qgroups;
+    // One-dimensional grid, decoded so that the query groups of one (sequence, KV head, split) unit sit 8 apart in
+    // launch order: workgroups go to the 8 XCDs round-robin, so those groups land on the same XCD one after the
+    // other and all but the first read the unit's K/V from that XCD's L2.
+    const int xcd = blockIdx.x & 7, rr = blockIdx.x >> 3;
+    const int qg = rr % qgroups, unit = (rr / qgroups) * 8 + xcd;
+    if (unit >= n_units) return;
+    const int split = unit % nsplit, g = (unit / nsplit) % n_kv, b = unit / (nsplit * n_kv);
     const int group = n_q / n_kv;
     const int R = M * group;
     const int pos0 = pos0_arr ? pos0_arr[b] : pos0_all;
@@ -216,13 +225,75 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const bf16_t* __restrict
                 const int i = r / group, hq = r % group;
                 att[(((size_t)b * M + i) * n_q + g * group + hq) * HD + d] = (bf16_t)(acc / L);
             }
-        } else if (r < rpad) {
-            part_o[(pbase + r) * HD + d] = acc;
-            if (d == 0) {
-                part_ml[(pbase + r) * 2] = m;
-                part_ml[(pbase + r) * 2 + 1] = L;
+        } else if (r < R) {
+            if (tickets) {          // the last split to arrive merges: device-scope stores, performed where all XCDs see them
+                __hip_atomic_store(part_o + (pbase + r) * HD + d, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (d == 0) {
+                    __hip_atomic_store(part_ml + (pbase + r) * 2, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(part_ml + (pbase + r) * 2 + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            } else {
+                part_o[(pbase + r) * HD + d] = acc;
+                if (d == 0) {
+                    part_ml[(pbase + r) * 2] = m;
+                    part_ml[(pbase + r) * 2 + 1] = L;
+                }
             }
         }
+    }
+    if (nsplit == 1 || !tickets) return;
+
+    // ---- merge of the splits inside this launch (few splits, one query tile: the partial states of a
+    // (sequence, KV head, query group) are a few KB).  Every wave waits until its device-scope stores have been
+    // acknowledged, the barrier collects the waves, thread 0 takes a ticket; the last of the nsplit workgroups
+    // reads all partial states back with device-scope loads (issued after its own ticket returned, i.e. after
+    // every other split's stores were acknowledged) and writes the normalised rows.  Splits are added in split
+    // order, so the result does not depend on who arrives last.
+    __shared__ bool sh_last;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    int* ticket = tickets + ((size_t)b * n_kv + g) * qgroups + qg;
+    if (tid == 0) sh_last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nsplit - 1;
+    __syncthreads();
+    if (!sh_last) return;
+    if (tid == 0) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);     // for the next launch
+    const size_t hbase = ((size_t)b * n_kv + g) * nsplit;
+    float* wl = lds;                                    // [QT*16][nsplit] normalised weights; the waves' states are no longer needed
+    for (int idx = tid; idx < QT * 16 * nsplit; idx += blockDim.x) {
+        const int rl = idx / nsplit, sp = idx % nsplit;
+        const int r = qg * QT * 16 + rl;
+        float ms = -INFINITY, ls = 0.f;
+        if (r < R) {
+            ms = __hip_atomic_load(part_ml + ((hbase + sp) * rpad + r) * 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ls = __hip_atomic_load(part_ml + ((hbase + sp) * rpad + r) * 2 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        wl[idx] = ms;
+        wl[QT * 16 * nsplit + idx] = ls;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < QT * 16 * HD; idx += blockDim.x) {
+        const int rl = idx / HD, d = idx % HD;
+        const int r = qg * QT * 16 + rl;
+        if (r >= R) continue;
+        float v[ATTN_FUSED_MAX_SPLITS];                 // all splits' values requested together: one memory latency
+#pragma unroll
+        for (int sp = 0; sp < ATTN_FUSED_MAX_SPLITS; ++sp)
+            v[sp] = sp < nsplit ? __hip_atomic_load(part_o + ((hbase + sp) * rpad + r) * HD + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+        float mx = -INFINITY;
+        for (int sp = 0; sp < nsplit; ++sp) mx = fmaxf(mx, wl[rl * nsplit + sp]);
+        float L = 0.f, acc = 0.f;
+#pragma unroll
+        for (int sp = 0; sp < ATTN_FUSED_MAX_SPLITS; ++sp) {
+            if (sp < nsplit) {
+                const float ms = wl[rl * nsplit + sp];
+                const float w = ms == -INFINITY ? 0.f : exp2f(ms - mx);
+                L += w * wl[QT * 16 * nsplit + rl * nsplit + sp];
+                acc += w == 0.f ? 0.f : w * v[sp];
+            }
+        }
+        const int i = r / group, hq = r % group;
+        att[(((size_t)b * M + i) * n_q + g * group + hq) * HD + d] = (bf16_t)(acc / L);
     }
 }
 
@@ -306,37 +377,63 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(const T* __restrict__ q
 }
 
 // ------------------------------------------------------------------------------------------------
-// merge: one wave per (query row, KV head, batch).  grid (R, n_kv, batch), 64 threads.
+// merge of the sequence splits: one workgroup of four waves per (query row, KV head, batch).  grid (R, n_kv, batch).
+// Wave 0 turns the splits' (max, sum) pairs into one weight per split (at most 64 splits: one per lane); then every
+// wave adds up its quarter of the splits' outputs (independent loads, four dims per lane) and the four partial sums
+// are added in wave order.
 // ------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(64) void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
-                                                        int nsplit, int rpad, int M, int n_q, int n_kv, int hd,
-                                                        T* __restrict__ att) {
-    const int r = blockIdx.x, g = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                                         int nsplit, int rpad, int M, int n_q, int n_kv, int hd,
+                                                         T* __restrict__ att) {
+    __shared__ float4 sh_acc[4][64];
+    const int r = blockIdx.x, g = blockIdx.y, b = blockIdx.z, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int group = n_q / n_kv, i = r / group, hq = r % group;
     const size_t base = ((size_t)b * n_kv + g) * nsplit;
-    float m = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) m = fmaxf(m, part_ml[((base + s) * rpad + r) * 2]);
-    float L = 0.f;
-    float o[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < nsplit; ++s) {
-        const size_t pr = (base + s) * rpad + r;
-        const float ms = part_ml[pr * 2];
-        if (ms == -INFINITY) continue;
-        const float w = exp2f(ms - m);
-        L += w * part_ml[pr * 2 + 1];
+    const int nvec = hd >> 2;                          // float4 chunks of a row, at most 64
+    // every wave requests the (max, sum) pairs of all splits (lane s: split s) together with its own quarter of the
+    // splits' outputs, so that one memory latency covers both; the weights are then computed redundantly per wave
+    float ms = -INFINITY, ls = 0.f;
+    if (lane < nsplit) {
+        const float2 ml = *reinterpret_cast<const float2*>(part_ml + ((base + lane) * rpad + r) * 2);
+        ms = ml.x;
+        ls = ml.y;
+    }
+    constexpr int PER = 16;                            // splits per wave: 64 / 4
+    float4 v[PER];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int d = lane + 64 * k;
-            if (d < hd) o[k] += w * part_o[pr * hd + d];
+    for (int k = 0; k < PER; ++k) {
+        const int s = wave + 4 * k;
+        v[k] = float4{0.f, 0.f, 0.f, 0.f};
+        if (s < nsplit && lane < nvec) v[k] = *reinterpret_cast<const float4*>(part_o + ((base + s) * rpad + r) * hd + 4 * lane);
+    }
+    const float m = wave_max(ms);
+    const float wgt = ms == -INFINITY ? 0.f : exp2f(ms - m);
+    const float L = wave_sum(wgt * ls);
+    const float wn = wgt / L;                          // lane s: normalised weight of split s
+    float4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int s = wave + 4 * k;
+        const float w = __shfl(wn, s & 63, 64);
+        if (s < nsplit && w != 0.f) {
+            acc.x += w * v[k].x; acc.y += w * v[k].y; acc.z += w * v[k].z; acc.w += w * v[k].w;
         }
     }
-    T* dst = att + (((size_t)b * M + i) * n_q + g * group + hq) * hd;
-    const float inv = 1.0f / L;
+    sh_acc[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0 && lane < nvec) {
+        float4 o = sh_acc[0][lane];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int d = lane + 64 * k;
-        if (d < hd) dst[d] = from_f32<T>(o[k] * inv);
+        for (int w = 1; w < 4; ++w) {
+            const float4 v = sh_acc[w][lane];
+            o.x += v.x; o.y += v.y; o.z += v.z; o.w += v.w;
+        }
+        T* dst = att + (((size_t)b * M + i) * n_q + g * group + hq) * hd + 4 * lane;
+        dst[0] = from_f32<T>(o.x);
+        dst[1] = from_f32<T>(o.y);
+        dst[2] = from_f32<T>(o.z);
+        dst[3] = from_f32<T>(o.w);
     }
 }
 
@@ -345,6 +442,7 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(const float* __restrict_
 // ------------------------------------------------------------------------------------------------
 struct AttnPlan {
     int nsplit, steps_per_split, rpad, qt, qgroups, nw;
+    bool fused_merge;     // the kernel's last split to arrive merges (no second launch)
 };
 
 // Up to this many query rows per KV head, one 16-row tile per workgroup (more workgroups, each re-reading the
@@ -353,6 +451,9 @@ struct AttnPlan {
 // tiles per workgroup; a tuning knob (hsd_tune key 101).
 int g_attn_qt1_rows = 1 << 30;
 int g_attn_steps_per_wave = 0;      // tuning override (hsd_tune key 102); 0: the default below
+
+int g_attn_target_wgs = 256;
+int g_attn_fused_merge = 1;          // tuning override (hsd_tune key 110): 0 always merges in a second launch        // tuning override (hsd_tune key 109): workgroups a split launch aims for
 
 AttnPlan attn_plan(int batch, int m, int n_q, int n_kv, int hd, int max_len, bool mfma) {
     AttnPlan p;
@@ -364,24 +465,32 @@ AttnPlan attn_plan(int batch, int m, int n_q, int n_kv, int hd, int max_len, boo
     if (mfma) {
         total_steps = ceil_div(max_len, hd == 64 ? 64 : 32);     // the MFMA kernel steps over a whole page for hd 64
         const int per_wave = p.qt * 16 * (hd + 2) * 4;               // LDS bytes of one wave's state
-        p.nw = 65536 / per_wave;
+        p.nw = (144 * 1024) / per_wave;
         if (p.nw > 8) p.nw = 8;
         if (p.nw < 1) p.nw = 1;
-        // one workgroup per (head, query group) while its waves get at most ~6 steps each; beyond that split the
-        // sequence over workgroups and merge, but only up to about 160 workgroups in all: measured on sequences of
-        // 4096 to 32768 positions, 100-250 fat workgroups stream K/V faster than a thousand thin ones (the partial
-        // states and their merge cost more than the extra parallelism gives)
-        const int spw = g_attn_steps_per_wave > 0 ? g_attn_steps_per_wave : (hd == 64 ? 3 : 6);
-        int want = ceil_div(total_steps, p.nw * spw);
+        // One workgroup per (sequence, KV head, query group) while the sequence is short: up to 24 steps (16 KB of
+        // K/V each) a second launch for the merge costs more than the idle CUs.  Beyond that the sequence is split so
+        // that the launch has about one workgroup per CU (a CU pulls only ~40 GB/s, so the stream needs all 256 of
+        // them, evenly loaded), each keeping at least 4 steps.
         const int heads = batch * n_kv * p.qgroups;
-        const int cap = g_attn_steps_per_wave > 0 ? 64 : (160 / heads > 0 ? 160 / heads : 1);
-        if (want > cap) want = cap;
+        int want = 1;
+        if (g_attn_steps_per_wave > 0) {
+            want = ceil_div(total_steps, p.nw * g_attn_steps_per_wave);
+        } else if (total_steps > 24) {
+            want = (g_attn_target_wgs + heads / 2) / heads;
+            if (want > total_steps / 4) want = total_steps / 4;
+        }
         if (want > 64) want = 64;
         if (want < 1) want = 1;
         p.steps_per_split = ceil_div(total_steps, want);
         p.nsplit = ceil_div(total_steps, p.steps_per_split);
+        // few splits of very few rows (7B shape, context 4096, 8 splits; microseconds, merged by the last arriver /
+        // by a second launch: 1 row 18.3 / 19.3, 4 rows 18.5 / 19.5, 8 rows 20.1 / 19.6, 16 rows 23.4 / 20.1): the
+        // last arriver's serial tail (acknowledged stores, ticket, two rounds of loads) grows with the rows
+        p.fused_merge = g_attn_fused_merge && p.nsplit > 1 && p.nsplit <= ATTN_FUSED_MAX_SPLITS && p.nsplit * R <= 32;
         return p;
     }
+    p.fused_merge = false;
     p.nw = 1;
     int want = 2048 / (batch * n_kv * p.qgroups);
     if (want < 1) want = 1;
@@ -393,11 +502,19 @@ AttnPlan attn_plan(int batch, int m, int n_q, int n_kv, int hd, int max_len, boo
     return p;
 }
 
+// workspace: [arrival counters of the in-kernel merge, one per (sequence, KV head, query group); zero between
+// launches][partial outputs][partial (max, sum) pairs]
+// (sized for the most rows a launch may have, so that the counters sit at the same place for every launch)
+size_t attn_ticket_bytes(int batch, int n_q, int n_kv) {
+    const int R = HSD_MAX_PASS_ROWS * (n_q / n_kv);
+    return align_up((size_t)batch * n_kv * ceil_div(R, 16) * sizeof(int), 256);
+}
+
 size_t attn_workspace_bytes(int batch, int m, int n_q, int n_kv, int hd, int max_len) {
     // worst case over the lengths a plan may be made for: nsplit <= 64
     const int R = m * (n_q / n_kv);
     const int rpad = ceil_div(R, 16) * 16 + 48;
-    return align_up((size_t)batch * n_kv * 64 * rpad * (hd + 2) * sizeof(float), 256);
+    return attn_ticket_bytes(batch, n_q, n_kv) + align_up((size_t)batch * n_kv * 64 * rpad * (hd + 2) * sizeof(float), 256);
 }
 
 int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, int max_pages, const int32_t* pos0_dev,
@@ -408,16 +525,26 @@ int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, 
     const bool mfma = dtype == HSD_BF16 && !force_simple && (hd == 64 || hd == 128);
     AttnPlan p = attn_plan(batch, m, n_q, n_kv, hd, max_len, mfma);
     const int R = m * (n_q / n_kv);
-    float* part_o = workspace;
-    float* part_ml = workspace + (size_t)batch * n_kv * p.nsplit * p.rpad * hd;
+    int* tickets = (int*)workspace;
+    float* part_o = (float*)((char*)workspace + attn_ticket_bytes(batch, n_q, n_kv));
+    float* part_ml = part_o + (size_t)batch * n_kv * p.nsplit * p.rpad * hd;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)hd);
     if (mfma) {
-        dim3 grid(p.nsplit, n_kv, batch * p.qgroups);
+        const int n_units = batch * n_kv * p.nsplit;
+        dim3 grid(ceil_div(n_units, 8) * 8 * p.qgroups);
 #define HSD_ATT(HD_, QT_)                                                                                              \
-    if (hd == HD_ && p.qt == QT_)                                                                                      \
-        attn_mfma_kernel<HD_, QT_><<<grid, p.nw * 64, (size_t)p.nw * QT_ * 16 * (HD_ + 2) * 4, s>>>(                    \
+    if (hd == HD_ && p.qt == QT_) {                                                                                    \
+        const size_t lds_bytes = (size_t)p.nw * QT_ * 16 * (HD_ + 2) * 4;                                              \
+        static size_t lds_allowed = 64 * 1024;   /* above the default limit the kernel needs an attribute, once */    \
+        if (lds_bytes > lds_allowed) {                                                                                 \
+            HSD_HIP(hipFuncSetAttribute((const void*)attn_mfma_kernel<HD_, QT_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes)); \
+            lds_allowed = lds_bytes;                                                                                   \
+        }                                                                                                              \
+        attn_mfma_kernel<HD_, QT_><<<grid, p.nw * 64, lds_bytes, s>>>(                                                 \
             (const bf16_t*)q, (const bf16_t*)kv_layer, pages, max_pages, pos0_dev, pos0_all, m, n_q, n_kv, scale_log2, \
-            p.steps_per_split, p.qgroups, part_o, part_ml, p.rpad, (bf16_t*)att);
+            p.steps_per_split, p.nsplit, p.qgroups, n_units, part_o, part_ml, p.rpad, (bf16_t*)att,                    \
+            p.fused_merge ? tickets : nullptr);                                                                        \
+    }
         HSD_ATT(64, 1) HSD_ATT(64, 2) HSD_ATT(128, 1) HSD_ATT(128, 2)
 #undef HSD_ATT
     } else {
@@ -432,12 +559,12 @@ int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, 
                                                           p.steps_per_split, part_o, part_ml, p.rpad);
     }
     HSD_LAUNCH_CHECK();
-    if (mfma && p.nsplit == 1) return HSD_OK;            // the kernel wrote the normalised output itself
+    if (mfma && (p.nsplit == 1 || p.fused_merge)) return HSD_OK;            // the kernel wrote the normalised output itself
     dim3 mg(R, n_kv, batch);
     if (dtype == HSD_BF16)
-        attn_merge_kernel<bf16_t><<<mg, 64, 0, s>>>(part_o, part_ml, p.nsplit, p.rpad, m, n_q, n_kv, hd, (bf16_t*)att);
+        attn_merge_kernel<bf16_t><<<mg, 256, 0, s>>>(part_o, part_ml, p.nsplit, p.rpad, m, n_q, n_kv, hd, (bf16_t*)att);
     else
-        attn_merge_kernel<float><<<mg, 64, 0, s>>>(part_o, part_ml, p.nsplit, p.rpad, m, n_q, n_kv, hd, (float*)att);
+        attn_merge_kernel<float><<<mg, 256, 0, s>>>(part_o, part_ml, p.nsplit, p.rpad, m, n_q, n_kv, hd, (float*)att);
     HSD_LAUNCH_CHECK();
     return HSD_OK;
 }

@@ -253,18 +253,27 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
         }
     }
 
-    int kt = kb;
-    for (; kt + U <= ke; kt += U) {
+    // Batches of U k-steps: all loads of a batch are issued before its MFMAs.  A last, partial batch requests its
+    // missing steps at the wave's last tile again (cache hits) and feeds them zero activations, so that no step is
+    // ever a load-wait-multiply round trip of its own.
+    for (int kt = kb; kt < ke; kt += U) {
         bf16x8 b[U][NT], a[U][MT];
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int u = 0; u < U; ++u) {
+            const int kk = min(kt + u, ke - 1);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) b[u][nt] = load_b(nt, kt + u);
+            for (int nt = 0; nt < NT; ++nt) b[u][nt] = load_b(nt, kk);
+        }
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int u = 0; u < U; ++u) {
+            const int kk = min(kt + u, ke - 1);
+            const bool live = kt + u < ke;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-                a[u][mt] = av[mt] ? *reinterpret_cast<const bf16x8*>(ap[mt] + koff(kt + u)) : zero;
+            for (int mt = 0; mt < MT; ++mt) {
+                const bf16x8 v = *reinterpret_cast<const bf16x8*>(ap[mt] + koff(kk));     // row 0 for lanes past M: always mapped
+                a[u][mt] = av[mt] && live ? v : zero;
+            }
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -272,18 +281,6 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
                     acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][mt], b[u][nt], acc[mt][nt], 0, 0, 0);
-    }
-    for (; kt < ke; ++kt) {
-        bf16x8 b[NT], a[MT];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) b[nt] = load_b(nt, kt);
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) a[mt] = av[mt] ? *reinterpret_cast<const bf16x8*>(ap[mt] + koff(kt)) : zero;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
     }
 
     // cross-wave reduction through LDS: red[wave][tile][r][lane]; element (tile, r, lane) is
@@ -558,6 +555,7 @@ __global__ void gemm_f32_kernel(const float* __restrict__ x, const float* __rest
 // ------------------------------------------------------------------------------------------------
 static int g_tune_nt[4] = {0, 0, 0, 0};      // optional overrides per epilogue kind (0 = heuristic)
 static int g_tune_ksplit[4] = {0, 0, 0, 0};
+static int g_tune_deep = 0;                  // hsd_tune key 111: 1 / -1 force the deeper / shallower load batches, 0: the rule
 // Most tokens of a pass that a projection serves from its row-major copy (1B shape, microseconds, row kernel against
 // tile kernel: q/k/v 6.9 / 6.1 at one row, 7.9 / 6.3 at two: the tile kernel with two workgroups per column group
 // always wins; attention output 4.4 / 4.9 and 5.2 / 5.0; FFN down 7.8 / 9.4 and 9.5 / 9.5).
@@ -579,6 +577,9 @@ void gemm_tune(int epilogue, int nt, int ksplit, int waves) {
     if (epilogue == 100) { g_gemv_max_m_o = nt; g_gemv_max_m_down = ksplit; g_gemv_max_m_qkv = waves; return; }
     if (epilogue == 101) { g_attn_qt1_rows = nt; return; }
     if (epilogue == 102) { g_attn_steps_per_wave = nt; return; }
+    if (epilogue == 111) { g_tune_deep = nt; return; }
+    if (epilogue == 110) { g_attn_fused_merge = nt; return; }
+    if (epilogue == 109) { g_attn_target_wgs = nt > 0 ? nt : 256; return; }
     if (epilogue == 103) { g_fused_sampler_max_v = nt; return; }
     if (epilogue == 104) { g_preembed = nt; return; }
     if (epilogue == 105) { g_poll_mailbox = nt; return; }
@@ -651,7 +652,8 @@ static void launch_inst(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     GemmArgs a = g;
     a.halves = p.halves && p.ksplit == 1;
     dim3 grid(ceil_div(ntiles, NT) * (a.halves ? 2 : 1), p.ksplit);
-    if (a.K / p.ksplit >= 4096 && a.K / p.ksplit < 8192)
+    const bool deep = g_tune_deep ? g_tune_deep > 0 : (a.K / p.ksplit >= 4096 && a.K / p.ksplit < 8192);
+    if (deep)
         gemm_bf16_kernel<NT, MT, EPI, true><<<grid, p.waves * 64, gemm_lds_bytes(p, a.M, EPI), s>>>(a);
     else
         gemm_bf16_kernel<NT, MT, EPI, false><<<grid, p.waves * 64, gemm_lds_bytes(p, a.M, EPI), s>>>(a);

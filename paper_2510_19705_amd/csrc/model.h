@@ -68,6 +68,7 @@ int launch_softmax(const float* z, float* p, int rows, int vocab, float temperat
 int launch_scale_rows_bf16(const float* x, const float* w, void* out, int rows, int d, hipStream_t s);
 // kernels_attn.hip
 size_t attn_workspace_bytes(int batch, int m, int n_q, int n_kv, int hd, int max_len);
+size_t attn_ticket_bytes(int batch, int n_q, int n_kv);   // leading bytes of the workspace that must be zero between launches
 int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, int max_pages, const int32_t* pos0_dev,
                      int pos0_all, int batch, int m, int max_len, int n_q, int n_kv, int hd, int dtype, void* att,
                      float* workspace, int force_simple, hipStream_t s);

@@ -75,6 +75,11 @@ size_t part_elems_needed(const hsd_model_desc& d) {
                              gemm_part_bytes(m, d.d, d.ffn, EPI_RESID)};
         for (int j = 0; j < 5; ++j)
             if (b[j] / 4 > need) need = b[j] / 4;
+        // room for any layer projection cut in up to four K slices (tuning overrides of the plans)
+        const int mt = m <= 16 ? 1 : (m <= 32 ? 2 : 4);
+        const int widest = 2 * d.ffn > nqkv ? 2 * d.ffn : nqkv;
+        const size_t four = (size_t)ceil_div(widest, 16) * 4 * mt * 256;
+        if (four > need) need = four;
     }
     return need;
 }
@@ -168,6 +173,7 @@ extern "C" int hsd_model_create(const hsd_model_desc* desc, void* weights_dev, v
     // Cache rows beyond the valid length are read (and masked) by the attention kernels: keep them finite.
     hipError_t e = hipMemsetAsync(kv_dev, 0, m->kv_layer_bytes * desc->n_layers, m->stream);
     if (e == hipSuccess) e = hipMemsetAsync(m->tickets, 0, ticket_count(*desc) * 4, m->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(m->attn_ws, 0, attn_ticket_bytes(1, desc->n_q, desc->n_kv), m->stream);
     // Padded rows of packed matrices must be zero.
     if (e == hipSuccess) e = hipMemsetAsync(m->head, 0, hsd_packed_bytes(desc->vocab, desc->d, desc->dtype), m->stream);
     std::vector<int32_t> ident(m->max_pages);

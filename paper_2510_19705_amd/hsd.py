@@ -336,8 +336,8 @@ class KvLayer:
     def attention(self, q, pos0, max_len, ws=None):
         """q: [batch, m, n_q, hd]; returns att of the same shape and type."""
         b, m, n_q, hd = q.shape
-        if ws is None:
-            ws = _buf(lib.hsd_attention_workspace_bytes(b, m, n_q, self.n_kv, hd, max_len))
+        if ws is None:       # zero on first use: the workspace begins with arrival counters
+            ws = torch.zeros(max(256, lib.hsd_attention_workspace_bytes(b, m, n_q, self.n_kv, hd, max_len)), dtype=torch.uint8, device="cuda")
         out = torch.empty_like(q)
         _check(lib.hsd_attention(q.contiguous().data_ptr(), self.buf.data_ptr(), self.pages.data_ptr(), self.max_pages,
                                  pos0.data_ptr(), b, m, max_len, n_q, self.n_kv, hd, self.dtype, out.data_ptr(),

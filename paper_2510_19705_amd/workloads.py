@@ -273,7 +273,7 @@ def microbench():
                 pos0 = torch.full((B,), S - k, dtype=torch.int32, device="cuda")
                 nb = hsd.lib.hsd_attention_workspace_bytes(B, k, n_q, n_kv, hd, S)
                 if ws is None or ws.numel() < nb:
-                    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+                    ws = torch.zeros(nb, dtype=torch.uint8, device="cuda")
                 att_us = _time(torch, lambda: cache.attention(q, pos0, S, ws), 5 if kv_bytes > 4e9 else 20)
                 rows = B * k
                 cell = {"batch": B, "kv_len": S, "k": k, "kv_GB": kv_bytes / 1e9, "attention_us": att_us,
