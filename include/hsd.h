@@ -116,6 +116,11 @@ int hsd_profile_end(hsd_model*, hsd_site_times* out);
  * rows at pos0.. are overwritten, so run a pass before trusting the model's state again. */
 int hsd_measure_site(hsd_model*, int site, int rows, int pos0, int iters, double* us_out);
 
+/* Name of the kernel instance (as a profiler prints it, e.g. "gemm_bf16_kernel<2, 1, 2, true>") that a pass of
+ * `rows` tokens launches at a projection site (HSD_SITE_QKV, _O, _GATEUP, _DOWN, _HEAD) of a bf16 model, in layers
+ * without row-major copies: lets a measurement be matched with a profile of the same kernel. */
+int hsd_site_kernel(const hsd_model*, int site, int rows, char* name_out, int cap);
+
 /* ---------------------------------------------------------------------------------------------
  * Stand-alone kernels of the path (each is what the pass / the driver launches internally).
  * ------------------------------------------------------------------------------------------- */
@@ -189,6 +194,18 @@ int hsd_calibrate(hsd_model*, const int* exits, int n_exits, const int32_t* toke
                   float temperature, int cost_rows, void* workspace_dev, size_t workspace_bytes, double* alpha_out,
                   double* cost_ms_out);
 
+/* The same calibration over candidates that may be different networks (Sec. 3.2: the models of a hierarchy share only
+ * the vocabulary): levels = n candidates (model, exit layer) in the order the selection should number them, exits of
+ * one network in ascending order; every network is teacher-forced over tokens_dev, the first n_ctx positions through
+ * its deepest listed exit only; alpha_out [n, n] and cost_ms_out [n] (may be null) as for hsd_calibrate, indexed by
+ * candidate.  Overwrites every listed network's KV cache for positions 0..n_tokens-1 (so it doubles as the prefill of
+ * a hierarchy built from the candidates on the same tokens); synchronises the stream.  hsd_level is declared below. */
+struct hsd_level_;
+size_t hsd_calibrate_levels_workspace_bytes(int n, const struct hsd_level_* levels, int n_tokens, int n_ctx);
+int hsd_calibrate_levels(int n, const struct hsd_level_* levels, const int32_t* tokens_dev, int n_tokens, int n_ctx,
+                         float temperature, int cost_rows, void* workspace_dev, size_t workspace_bytes,
+                         double* alpha_out, double* cost_ms_out);
+
 /* k-query attention over a paged KV cache, for a batch of sequences (the pass uses it with batch 1).
  * One layer's cache: hsd_kv_layer_bytes(n_pages, ...) bytes; pages_dev [batch, max_pages] int32 gives the physical
  * page (HSD_KV_PAGE positions) of each logical page of each sequence.  hsd_kv_write stores logical K/V
@@ -252,7 +269,7 @@ int hsd_tune(int key, int nt, int ksplit, int waves);
  * level K is the target.  Levels that name the same hsd_model are early exits of one network and
  * share its KV cache; all levels must share the vocabulary (Sec. 2).
  * ------------------------------------------------------------------------------------------- */
-typedef struct {
+typedef struct hsd_level_ {
     hsd_model* model;
     int exit_layer;        /* 1..n_layers */
 } hsd_level;
@@ -270,6 +287,12 @@ void hsd_hier_destroy(hsd_hier*);
 /* Resets the hierarchy to the context `prompt` (n >= 1 tokens): fills every model's KV cache for
  * prompt[0..n-2]; the last prompt token is fed by the first pass of each level.  Counters restart. */
 int hsd_prefill(hsd_hier*, const int32_t* prompt, int n);
+/* hsd_prefill for a prompt whose first n_cached tokens (0 <= n_cached <= n-1) already have their K/V in the cache of
+ * every network of the hierarchy, through at least the deepest exit the hierarchy uses of it: left there by another
+ * hierarchy over the same networks, or by hsd_calibrate_levels, on the same tokens (the caller's responsibility; the
+ * library cannot check it).  Only tokens n_cached..n-2 are fed.  Lets several hierarchies over one set of networks
+ * share one prefill of a long prompt. */
+int hsd_prefill_cached(hsd_hier*, const int32_t* prompt, int n, int n_cached);
 /* Drops everything after the first n tokens of the sequence (n >= 1) and restarts the Philox call
  * counters and statistics, keeping the KV cache of the first n-1 tokens: used to repeat a
  * generation from the same prompt without repeating the prefill. */
@@ -279,10 +302,11 @@ int hsd_rewind(hsd_hier*, int n);
  * another sample path. */
 int hsd_hier_set_seed(hsd_hier*, uint64_t seed);
 
-/* Base case of Alg. 1: level 0 generates k tokens autoregressively after the current sequence.
- * tokens_out (cap k, may be NULL) receives them; *probs_dev_out the k distribution rows [k, vocab]
- * (borrowed, valid until the level's next draft). */
-int hsd_draft(hsd_hier*, int k, int32_t* tokens_out, const float** probs_dev_out);
+/* Base case of Alg. 1 (draft(level, k) of the problem statement): `level` generates k tokens autoregressively after
+ * the current sequence.  Only the lowest level drafts in Alg. 1, so level must be 0 (HSD_EINVAL otherwise; a higher
+ * level produces tokens through hsd_run).  tokens_out (cap k, may be NULL) receives them; *probs_dev_out the k
+ * distribution rows [k, vocab] (borrowed, valid until the level's next draft). */
+int hsd_draft(hsd_hier*, int level, int k, int32_t* tokens_out, const float** probs_dev_out);
 
 /* Verify (Alg. 2) at `level` >= 1: the last t tokens of the sequence are the drafts x_1..x_t; if
  * draft_tokens != NULL they are first appended to the sequence from this host array.

@@ -125,6 +125,7 @@ GemmPlan gemm_plan(int m, int n, int k, int epi);
 size_t gemm_part_bytes(int m, int n, int k, int epi);
 void gemm_tune(int epilogue, int nt, int ksplit, int waves);
 int launch_gemm_bf16(const GemmArgs& g, int epi, const GemmPlan& p, hipStream_t s);   // W in MFMA tiles
+void gemm_kernel_name(int m, int k, int epi, const GemmPlan& p, char* out, size_t cap);
 extern int g_gemv_max_m_qkv, g_gemv_max_m_o, g_gemv_max_m_down;
 extern int g_attn_qt1_rows;
 extern int g_attn_steps_per_wave;

@@ -430,11 +430,12 @@ extern "C" double hsd_stats_cost(const hsd_stats* st, int n_levels, const double
     return c;
 }
 
-extern "C" int hsd_prefill(hsd_hier* h, const int32_t* prompt, int n) {
-    if (!h || !prompt) HSD_FAIL(HSD_EINVAL, "hsd_prefill: null pointer");
-    if (n < 1 || n >= h->max_seq) HSD_FAIL(HSD_ECAPACITY, "hsd_prefill: prompt of %d tokens, capacity %d", n, h->max_seq);
+static int prefill_from(hsd_hier* h, const int32_t* prompt, int n, int n_cached, const char* who) {
+    if (!h || !prompt) HSD_FAIL(HSD_EINVAL, "%s: null pointer", who);
+    if (n < 1 || n >= h->max_seq) HSD_FAIL(HSD_ECAPACITY, "%s: prompt of %d tokens, capacity %d", who, n, h->max_seq);
+    if (n_cached < 0 || n_cached > n - 1) HSD_FAIL(HSD_EINVAL, "%s: %d cached tokens outside 0..%d", who, n_cached, n - 1);
     for (int i = 0; i < n; ++i)
-        if (prompt[i] < 0 || prompt[i] >= h->V) HSD_FAIL(HSD_EINVAL, "hsd_prefill: token %d at position %d outside the vocabulary of %d", prompt[i], i, h->V);
+        if (prompt[i] < 0 || prompt[i] >= h->V) HSD_FAIL(HSD_EINVAL, "%s: token %d at position %d outside the vocabulary of %d", who, prompt[i], i, h->V);
     std::copy(prompt, prompt + n, h->tok_host.begin());
     HSD_HIP(hipMemcpyAsync(h->tok_dev, h->tok_host.data(), (size_t)n * 4, hipMemcpyHostToDevice, h->stream));
     HSD_HIP(hipStreamSynchronize(h->stream));
@@ -448,7 +449,7 @@ extern "C" int hsd_prefill(hsd_hier* h, const int32_t* prompt, int n) {
                 deepest = false;
         if (!deepest || n < 2) continue;
         const int max_rows = h->lv[i].model->desc.max_rows;
-        for (int pos = 0; pos < n - 1; pos += max_rows) {
+        for (int pos = n_cached; pos < n - 1; pos += max_rows) {
             const int chunk = std::min(max_rows, n - 1 - pos);
             if (int rc = model_pass(h->lv[i].model, h->tok_dev + pos, pos, chunk, h->lv[i].exit_layer, 0, nullptr)) return rc;
         }
@@ -458,6 +459,12 @@ extern "C" int hsd_prefill(hsd_hier* h, const int32_t* prompt, int n) {
     h->pre_model = nullptr;
     for (int i = 0; i <= h->K; ++i) h->lv[i].cached_len = n - 1;
     return HSD_OK;
+}
+
+extern "C" int hsd_prefill(hsd_hier* h, const int32_t* prompt, int n) { return prefill_from(h, prompt, n, 0, "hsd_prefill"); }
+
+extern "C" int hsd_prefill_cached(hsd_hier* h, const int32_t* prompt, int n, int n_cached) {
+    return prefill_from(h, prompt, n, n_cached, "hsd_prefill_cached");
 }
 
 extern "C" int hsd_hier_set_seed(hsd_hier* h, uint64_t seed) {
@@ -479,8 +486,9 @@ extern "C" int hsd_rewind(hsd_hier* h, int n) {
     return HSD_OK;
 }
 
-extern "C" int hsd_draft(hsd_hier* h, int k, int32_t* tokens_out, const float** probs_dev_out) {
+extern "C" int hsd_draft(hsd_hier* h, int level, int k, int32_t* tokens_out, const float** probs_dev_out) {
     if (!h) HSD_FAIL(HSD_EINVAL, "hsd_draft: null pointer");
+    if (level != 0) HSD_FAIL(HSD_EINVAL, "hsd_draft: level %d (only level 0 drafts autoregressively; higher levels produce tokens through hsd_run)", level);
     if (k < 1 || k > h->lv[0].rows_cap) HSD_FAIL(HSD_ECAPACITY, "hsd_draft: k=%d outside 1..%d (T_0)", k, h->lv[0].rows_cap);
     const int base = h->len;
     h->lv[0].count = 0;

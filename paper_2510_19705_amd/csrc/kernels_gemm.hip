@@ -659,6 +659,13 @@ static void launch_inst(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
         gemm_bf16_kernel<NT, MT, EPI, false><<<grid, p.waves * 64, gemm_lds_bytes(p, a.M, EPI), s>>>(a);
 }
 
+// Name of the kernel instance launch_gemm_bf16 runs for a plan, as a profiler prints it.
+void gemm_kernel_name(int m, int k, int epi, const GemmPlan& p, char* out, size_t cap) {
+    const int mt = m <= 16 ? 1 : (m <= 32 ? 2 : 4);
+    const bool deep = g_tune_deep ? g_tune_deep > 0 : (k / p.ksplit >= 4096 && k / p.ksplit < 8192);
+    snprintf(out, cap, "gemm_bf16_kernel<%d, %d, %d, %s>", p.nt, mt, epi, deep ? "true" : "false");
+}
+
 static int check_gemm(int m, int n, int k, int max_rows = HSD_MAX_PASS_ROWS) {
     if (m < 1 || m > max_rows) HSD_FAIL(HSD_EINVAL, "gemm: m=%d outside 1..%d", m, max_rows);
     if (n < 1 || k < 32 || k % 32 != 0) HSD_FAIL(HSD_EINVAL, "gemm: n=%d k=%d (k must be a positive multiple of 32)", n, k);

@@ -491,6 +491,26 @@ extern "C" int hsd_measure_site(hsd_model* m, int site, int rows, int pos0, int 
     return HSD_OK;
 }
 
+extern "C" int hsd_site_kernel(const hsd_model* m, int site, int rows, char* name_out, int cap) {
+    if (!m || !name_out || cap < 8) HSD_FAIL(HSD_EINVAL, "hsd_site_kernel: bad arguments");
+    const hsd_model_desc& d = m->desc;
+    if (d.dtype != HSD_BF16) HSD_FAIL(HSD_EINVAL, "hsd_site_kernel: bf16 models only");
+    if (rows < 1 || rows > d.max_rows) HSD_FAIL(HSD_EINVAL, "hsd_site_kernel: rows=%d", rows);
+    const int nq = d.n_q * d.hd, nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
+    int n = 0, k = 0, epi = 0;
+    switch (site) {
+        case HSD_SITE_QKV: n = nqkv; k = d.d; epi = EPI_ROPE; break;
+        case HSD_SITE_O: n = d.d; k = nq; epi = EPI_RESID; break;
+        case HSD_SITE_GATEUP: n = 2 * d.ffn; k = d.d; epi = EPI_SWIGLU; break;
+        case HSD_SITE_DOWN: n = d.d; k = d.ffn; epi = EPI_RESID; break;
+        case HSD_SITE_HEAD: n = d.vocab; k = d.d; epi = EPI_STORE; break;
+        default: HSD_FAIL(HSD_EINVAL, "hsd_site_kernel: site %d is not a projection", site);
+    }
+    // layers without row-major copies (rows_copy_layers counts from the first layer): the tiled kernel
+    gemm_kernel_name(rows, k, epi, gemm_plan(rows, n, k, epi), name_out, (size_t)cap);
+    return HSD_OK;
+}
+
 // One pass: rows tokens at positions pos0.., layers [0, exit_layer), logits of the last n_logit_rows rows.
 static int pass_checked(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
                         float* logits, bool embedded);

@@ -68,11 +68,15 @@ _SIGS = {
     "hsd_model_pass_exits": (_i, [_vp, _vp, _i, _i, C.POINTER(C.c_int), _i, _i, _vp]),
     "hsd_overlap": (_i, [_vp, _i, _i, _i, _vp, _vp]),
     "hsd_calibrate_workspace_bytes": (C.c_size_t, [_vp, _i, _i, _i]),
+    "hsd_calibrate_levels_workspace_bytes": (C.c_size_t, [_i, C.POINTER(Level), _i, _i]),
+    "hsd_calibrate_levels": (_i, [_i, C.POINTER(Level), _vp, _i, _i, C.c_float, _i, _vp, C.c_size_t, C.POINTER(C.c_double),
+                                  C.POINTER(C.c_double)]),
     "hsd_calibrate": (_i, [_vp, C.POINTER(C.c_int), _i, _vp, _i, _i, C.c_float, _i, _vp, C.c_size_t, C.POINTER(C.c_double),
                            C.POINTER(C.c_double)]),
     "hsd_profile_begin": (_i, [_vp, _i]),
     "hsd_profile_end": (_i, [_vp, C.POINTER(SiteTimes)]),
     "hsd_measure_site": (_i, [_vp, _i, _i, _i, _i, _dp]),
+    "hsd_site_kernel": (_i, [_vp, _i, _i, C.c_char_p, _i]),
     "hsd_softmax_scratch_bytes": (_sz, [_i, _i]),
     "hsd_softmax": (_i, [_vp, _vp, _i, _i, _f, _vp, _vp]),
     "hsd_sampler_scratch_bytes": (_sz, [_i]),
@@ -92,9 +96,10 @@ _SIGS = {
     "hsd_hier_create": (_i, [_i, C.POINTER(Level), _ip, _f, C.c_uint64, _vp, _sz, _vp, C.POINTER(_vp)]),
     "hsd_hier_destroy": (None, [_vp]),
     "hsd_prefill": (_i, [_vp, C.POINTER(C.c_int32), _i]),
+    "hsd_prefill_cached": (_i, [_vp, C.POINTER(C.c_int32), _i, _i]),
     "hsd_rewind": (_i, [_vp, _i]),
     "hsd_hier_set_seed": (_i, [_vp, C.c_uint64]),
-    "hsd_draft": (_i, [_vp, _i, C.POINTER(C.c_int32), C.POINTER(_vp)]),
+    "hsd_draft": (_i, [_vp, _i, _i, C.POINTER(C.c_int32), C.POINTER(_vp)]),
     "hsd_verify": (_i, [_vp, _i, C.POINTER(C.c_int32), _vp, _i, _i, C.POINTER(C.c_int32), _ip, C.POINTER(_vp)]),
     "hsd_run": (_i, [_vp, _i, C.POINTER(C.c_int32), _i, _ip, C.POINTER(_vp)]),
     "hsd_generate": (_i, [_vp, _i, C.POINTER(C.c_int32), C.POINTER(Stats)]),
@@ -220,6 +225,11 @@ class Model:
         _check(lib.hsd_measure_site(self.handle, SITE_NAMES.index(site), rows, pos0, iters, C.byref(us)))
         return us.value
 
+    def site_kernel(self, site, rows):
+        buf = C.create_string_buffer(128)
+        _check(lib.hsd_site_kernel(self.handle, SITE_NAMES.index(site), rows, buf, 128))
+        return buf.value.decode()
+
     def set_pages(self, table):
         a, p = _i32(table)
         _check(lib.hsd_model_set_pages(self.handle, p, len(a)))
@@ -250,6 +260,19 @@ class Model:
         _check(lib.hsd_calibrate(self.handle, arr, n, tokens_dev.data_ptr(), n_tokens, n_ctx, float(temperature), cost_rows,
                                  ws.data_ptr(), nbytes, alpha, cost))
         return np.array(alpha[:]).reshape(n, n), (np.array(cost[:]) if cost is not None else None)
+
+
+def calibrate_levels(levels, tokens_dev, n_ctx, temperature, cost_rows=0):
+    """hsd_calibrate_levels.  levels: list of (Model, exit_layer).  Returns (alpha [n, n] numpy fp64, costs in ms or None)."""
+    n, n_tokens = len(levels), tokens_dev.numel()
+    lv = (Level * n)(*[Level(m.handle, e) for m, e in levels])
+    nbytes = lib.hsd_calibrate_levels_workspace_bytes(n, lv, n_tokens, n_ctx)
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+    alpha = (C.c_double * (n * n))()
+    cost = (C.c_double * n)() if cost_rows > 0 else None
+    _check(lib.hsd_calibrate_levels(n, lv, tokens_dev.data_ptr(), n_tokens, n_ctx, float(temperature), cost_rows, ws.data_ptr(),
+                                    nbytes, alpha, cost))
+    return np.array(alpha[:]).reshape(n, n), (np.array(cost[:]) if cost is not None else None)
 
 
 def overlap(rows):
@@ -392,16 +415,21 @@ class Hierarchy:
         a, p = _i32(prompt)
         _check(lib.hsd_prefill(self.handle, p, len(a)))
 
+    def prefill_cached(self, prompt, n_cached):
+        """hsd_prefill_cached: the first n_cached tokens' K/V are already in every network's cache."""
+        a, p = _i32(prompt)
+        _check(lib.hsd_prefill_cached(self.handle, p, len(a), n_cached))
+
     def rewind(self, n):
         _check(lib.hsd_rewind(self.handle, n))
 
     def set_seed(self, seed):
         _check(lib.hsd_hier_set_seed(self.handle, seed))
 
-    def draft(self, k):
+    def draft(self, k, level=0):
         toks = np.zeros(k, dtype=np.int32)
         ptr = C.c_void_p()
-        _check(lib.hsd_draft(self.handle, k, toks.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(ptr)))
+        _check(lib.hsd_draft(self.handle, level, k, toks.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(ptr)))
         return toks, _rows_view(ptr.value, k, self.vocab, self.workspace)
 
     def verify(self, level, draft_tokens, draft_probs, t, append=False):

@@ -1,0 +1,122 @@
+"""Turns rocprofv3 result databases into the short text summaries kept under profiles/.  CPU only.
+
+    # per-kernel calls / total / mean duration of a run made with `rocprofv3 --kernel-trace --stats -d DIR -o NAME -- ...`
+    python -m paper_2510_19705_amd.profsum trace DIR/NAME_results.db --cmd "<the command>" --out profiles/<file>.txt
+
+    # HBM bytes per launch of the layer kernels, from two runs of `workloads --config counters` (one with
+    # `--pmc FETCH_SIZE --kernel-trace`, one with `--pmc WRITE_SIZE --kernel-trace`) and the manifest that workload printed
+    python -m paper_2510_19705_amd.profsum traffic --fetch F_results.db --write W_results.db --manifest manifest.json \
+        --cmd "<the command>" --out profiles/<file>.txt
+
+The traffic summary scales both counters by what they read for a plain element-wise kernel of known size in the same
+run (the factor is printed) and ends each layer site with a `traffic_bytes_per_launch_<site>: N kernel=<instance> rows=R`
+line, which bench.py quotes only if it timed the same kernel instance at the same row count.
+"""
+import argparse
+import json
+import sqlite3
+
+
+def _tables(cur):
+    return [r[0] for r in cur.execute("select name from sqlite_master where type in ('table', 'view')")]
+
+
+def trace(db, cmd, out, note=""):
+    cur = sqlite3.connect(db).cursor()
+    rows = list(cur.execute("select name, total_calls, total_duration, average, percentage from top_kernels"))
+    with open(out, "w") as f:
+        f.write("rocprofv3 --kernel-trace --stats summary (durations in microseconds)\n")
+        f.write("command: %s\n" % cmd)
+        if note:
+            f.write(note + "\n")
+        f.write("%-96s %9s %14s %10s %7s\n" % ("kernel", "calls", "total_us", "avg_us", "pct"))
+        for n, c, t, a, p in rows:
+            n = n.replace("bool _Accum", "bf16")
+            f.write("%-96s %9d %14.1f %10.3f %7.2f\n" % (n[:96], c, t, a, p))
+    return open(out).read()
+
+
+def _counter_rows(db):
+    """[(kernel name, dispatch id, counter value)] in dispatch order."""
+    cur = sqlite3.connect(db).cursor()
+    return list(cur.execute("select kernel_name, dispatch_id, value from counters_collection order by dispatch_id"))
+
+
+def traffic(fetch_db, write_db, manifest, cmd, out):
+    man = json.load(open(manifest))
+    f_rows, w_rows = _counter_rows(fetch_db), _counter_rows(write_db)
+    ref_kib = man["reference_MiB_each_way"] * 1024
+
+    def mean_of(rows, pred):
+        # the reference launches are the largest of their kind (weight initialisation uses the same element-wise
+        # kernels on small tensors)
+        v = [val for name, _, val in rows if pred(name)]
+        v = [x for x in v if x >= 0.5 * max(v)] if v else v
+        return (len(v), sum(v) / len(v)) if v else (0, 0.0)
+
+    is_ref = lambda n: "vectorized_elementwise_kernel" in n and "add" in n.lower()
+    nf, rf = mean_of(f_rows, is_ref)
+    nw, rw = mean_of(w_rows, is_ref)
+    if not nf or not nw:
+        raise SystemExit("reference kernel not found in the counter databases")
+    sf, sw = ref_kib / rf, ref_kib / rw
+    lines = ["HBM traffic per launch from rocprofv3 hardware counters (%s-shaped layers: %s, bf16; %d rows per pass, %d cached positions)"
+             % (man["shape"], ", ".join("%s %s" % (k, v) for k, v in man["shape_dims"].items() if k != "n_layers"), man["rows"], man["ctx"]),
+             "commands (two runs, one counter each; both run committed files only):"]
+    lines += ["  " + c for c in cmd.split(" ;; ")]
+    lines.append("scale reference: %s over %d MiB (reads %d KiB, writes %d KiB): FETCH_SIZE read %.1f -> factor %.4f, WRITE_SIZE read %.1f -> factor %.4f"
+                 % (man["reference_kernel"], man["reference_MiB_each_way"], ref_kib, ref_kib, rf, sf, rw, sw))
+    lines.append("%-44s %-10s %6s %14s %14s %14s %8s" % ("kernel", "site", "calls", "fetch_bytes", "write_bytes", "algorithmic", "ratio"))
+    sites = man["sites"]
+    # sites that share one kernel instance are told apart by their order inside a layer
+    by_kernel = {}
+    for site in man["order_within_layer"] + ["head"]:
+        by_kernel.setdefault(sites[site]["kernel"], []).append(site)
+    for kernel, group in by_kernel.items():
+        match = lambda n: kernel in n.replace("bool _Accum", "bf16")
+        fv = [val for name, _, val in f_rows if match(name)]
+        wv = [val for name, _, val in w_rows if match(name)]
+        # the last launches of the run are the ten measured passes (earlier ones: the prefill, at other row counts)
+        want = sum(sites[s]["launches"] for s in group)
+        fv, wv = fv[-want:], wv[-want:]
+        if len(fv) < want or len(wv) < want:
+            lines.append("%-44s %-10s   not found in the databases" % (kernel, "/".join(group)))
+            continue
+        for i, site in enumerate(group):
+            # within a pass the group's sites alternate in layer order; the head (one launch per pass) never shares
+            if len(group) == 1:
+                fs, ws = fv, wv
+            else:
+                fs, ws = fv[i::len(group)], wv[i::len(group)]
+            fb, wb = sum(fs) / len(fs) * sf * 1024, sum(ws) / len(ws) * sw * 1024
+            alg = sites[site]["algorithmic_bytes"]
+            lines.append("%-44s %-10s %6d %14.0f %14.0f %14.0f %8.3f" % (kernel, site, len(fs), fb, wb, alg, (fb + wb) / alg))
+            lines.append("traffic_bytes_per_launch_%s: %d kernel=%s rows=%d" % (site, round(fb + wb), kernel, man["rows"]))
+    with open(out, "w") as f:
+        f.write("\n".join(lines) + "\n")
+    return open(out).read()
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    sub = ap.add_subparsers(dest="what", required=True)
+    t = sub.add_parser("trace")
+    t.add_argument("db")
+    t.add_argument("--cmd", required=True)
+    t.add_argument("--note", default="")
+    t.add_argument("--out", required=True)
+    c = sub.add_parser("traffic")
+    c.add_argument("--fetch", required=True)
+    c.add_argument("--write", required=True)
+    c.add_argument("--manifest", required=True)
+    c.add_argument("--cmd", required=True, help="the two commands, separated by ' ;; '")
+    c.add_argument("--out", required=True)
+    args = ap.parse_args()
+    if args.what == "trace":
+        print(trace(args.db, args.cmd, args.out, args.note))
+    else:
+        print(traffic(args.fetch, args.write, args.manifest, args.cmd, args.out))
+
+
+if __name__ == "__main__":
+    main()

@@ -6,6 +6,7 @@ networks, up to a 70B-shaped target (140 GB of bf16 weights resident in HBM).
     python -m paper_2510_19705_amd.workloads --config microbench      # one 7B-shaped layer: KV length x query tokens x batch
     python -m paper_2510_19705_amd.workloads --config projections     # its four projections alone, 1 to 1024 rows
     python -m paper_2510_19705_amd.workloads --config independent --distill   # drafters = target logits + noise (std 1.0 / 0.5)
+    python -m paper_2510_19705_amd.workloads --config counters --shape 70b    # the workload of the hardware-counter runs
 
 Weights are drawn on the device (seeded normal, residual-writing matrices scaled by 0.1); prompts are uniform-random
 ids.  For each workload: pass time and HBM fraction of every candidate (algorithmic bytes / time / 8 TB/s), pairwise
@@ -55,11 +56,11 @@ def shapes(inputs):
     return s
 
 
-def random_model(hsd, inputs, torch, shape, seed, max_seq, max_rows=64):
+def random_model(hsd, inputs, torch, shape, seed, max_seq, max_rows=64, rows_copy_layers=0):
     """A bf16 model of `shape` with weights drawn on the device."""
     d, F, V = shape["d"], shape["ffn"], shape["vocab"]
     nq, nkv = shape["n_q"] * shape["hd"], shape["n_kv"] * shape["hd"]
-    model = hsd.Model(shape, hsd.BF16, max_seq, max_rows, inputs.ROPE_BASE, inputs.EPS)
+    model = hsd.Model(shape, hsd.BF16, max_seq, max_rows, inputs.ROPE_BASE, inputs.EPS, rows_copy_layers=rows_copy_layers)
     g = torch.Generator(device="cuda").manual_seed(seed)
     rnd = lambda r, c, std: (torch.randn((r, c), device="cuda", generator=g) * std).to(torch.bfloat16)
     norm = lambda: 1 + 0.1 * torch.randn(d, device="cuda", generator=g)
@@ -227,12 +228,23 @@ def projections():
         gemm[rows] = us
         log("rows %2d: " % rows + "  ".join("%s %.1f us (%.2f TB/s)" % (k, v, site_mb[k] / v) for k, v in us.items()))
     model.close()
-    # many-row cells: plain products y = x W^T at the four projection shapes (no fused epilogue at these row counts)
+    gemm_many = many_rows_mfma(hsd, torch, shape, (128, 256, 512, 1024))
+    torch.cuda.empty_cache()
+    site_nk = {"qkv": ((n_q + 2 * n_kv) * hd, d), "o": (d, n_q * hd), "gateup": (2 * F, d), "down": (d, F)}
+    return {"shape": shape, "weight_MB": site_mb, "site_nk": site_nk, "projections_us_by_rows": gemm, "projections_many_rows": gemm_many}
+
+
+def many_rows_mfma(hsd, torch, shape, rows_list):
+    """Many-row cells (a batch of sequences times their drafted tokens): plain products y = x W^T through hsd_gemm at
+    the four projection shapes of one layer (no fused epilogue at these row counts): microseconds, TFLOP/s and the
+    fraction of the dense bf16 MFMA peak of the four together, by row count."""
+    d, F = shape["d"], shape["ffn"]
+    n_q, n_kv, hd = shape["n_q"], shape["n_kv"], shape["hd"]
     site_nk = {"qkv": ((n_q + 2 * n_kv) * hd, d), "o": (d, n_q * hd), "gateup": (2 * F, d), "down": (d, F)}
     packed = {k: hsd.pack_weight((torch.randn(n, kk, device="cuda") * kk ** -0.5).to(torch.bfloat16), hsd.BF16, 0)
               for k, (n, kk) in site_nk.items()}
     gemm_many = {}
-    for rows in (128, 256, 512, 1024):
+    for rows in rows_list:
         us = {}
         for k, (n, kk) in site_nk.items():
             x = torch.randn(rows, kk, device="cuda").to(torch.bfloat16)
@@ -244,8 +256,7 @@ def projections():
         log("rows %4d: " % rows + "  ".join("%s %.1f us (%.0f TFLOP/s)" % (k, v, flop[k] / v / 1e6) for k, v in us.items()) +
             "  | MFMA fraction of the four: %.3f" % gemm_many[rows]["mfma_frac"])
     del packed
-    torch.cuda.empty_cache()
-    return {"shape": shape, "weight_MB": site_mb, "site_nk": site_nk, "projections_us_by_rows": gemm, "projections_many_rows": gemm_many}
+    return gemm_many
 
 
 def microbench():
@@ -316,6 +327,55 @@ def microbench():
             log(sampler[-1])
     return {"config": "microbench", "projections_us_by_rows": gemm, "projections_many_rows": gemm_many, "weight_MB": site_mb,
             "cells": cells, "sampler": sampler}
+
+
+def site_bytes(shape, site, m, ctx=0):
+    """Algorithmic bytes of one launch at a layer site: the weight matrix (or the K/V of the context) once +
+    activations in and out."""
+    d, F, V = shape["d"], shape["ffn"], shape["vocab"]
+    nq, nkv = shape["n_q"] * shape["hd"], shape["n_kv"] * shape["hd"]
+    if site == "attn":
+        return 2 * (ctx + m) * nkv * 2 + 2 * m * nq * 2
+    n, k, out_b = {"qkv": (nq + 2 * nkv, d, 2), "o": (d, nq, 10), "gateup": (2 * F, d, 1), "down": (d, F, 10),
+                   "head": (V, d, 4)}[site]
+    return n * k * 2 + m * k * 2 + m * n * out_b
+
+
+REF_MIB = 256
+
+
+def counters(shape_name, n_layers, rows, ctx):
+    """Workload for hardware-counter runs (rocprofv3 --pmc FETCH_SIZE, then --pmc WRITE_SIZE, each with --kernel-trace):
+    a plain element-wise kernel of known traffic (the scale reference: torch.add over REF_MIB MiB reads and writes that
+    much), then ten verify passes of `rows` tokens through `n_layers` layers of the shape at context `ctx`, so that every
+    kernel of a pass shows up with its per-dispatch counters.  Prints the manifest that profsum.py needs to label
+    them: per site the kernel instance and the algorithmic bytes of a launch."""
+    import torch
+    assert torch.cuda.is_available(), "needs the GPU"
+    from . import hsd, inputs
+    shape = dict(shapes(inputs)[shape_name], n_layers=n_layers)
+    model = random_model(hsd, inputs, torch, shape, 1, (ctx + 128 + 63) // 64 * 64)
+    tok = torch.randint(0, shape["vocab"], (ctx + 64,), device="cuda", dtype=torch.int32)
+    for p0 in range(0, ctx, 64):
+        model.model_pass(tok[p0:p0 + min(64, ctx - p0)], p0, n_layers, 0)
+    src = torch.ones(REF_MIB * (1 << 20) // 4, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(5):
+        torch.add(src, 1.0, out=dst)
+    torch.cuda.synchronize()
+    for _ in range(10):
+        model.model_pass(tok[ctx:ctx + rows], ctx, n_layers, rows)
+    torch.cuda.synchronize()
+    sites = {}
+    for site in ("qkv", "o", "gateup", "down", "head"):
+        sites[site] = {"kernel": model.site_kernel(site, rows), "algorithmic_bytes": site_bytes(shape, site, rows, ctx),
+                       "launches": 10 * (1 if site == "head" else n_layers)}
+    sites["attn"] = {"kernel": "attn_mfma_kernel<%d, 1>" % shape["hd"], "algorithmic_bytes": site_bytes(shape, "attn", rows, ctx),
+                     "launches": 10 * n_layers}
+    model.close()
+    return {"config": "counters", "shape": shape_name, "shape_dims": shape, "layers": n_layers, "rows": rows, "ctx": ctx,
+            "reference_kernel": "torch.add (vectorized_elementwise_kernel)", "reference_MiB_each_way": REF_MIB,
+            "order_within_layer": ["qkv", "attn", "o", "gateup", "down"], "sites": sites}
 
 
 def run_distilled(config, stds, seed=20251019, temperature=1.0, gen=None):
@@ -397,7 +457,11 @@ def run_distilled(config, stds, seed=20251019, temperature=1.0, gen=None):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", choices=sorted(CONFIGS) + ["microbench", "projections"], default="independent")
+    ap.add_argument("--config", choices=sorted(CONFIGS) + ["microbench", "projections", "counters"], default="independent")
+    ap.add_argument("--shape", default="70b", help="counters: model shape")
+    ap.add_argument("--layers", type=int, default=2, help="counters: layers of that shape")
+    ap.add_argument("--rows", type=int, default=4, help="counters: tokens per verify pass")
+    ap.add_argument("--ctx", type=int, default=8192, help="counters: cached positions")
     ap.add_argument("--distill", action="store_true", help="synthetic drafters: target logits + noise, fixed-cost accounting")
     ap.add_argument("--gen", type=int, default=0)
     args = ap.parse_args()
@@ -405,6 +469,8 @@ def main():
         out = microbench()
     elif args.config == "projections":
         out = projections()
+    elif args.config == "counters":
+        out = counters(args.shape, args.layers, args.rows, args.ctx)
     elif args.distill:
         K = len(CONFIGS[args.config]["levels"]) - 1
         stds = [1.0, 0.5, 0.35, 0.25][:K] if K > 1 else [0.7]

@@ -120,3 +120,41 @@ def test_calibrate_matrix_and_selection(bf16):
     with pytest.raises(hsd.HsdError):
         model.calibrate([2, 1], _cuda(toks.astype(np.int32)), 30, 1.0)
     model.close()
+
+
+def test_calibrate_levels_across_networks():
+    """Candidates from two networks (a small independent drafter; three exits of a second network, listed between and
+    after it) in one call: the acceptance matrix against the oracle's rows of each candidate, indexed by candidate
+    whatever the order the networks are scored in; costs positive; every network's cache left filled (a later pass of
+    each agrees with a freshly prefilled copy); bad candidate lists are refused."""
+    import torch
+    from paper_2510_19705_amd import hsd
+    big = SMALL_F32
+    small = dict(n_layers=2, d=64, n_q=2, n_kv=1, hd=32, ffn=96, vocab=big["vocab"])
+    wb, ws = inputs.make_weights(big, seed=43, bf16=False), inputs.make_weights(small, seed=44, bf16=False)
+    toks = inputs.make_prompt(big["vocab"], 70, seed=45)
+    mb, ms = gpu_model(big, wb, False, max_seq=128, max_rows=24), gpu_model(small, ws, False, max_seq=128, max_rows=8)
+    cands = [(mb, 1), (ms, 2), (mb, 3), (mb, 4)]
+    td = _cuda(toks.astype(np.int32))
+    alpha, cost = hsd.calibrate_levels(cands, td, 25, 1.0, cost_rows=4)
+    rows_b = calibrate.exit_distributions(oracle_decoder(big, wb, 128), [1, 3, 4], toks, 25, 1.0)
+    rows_s = calibrate.exit_distributions(oracle_decoder(small, ws, 128), [2], toks, 25, 1.0)
+    ref = calibrate.acceptance_matrix(np.stack([rows_b[0], rows_s[0], rows_b[1], rows_b[2]]))
+    say("alpha library\n", np.round(alpha, 4), "\nalpha oracle\n", np.round(ref, 4), "\ncost ms", cost)
+    assert np.abs(alpha - ref).max() < 1e-5
+    assert np.array_equal(alpha, alpha.T) and (np.diag(alpha) == 1).all() and (cost > 0).all()
+    assert calibrate.triangle_violation(alpha) <= 1e-9
+    # the call doubles as a prefill: one more pass of each network equals the same pass after a plain prefill
+    for model, shape, w, e in ((mb, big, wb, 4), (ms, small, ws, 2)):
+        fresh = gpu_model(shape, w, False, max_seq=128, max_rows=24)
+        for p0 in range(0, 66, 22):
+            fresh.model_pass(td[p0:p0 + 22], p0, e, 0)
+        assert torch.equal(model.model_pass(td[66:70], 66, e, 4), fresh.model_pass(td[66:70], 66, e, 4))
+        fresh.close()
+    with pytest.raises(hsd.HsdError):
+        hsd.calibrate_levels([(mb, 3), (ms, 2), (mb, 1)], td, 25, 1.0)          # exits of one network out of order
+    other = gpu_model(dict(small, vocab=500), inputs.make_weights(dict(small, vocab=500), seed=46, bf16=False), False, 128, 8)
+    with pytest.raises(hsd.HsdError):
+        hsd.calibrate_levels([(other, 1), (mb, 4)], td, 25, 1.0)                # different vocabularies
+    for m in (mb, ms, other):
+        m.close()

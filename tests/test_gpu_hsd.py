@@ -240,6 +240,9 @@ def test_driver_error_paths(tiny):
         h.verify(3, [1, 2], q, 2)
     with pytest.raises(hsd.HsdError):                      # more drafts than T_0
         h.draft(5)
+    with pytest.raises(hsd.HsdError) as e:                 # only the lowest level drafts autoregressively (Alg. 1)
+        h.draft(2, level=1)
+    assert e.value.code == -1
     with pytest.raises(hsd.HsdError):                      # draft id outside the vocabulary
         h.verify(1, [1, -5], q, 2)
     h.close()
