@@ -361,7 +361,7 @@ def cpu_baseline(inputs, workloads, big):
         total_s += st["passes"][lvl] * per_pass
         parts.append("%s: %d rows, layer %.3f s, head %.3f s, pass %.2f s x %d passes" % (label, m, t_layer, t_head, per_pass, st["passes"][lvl]))
         del dec, w
-    tokens = BIG["gen"]
+    tokens = BIG["gen"] * big["hsd"]["sample_paths"]            # the pass counts are sums over that many generations
     return {"value": tokens / total_s, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
             "sample": "EXTRAPOLATED from one fp64 numpy oracle layer per shape of the selected hierarchy at that level's pass size "
                       "(plus one eighth of the LM head): pass = layers run x layer time + 8 x head-slice time; run = sum over levels "

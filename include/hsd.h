@@ -87,6 +87,22 @@ int hsd_model_set_pages(hsd_model*, const int32_t* page_table, int n_pages);
 int hsd_model_pass(hsd_model*, const int32_t* tokens_dev, int pos0, int m, int exit_layer,
                    int n_logit_rows, float* logits_dev);
 
+/* Passes over a batch of sequences (Sec. 3.1: each load of the weights should serve as many tokens as possible; the
+ * paper itself decodes one sequence).  hsd_model_set_batch shares the model's KV pages (max_seq / HSD_KV_PAGE of them)
+ * out among `batch` sequences: page_table (host) [batch, pages_per_seq] names the physical page of every logical
+ * page of every sequence, all entries distinct; batch * pages_per_seq must not exceed the model's pages and batch not
+ * max_rows.  batch == 0 returns to one sequence.  Synchronises the stream.
+ * hsd_model_pass_batch then feeds tokens_per_seq tokens of every sequence in one pass (batch * tokens_per_seq <=
+ * max_rows): tokens_dev (device int32) [batch, tokens_per_seq]; pos0 (host) [batch] the position of each sequence's
+ * first token, whose earlier positions must already be cached; each token attends to its own sequence only, causally.
+ * with_logits != 0 writes the fp32 logits of every row to logits_dev [batch, tokens_per_seq, vocab].  Row for row the
+ * result equals hsd_model_pass of the same sequence alone up to the summation order of the kernels a different row
+ * count selects.  The plain hsd_model_pass keeps using the single-sequence page order (hsd_model_set_pages) over the
+ * same physical pages: do not mix the two on one cache content. */
+int hsd_model_set_batch(hsd_model*, int batch, int pages_per_seq, const int32_t* page_table);
+int hsd_model_pass_batch(hsd_model*, const int32_t* tokens_dev, const int32_t* pos0, int tokens_per_seq, int exit_layer,
+                         int with_logits, float* logits_dev);
+
 /* The same pass through the deepest of several exits, emitting every listed exit's logits on the way (Sec. 5.1:
  * the output distributions of all candidate layers are recorded during one forward pass): exits = n_exits ascending
  * layer counts; logits_dev [n_exits, n_logit_rows, vocab].  Each exit's rows equal, bit for bit, what

@@ -113,7 +113,23 @@ struct GemmArgs {
     const int32_t* pages;
     int pos0, n_q, n_kv, hd;
     float rope_base;
+    // EPI_ROPE over a batch of sequences: row ml is token ml % m_seq of sequence ml / m_seq, at position
+    // pos0_arr[sequence] + ml % m_seq, with the sequence's page table at pages + sequence * max_pages.
+    // pos0_arr == null: one sequence, row ml at position pos0 + ml.
+    const int32_t* pos0_arr;
+    int m_seq, max_pages;
 };
+
+// position and page table of row ml under the geometry above
+__device__ __forceinline__ int gemm_row_position(const GemmArgs& g, int ml, const int32_t** ptab) {
+    if (!g.pos0_arr) {
+        *ptab = g.pages;
+        return g.pos0 + ml;
+    }
+    const int b = ml / g.m_seq;
+    *ptab = g.pages + (size_t)b * g.max_pages;
+    return g.pos0_arr[b] + ml % g.m_seq;
+}
 
 struct GemmPlan {
     int nt;       // 16-column tiles per workgroup

@@ -50,6 +50,8 @@ __device__ __forceinline__ void load_kv(KvTiles<HD, SP>& t, const bf16_t* __rest
             t.v[sb][dt] = *reinterpret_cast<const bf16x8*>(vblk + (size_t)(((inpage >> 5) + sb) * DT + dt) * 512 + lane * 8);
 }
 
+constexpr size_t ATTN_TICKET_BYTES = 64 * 1024;  // arrival counters at the start of every attention workspace
+int attn_max_splits(int batch, int m, int n_q, int n_kv);
 constexpr int ATTN_FUSED_MAX_SPLITS = 16;     // most splits the attention kernel merges itself (last arriver)
 
 template <int HD, int QT>
@@ -480,21 +482,22 @@ AttnPlan attn_plan(int batch, int m, int n_q, int n_kv, int hd, int max_len, boo
             want = (g_attn_target_wgs + heads / 2) / heads;
             if (want > total_steps / 4) want = total_steps / 4;
         }
-        if (want > 64) want = 64;
+        want = std::min(want, attn_max_splits(batch, m, n_q, n_kv));
         if (want < 1) want = 1;
         p.steps_per_split = ceil_div(total_steps, want);
         p.nsplit = ceil_div(total_steps, p.steps_per_split);
         // few splits of very few rows (7B shape, context 4096, 8 splits; microseconds, merged by the last arriver /
         // by a second launch: 1 row 18.3 / 19.3, 4 rows 18.5 / 19.5, 8 rows 20.1 / 19.6, 16 rows 23.4 / 20.1): the
         // last arriver's serial tail (acknowledged stores, ticket, two rounds of loads) grows with the rows
-        p.fused_merge = g_attn_fused_merge && p.nsplit > 1 && p.nsplit <= ATTN_FUSED_MAX_SPLITS && p.nsplit * R <= 32;
+        p.fused_merge = g_attn_fused_merge && p.nsplit > 1 && p.nsplit <= ATTN_FUSED_MAX_SPLITS && p.nsplit * R <= 32 &&
+                        (size_t)heads * sizeof(int) <= ATTN_TICKET_BYTES;
         return p;
     }
     p.fused_merge = false;
     p.nw = 1;
     int want = 2048 / (batch * n_kv * p.qgroups);
     if (want < 1) want = 1;
-    if (want > 64) want = 64;
+    want = std::min(want, attn_max_splits(batch, m, n_q, n_kv));
     int sps = ceil_div(total_steps, want);
     if (sps < 4) sps = 4;
     p.steps_per_split = sps;
@@ -502,19 +505,26 @@ AttnPlan attn_plan(int batch, int m, int n_q, int n_kv, int hd, int max_len, boo
     return p;
 }
 
-// workspace: [arrival counters of the in-kernel merge, one per (sequence, KV head, query group); zero between
-// launches][partial outputs][partial (max, sum) pairs]
-// (sized for the most rows a launch may have, so that the counters sit at the same place for every launch)
-size_t attn_ticket_bytes(int batch, int n_q, int n_kv) {
-    const int R = HSD_MAX_PASS_ROWS * (n_q / n_kv);
-    return align_up((size_t)batch * n_kv * ceil_div(R, 16) * sizeof(int), 256);
+// workspace: [arrival counters of the in-kernel merge, one per (sequence, KV head, query group), zero between
+// launches: a region of fixed size, so that the counters sit at the same place whatever the launch][partial
+// outputs][partial (max, sum) pairs]
+size_t attn_ticket_bytes() { return ATTN_TICKET_BYTES; }
+
+// Most splits of a sequence a launch may use: the plans aim for a few hundred workgroups, so launches with many
+// (sequence, KV head, query group) units split less; the bound sizes the partial buffers.
+int attn_max_splits(int batch, int m, int n_q, int n_kv) {
+    const int R = m * (n_q / n_kv);
+    const long long heads = (long long)batch * n_kv * ceil_div(R, 16);
+    const long long s = (1024 + heads - 1) / heads;
+    return (int)(s > 64 ? 64 : (s < 1 ? 1 : s));
 }
 
 size_t attn_workspace_bytes(int batch, int m, int n_q, int n_kv, int hd, int max_len) {
-    // worst case over the lengths a plan may be made for: nsplit <= 64
+    (void)max_len;
     const int R = m * (n_q / n_kv);
-    const int rpad = ceil_div(R, 16) * 16 + 48;
-    return attn_ticket_bytes(batch, n_q, n_kv) + align_up((size_t)batch * n_kv * 64 * rpad * (hd + 2) * sizeof(float), 256);
+    const int rpad = ceil_div(R, 16) * 16 + 16;        // + 16: two query tiles per workgroup round the rows up to 32
+    return attn_ticket_bytes() +
+           align_up((size_t)batch * n_kv * attn_max_splits(batch, m, n_q, n_kv) * rpad * (hd + 2) * sizeof(float), 256);
 }
 
 int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, int max_pages, const int32_t* pos0_dev,
@@ -526,7 +536,7 @@ int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, 
     AttnPlan p = attn_plan(batch, m, n_q, n_kv, hd, max_len, mfma);
     const int R = m * (n_q / n_kv);
     int* tickets = (int*)workspace;
-    float* part_o = (float*)((char*)workspace + attn_ticket_bytes(batch, n_q, n_kv));
+    float* part_o = (float*)((char*)workspace + attn_ticket_bytes());
     float* part_ml = part_o + (size_t)batch * n_kv * p.nsplit * p.rpad * hd;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)hd);
     if (mfma) {

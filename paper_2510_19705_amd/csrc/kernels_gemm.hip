@@ -118,18 +118,20 @@ struct RopePre {
 
 __device__ __forceinline__ RopePre rope_prepare(const GemmArgs& g, int head, int j, int ml) {
     RopePre r{1.0, 0.0, 0};
-    const int pos = g.pos0 + ml;
+    const int32_t* ptab;
+    const int pos = gemm_row_position(g, ml, &ptab);
     if (head < g.n_q + g.n_kv) {
         const double ang = (double)pos * exp2(-2.0 * (double)j / (double)g.hd * log2((double)g.rope_base));
         sincos(ang, &r.sn, &r.cs);
     }
-    if (head >= g.n_q) r.page = g.pages[pos / HSD_KV_PAGE];
+    if (head >= g.n_q) r.page = ptab[pos / HSD_KV_PAGE];
     return r;
 }
 
 __device__ __forceinline__ void rope_finish(const GemmArgs& g, int head, int j, int ml, float a, float b, const RopePre& pre) {
     const int hd = g.hd, half = hd >> 1;
-    const int pos = g.pos0 + ml;
+    const int32_t* ptab;
+    const int pos = gemm_row_position(g, ml, &ptab);
     const bool is_q = head < g.n_q, is_v = head >= g.n_q + g.n_kv;
     float ra = a, rb = b;
     if (!is_v) {
@@ -728,6 +730,7 @@ int launch_gemv_bf16(const GemmArgs& g0, int epi, hipStream_t s) {
         if (g.ss_out) g.ss_out = g0.ss_out + m0;
         if (m0 > 0) g.ss_zero = nullptr;
         if (epi == EPI_ROPE) {
+            if (g0.pos0_arr && g0.M > 16) HSD_FAIL(HSD_EINVAL, "gemv: a batch of sequences takes at most 16 rows here");
             g.out_bf16 = g0.out_bf16 + (size_t)m0 * g0.n_q * g0.hd;
             g.pos0 = g0.pos0 + m0;
         } else {

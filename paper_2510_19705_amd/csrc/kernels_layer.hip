@@ -80,11 +80,14 @@ __global__ void scale_rows_bf16_kernel(const float* __restrict__ x, const float*
 // through the page table.  grid (m, n_q + 2 n_kv), 64 threads.
 template <typename T>
 __global__ void rope_kv_kernel(const float* __restrict__ part, int ksplit, int M, T* __restrict__ q, T* __restrict__ kv_layer,
-                               const int32_t* __restrict__ pages, int pos0, int n_q, int n_kv, int hd, float rope_base) {
+                               const int32_t* __restrict__ pages, int pos0, int n_q, int n_kv, int hd, float rope_base,
+                               const int32_t* __restrict__ pos0_arr, int m_seq, int max_pages) {
     const int m = blockIdx.x, head = blockIdx.y;
     const int width = (n_q + 2 * n_kv) * hd;
     const int half = hd >> 1;
-    const int pos = pos0 + m;
+    // a batch of sequences: row m is token m % m_seq of sequence m / m_seq, with that sequence's page table
+    const int pos = pos0_arr ? pos0_arr[m / m_seq] + m % m_seq : pos0 + m;
+    if (pos0_arr) pages += (size_t)(m / m_seq) * max_pages;
     const size_t stride = (size_t)M * width;
     const float* src = part + (size_t)m * width + (size_t)head * hd;
     const bool is_v = head >= n_q + n_kv;
@@ -246,14 +249,14 @@ int launch_scale_rows_bf16(const float* x, const float* w, void* out, int rows, 
 }
 
 int launch_rope_kv(const float* part, int ksplit, int m, void* q, void* kv_layer, const int32_t* pages, int pos0, int n_q,
-                   int n_kv, int hd, float rope_base, int dtype, hipStream_t s) {
+                   int n_kv, int hd, float rope_base, int dtype, hipStream_t s, const int32_t* pos0_arr, int m_seq, int max_pages) {
     dim3 grid(m, n_q + 2 * n_kv);
     if (dtype == HSD_BF16)
         rope_kv_kernel<bf16_t><<<grid, 64, 0, s>>>(part, ksplit, m, (bf16_t*)q, (bf16_t*)kv_layer, pages, pos0, n_q, n_kv, hd,
-                                                   rope_base);
+                                                   rope_base, pos0_arr, m_seq, max_pages);
     else
         rope_kv_kernel<float><<<grid, 64, 0, s>>>(part, ksplit, m, (float*)q, (float*)kv_layer, pages, pos0, n_q, n_kv, hd,
-                                                  rope_base);
+                                                  rope_base, pos0_arr, m_seq, max_pages);
     HSD_LAUNCH_CHECK();
     return HSD_OK;
 }

@@ -41,6 +41,10 @@ struct hsd_model {
     size_t part_elems;
     std::vector<bool> layer_loaded;
     bool head_loaded;
+    // batch of sequences (hsd_model_set_batch / hsd_model_pass_batch): the KV pages shared out among the sequences
+    int32_t* batch_pages_dev;   // [batch][batch_pages_per_seq]
+    int32_t* batch_pos0_dev;    // [batch]
+    int batch, batch_pages_per_seq;
     unsigned long long pass_serial;   // counts passes: whoever left something in the activation buffers can tell if it is still there
     // optional per-site event timing (hsd_profile_begin / hsd_profile_end)
     bool prof_on;
@@ -62,13 +66,14 @@ int launch_embed(const int32_t* tok, const void* E, float* x, int m, int d, int 
 int launch_resid_rmsnorm(float* x, const float* part, int ksplit, int part_rows, int part_row0, const float* w, void* xn,
                          int rows, int row0, int d, float eps, int dtype, hipStream_t s);
 int launch_rope_kv(const float* part, int ksplit, int m, void* q, void* kv_layer, const int32_t* pages, int pos0, int n_q,
-                   int n_kv, int hd, float rope_base, int dtype, hipStream_t s);
+                   int n_kv, int hd, float rope_base, int dtype, hipStream_t s, const int32_t* pos0_arr = nullptr, int m_seq = 0,
+                   int max_pages = 0);
 size_t softmax_scratch_bytes(int rows, int vocab);
 int launch_softmax(const float* z, float* p, int rows, int vocab, float temperature, float* scratch, hipStream_t s);
 int launch_scale_rows_bf16(const float* x, const float* w, void* out, int rows, int d, hipStream_t s);
 // kernels_attn.hip
 size_t attn_workspace_bytes(int batch, int m, int n_q, int n_kv, int hd, int max_len);
-size_t attn_ticket_bytes(int batch, int n_q, int n_kv);   // leading bytes of the workspace that must be zero between launches
+size_t attn_ticket_bytes();   // leading bytes of an attention workspace that must be zero between launches
 int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, int max_pages, const int32_t* pos0_dev,
                      int pos0_all, int batch, int m, int max_len, int n_q, int n_kv, int hd, int dtype, void* att,
                      float* workspace, int force_simple, hipStream_t s);

@@ -2,6 +2,8 @@
 // (the verifier's parallel scoring of all prefixes in Alg. 2; with one row, a draft step of Alg. 1).
 #include <string.h>
 
+#include <algorithm>
+
 #include "model.h"
 
 static thread_local char g_err[512] = "";
@@ -94,8 +96,17 @@ size_t ticket_count(const hsd_model_desc& d) {
 }
 
 struct ScratchLayout {
-    size_t pages, ss, tickets, x, xn, part, q, att, h, attn, total;
+    size_t pages, batch_pages, batch_pos0, ss, tickets, x, xn, part, q, att, h, attn, total;
 };
+
+// The attention workspace must hold the partial states of any launch the model may make: one sequence of up to
+// max_rows tokens, or a batch of sequences with batch * tokens <= max_rows.
+size_t attn_ws_bytes_of(const hsd_model_desc& d) {
+    size_t need = 0;
+    for (int b = 1; b <= d.max_rows; ++b)
+        need = std::max(need, attn_workspace_bytes(b, d.max_rows / b, d.n_q, d.n_kv, d.hd, d.max_seq));
+    return need;
+}
 
 ScratchLayout scratch_layout(const hsd_model_desc& d) {
     ScratchLayout L;
@@ -103,6 +114,8 @@ ScratchLayout scratch_layout(const hsd_model_desc& d) {
     const int R = d.max_rows;
     size_t o = 0;
     L.pages = o; o += align_up((size_t)(d.max_seq / HSD_KV_PAGE) * 4, 256);
+    L.batch_pages = o; o += align_up((size_t)(d.max_seq / HSD_KV_PAGE) * 4, 256);
+    L.batch_pos0 = o; o += align_up((size_t)HSD_MAX_PASS_ROWS * 4, 256);
     L.ss = o;    o += align_up((size_t)2 * SS_SLOTS * HSD_MAX_PASS_ROWS * 8, 256);
     L.tickets = o; o += align_up(ticket_count(d) * 4, 256);
     L.x = o;     o += align_up((size_t)R * d.d * 4, 256);
@@ -111,7 +124,7 @@ ScratchLayout scratch_layout(const hsd_model_desc& d) {
     L.q = o;     o += align_up((size_t)R * d.n_q * d.hd * es, 256);
     L.att = o;   o += align_up((size_t)R * d.n_q * d.hd * es, 256);
     L.h = o;     o += align_up((size_t)R * d.ffn * es, 256);
-    L.attn = o;  o += attn_workspace_bytes(1, R, d.n_q, d.n_kv, d.hd, d.max_seq);
+    L.attn = o;  o += attn_ws_bytes_of(d);
     L.total = o;
     return L;
 }
@@ -154,6 +167,10 @@ extern "C" int hsd_model_create(const hsd_model_desc* desc, void* weights_dev, v
     const ScratchLayout S = scratch_layout(*desc);
     char* sb = (char*)scratch_dev;
     m->pages_dev = (int32_t*)(sb + S.pages);
+    m->batch_pages_dev = (int32_t*)(sb + S.batch_pages);
+    m->batch_pos0_dev = (int32_t*)(sb + S.batch_pos0);
+    m->batch = 0;
+    m->batch_pages_per_seq = 0;
     m->ss[0] = (unsigned long long*)(sb + S.ss);
     m->ss[1] = m->ss[0] + SS_SLOTS * HSD_MAX_PASS_ROWS;
     m->tickets = (int*)(sb + S.tickets);
@@ -173,7 +190,7 @@ extern "C" int hsd_model_create(const hsd_model_desc* desc, void* weights_dev, v
     // Cache rows beyond the valid length are read (and masked) by the attention kernels: keep them finite.
     hipError_t e = hipMemsetAsync(kv_dev, 0, m->kv_layer_bytes * desc->n_layers, m->stream);
     if (e == hipSuccess) e = hipMemsetAsync(m->tickets, 0, ticket_count(*desc) * 4, m->stream);
-    if (e == hipSuccess) e = hipMemsetAsync(m->attn_ws, 0, attn_ticket_bytes(1, desc->n_q, desc->n_kv), m->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(m->attn_ws, 0, attn_ticket_bytes(), m->stream);
     // Padded rows of packed matrices must be zero.
     if (e == hipSuccess) e = hipMemsetAsync(m->head, 0, hsd_packed_bytes(desc->vocab, desc->d, desc->dtype), m->stream);
     std::vector<int32_t> ident(m->max_pages);
@@ -314,9 +331,15 @@ extern "C" int hsd_model_load_head(hsd_model* m, const void* embed_dev, const vo
     return HSD_OK;
 }
 
+// A pass over a batch of sequences: `rows` = batch * m_seq tokens, row r = token r % m_seq of sequence r / m_seq at
+// position pos0_dev[sequence] + r % m_seq; null for one sequence at pos0.
+struct BatchGeom {
+    int batch, m_seq, max_len;
+};
+
 // fp32 storage: plain kernels, one per step (the small correctness configuration).
 static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
-                    float* logits, bool embedded) {
+                    float* logits, bool embedded, const BatchGeom* bg) {
     const hsd_model_desc& d = m->desc;
     hipStream_t s = m->stream;
     const int nq = d.n_q * d.hd, nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
@@ -334,11 +357,21 @@ static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, const 
             SiteTimer t(m, HSD_SITE_QKV);
             if ((rc = launch_gemm_f32((const float*)m->xn, (const float*)L.wqkv, m->part, rows, nqkv, d.d, false, s))) return rc;
         }
-        if ((rc = launch_rope_kv(m->part, 1, rows, m->q, kv_layer, m->pages_dev, pos0, d.n_q, d.n_kv, d.hd, d.rope_base, d.dtype, s))) return rc;
+        if (bg) {
+            if ((rc = launch_rope_kv(m->part, 1, rows, m->q, kv_layer, m->batch_pages_dev, 0, d.n_q, d.n_kv, d.hd, d.rope_base, d.dtype, s,
+                                     m->batch_pos0_dev, bg->m_seq, m->batch_pages_per_seq))) return rc;
+        } else if ((rc = launch_rope_kv(m->part, 1, rows, m->q, kv_layer, m->pages_dev, pos0, d.n_q, d.n_kv, d.hd, d.rope_base, d.dtype, s))) {
+            return rc;
+        }
         {
             SiteTimer t(m, HSD_SITE_ATTN);
-            if ((rc = launch_attention(m->q, kv_layer, m->pages_dev, m->max_pages, nullptr, pos0, 1, rows, pos0 + rows, d.n_q, d.n_kv,
-                                       d.hd, d.dtype, m->att, m->attn_ws, 0, s))) return rc;
+            if (bg)
+                rc = launch_attention(m->q, kv_layer, m->batch_pages_dev, m->batch_pages_per_seq, m->batch_pos0_dev, 0, bg->batch, bg->m_seq,
+                                      bg->max_len, d.n_q, d.n_kv, d.hd, d.dtype, m->att, m->attn_ws, 0, s);
+            else
+                rc = launch_attention(m->q, kv_layer, m->pages_dev, m->max_pages, nullptr, pos0, 1, rows, pos0 + rows, d.n_q, d.n_kv,
+                                      d.hd, d.dtype, m->att, m->attn_ws, 0, s);
+            if (rc) return rc;
         }
         {
             SiteTimer t(m, HSD_SITE_O);
@@ -379,14 +412,14 @@ static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, const 
 // RMSNorm: they store bf16(x * w_norm) into m->xn and add the rows' sums of squares into m->ss[1]
 // (second norm of the layer) or m->ss[0] (first norm of the next layer, or the final norm at the exit);
 // the GEMM that consumes m->xn multiplies by 1/rms in its epilogue.
-static int launch_site_bf16(hsd_model* m, int site, int l, int pos0, int rows, const float* next_norm_w) {
+static int launch_site_bf16(hsd_model* m, int site, int l, int pos0, int rows, const float* next_norm_w, const BatchGeom* bg = nullptr) {
     const hsd_model_desc& d = m->desc;
     hipStream_t s = m->stream;
     const int nq = d.n_q * d.hd, nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
     const LayerWeights& L = m->layers[l];
     bf16_t* kv_layer = (bf16_t*)(m->kv + m->kv_layer_bytes * l);
     // one or two tokens: some projections stream their row-major copies
-    const bool rowk = L.wqkv_rows && rows <= (site == HSD_SITE_QKV ? g_gemv_max_m_qkv : (site == HSD_SITE_O ? g_gemv_max_m_o : g_gemv_max_m_down));
+    const bool rowk = L.wqkv_rows && !bg && rows <= (site == HSD_SITE_QKV ? g_gemv_max_m_qkv : (site == HSD_SITE_O ? g_gemv_max_m_o : g_gemv_max_m_down));
     GemmArgs g = {};
     g.M = rows; g.part = m->part; g.part_bytes = m->part_elems * sizeof(float); g.tickets = m->tickets; g.eps = d.eps;
     switch (site) {
@@ -395,8 +428,12 @@ static int launch_site_bf16(hsd_model* m, int site, int l, int pos0, int rows, c
             g.wp = (const bf16x8*)(rowk ? L.wqkv_rows : L.wqkv); g.N = nqkv; g.K = d.d;
             g.out_bf16 = (bf16_t*)m->q; g.kv_layer = kv_layer; g.pages = m->pages_dev;
             g.pos0 = pos0; g.n_q = d.n_q; g.n_kv = d.n_kv; g.hd = d.hd; g.rope_base = d.rope_base;
+            if (bg) { g.pages = m->batch_pages_dev; g.pos0_arr = m->batch_pos0_dev; g.m_seq = bg->m_seq; g.max_pages = m->batch_pages_per_seq; }
             return rowk ? launch_gemv_bf16(g, EPI_ROPE, s) : launch_gemm_bf16(g, EPI_ROPE, gemm_plan(rows, nqkv, d.d, EPI_ROPE), s);
         case HSD_SITE_ATTN:
+            if (bg)
+                return launch_attention(m->q, kv_layer, m->batch_pages_dev, m->batch_pages_per_seq, m->batch_pos0_dev, 0, bg->batch,
+                                        bg->m_seq, bg->max_len, d.n_q, d.n_kv, d.hd, d.dtype, m->att, m->attn_ws, 0, s);
             return launch_attention(m->q, kv_layer, m->pages_dev, m->max_pages, nullptr, pos0, 1, rows, pos0 + rows, d.n_q, d.n_kv,
                                     d.hd, d.dtype, m->att, m->attn_ws, 0, s);
         case HSD_SITE_O:
@@ -430,7 +467,7 @@ static int launch_head_bf16(hsd_model* m, const void* xn, int rows, int n_logit_
 }
 
 static int pass_bf16(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
-                     float* logits, bool embedded) {
+                     float* logits, bool embedded, const BatchGeom* bg) {
     const hsd_model_desc& d = m->desc;
     const int exit_layer = exits[n_exits - 1];
     const size_t logit_stride = (size_t)n_logit_rows * d.vocab;
@@ -443,7 +480,7 @@ static int pass_bf16(hsd_model* m, const int32_t* tok, int pos0, int rows, const
         const float* next_norm = l + 1 == exit_layer ? m->norm_f : m->layers[l + 1].norm1;
         for (int site = HSD_SITE_QKV; site <= HSD_SITE_DOWN; ++site) {
             SiteTimer t(m, site);
-            if ((rc = launch_site_bf16(m, site, l, pos0, rows, next_norm))) return rc;
+            if ((rc = launch_site_bf16(m, site, l, pos0, rows, next_norm, bg))) return rc;
         }
         if (l + 1 == exits[ei] && l + 1 < exit_layer) {
             // an exit on the way: m->xn holds x scaled by the next layer's norm weights, the head needs the final
@@ -513,7 +550,7 @@ extern "C" int hsd_site_kernel(const hsd_model* m, int site, int rows, char* nam
 
 // One pass: rows tokens at positions pos0.., layers [0, exit_layer), logits of the last n_logit_rows rows.
 static int pass_checked(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
-                        float* logits, bool embedded);
+                        float* logits, bool embedded, const BatchGeom* bg = nullptr);
 
 // embedded: row 0 of the residual stream (and, bf16, of the normalised input and the sums of squares) already holds
 // the one token of this pass, left there by the fused sampler (EmbedNext); only for rows == 1.
@@ -534,7 +571,7 @@ EmbedNext embed_next_of(const hsd_model* m) {
 }
 
 static int pass_checked(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
-                        float* logits, bool embedded) {
+                        float* logits, bool embedded, const BatchGeom* bg) {
     const hsd_model_desc& d = m->desc;
     if (!exits || n_exits < 1 || n_exits > d.n_layers) HSD_FAIL(HSD_EINVAL, "pass: %d exits", n_exits);
     for (int i = 0; i < n_exits; ++i)
@@ -544,15 +581,61 @@ static int pass_checked(hsd_model* m, const int32_t* tok, int pos0, int rows, co
     if (n_exits > 1 && d.dtype == HSD_BF16 && d.ffn < d.d)
         HSD_FAIL(HSD_ECAPACITY, "pass: several exits need ffn >= d for the exit rows (ffn=%d d=%d)", d.ffn, d.d);
     if (rows < 1 || rows > d.max_rows) HSD_FAIL(HSD_ECAPACITY, "pass: %d rows, model allows 1..%d", rows, d.max_rows);
-    if (pos0 < 0 || pos0 + rows > d.max_seq) HSD_FAIL(HSD_ECAPACITY, "pass: positions %d..%d exceed the KV capacity %d", pos0, pos0 + rows - 1, d.max_seq);
+    if (!bg && (pos0 < 0 || pos0 + rows > d.max_seq)) HSD_FAIL(HSD_ECAPACITY, "pass: positions %d..%d exceed the KV capacity %d", pos0, pos0 + rows - 1, d.max_seq);
     if (n_logit_rows < 0 || n_logit_rows > rows) HSD_FAIL(HSD_EINVAL, "pass: %d logit rows of %d", n_logit_rows, rows);
     if (n_logit_rows > 0 && !logits) HSD_FAIL(HSD_EINVAL, "pass: logits buffer missing");
     if (!m->head_loaded) HSD_FAIL(HSD_ESTATE, "pass: embedding / head not loaded");
     for (int l = 0; l < exit_layer; ++l)
         if (!m->layer_loaded[l]) HSD_FAIL(HSD_ESTATE, "pass: layer %d not loaded", l);
     ++m->pass_serial;
-    return d.dtype == HSD_BF16 ? pass_bf16(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits, embedded)
-                               : pass_f32(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits, embedded);
+    return d.dtype == HSD_BF16 ? pass_bf16(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits, embedded, bg)
+                               : pass_f32(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits, embedded, bg);
+}
+
+// ---- batch of sequences ------------------------------------------------------------------------------------------
+extern "C" int hsd_model_set_batch(hsd_model* m, int batch, int pages_per_seq, const int32_t* page_table) {
+    if (!m) HSD_FAIL(HSD_EINVAL, "hsd_model_set_batch: null pointer");
+    if (batch == 0) {                                    // back to one sequence
+        m->batch = 0;
+        m->batch_pages_per_seq = 0;
+        return HSD_OK;
+    }
+    if (!page_table) HSD_FAIL(HSD_EINVAL, "hsd_model_set_batch: null page table");
+    if (batch < 1 || batch > m->desc.max_rows) HSD_FAIL(HSD_ECAPACITY, "hsd_model_set_batch: batch %d outside 1..%d (max_rows)", batch, m->desc.max_rows);
+    if (pages_per_seq < 1 || (long long)batch * pages_per_seq > m->max_pages)
+        HSD_FAIL(HSD_ECAPACITY, "hsd_model_set_batch: %d sequences x %d pages exceed the model's %d KV pages", batch, pages_per_seq, m->max_pages);
+    std::vector<char> seen(m->max_pages, 0);
+    for (int i = 0; i < batch * pages_per_seq; ++i) {
+        if (page_table[i] < 0 || page_table[i] >= m->max_pages || seen[page_table[i]])
+            HSD_FAIL(HSD_EINVAL, "hsd_model_set_batch: entry %d (=%d) is outside 0..%d or used twice", i, page_table[i], m->max_pages - 1);
+        seen[page_table[i]] = 1;
+    }
+    HSD_HIP(hipMemcpyAsync(m->batch_pages_dev, page_table, (size_t)batch * pages_per_seq * 4, hipMemcpyHostToDevice, m->stream));
+    HSD_HIP(hipStreamSynchronize(m->stream));
+    m->batch = batch;
+    m->batch_pages_per_seq = pages_per_seq;
+    return HSD_OK;
+}
+
+extern "C" int hsd_model_pass_batch(hsd_model* m, const int32_t* tokens_dev, const int32_t* pos0, int tokens_per_seq, int exit_layer,
+                                    int with_logits, float* logits_dev) {
+    if (!m || !tokens_dev || !pos0) HSD_FAIL(HSD_EINVAL, "hsd_model_pass_batch: null pointer");
+    if (m->batch < 1) HSD_FAIL(HSD_ESTATE, "hsd_model_pass_batch: no batch geometry (call hsd_model_set_batch first)");
+    const int rows = m->batch * tokens_per_seq;
+    if (tokens_per_seq < 1 || rows > m->desc.max_rows)
+        HSD_FAIL(HSD_ECAPACITY, "hsd_model_pass_batch: %d sequences x %d tokens exceed the %d rows of a pass", m->batch, tokens_per_seq, m->desc.max_rows);
+    const int cap = m->batch_pages_per_seq * HSD_KV_PAGE;
+    int max_len = 0;
+    for (int b = 0; b < m->batch; ++b) {
+        if (pos0[b] < 0 || pos0[b] + tokens_per_seq > cap)
+            HSD_FAIL(HSD_ECAPACITY, "hsd_model_pass_batch: sequence %d at positions %d..%d exceeds its %d cache positions", b, pos0[b],
+                     pos0[b] + tokens_per_seq - 1, cap);
+        max_len = std::max(max_len, pos0[b] + tokens_per_seq);
+    }
+    // pageable host memory: the runtime has staged the copy when the call returns, the caller's array is free again
+    HSD_HIP(hipMemcpyAsync(m->batch_pos0_dev, pos0, (size_t)m->batch * 4, hipMemcpyHostToDevice, m->stream));
+    const BatchGeom bg{m->batch, tokens_per_seq, max_len};
+    return pass_checked(m, tokens_dev, 0, rows, &exit_layer, 1, with_logits ? rows : 0, logits_dev, false, &bg);
 }
 
 extern "C" int hsd_model_pass(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows, int exit_layer, int n_logit_rows,

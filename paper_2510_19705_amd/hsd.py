@@ -62,6 +62,8 @@ _SIGS = {
     "hsd_model_load_head": (_i, [_vp, _vp, _vp, _vp]),
     "hsd_model_set_pages": (_i, [_vp, C.POINTER(C.c_int32), _i]),
     "hsd_model_pass": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
+    "hsd_model_set_batch": (_i, [_vp, _i, _i, C.POINTER(C.c_int32)]),
+    "hsd_model_pass_batch": (_i, [_vp, _vp, C.POINTER(C.c_int32), _i, _i, _i, _vp]),
     "hsd_hier_set_ablation": (_i, [_vp, C.POINTER(C.c_float), _i]),
     "hsd_hier_set_distilled": (_i, [_vp, _i, _i, _f]),
     "hsd_stats_cost": (C.c_double, [C.POINTER(Stats), _i, C.POINTER(C.c_double)]),
@@ -240,6 +242,26 @@ class Model:
         _check(lib.hsd_model_pass(self.handle, tokens_dev.data_ptr(), pos0, tokens_dev.numel(), exit_layer, n_logit_rows,
                                   logits.data_ptr()))
         return logits[:n_logit_rows]
+
+    def set_batch(self, batch, pages_per_seq=0, page_table=None):
+        """hsd_model_set_batch; page_table: [batch, pages_per_seq] ints (default: consecutive pages per sequence)."""
+        if batch == 0:
+            _check(lib.hsd_model_set_batch(self.handle, 0, 0, None))
+            return
+        if page_table is None:
+            page_table = np.arange(batch * pages_per_seq, dtype=np.int32)
+        a, p = _i32(np.asarray(page_table).reshape(-1))
+        _check(lib.hsd_model_set_batch(self.handle, batch, pages_per_seq, p))
+
+    def model_pass_batch(self, tokens_dev, pos0, exit_layer, with_logits=True):
+        """hsd_model_pass_batch; tokens_dev: int32 cuda tensor [batch, m]; pos0: host ints [batch].
+        Returns fp32 logits [batch, m, vocab] (None without logits)."""
+        batch, m = tokens_dev.shape
+        a, p = _i32(pos0)
+        logits = torch.empty((batch, m, self.desc.vocab), dtype=torch.float32, device="cuda") if with_logits else None
+        _check(lib.hsd_model_pass_batch(self.handle, tokens_dev.contiguous().data_ptr(), p, m, exit_layer, int(with_logits),
+                                        logits.data_ptr() if with_logits else None))
+        return logits
 
     def model_pass_exits(self, tokens_dev, pos0, exits, n_logit_rows):
         """hsd_model_pass_exits.  Returns fp32 logits [len(exits), n_logit_rows, vocab]."""

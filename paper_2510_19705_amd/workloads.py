@@ -304,6 +304,28 @@ def microbench():
                 log(cell)
             del cache
             torch.cuda.empty_cache()
+    # the same cells as ONE fused layer of the model (hsd_model_pass_batch: q/k/v + RoPE + KV append, attention,
+    # o + residual, gate/up + SwiGLU, down + residual over the batch's rows), where batch x k fits the 64 rows of a pass
+    fused = []
+    one = dict(shape, n_layers=1)
+    for B in (1, 8, 64):
+        for S in (4096, 16384, 32768):
+            pps = (S + 64) // 64
+            model = random_model(hsd, inputs, torch, one, 3, B * pps * 64)
+            model.set_batch(B, pps)
+            for k in (1, 2, 4, 8, 16):
+                if B * k > 64:
+                    continue
+                tk = torch.randint(0, one["vocab"], (B, k), device="cuda", dtype=torch.int32)
+                us = _time(torch, lambda: model.model_pass_batch(tk, [S - k] * B, 1, with_logits=False), 10 if B * S > 500000 else 30)
+                kv_bytes = 2 * S * n_kv * hd * 2 * B
+                cell = {"batch": B, "kv_len": S, "k": k, "fused_layer_us": us,
+                        "layer_hbm_frac": (sum(site_mb.values()) * 1e6 + kv_bytes) / us / 1e3 / HBM_PEAK_GBS}
+                fused.append(cell)
+                log(cell)
+            model.close()
+            del model
+            torch.cuda.empty_cache()
     # sampler at the largest vocabulary (two launches: softmax, then accept / resample)
     sampler = []
     V = 128256
@@ -326,7 +348,7 @@ def microbench():
             sampler.append({"vocab": V, "sigma": sigma, "t": t, "softmax_plus_accept_us": _time(torch, both, 50)})
             log(sampler[-1])
     return {"config": "microbench", "projections_us_by_rows": gemm, "projections_many_rows": gemm_many, "weight_MB": site_mb,
-            "cells": cells, "sampler": sampler}
+            "cells": cells, "fused_layer_cells": fused, "sampler": sampler}
 
 
 def site_bytes(shape, site, m, ctx=0):

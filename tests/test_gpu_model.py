@@ -176,3 +176,61 @@ def test_pass_rejects_bad_arguments():
     with pytest.raises(hsd.HsdError):
         model.set_pages([0, 0])
     model.close()
+
+
+@pytest.mark.parametrize("name,shape,bf16,batch,m", [
+    ("f32_3x4", SMALL_F32, False, 3, 4), ("f32_9x1", SMALL_F32, False, 9, 1),
+    ("bf16_gqa_5x4", SMALL_BF16, True, 5, 4), ("bf16_gqa_16x4", SMALL_BF16, True, 16, 4), ("bf16_gqa_64x1", SMALL_BF16, True, 64, 1),
+    ("bf16_mha_8x8", SMALL_BF16_MHA, True, 8, 8),
+])
+def test_pass_batch_matches_the_oracle_per_sequence(name, shape, bf16, batch, m):
+    """A batch of sequences through hsd_model_pass_batch (per-sequence positions and page tables in the RoPE / KV
+    append epilogue and in the attention; residual, SwiGLU, norms and head by row): sequences of different lengths,
+    pages dealt out in a random order; the verify pass of m tokens per sequence against the oracle run on each
+    sequence by itself, every logit.  fp32 1e-4 relative, bf16 2e-2 absolute."""
+    import torch
+    w = inputs.make_weights(shape, seed=61, bf16=bf16)
+    L = shape["n_layers"]
+    chunk = 64 // batch if 64 // batch >= 1 else 1
+    chunk = max(1, min(chunk, 8))
+    lens = [2 * chunk + (b * 3) % (chunk + 1) for b in range(batch)]        # cached positions before the verify pass
+    pages_per_seq = (max(lens) + m + 63) // 64
+    max_seq = ((batch * pages_per_seq + 1) * 64)
+    rng = np.random.default_rng(7)
+    toks = rng.integers(0, shape["vocab"], size=(batch, max(lens) + m), dtype=np.int32)
+    model = gpu_model(shape, w, bf16, max_seq=max_seq, max_rows=64)
+    table = rng.permutation(max_seq // 64)[:batch * pages_per_seq].reshape(batch, pages_per_seq)
+    model.set_batch(batch, pages_per_seq, table)
+    td = _tokens_dev(toks)
+    # prefill: two passes of `chunk` tokens per sequence, then one whose start differs per sequence (tokens fed twice
+    # rewrite the same K/V), so that the sequences end at different lengths
+    for start in ([0] * batch, [chunk] * batch, [l - chunk for l in lens]):
+        idx = torch.tensor([[s + i for i in range(chunk)] for s in start], device="cuda")
+        model.model_pass_batch(torch.gather(td, 1, idx).contiguous(), start, L, with_logits=False)
+    idx = torch.tensor([[l + i for i in range(m)] for l in lens], device="cuda")
+    got = model.model_pass_batch(torch.gather(td, 1, idx).contiguous(), lens, L).cpu().numpy()
+    oracle = oracle_decoder(shape, w, max(lens) + m + 1)
+    worst = 0.0
+    for b in range(batch):
+        oracle.reset()
+        ref = oracle.forward([int(t) for t in toks[b, :lens[b] + m]], 0, L)[lens[b]:]
+        err = np.abs(got[b] - ref).max()
+        err = err if bf16 else err / np.abs(ref).max()
+        worst = max(worst, err)
+        assert err < (2e-2 if bf16 else 1e-4), (name, b, err)
+    say("batch pass", name, "lengths", lens[:6], "worst err %.2e" % worst)
+    # an early exit of the same batch, and the error paths
+    got2 = model.model_pass_batch(torch.gather(td, 1, idx).contiguous(), lens, 1).cpu().numpy()
+    oracle.reset()
+    ref2 = oracle.forward([int(t) for t in toks[0, :lens[0] + m]], 0, 1)[lens[0]:]
+    e2 = np.abs(got2[0] - ref2).max()
+    assert (e2 if bf16 else e2 / np.abs(ref2).max()) < (2e-2 if bf16 else 1e-4)
+    from paper_2510_19705_amd import hsd
+    with pytest.raises(hsd.HsdError):
+        model.model_pass_batch(td[:, :m].contiguous(), [pages_per_seq * 64 - m + 1] * batch, L)     # beyond a sequence's pages
+    with pytest.raises(hsd.HsdError):
+        model.set_batch(batch, pages_per_seq, np.zeros((batch, pages_per_seq), dtype=np.int32))        # a page used twice
+    model.set_batch(0)
+    with pytest.raises(hsd.HsdError):
+        model.model_pass_batch(td[:, :m].contiguous(), lens, L)                                        # no geometry
+    model.close()
