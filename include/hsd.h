@@ -110,33 +110,6 @@ int hsd_model_pass_batch(hsd_model*, const int32_t* tokens_dev, const int32_t* p
 int hsd_model_pass_exits(hsd_model*, const int32_t* tokens_dev, int pos0, int m, const int* exits, int n_exits,
                          int n_logit_rows, float* logits_dev);
 
-/* Per-site device timing of a model's passes, for roofline accounting.  Between begin and end every
- * launch at the sites below is bracketed by two events on the model's stream (up to max_launches
- * launches, later ones are not timed; the brackets add a little host and device overhead, so throughput
- * is measured without them).  end synchronises the stream and returns launches and total
- * milliseconds per site (raw: subtract launches * empty_bracket_ms for the kernels alone). */
-enum { HSD_SITE_QKV = 0, HSD_SITE_ATTN = 1, HSD_SITE_O = 2, HSD_SITE_GATEUP = 3, HSD_SITE_DOWN = 4, HSD_SITE_HEAD = 5,
-       HSD_N_SITES = 6 };
-typedef struct {
-    int64_t launches[HSD_N_SITES];
-    double ms[HSD_N_SITES];
-    double empty_bracket_ms; /* mean time between the two events of a bracket with nothing inside, measured by
-                                hsd_profile_end on the same stream: what a bracket adds to the launch it times */
-} hsd_site_times;
-int hsd_profile_begin(hsd_model*, int max_launches);
-int hsd_profile_end(hsd_model*, hsd_site_times* out);
-/* Mean duration, in microseconds, of one launch of a layer site (bf16 models; HSD_SITE_QKV .. HSD_SITE_DOWN) in the
- * configuration a pass of `rows` tokens at position pos0 uses: `iters` launches
- * back to back between two events on the model's stream, cycling through the layers so that every launch streams
- * different weights.  Inputs are whatever the last pass left in the activation buffers; the residual stream and the KV
- * rows at pos0.. are overwritten, so run a pass before trusting the model's state again. */
-int hsd_measure_site(hsd_model*, int site, int rows, int pos0, int iters, double* us_out);
-
-/* Name of the kernel instance (as a profiler prints it, e.g. "gemm_bf16_kernel<2, 1, 2, true>") that a pass of
- * `rows` tokens launches at a projection site (HSD_SITE_QKV, _O, _GATEUP, _DOWN, _HEAD) of a bf16 model, in layers
- * without row-major copies: lets a measurement be matched with a profile of the same kernel. */
-int hsd_site_kernel(const hsd_model*, int site, int rows, char* name_out, int cap);
-
 /* ---------------------------------------------------------------------------------------------
  * Stand-alone kernels of the path (each is what the pass / the driver launches internally).
  * ------------------------------------------------------------------------------------------- */
@@ -258,27 +231,6 @@ size_t hsd_gemm_workspace_bytes(int m, int n, int k);
 int hsd_pack_weight(const void* w_dev, void* packed_dev, int n, int k, int dtype, int layout, void* stream);
 int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int n, int k, int dtype, int layout,
              void* workspace_dev, void* stream);
-
-/* Overrides of the GEMM launch heuristics, for tuning sweeps (process-wide; 0 restores the heuristic).
- * key 0..3 = epilogue kind (store, residual, SwiGLU, RoPE) of the tiled kernel: nt column tiles per
- * workgroup, ksplit workgroups along K (waves is ignored: workgroups have 8 waves).  key 100: most tokens of a pass
- * that a projection serves from its row-major copy with the row kernel before the MFMA kernel takes over: nt for the
- * attention output (default 1), ksplit for the FFN down projection (default 2), waves for q/k/v (default 0: never).  key 101: nt = most query rows per KV head
- * (tokens x query heads per KV head) for which the MFMA attention gives each workgroup one 16-row tile; above
- * it, two.  key 102: nt = K/V steps per wave the attention plans for when it splits a sequence over workgroups
- * (0: default, which also caps the split at about 160 workgroups).  key 103: nt = largest vocabulary the driver
- * hands to the fused softmax + verify launch (default 32768, its limit); smaller values exercise the two-launch
- * path hsd_softmax + hsd_accept_resample on small vocabularies.  key 104: nt = 0 stops the driver's fused sampler
- * from embedding the token it emits for the one-token pass that follows (default 1; same results either way).
- * key 105: nt = 0 makes the driver synchronise the stream after each Verify instead of polling the sampler's
- * sequence number in pinned host memory (default 1; same results either way).  key 106: nt = fewest rows of an
- * hsd_gemm call (above HSD_MAX_PASS_ROWS) that the kernel tiled for the matrix cores serves; calls with fewer rows
- * stream the weights once per 64 rows (0: default, every call above HSD_MAX_PASS_ROWS rows).  key 107: nt = 128 or 256
- * fixes the columns per workgroup of that kernel (0: default, 256 unless that leaves half the CUs without a workgroup).
- * key 108: nt = most column groups of a residual or RoPE projection that still get two workgroups per group, each owning
- * half of the columns of its tiles, for passes of few rows (default 128; 0 switches the scheme off; the results differ
- * by the rounding of a different summation order at most). */
-int hsd_tune(int key, int nt, int ksplit, int waves);
 
 /* ---------------------------------------------------------------------------------------------
  * Hierarchy M_0..M_K with parameters T_0..T_{K-1} (Alg. 1).  Level 0 drafts autoregressively,

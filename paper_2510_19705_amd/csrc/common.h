@@ -5,7 +5,7 @@
 #include <stdio.h>
 #include <stdarg.h>
 
-#include "../../include/hsd.h"
+#include "../../include/hsd_dev.h"
 
 typedef __bf16 bf16_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -136,24 +136,17 @@ struct GemmPlan {
     int ksplit;   // workgroups along K per column group
     int waves;    // waves per workgroup; they split the workgroup's K slice
     int halves;   // 1: two workgroups per column group, each owning 8 of the 16 columns of its tiles (ksplit = 1 only)
+    int deep;     // 1 / -1: the deeper / shallower load batches whatever K; 0: by K
 };
-GemmPlan gemm_plan(int m, int n, int k, int epi);
+const hsd_kernel_tuning& default_kernel_tuning();
+const hsd_driver_tuning& default_driver_tuning();
+GemmPlan gemm_plan(int m, int n, int k, int epi, const hsd_kernel_tuning& t = default_kernel_tuning());
 size_t gemm_part_bytes(int m, int n, int k, int epi);
-void gemm_tune(int epilogue, int nt, int ksplit, int waves);
 int launch_gemm_bf16(const GemmArgs& g, int epi, const GemmPlan& p, hipStream_t s);   // W in MFMA tiles
 void gemm_kernel_name(int m, int k, int epi, const GemmPlan& p, char* out, size_t cap);
-extern int g_gemv_max_m_qkv, g_gemv_max_m_o, g_gemv_max_m_down;
-extern int g_attn_qt1_rows;
-extern int g_attn_steps_per_wave;
-extern int g_attn_target_wgs;
-extern int g_attn_fused_merge;
-extern int g_fused_sampler_max_v;
-extern int g_preembed;
-extern int g_poll_mailbox;
 int launch_gemv_bf16(const GemmArgs& g, int epi, hipStream_t s);   // row-major W: EPI_STORE, EPI_RESID, EPI_ROPE
 // more than 64 rows, W in MFMA tiles, plain store (kernels_gemm_wide.hip)
-int launch_gemm_wide_bf16(const bf16_t* a, const bf16x8* wp, float* out, int m, int n, int k, hipStream_t s);
-extern int g_wide_cols;
+int launch_gemm_wide_bf16(const bf16_t* a, const bf16x8* wp, float* out, int m, int n, int k, int wide_cols, hipStream_t s);
 int launch_gemm_f32(const float* x, const float* w, float* out, int m, int n, int k, bool swiglu, hipStream_t s);
 // interleave: 0 plain rows at row_offset, 1 / 2 gate / up of a fused SwiGLU matrix, 3 attention heads of hd rows
 // with each 16-dim block followed by the block of its RoPE partners, 4 heads with each dim followed by its partner.

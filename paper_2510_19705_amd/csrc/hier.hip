@@ -62,6 +62,7 @@ struct hsd_hier {
     float coin[HSD_MAX_LEVELS];   // >= 0: fixed acceptance probability at that level's Verify (ablation), < 0: Alg. 2
     bool exactly_T;               // intermediate levels hand up exactly T tokens (ablation)
     bool skip_target_rows;        // set while hsd_generate runs
+    hsd_driver_tuning tuning;     // hsd_hier_set_tuning
     hsd_stats stats;
 };
 
@@ -185,8 +186,8 @@ int draft_step(hsd_hier* h, int row) {
     if (int rc = level_pass(h, 0, start, 1)) return rc;
     float* p = L.rows + (size_t)row * h->V;
     h->pre_model = nullptr;
-    if (softmax_verify_supported(h->V)) {
-        const bool pre = g_preembed != 0;
+    if (softmax_verify_supported(h->V, h->tuning.fused_sampler_max_v)) {
+        const bool pre = h->tuning.preembed != 0;
         if (int rc = launch_softmax_verify(h->logits, nullptr, h->tok_dev + h->len, 0, h->V, h->temperature, h->seed, 0u, L.call++, p,
                                            h->result_dev, h->sampler_scratch, nullptr, pre ? embed_next_of(L.model) : EmbedNext{}, -1.f,
                                            0, h->stream))
@@ -211,7 +212,7 @@ int draft_step(hsd_hier* h, int row) {
 // microseconds after the kernel wrote it, without the wake-up latency of a stream synchronisation, and queues the
 // next pass while the kernel finishes.  Gives up after a while (returns false: the caller synchronises the stream).
 bool wait_mailbox(hsd_hier* h) {
-    if (!g_poll_mailbox) return false;
+    if (!h->tuning.poll_mailbox) return false;
     volatile int32_t* slot = h->mailbox + MAILBOX_SEQ_SLOT;
     const auto t0 = std::chrono::steady_clock::now();
     for (unsigned spins = 0;; ++spins) {
@@ -234,14 +235,14 @@ int verify_step(hsd_hier* h, int idx, int t, const float* q_dev, int* n_out) {
     float* p = L.rows + (size_t)L.count * h->V;
     // Nobody verifies the target's tokens, so inside hsd_generate its rows p_1..p_{n+1} need not be stored (the
     // fused kernel keeps each row in registers); single calls (hsd_verify, hsd_run) always return them.
-    float* p_store = h->skip_target_rows && idx == h->K && softmax_verify_supported(h->V) ? nullptr : p;
+    float* p_store = h->skip_target_rows && idx == h->K && softmax_verify_supported(h->V, h->tuning.fused_sampler_max_v) ? nullptr : p;
     h->pre_model = nullptr;
     hsd_model* m0 = h->lv[0].model;
     bool pre = false, polled = false;
-    if (softmax_verify_supported(h->V)) {
+    if (softmax_verify_supported(h->V, h->tuning.fused_sampler_max_v)) {
         // one launch; the kernel writes n, m and the surviving tokens straight into the pinned mailbox, and leaves m
         // embedded in level 0's model, whose next draft pass is that one token
-        pre = g_preembed != 0;
+        pre = h->tuning.preembed != 0;
         if (int rc = launch_softmax_verify(h->logits, q_dev, h->tok_dev + ctx_end, t, h->V, h->temperature, h->seed, (uint32_t)idx,
                                            L.call++, p_store, h->result_dev, h->sampler_scratch, h->mailbox_dev,
                                            pre ? embed_next_of(m0) : EmbedNext{}, h->coin[idx], ++h->mailbox_seq, h->stream))
@@ -376,6 +377,7 @@ extern "C" int hsd_hier_create(int n_levels, const hsd_level* levels, const int*
     h->pre_model = nullptr;
     h->exactly_T = false;
     h->skip_target_rows = false;
+    h->tuning = default_driver_tuning();
     for (int i = 0; i < HSD_MAX_LEVELS; ++i) h->coin[i] = -1.f;
     reset_counters(h);
     hipError_t e = hipHostMalloc((void**)&h->mailbox, 68 * sizeof(int32_t), hipHostMallocMapped);
@@ -410,6 +412,13 @@ extern "C" int hsd_hier_set_distilled(hsd_hier* h, int level, int source_level, 
     if (!(noise_std >= 0.f)) HSD_FAIL(HSD_EINVAL, "hsd_hier_set_distilled: noise_std %g", noise_std);
     h->lv[level].distill_src = source_level;
     h->lv[level].distill_std = noise_std;
+    return HSD_OK;
+}
+
+extern "C" int hsd_hier_set_tuning(hsd_hier* h, const hsd_driver_tuning* t) {
+    if (!h) HSD_FAIL(HSD_EINVAL, "hsd_hier_set_tuning: null pointer");
+    h->tuning = t ? *t : default_driver_tuning();
+    h->pre_model = nullptr;
     return HSD_OK;
 }
 

@@ -447,20 +447,14 @@ struct AttnPlan {
     bool fused_merge;     // the kernel's last split to arrive merges (no second launch)
 };
 
-// Up to this many query rows per KV head, one 16-row tile per workgroup (more workgroups, each re-reading the
-// head's K/V from L2, instead of more tiles per workgroup): measured faster at every pass size up to 64 tokens and
-// contexts up to 4096 (two tiles per workgroup double the registers and halve what is in flight).  Beyond it two
-// tiles per workgroup; a tuning knob (hsd_tune key 101).
-int g_attn_qt1_rows = 1 << 30;
-int g_attn_steps_per_wave = 0;      // tuning override (hsd_tune key 102); 0: the default below
-
-int g_attn_target_wgs = 256;
-int g_attn_fused_merge = 1;          // tuning override (hsd_tune key 110): 0 always merges in a second launch        // tuning override (hsd_tune key 109): workgroups a split launch aims for
-
-AttnPlan attn_plan(int batch, int m, int n_q, int n_kv, int hd, int max_len, bool mfma) {
+// Query tiles: up to attn_qt1_rows query rows per KV head every workgroup takes one 16-row tile (more workgroups, each
+// re-reading the head's K/V from L2, instead of more tiles per workgroup): measured faster at every pass size up to
+// 64 tokens and contexts up to 4096 (two tiles per workgroup double the registers and halve what is in flight), so
+// the default never takes two.
+AttnPlan attn_plan(int batch, int m, int n_q, int n_kv, int hd, int max_len, bool mfma, const hsd_kernel_tuning& t) {
     AttnPlan p;
     const int R = m * (n_q / n_kv);
-    p.qt = R <= 16 || R <= g_attn_qt1_rows ? 1 : 2;
+    p.qt = R <= 16 || R <= t.attn_qt1_rows ? 1 : 2;
     p.qgroups = ceil_div(R, 16 * p.qt);
     p.rpad = p.qgroups * p.qt * 16;
     int total_steps = ceil_div(max_len, 32);
@@ -476,10 +470,10 @@ AttnPlan attn_plan(int batch, int m, int n_q, int n_kv, int hd, int max_len, boo
         // them, evenly loaded), each keeping at least 4 steps.
         const int heads = batch * n_kv * p.qgroups;
         int want = 1;
-        if (g_attn_steps_per_wave > 0) {
-            want = ceil_div(total_steps, p.nw * g_attn_steps_per_wave);
+        if (t.attn_steps_per_wave > 0) {
+            want = ceil_div(total_steps, p.nw * t.attn_steps_per_wave);
         } else if (total_steps > 24) {
-            want = (g_attn_target_wgs + heads / 2) / heads;
+            want = ((t.attn_target_wgs > 0 ? t.attn_target_wgs : 256) + heads / 2) / heads;
             if (want > total_steps / 4) want = total_steps / 4;
         }
         want = std::min(want, attn_max_splits(batch, m, n_q, n_kv));
@@ -489,7 +483,7 @@ AttnPlan attn_plan(int batch, int m, int n_q, int n_kv, int hd, int max_len, boo
         // few splits of very few rows (7B shape, context 4096, 8 splits; microseconds, merged by the last arriver /
         // by a second launch: 1 row 18.3 / 19.3, 4 rows 18.5 / 19.5, 8 rows 20.1 / 19.6, 16 rows 23.4 / 20.1): the
         // last arriver's serial tail (acknowledged stores, ticket, two rounds of loads) grows with the rows
-        p.fused_merge = g_attn_fused_merge && p.nsplit > 1 && p.nsplit <= ATTN_FUSED_MAX_SPLITS && p.nsplit * R <= 32 &&
+        p.fused_merge = t.attn_fused_merge && p.nsplit > 1 && p.nsplit <= ATTN_FUSED_MAX_SPLITS && p.nsplit * R <= 32 &&
                         (size_t)heads * sizeof(int) <= ATTN_TICKET_BYTES;
         return p;
     }
@@ -529,11 +523,11 @@ size_t attn_workspace_bytes(int batch, int m, int n_q, int n_kv, int hd, int max
 
 int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, int max_pages, const int32_t* pos0_dev,
                      int pos0_all, int batch, int m, int max_len, int n_q, int n_kv, int hd, int dtype, void* att, float* workspace,
-                     int force_simple, hipStream_t s) {
+                     int force_simple, hipStream_t s, const hsd_kernel_tuning& t) {
     if (n_q % n_kv != 0) HSD_FAIL(HSD_EINVAL, "attention: n_q=%d not a multiple of n_kv=%d", n_q, n_kv);
     if (hd % 32 != 0 || hd > 256) HSD_FAIL(HSD_EINVAL, "attention: head dim %d must be a multiple of 32, at most 256", hd);
     const bool mfma = dtype == HSD_BF16 && !force_simple && (hd == 64 || hd == 128);
-    AttnPlan p = attn_plan(batch, m, n_q, n_kv, hd, max_len, mfma);
+    AttnPlan p = attn_plan(batch, m, n_q, n_kv, hd, max_len, mfma, t);
     const int R = m * (n_q / n_kv);
     int* tickets = (int*)workspace;
     float* part_o = (float*)((char*)workspace + attn_ticket_bytes());
@@ -637,12 +631,26 @@ extern "C" int hsd_kv_write(void* kv_layer_dev, const int32_t* pages_dev, int ma
     return HSD_OK;
 }
 
+static int attention_entry(const void* q_dev, const void* kv_layer_dev, const int32_t* pages_dev, int max_pages,
+                           const int32_t* pos0_dev, int batch, int m, int max_len, int n_q, int n_kv, int hd, int dtype,
+                           void* att_dev, void* workspace_dev, void* stream, const hsd_kernel_tuning& t, const char* who) {
+    if (!q_dev || !kv_layer_dev || !pages_dev || !pos0_dev || !att_dev || !workspace_dev) HSD_FAIL(HSD_EINVAL, "%s: null pointer", who);
+    if (int rc = check_attn_args(batch, m, n_q, n_kv, hd, dtype)) return rc;
+    if (max_len < m || max_len > max_pages * HSD_KV_PAGE) HSD_FAIL(HSD_EINVAL, "%s: max_len=%d outside %d..%d", who, max_len, m, max_pages * HSD_KV_PAGE);
+    return launch_attention(q_dev, kv_layer_dev, pages_dev, max_pages, pos0_dev, 0, batch, m, max_len, n_q, n_kv, hd, dtype, att_dev,
+                            (float*)workspace_dev, 0, (hipStream_t)stream, t);
+}
+
 extern "C" int hsd_attention(const void* q_dev, const void* kv_layer_dev, const int32_t* pages_dev, int max_pages,
                              const int32_t* pos0_dev, int batch, int m, int max_len, int n_q, int n_kv, int hd, int dtype,
                              void* att_dev, void* workspace_dev, void* stream) {
-    if (!q_dev || !kv_layer_dev || !pages_dev || !pos0_dev || !att_dev || !workspace_dev) HSD_FAIL(HSD_EINVAL, "hsd_attention: null pointer");
-    if (int rc = check_attn_args(batch, m, n_q, n_kv, hd, dtype)) return rc;
-    if (max_len < m || max_len > max_pages * HSD_KV_PAGE) HSD_FAIL(HSD_EINVAL, "hsd_attention: max_len=%d outside %d..%d", max_len, m, max_pages * HSD_KV_PAGE);
-    return launch_attention(q_dev, kv_layer_dev, pages_dev, max_pages, pos0_dev, 0, batch, m, max_len, n_q, n_kv, hd, dtype, att_dev,
-                            (float*)workspace_dev, 0, (hipStream_t)stream);
+    return attention_entry(q_dev, kv_layer_dev, pages_dev, max_pages, pos0_dev, batch, m, max_len, n_q, n_kv, hd, dtype, att_dev,
+                           workspace_dev, stream, default_kernel_tuning(), "hsd_attention");
+}
+
+extern "C" int hsd_attention_tuned(const void* q_dev, const void* kv_layer_dev, const int32_t* pages_dev, int max_pages,
+                                   const int32_t* pos0_dev, int batch, int m, int max_len, int n_q, int n_kv, int hd, int dtype,
+                                   void* att_dev, void* workspace_dev, void* stream, const hsd_kernel_tuning* t) {
+    return attention_entry(q_dev, kv_layer_dev, pages_dev, max_pages, pos0_dev, batch, m, max_len, n_q, n_kv, hd, dtype, att_dev,
+                           workspace_dev, stream, t ? *t : default_kernel_tuning(), "hsd_attention_tuned");
 }

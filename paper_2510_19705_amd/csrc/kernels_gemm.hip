@@ -555,48 +555,37 @@ __global__ void gemm_f32_kernel(const float* __restrict__ x, const float* __rest
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
-static int g_tune_nt[4] = {0, 0, 0, 0};      // optional overrides per epilogue kind (0 = heuristic)
-static int g_tune_ksplit[4] = {0, 0, 0, 0};
-static int g_tune_deep = 0;                  // hsd_tune key 111: 1 / -1 force the deeper / shallower load batches, 0: the rule
-// Most tokens of a pass that a projection serves from its row-major copy (1B shape, microseconds, row kernel against
-// tile kernel: q/k/v 6.9 / 6.1 at one row, 7.9 / 6.3 at two: the tile kernel with two workgroups per column group
-// always wins; attention output 4.4 / 4.9 and 5.2 / 5.0; FFN down 7.8 / 9.4 and 9.5 / 9.5).
-int g_gemv_max_m_qkv = 0, g_gemv_max_m_o = 1, g_gemv_max_m_down = 2;
-static int g_halves_max_groups = 128;   // residual / RoPE projections of at most this many column groups: two workgroups per group (hsd_tune key 108)
-// Fewest rows of an hsd_gemm call (above 64) served by the kernel tiled for the matrix cores; 0: the measured rule in
-// use_wide_kernel.  A tuning knob (hsd_tune key 106).
-static int g_wide_min_rows = 0;
+// The library's own launch choices.  Most tokens of a pass that a projection serves from its row-major copy (1B
+// shape, microseconds, row kernel against tile kernel: q/k/v 6.9 / 6.1 at one row, 7.9 / 6.3 at two: the tile kernel
+// with two workgroups per column group always wins; attention output 4.4 / 4.9 and 5.2 / 5.0; FFN down 7.8 / 9.4 and
+// 9.5 / 9.5).
+const hsd_kernel_tuning& default_kernel_tuning() {
+    static const hsd_kernel_tuning t = {{0, 0, 0, 0}, {0, 0, 0, 0}, 0, 0, 1, 2, 128, 1 << 30, 0, 256, 1, 0, 0};
+    return t;
+}
+
+const hsd_driver_tuning& default_driver_tuning() {
+    static const hsd_driver_tuning t = {32768, 1, 1};
+    return t;
+}
+
+extern "C" void hsd_kernel_tuning_default(hsd_kernel_tuning* t) {
+    if (t) *t = default_kernel_tuning();
+}
+
+extern "C" void hsd_driver_tuning_default(hsd_driver_tuning* t) {
+    if (t) *t = default_driver_tuning();
+}
 
 // Above 64 rows the tiled kernel wins at every shape measured (7B-shaped layer, 128 rows: 42-100 us against 48-130 us
-// for two weight streams; 256 rows: 1.8-4 x); the per-64-rows path stays as the alternative the knob selects.
-static bool use_wide_kernel(int m, int n) {
-    (void)n;
+// for two weight streams; 256 rows: 1.8-4 x); the per-64-rows path stays as the alternative the setting selects.
+static bool use_wide_kernel(int m, const hsd_kernel_tuning& t) {
     if (m <= HSD_MAX_PASS_ROWS) return false;
-    return g_wide_min_rows > 0 ? m >= g_wide_min_rows : true;
+    return t.wide_min_rows > 0 ? m >= t.wide_min_rows : true;
 }
 
-void gemm_tune(int epilogue, int nt, int ksplit, int waves) {
-    if (epilogue == 100) { g_gemv_max_m_o = nt; g_gemv_max_m_down = ksplit; g_gemv_max_m_qkv = waves; return; }
-    if (epilogue == 101) { g_attn_qt1_rows = nt; return; }
-    if (epilogue == 102) { g_attn_steps_per_wave = nt; return; }
-    if (epilogue == 111) { g_tune_deep = nt; return; }
-    if (epilogue == 110) { g_attn_fused_merge = nt; return; }
-    if (epilogue == 109) { g_attn_target_wgs = nt > 0 ? nt : 256; return; }
-    if (epilogue == 103) { g_fused_sampler_max_v = nt; return; }
-    if (epilogue == 104) { g_preembed = nt; return; }
-    if (epilogue == 105) { g_poll_mailbox = nt; return; }
-    if (epilogue == 106) { g_wide_min_rows = nt > 0 ? nt : 0; return; }
-    if (epilogue == 108) { g_halves_max_groups = nt; return; }
-    if (epilogue == 107) { g_wide_cols = nt; return; }
-    if (epilogue >= 0 && epilogue < 4) {
-        g_tune_nt[epilogue] = nt;
-        g_tune_ksplit[epilogue] = ksplit;
-    }
-    (void)waves;
-}
-
-GemmPlan gemm_plan(int m, int n, int k, int epi) {
-    GemmPlan p{1, 1, 8, 0};
+GemmPlan gemm_plan(int m, int n, int k, int epi, const hsd_kernel_tuning& t) {
+    GemmPlan p{1, 1, 8, 0, t.gemm_deep};
     const int mt = m <= 16 ? 1 : (m <= 32 ? 2 : 4);
     const int ntiles = ceil_div(n, 16), KT = k / 32;
     switch (epi) {
@@ -605,7 +594,7 @@ GemmPlan gemm_plan(int m, int n, int k, int epi) {
         case EPI_RESID: p.nt = ntiles >= 2048 ? 2 : 1; break;
         default: p.nt = ntiles >= 8192 && mt <= 2 ? 4 : (ntiles >= 1024 ? 2 : 1); break;
     }
-    if (epi != EPI_ROPE && g_tune_nt[epi]) p.nt = g_tune_nt[epi];
+    if (epi != EPI_ROPE && t.gemm_nt[epi]) p.nt = t.gemm_nt[epi];
     if (mt == 4 && p.nt > 2) p.nt = 2;
     // about a thousand workgroups: every CU must be pulling for the HBM stream to reach its peak
     // Splitting K across workgroups costs a round trip through memory for the partial tiles, which only pays for
@@ -622,12 +611,12 @@ GemmPlan gemm_plan(int m, int n, int k, int epi) {
     // (1B shape, 4-8 rows: down 10.8 -> 10.2 us, q/k/v 7.4 -> 6.9; 16 layers: -3.5 % per pass).  Each half reads all the
     // activations, which from 16 rows on costs the residual projections more than the extra workgroups give
     // (32 rows: down 16.6 -> 21 us), and 256-group matrices (7B shape) lose at every row count.
-    if (epi == EPI_RESID && p.nt == 1 && groups <= g_halves_max_groups && m <= 8) {
+    if (epi == EPI_RESID && p.nt == 1 && groups <= t.halves_max_groups && m <= 8) {
         p.halves = 1;
         p.ksplit = 1;
     }
-    if (epi == EPI_ROPE && p.ksplit == 1 && groups <= g_halves_max_groups && m <= 32) p.halves = 1;
-    if (g_tune_ksplit[epi]) { p.ksplit = g_tune_ksplit[epi]; p.halves = 0; }
+    if (epi == EPI_ROPE && p.ksplit == 1 && groups <= t.halves_max_groups && m <= 32) p.halves = 1;
+    if (t.gemm_ksplit[epi]) { p.ksplit = t.gemm_ksplit[epi]; p.halves = 0; }
     if (p.ksplit > 8) p.ksplit = 8;
     if (p.ksplit > KT) p.ksplit = KT;
     if (p.ksplit < 1) p.ksplit = 1;
@@ -654,7 +643,7 @@ static void launch_inst(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     GemmArgs a = g;
     a.halves = p.halves && p.ksplit == 1;
     dim3 grid(ceil_div(ntiles, NT) * (a.halves ? 2 : 1), p.ksplit);
-    const bool deep = g_tune_deep ? g_tune_deep > 0 : (a.K / p.ksplit >= 4096 && a.K / p.ksplit < 8192);
+    const bool deep = p.deep ? p.deep > 0 : (a.K / p.ksplit >= 4096 && a.K / p.ksplit < 8192);
     if (deep)
         gemm_bf16_kernel<NT, MT, EPI, true><<<grid, p.waves * 64, gemm_lds_bytes(p, a.M, EPI), s>>>(a);
     else
@@ -664,7 +653,7 @@ static void launch_inst(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
 // Name of the kernel instance launch_gemm_bf16 runs for a plan, as a profiler prints it.
 void gemm_kernel_name(int m, int k, int epi, const GemmPlan& p, char* out, size_t cap) {
     const int mt = m <= 16 ? 1 : (m <= 32 ? 2 : 4);
-    const bool deep = g_tune_deep ? g_tune_deep > 0 : (k / p.ksplit >= 4096 && k / p.ksplit < 8192);
+    const bool deep = p.deep ? p.deep > 0 : (k / p.ksplit >= 4096 && k / p.ksplit < 8192);
     snprintf(out, cap, "gemm_bf16_kernel<%d, %d, %d, %s>", p.nt, mt, epi, deep ? "true" : "false");
 }
 
@@ -759,11 +748,6 @@ int launch_gemm_f32(const float* x, const float* w, float* out, int m, int n, in
 // ------------------------------------------------------------------------------------------------
 // C ABI
 // ------------------------------------------------------------------------------------------------
-extern "C" int hsd_tune(int key, int nt, int ksplit, int waves) {
-    gemm_tune(key, nt, ksplit, waves);
-    return HSD_OK;
-}
-
 extern "C" size_t hsd_packed_bytes(int n, int k, int dtype) {
     return align_up((size_t)ceil_div(n, 16) * 16 * k * dtype_size(dtype), 256);
 }
@@ -788,11 +772,11 @@ extern "C" size_t hsd_gemm_workspace_bytes(int m, int n, int k) {
     return gemm_store_part_bytes(m, n, k) + align_up((size_t)ceil_div(n, 16) * sizeof(int), 256);
 }
 
-extern "C" int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int n, int k, int dtype, int layout,
-                        void* workspace_dev, void* stream) {
+static int gemm_entry(const void* x_dev, const void* packed_dev, float* y_dev, int m, int n, int k, int dtype, int layout,
+                      void* workspace_dev, void* stream, const hsd_kernel_tuning& t, const char* who) {
     if (!x_dev || !packed_dev || !y_dev || !workspace_dev || (dtype != HSD_F32 && dtype != HSD_BF16) ||
         (layout != HSD_LAYOUT_TILES && layout != HSD_LAYOUT_ROWS))
-        HSD_FAIL(HSD_EINVAL, "hsd_gemm: bad arguments");
+        HSD_FAIL(HSD_EINVAL, "%s: bad arguments", who);
     if (int rc = check_gemm(m, n, k, HSD_MAX_GEMM_ROWS)) return rc;
     hipStream_t s = (hipStream_t)stream;
     if (dtype == HSD_F32) return launch_gemm_f32((const float*)x_dev, (const float*)packed_dev, y_dev, m, n, k, false, s);
@@ -804,8 +788,8 @@ extern "C" int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev,
         g.out_f32 = y_dev;
         return launch_gemv_bf16(g, EPI_STORE, s);
     }
-    if (use_wide_kernel(m, n))
-        return launch_gemm_wide_bf16((const bf16_t*)x_dev, (const bf16x8*)packed_dev, y_dev, m, n, k, s);
+    if (use_wide_kernel(m, t))
+        return launch_gemm_wide_bf16((const bf16_t*)x_dev, (const bf16x8*)packed_dev, y_dev, m, n, k, t.wide_cols, s);
     const size_t part_bytes = gemm_store_part_bytes(m, n, k);
     GemmArgs g = {};
     g.wp = (const bf16x8*)packed_dev;
@@ -820,7 +804,18 @@ extern "C" int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev,
         g.M = std::min((int)HSD_MAX_PASS_ROWS, m - m0);
         g.a = (const bf16_t*)x_dev + (size_t)m0 * k;
         g.out_f32 = y_dev + (size_t)m0 * n;
-        if (int rc = launch_gemm_bf16(g, EPI_STORE, gemm_plan(g.M, n, k, EPI_STORE), s)) return rc;
+        if (int rc = launch_gemm_bf16(g, EPI_STORE, gemm_plan(g.M, n, k, EPI_STORE, t), s)) return rc;
     }
     return HSD_OK;
+}
+
+extern "C" int hsd_gemm(const void* x_dev, const void* packed_dev, float* y_dev, int m, int n, int k, int dtype, int layout,
+                        void* workspace_dev, void* stream) {
+    return gemm_entry(x_dev, packed_dev, y_dev, m, n, k, dtype, layout, workspace_dev, stream, default_kernel_tuning(), "hsd_gemm");
+}
+
+extern "C" int hsd_gemm_tuned(const void* x_dev, const void* packed_dev, float* y_dev, int m, int n, int k, int dtype, int layout,
+                              void* workspace_dev, void* stream, const hsd_kernel_tuning* t) {
+    return gemm_entry(x_dev, packed_dev, y_dev, m, n, k, dtype, layout, workspace_dev, stream, t ? *t : default_kernel_tuning(),
+                      "hsd_gemm_tuned");
 }

@@ -172,19 +172,17 @@ __global__ __launch_bounds__(WIDE_WAVES * 64) __attribute__((amdgpu_waves_per_eu
 
 }  // namespace
 
-int g_wide_cols = 0;      // tuning override (hsd_tune key 107): 128 or 256 columns per workgroup, 0: the rule below
-
 // Column strips of 256, unless they leave at least half of the 256 CUs idle: then strips of 128 (twice the workgroups,
-// still one round).
-static int wide_nt(int m, int n) {
-    if (g_wide_cols == 128) return 2;
-    if (g_wide_cols == 256) return 4;
+// still one round).  wide_cols = 128 or 256 fixes the width (a tuning setting), 0 takes the rule.
+static int wide_nt(int m, int n, int wide_cols) {
+    if (wide_cols == 128) return 2;
+    if (wide_cols == 256) return 4;
     return ceil_div(m, WIDE_ROWS) * ceil_div(n, 256) <= 128 ? 2 : 4;
 }
 
 // bf16, packed tiles.  Shapes are the caller's to check (m >= 1, k a positive multiple of 32).
-int launch_gemm_wide_bf16(const bf16_t* a, const bf16x8* wp, float* out, int m, int n, int k, hipStream_t s) {
-    const int nt = wide_nt(m, n);
+int launch_gemm_wide_bf16(const bf16_t* a, const bf16x8* wp, float* out, int m, int n, int k, int wide_cols, hipStream_t s) {
+    const int nt = wide_nt(m, n, wide_cols);
     const int mblocks = ceil_div(m, WIDE_ROWS), nblocks = ceil_div(n, WIDE_WAVES * nt * 16);
     const long long grid = 8ll * mblocks * ceil_div(nblocks, 8);
     if (grid > 0x7fffffffll) HSD_FAIL(HSD_EINVAL, "gemm: %d x %d is too large for one launch", m, n);

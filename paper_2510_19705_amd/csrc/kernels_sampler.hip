@@ -544,15 +544,12 @@ int launch_accept_resample(const float* p, const float* q, int32_t* x, int t, in
 
 // Fused softmax + Alg. 2 (vocabularies up to 32768 only); scratch as for launch_accept_resample (ticket in word 0,
 // the key in bytes 8..15, both zero between launches).
-int g_poll_mailbox = 1;                       // hsd_tune key 105: 0 makes the driver wait for the stream after each Verify instead
-int g_preembed = 1;                           // hsd_tune key 104: 0 keeps the embedding of the emitted token in the next pass
-int g_fused_sampler_max_v = SMALL_MAX_V;       // hsd_tune key 103: lower it to send smaller vocabularies down the two-launch path
-bool softmax_verify_supported(int vocab) { return vocab <= SMALL_MAX_V && vocab <= g_fused_sampler_max_v; }
+bool softmax_verify_supported(int vocab, int max_v) { return vocab <= SMALL_MAX_V && vocab <= max_v; }
 
 int launch_softmax_verify(const float* z, const float* q, int32_t* x, int t, int vocab, float temperature, uint64_t seed,
                           uint32_t level, uint32_t call, float* p_out, int32_t* result, void* scratch, int32_t* mailbox,
                           const EmbedNext& next, float coin, int mailbox_seq, hipStream_t s) {
-    if (!softmax_verify_supported(vocab)) HSD_FAIL(HSD_ECAPACITY, "fused softmax + verify: vocabulary %d above %d", vocab, SMALL_MAX_V < g_fused_sampler_max_v ? SMALL_MAX_V : g_fused_sampler_max_v);
+    if (!softmax_verify_supported(vocab)) HSD_FAIL(HSD_ECAPACITY, "fused softmax + verify: vocabulary %d above %d", vocab, SMALL_MAX_V);
     softmax_verify_kernel<<<t + 1, SMALL_THREADS, 0, s>>>(z, q, x, t, vocab, temperature, (uint32_t)seed, (uint32_t)(seed >> 32), level,
                                                           call, p_out, result, (uint32_t*)scratch,
                                                           (unsigned long long*)((char*)scratch + 8), mailbox, next, coin, mailbox_seq);

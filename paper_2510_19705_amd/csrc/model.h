@@ -45,6 +45,7 @@ struct hsd_model {
     int32_t* batch_pages_dev;   // [batch][batch_pages_per_seq]
     int32_t* batch_pos0_dev;    // [batch]
     int batch, batch_pages_per_seq;
+    hsd_kernel_tuning tuning;   // launch heuristics of this model's passes (hsd_model_set_tuning)
     unsigned long long pass_serial;   // counts passes: whoever left something in the activation buffers can tell if it is still there
     // optional per-site event timing (hsd_profile_begin / hsd_profile_end)
     bool prof_on;
@@ -76,12 +77,12 @@ size_t attn_workspace_bytes(int batch, int m, int n_q, int n_kv, int hd, int max
 size_t attn_ticket_bytes();   // leading bytes of an attention workspace that must be zero between launches
 int launch_attention(const void* q, const void* kv_layer, const int32_t* pages, int max_pages, const int32_t* pos0_dev,
                      int pos0_all, int batch, int m, int max_len, int n_q, int n_kv, int hd, int dtype, void* att,
-                     float* workspace, int force_simple, hipStream_t s);
+                     float* workspace, int force_simple, hipStream_t s, const hsd_kernel_tuning& t = default_kernel_tuning());
 // kernels_sampler.hip
 int launch_accept_resample(const float* p, const float* q, int32_t* x, int t, int vocab, uint64_t seed, uint32_t level,
                            uint32_t call, int32_t* result, void* scratch, float coin, hipStream_t s);
 int launch_add_noise(float* z, int rows, int vocab, uint64_t seed, uint32_t level, int pos0, float std, hipStream_t s);
-bool softmax_verify_supported(int vocab);
+bool softmax_verify_supported(int vocab, int max_v = 1 << 30);   // max_v: the driver's own limit (a tuning setting)
 // What the fused sampler needs to leave the emitted token embedded for a following one-token pass of `model`
 // (row 0 of its residual stream, normalised input and sums of squares, exactly as the embedding kernel would):
 // E == nullptr switches it off.

@@ -185,6 +185,7 @@ extern "C" int hsd_model_create(const hsd_model_desc* desc, void* weights_dev, v
     m->layer_loaded.assign(desc->n_layers, false);
     m->head_loaded = false;
     m->pass_serial = 0;
+    m->tuning = default_kernel_tuning();
     m->prof_on = false;
     m->prof_used = 0;
     // Cache rows beyond the valid length are read (and masked) by the attention kernels: keep them finite.
@@ -367,10 +368,10 @@ static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, const 
             SiteTimer t(m, HSD_SITE_ATTN);
             if (bg)
                 rc = launch_attention(m->q, kv_layer, m->batch_pages_dev, m->batch_pages_per_seq, m->batch_pos0_dev, 0, bg->batch, bg->m_seq,
-                                      bg->max_len, d.n_q, d.n_kv, d.hd, d.dtype, m->att, m->attn_ws, 0, s);
+                                      bg->max_len, d.n_q, d.n_kv, d.hd, d.dtype, m->att, m->attn_ws, 0, s, m->tuning);
             else
                 rc = launch_attention(m->q, kv_layer, m->pages_dev, m->max_pages, nullptr, pos0, 1, rows, pos0 + rows, d.n_q, d.n_kv,
-                                      d.hd, d.dtype, m->att, m->attn_ws, 0, s);
+                                      d.hd, d.dtype, m->att, m->attn_ws, 0, s, m->tuning);
             if (rc) return rc;
         }
         {
@@ -419,7 +420,8 @@ static int launch_site_bf16(hsd_model* m, int site, int l, int pos0, int rows, c
     const LayerWeights& L = m->layers[l];
     bf16_t* kv_layer = (bf16_t*)(m->kv + m->kv_layer_bytes * l);
     // one or two tokens: some projections stream their row-major copies
-    const bool rowk = L.wqkv_rows && !bg && rows <= (site == HSD_SITE_QKV ? g_gemv_max_m_qkv : (site == HSD_SITE_O ? g_gemv_max_m_o : g_gemv_max_m_down));
+    const hsd_kernel_tuning& tn = m->tuning;
+    const bool rowk = L.wqkv_rows && !bg && rows <= (site == HSD_SITE_QKV ? tn.gemv_max_m_qkv : (site == HSD_SITE_O ? tn.gemv_max_m_o : tn.gemv_max_m_down));
     GemmArgs g = {};
     g.M = rows; g.part = m->part; g.part_bytes = m->part_elems * sizeof(float); g.tickets = m->tickets; g.eps = d.eps;
     switch (site) {
@@ -429,26 +431,26 @@ static int launch_site_bf16(hsd_model* m, int site, int l, int pos0, int rows, c
             g.out_bf16 = (bf16_t*)m->q; g.kv_layer = kv_layer; g.pages = m->pages_dev;
             g.pos0 = pos0; g.n_q = d.n_q; g.n_kv = d.n_kv; g.hd = d.hd; g.rope_base = d.rope_base;
             if (bg) { g.pages = m->batch_pages_dev; g.pos0_arr = m->batch_pos0_dev; g.m_seq = bg->m_seq; g.max_pages = m->batch_pages_per_seq; }
-            return rowk ? launch_gemv_bf16(g, EPI_ROPE, s) : launch_gemm_bf16(g, EPI_ROPE, gemm_plan(rows, nqkv, d.d, EPI_ROPE), s);
+            return rowk ? launch_gemv_bf16(g, EPI_ROPE, s) : launch_gemm_bf16(g, EPI_ROPE, gemm_plan(rows, nqkv, d.d, EPI_ROPE, tn), s);
         case HSD_SITE_ATTN:
             if (bg)
                 return launch_attention(m->q, kv_layer, m->batch_pages_dev, m->batch_pages_per_seq, m->batch_pos0_dev, 0, bg->batch,
-                                        bg->m_seq, bg->max_len, d.n_q, d.n_kv, d.hd, d.dtype, m->att, m->attn_ws, 0, s);
+                                        bg->m_seq, bg->max_len, d.n_q, d.n_kv, d.hd, d.dtype, m->att, m->attn_ws, 0, s, m->tuning);
             return launch_attention(m->q, kv_layer, m->pages_dev, m->max_pages, nullptr, pos0, 1, rows, pos0 + rows, d.n_q, d.n_kv,
-                                    d.hd, d.dtype, m->att, m->attn_ws, 0, s);
+                                    d.hd, d.dtype, m->att, m->attn_ws, 0, s, m->tuning);
         case HSD_SITE_O:
             g.a = (const bf16_t*)m->att; g.wp = (const bf16x8*)(rowk ? L.wo_rows : L.wo); g.N = d.d; g.K = nq;
             g.out_f32 = m->x; g.ss_out = m->ss[1]; g.norm_w = L.norm2; g.out_bf16 = (bf16_t*)m->xn;
-            return rowk ? launch_gemv_bf16(g, EPI_RESID, s) : launch_gemm_bf16(g, EPI_RESID, gemm_plan(rows, d.d, nq, EPI_RESID), s);
+            return rowk ? launch_gemv_bf16(g, EPI_RESID, s) : launch_gemm_bf16(g, EPI_RESID, gemm_plan(rows, d.d, nq, EPI_RESID, tn), s);
         case HSD_SITE_GATEUP:
             g.a = (const bf16_t*)m->xn; g.ss_in = m->ss[1]; g.ss_zero = m->ss[0];
             g.wp = (const bf16x8*)L.wgu; g.N = 2 * d.ffn; g.K = d.d;
             g.out_bf16 = (bf16_t*)m->h;
-            return launch_gemm_bf16(g, EPI_SWIGLU, gemm_plan(rows, 2 * d.ffn, d.d, EPI_SWIGLU), s);
+            return launch_gemm_bf16(g, EPI_SWIGLU, gemm_plan(rows, 2 * d.ffn, d.d, EPI_SWIGLU, tn), s);
         case HSD_SITE_DOWN:
             g.a = (const bf16_t*)m->h; g.wp = (const bf16x8*)(rowk ? L.wd_rows : L.wd); g.N = d.d; g.K = d.ffn;
             g.out_f32 = m->x; g.ss_out = m->ss[0]; g.norm_w = next_norm_w; g.out_bf16 = (bf16_t*)m->xn;
-            return rowk ? launch_gemv_bf16(g, EPI_RESID, s) : launch_gemm_bf16(g, EPI_RESID, gemm_plan(rows, d.d, d.ffn, EPI_RESID), s);
+            return rowk ? launch_gemv_bf16(g, EPI_RESID, s) : launch_gemm_bf16(g, EPI_RESID, gemm_plan(rows, d.d, d.ffn, EPI_RESID, tn), s);
         default:
             HSD_FAIL(HSD_EINVAL, "unknown site %d", site);
     }
@@ -463,7 +465,7 @@ static int launch_head_bf16(hsd_model* m, const void* xn, int rows, int n_logit_
     g.a = (const bf16_t*)xn + (size_t)row0 * d.d; g.ss_in = m->ss[0] + row0;
     g.wp = (const bf16x8*)m->head; g.N = d.vocab; g.K = d.d;
     g.out_f32 = logits;
-    return launch_gemm_bf16(g, EPI_STORE, gemm_plan(n_logit_rows, d.vocab, d.d, EPI_STORE), m->stream);
+    return launch_gemm_bf16(g, EPI_STORE, gemm_plan(n_logit_rows, d.vocab, d.d, EPI_STORE, m->tuning), m->stream);
 }
 
 static int pass_bf16(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
@@ -544,7 +546,7 @@ extern "C" int hsd_site_kernel(const hsd_model* m, int site, int rows, char* nam
         default: HSD_FAIL(HSD_EINVAL, "hsd_site_kernel: site %d is not a projection", site);
     }
     // layers without row-major copies (rows_copy_layers counts from the first layer): the tiled kernel
-    gemm_kernel_name(rows, k, epi, gemm_plan(rows, n, k, epi), name_out, (size_t)cap);
+    gemm_kernel_name(rows, k, epi, gemm_plan(rows, n, k, epi, m->tuning), name_out, (size_t)cap);
     return HSD_OK;
 }
 
@@ -590,6 +592,12 @@ static int pass_checked(hsd_model* m, const int32_t* tok, int pos0, int rows, co
     ++m->pass_serial;
     return d.dtype == HSD_BF16 ? pass_bf16(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits, embedded, bg)
                                : pass_f32(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits, embedded, bg);
+}
+
+extern "C" int hsd_model_set_tuning(hsd_model* m, const hsd_kernel_tuning* t) {
+    if (!m) HSD_FAIL(HSD_EINVAL, "hsd_model_set_tuning: null pointer");
+    m->tuning = t ? *t : default_kernel_tuning();
+    return HSD_OK;
 }
 
 // ---- batch of sequences ------------------------------------------------------------------------------------------

@@ -44,6 +44,19 @@ class SiteTimes(C.Structure):
     _fields_ = [("launches", C.c_int64 * N_SITES), ("ms", C.c_double * N_SITES), ("empty_bracket_ms", C.c_double)]
 
 
+class KernelTuning(C.Structure):
+    """hsd_kernel_tuning (include/hsd_dev.h): launch heuristics of one model / one stand-alone call."""
+    _fields_ = [("gemm_nt", C.c_int * 4), ("gemm_ksplit", C.c_int * 4), ("gemm_deep", C.c_int),
+                ("gemv_max_m_qkv", C.c_int), ("gemv_max_m_o", C.c_int), ("gemv_max_m_down", C.c_int),
+                ("halves_max_groups", C.c_int), ("attn_qt1_rows", C.c_int), ("attn_steps_per_wave", C.c_int),
+                ("attn_target_wgs", C.c_int), ("attn_fused_merge", C.c_int), ("wide_min_rows", C.c_int), ("wide_cols", C.c_int)]
+
+
+class DriverTuning(C.Structure):
+    """hsd_driver_tuning: the round driver's choices for one hierarchy."""
+    _fields_ = [("fused_sampler_max_v", C.c_int), ("preembed", C.c_int), ("poll_mailbox", C.c_int)]
+
+
 class Stats(C.Structure):
     _fields_ = [("passes", C.c_int64 * MAX_LEVELS), ("pass_rows", C.c_int64 * MAX_LEVELS),
                 ("drafted", C.c_int64 * MAX_LEVELS), ("accepted", C.c_int64 * MAX_LEVELS),
@@ -93,7 +106,12 @@ _SIGS = {
     "hsd_gemm_workspace_bytes": (_sz, [_i, _i, _i]),
     "hsd_pack_weight": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
     "hsd_gemm": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp]),
-    "hsd_tune": (_i, [_i, _i, _i, _i]),
+    "hsd_kernel_tuning_default": (None, [C.POINTER(KernelTuning)]),
+    "hsd_driver_tuning_default": (None, [C.POINTER(DriverTuning)]),
+    "hsd_model_set_tuning": (_i, [_vp, C.POINTER(KernelTuning)]),
+    "hsd_hier_set_tuning": (_i, [_vp, C.POINTER(DriverTuning)]),
+    "hsd_gemm_tuned": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, C.POINTER(KernelTuning)]),
+    "hsd_attention_tuned": (_i, [_vp, _vp, _vp, _i, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, C.POINTER(KernelTuning)]),
     "hsd_hier_workspace_bytes": (_sz, [_i, C.POINTER(Level), _ip]),
     "hsd_hier_create": (_i, [_i, C.POINTER(Level), _ip, _f, C.c_uint64, _vp, _sz, _vp, C.POINTER(_vp)]),
     "hsd_hier_destroy": (None, [_vp]),
@@ -129,6 +147,31 @@ class HsdError(RuntimeError):
 def _check(rc):
     if rc != 0:
         raise HsdError(rc)
+
+
+def kernel_tuning(**settings):
+    """The library's default launch heuristics with the given fields replaced (gemm_nt / gemm_ksplit: dict epilogue -> value)."""
+    k = KernelTuning()
+    lib.hsd_kernel_tuning_default(C.byref(k))
+    for name, v in settings.items():
+        if name in ("gemm_nt", "gemm_ksplit"):
+            for epi, val in v.items():
+                getattr(k, name)[epi] = val
+        else:
+            if not hasattr(k, name):
+                raise AttributeError(name)
+            setattr(k, name, v)
+    return k
+
+
+def driver_tuning(**settings):
+    d = DriverTuning()
+    lib.hsd_driver_tuning_default(C.byref(d))
+    for name, v in settings.items():
+        if not hasattr(d, name):
+            raise AttributeError(name)
+        setattr(d, name, v)
+    return d
 
 
 def _stream():
@@ -226,6 +269,10 @@ class Model:
         us = C.c_double()
         _check(lib.hsd_measure_site(self.handle, SITE_NAMES.index(site), rows, pos0, iters, C.byref(us)))
         return us.value
+
+    def set_tuning(self, **settings):
+        """hsd_model_set_tuning: this model's launch heuristics = the defaults with `settings` replaced (none: defaults)."""
+        _check(lib.hsd_model_set_tuning(self.handle, C.byref(kernel_tuning(**settings)) if settings else None))
 
     def site_kernel(self, site, rows):
         buf = C.create_string_buffer(128)
@@ -378,15 +425,15 @@ class KvLayer:
                                 k.shape[1], self.n_kv, self.hd, self.dtype, k.contiguous().data_ptr(),
                                 v.contiguous().data_ptr(), _stream()))
 
-    def attention(self, q, pos0, max_len, ws=None):
-        """q: [batch, m, n_q, hd]; returns att of the same shape and type."""
+    def attention(self, q, pos0, max_len, ws=None, tuning=None):
+        """q: [batch, m, n_q, hd]; returns att of the same shape and type.  tuning: a KernelTuning (hsd_attention_tuned)."""
         b, m, n_q, hd = q.shape
         if ws is None:       # zero on first use: the workspace begins with arrival counters
             ws = torch.zeros(max(256, lib.hsd_attention_workspace_bytes(b, m, n_q, self.n_kv, hd, max_len)), dtype=torch.uint8, device="cuda")
         out = torch.empty_like(q)
-        _check(lib.hsd_attention(q.contiguous().data_ptr(), self.buf.data_ptr(), self.pages.data_ptr(), self.max_pages,
-                                 pos0.data_ptr(), b, m, max_len, n_q, self.n_kv, hd, self.dtype, out.data_ptr(),
-                                 ws.data_ptr(), _stream()))
+        args = (q.contiguous().data_ptr(), self.buf.data_ptr(), self.pages.data_ptr(), self.max_pages, pos0.data_ptr(), b, m, max_len,
+                n_q, self.n_kv, hd, self.dtype, out.data_ptr(), ws.data_ptr(), _stream())
+        _check(lib.hsd_attention(*args) if tuning is None else lib.hsd_attention_tuned(*args, C.byref(tuning)))
         return out
 
 
@@ -398,13 +445,13 @@ def pack_weight(w, dtype, layout=LAYOUT_TILES):
     return out
 
 
-def gemm(x, packed, n, dtype, ws=None, layout=LAYOUT_TILES):
+def gemm(x, packed, n, dtype, ws=None, layout=LAYOUT_TILES, tuning=None):
     m, k = x.shape
     y = torch.empty((m, n), dtype=torch.float32, device="cuda")
     if ws is None:
         ws = _buf(lib.hsd_gemm_workspace_bytes(m, n, k))
-    _check(lib.hsd_gemm(x.contiguous().data_ptr(), packed.data_ptr(), y.data_ptr(), m, n, k, dtype, layout, ws.data_ptr(),
-                        _stream()))
+    args = (x.contiguous().data_ptr(), packed.data_ptr(), y.data_ptr(), m, n, k, dtype, layout, ws.data_ptr(), _stream())
+    _check(lib.hsd_gemm(*args) if tuning is None else lib.hsd_gemm_tuned(*args, C.byref(tuning)))
     return y
 
 
@@ -482,6 +529,10 @@ class Hierarchy:
     def set_distilled(self, level, source_level, noise_std):
         """hsd_hier_set_distilled: level's logits = source level's logits + seeded Gaussian noise (synthetic drafter)."""
         _check(lib.hsd_hier_set_distilled(self.handle, level, source_level, float(noise_std)))
+
+    def set_tuning(self, **settings):
+        """hsd_hier_set_tuning: the driver's choices for this hierarchy = the defaults with `settings` replaced."""
+        _check(lib.hsd_hier_set_tuning(self.handle, C.byref(driver_tuning(**settings)) if settings else None))
 
     def set_ablation(self, coin=None, exactly_T=False):
         """hsd_hier_set_ablation: coin = per-level fixed acceptance probabilities (entry 0 ignored, negative = real)."""

@@ -306,20 +306,25 @@ def microbench():
             torch.cuda.empty_cache()
     # the same cells as ONE fused layer of the model (hsd_model_pass_batch: q/k/v + RoPE + KV append, attention,
     # o + residual, gate/up + SwiGLU, down + residual over the batch's rows), where batch x k fits the 64 rows of a pass
+    # (a pass through three layers minus a pass through one, halved: the embedding kernel and the host's share of a
+    # short pass drop out)
     fused = []
-    one = dict(shape, n_layers=1)
+    three = dict(shape, n_layers=3)
     for B in (1, 8, 64):
         for S in (4096, 16384, 32768):
             pps = (S + 64) // 64
-            model = random_model(hsd, inputs, torch, one, 3, B * pps * 64)
+            model = random_model(hsd, inputs, torch, three, 3, B * pps * 64)
             model.set_batch(B, pps)
             for k in (1, 2, 4, 8, 16):
                 if B * k > 64:
                     continue
-                tk = torch.randint(0, one["vocab"], (B, k), device="cuda", dtype=torch.int32)
-                us = _time(torch, lambda: model.model_pass_batch(tk, [S - k] * B, 1, with_logits=False), 10 if B * S > 500000 else 30)
+                tk = torch.randint(0, three["vocab"], (B, k), device="cuda", dtype=torch.int32)
+                iters = 10 if B * S > 500000 else 30
+                t3 = _time(torch, lambda: model.model_pass_batch(tk, [S - k] * B, 3, with_logits=False), iters)
+                t1 = _time(torch, lambda: model.model_pass_batch(tk, [S - k] * B, 1, with_logits=False), iters)
+                us = (t3 - t1) / 2
                 kv_bytes = 2 * S * n_kv * hd * 2 * B
-                cell = {"batch": B, "kv_len": S, "k": k, "fused_layer_us": us,
+                cell = {"batch": B, "kv_len": S, "k": k, "fused_layer_us": us, "three_layer_pass_us": t3, "one_layer_pass_us": t1,
                         "layer_hbm_frac": (sum(site_mb.values()) * 1e6 + kv_bytes) / us / 1e3 / HBM_PEAK_GBS}
                 fused.append(cell)
                 log(cell)

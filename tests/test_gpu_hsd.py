@@ -89,12 +89,9 @@ def test_temperature0_random_hierarchies(tiny):
 @pytest.fixture(params=["fused_sampler", "two_launch_sampler"])
 def sampler_path(request):
     """The driver's two ways from logits to (n, token): the fused launch (vocabularies up to 32768) and softmax +
-    accept/resample as two launches (larger vocabularies), the latter forced here on the small vocabulary."""
-    from paper_2510_19705_amd import hsd
-    if request.param == "two_launch_sampler":
-        hsd.lib.hsd_tune(103, 0, 0, 0)
-    yield request.param
-    hsd.lib.hsd_tune(103, 32768, 0, 0)
+    accept/resample as two launches (larger vocabularies), the latter forced on the small vocabulary through the
+    hierarchy's own settings.  Yields the settings to apply to a hierarchy."""
+    return {} if request.param == "fused_sampler" else {"fused_sampler_max_v": 0}
 
 
 @pytest.mark.parametrize("T,seed", [((4, 2), 104), ((3, 5), 100)])
@@ -112,6 +109,7 @@ def test_tiny_temperature1_stream(tiny, T, seed, sampler_path):
     say("oracle margins: accept %.2e sample %.2e" % (min(ch.accept_margins), min(ch.sample_margins)))
     assert min(ch.accept_margins) > 3e-4 and min(ch.sample_margins) > 3e-6
     h = _gpu_hier(model, TINY_EXITS, T, 1.0, seed=seed)
+    h.set_tuning(**sampler_path)
     h.prefill(prompt)
     got, st = h.generate(64)
     assert got.tolist() == ref
@@ -309,16 +307,13 @@ def test_token_embedded_by_the_sampler_changes_nothing(bf16):
     model = gpu_model(shape, w, bf16, max_seq=192, max_rows=16, rows_copy_layers=2 if bf16 else 0)
     runs = []
     for pre in (1, 0):
-        hsd.lib.hsd_tune(104, pre, 0, 0)
-        try:
-            h = hsd.Hierarchy([(model, 1), (model, 2), (model, 4)], (3, 2), 1.0, 77)
-            h.prefill(prompt)
-            toks, st = h.generate(60)
-            d = h.draft(2)                                  # explicit draft calls go the same way
-            runs.append((toks.tolist(), [st.passes[i] for i in range(3)], [st.accepted[i] for i in range(3)], d[0].tolist()))
-            h.close()
-        finally:
-            hsd.lib.hsd_tune(104, 1, 0, 0)
+        h = hsd.Hierarchy([(model, 1), (model, 2), (model, 4)], (3, 2), 1.0, 77)
+        h.set_tuning(preembed=pre)
+        h.prefill(prompt)
+        toks, st = h.generate(60)
+        d = h.draft(2)                                  # explicit draft calls go the same way
+        runs.append((toks.tolist(), [st.passes[i] for i in range(3)], [st.accepted[i] for i in range(3)], d[0].tolist()))
+        h.close()
     assert runs[0] == runs[1]
     model.close()
 
@@ -368,15 +363,12 @@ def test_polling_and_stream_wait_agree(tiny):
     _, prompt, model = tiny
     runs = []
     for poll in (1, 0, 1):
-        hsd.lib.hsd_tune(105, poll, 0, 0)
-        try:
-            h = _gpu_hier(model, TINY_EXITS, (2, 1), 1.0, seed=9)
-            h.prefill(prompt)
-            toks, st = h.generate(150)
-            runs.append((toks.tolist(), [st.passes[i] for i in range(3)], [st.accepted[i] for i in range(3)]))
-            h.close()
-        finally:
-            hsd.lib.hsd_tune(105, 1, 0, 0)
+        h = _gpu_hier(model, TINY_EXITS, (2, 1), 1.0, seed=9)
+        h.set_tuning(poll_mailbox=poll)
+        h.prefill(prompt)
+        toks, st = h.generate(150)
+        runs.append((toks.tolist(), [st.passes[i] for i in range(3)], [st.accepted[i] for i in range(3)]))
+        h.close()
     assert runs[0] == runs[1] == runs[2]
 
 

@@ -251,11 +251,8 @@ def test_gemm_many_rows(hsd, m, n, k, path):
     w = inputs.bf16_round((rng.standard_normal((n, k)) / np.sqrt(k)).astype(np.float32))
     ref = x.astype(np.float64) @ w.astype(np.float64).T
     packed = hsd.pack_weight(_cuda(w, torch.bfloat16), hsd.BF16, 0)
-    hsd.lib.hsd_tune(106, 65 if path == "tiled_for_mfma" else 1 << 30, 0, 0)
-    try:
-        got = hsd.gemm(_cuda(x, torch.bfloat16), packed, n, hsd.BF16, None, 0).cpu().numpy()
-    finally:
-        hsd.lib.hsd_tune(106, 0, 0, 0)
+    tuning = hsd.kernel_tuning(wide_min_rows=65 if path == "tiled_for_mfma" else 1 << 30)
+    got = hsd.gemm(_cuda(x, torch.bfloat16), packed, n, hsd.BF16, None, 0, tuning).cpu().numpy()
     tol = 4e-6 * np.sqrt(k) * np.abs(ref).max() + 1e-6
     assert np.abs(got - ref).max() < tol, (np.abs(got - ref).max(), tol)
 
@@ -369,11 +366,7 @@ def _attention_cell(hsd, B, S, ms, n_q, n_kv, hd, bf16, check_alt=True):
         assert err <= ATT_REL_TOL[bf16] * scale, (B, S, m, err, scale)
         if check_alt and bf16 and m * (n_q // n_kv) > 16:
             # the two-tiles-per-workgroup variant (a tuning alternative) on the same inputs
-            hsd.lib.hsd_tune(101, 16, 0, 0)
-            try:
-                got2 = cache.attention(_cuda(q, td), _cuda(pos0), max(lens)).float().cpu().numpy()
-            finally:
-                hsd.lib.hsd_tune(101, 1 << 30, 0, 0)
+            got2 = cache.attention(_cuda(q, td), _cuda(pos0), max(lens), tuning=hsd.kernel_tuning(attn_qt1_rows=16)).float().cpu().numpy()
             assert np.abs(got2 - ref).max() <= ATT_REL_TOL[bf16] * scale
 
 

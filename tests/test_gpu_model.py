@@ -114,19 +114,16 @@ def test_pass_bf16_row_kernel_on_every_projection():
     shape = SMALL_BF16
     w = inputs.make_weights(shape, seed=41, bf16=True)
     toks = inputs.make_prompt(shape["vocab"], 100, seed=42)
-    hsd.lib.hsd_tune(100, 3, 3, 3)
-    try:
-        model = gpu_model(shape, w, True, max_seq=128, max_rows=64, rows_copy_layers=shape["n_layers"])
-        oracle = oracle_decoder(shape, w, 128)
-        L = shape["n_layers"]
-        schedule = [(0, 40, L - 1, 1), (40, 1, L - 1, 1), (41, 2, L - 1, 2), (43, 3, L - 1, 3), (46, 4, L - 1, 4), (50, 1, 0, 1), (50, 1, L - 1, 1)]
-        for tag, got, ref in _run_passes(model, oracle, toks, schedule, tuple(range(1, L + 1))):
-            err = np.abs(got - ref).max()
-            say("row kernel everywhere", tag, "abs err %.2e" % err)
-            assert err < 2e-2, tag
-        model.close()
-    finally:
-        hsd.lib.hsd_tune(100, 1, 2, 0)
+    model = gpu_model(shape, w, True, max_seq=128, max_rows=64, rows_copy_layers=shape["n_layers"])
+    model.set_tuning(gemv_max_m_qkv=3, gemv_max_m_o=3, gemv_max_m_down=3)          # this model only
+    oracle = oracle_decoder(shape, w, 128)
+    L = shape["n_layers"]
+    schedule = [(0, 40, L - 1, 1), (40, 1, L - 1, 1), (41, 2, L - 1, 2), (43, 3, L - 1, 3), (46, 4, L - 1, 4), (50, 1, 0, 1), (50, 1, L - 1, 1)]
+    for tag, got, ref in _run_passes(model, oracle, toks, schedule, tuple(range(1, L + 1))):
+        err = np.abs(got - ref).max()
+        say("row kernel everywhere", tag, "abs err %.2e" % err)
+        assert err < 2e-2, tag
+    model.close()
 
 
 @pytest.mark.parametrize("max_groups", [0, 128], ids=["whole_tiles", "half_tiles"])
@@ -138,18 +135,15 @@ def test_pass_bf16_narrow_projection_schemes(max_groups):
     shape = dict(n_layers=2, d=512, n_q=8, n_kv=2, hd=64, ffn=8192, vocab=1000)       # down: K = 8192
     w = inputs.make_weights(shape, seed=31, bf16=True)
     toks = inputs.make_prompt(shape["vocab"], 120, seed=32)
-    hsd.lib.hsd_tune(108, max_groups, 0, 0)
-    try:
-        model = gpu_model(shape, w, True, max_seq=128, max_rows=64)
-        oracle = oracle_decoder(shape, w, 128)
-        schedule = [(0, 50, 1, 1), (50, 1, 1, 1), (51, 3, 1, 3), (54, 8, 1, 8), (62, 9, 1, 9), (71, 5, 0, 5), (71, 5, 1, 5)]
-        for tag, got, ref in _run_passes(model, oracle, toks, schedule, (1, 2)):
-            err = np.abs(got - ref).max()
-            say("narrow projections", "half tiles" if max_groups else "whole tiles", tag, "abs err %.2e" % err)
-            assert err < 2e-2, tag
-        model.close()
-    finally:
-        hsd.lib.hsd_tune(108, 128, 0, 0)
+    model = gpu_model(shape, w, True, max_seq=128, max_rows=64)
+    model.set_tuning(halves_max_groups=max_groups)
+    oracle = oracle_decoder(shape, w, 128)
+    schedule = [(0, 50, 1, 1), (50, 1, 1, 1), (51, 3, 1, 3), (54, 8, 1, 8), (62, 9, 1, 9), (71, 5, 0, 5), (71, 5, 1, 5)]
+    for tag, got, ref in _run_passes(model, oracle, toks, schedule, (1, 2)):
+        err = np.abs(got - ref).max()
+        say("narrow projections", "half tiles" if max_groups else "whole tiles", tag, "abs err %.2e" % err)
+        assert err < 2e-2, tag
+    model.close()
 
 
 def test_pass_rejects_bad_arguments():

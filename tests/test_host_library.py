@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_every_declared_symbol_is_exported():
-    header = open(os.path.join(ROOT, "include", "hsd.h")).read()
+    header = open(os.path.join(ROOT, "include", "hsd.h")).read() + open(os.path.join(ROOT, "include", "hsd_dev.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(hsd_[a-z0-9_]+)\s*\(", header))
     assert len(declared) >= 30
