@@ -97,6 +97,49 @@ def traffic(fetch_db, write_db, manifest, cmd, out):
     return open(out).read()
 
 
+def gap(db, report, plain_report, cmd, out):
+    """Kernel-busy share of the generations that `workloads --config launch-gap` brackets with two marker launches.
+    report: what the workload printed in the profiled run; plain_report: what it printed without the profiler (the
+    profiler slows the host's launches, so wall-clock and the graph-replay comparison are quoted from the plain run)."""
+    rep = json.load(open(report))
+    plain = json.load(open(plain_report))
+    cur = sqlite3.connect(db).cursor()
+    rows = list(cur.execute("select name, start, end from kernels order by start"))
+    marks = [i for i, r in enumerate(rows) if rep["marker_kernel"] in r[0]]
+    if len(marks) < 2:
+        raise SystemExit("marker launches not found")
+    a, b = marks[-2], marks[-1]
+    inside = rows[a + 1:b]
+    window = (rows[b][1] - rows[a][2]) / 1e3
+    busy = sum(e - st for _, st, e in inside) / 1e3
+    n = rep["generations_between_markers"]
+    per = {}
+    for name, st, e in inside:
+        k = name.replace("bool _Accum", "bf16").replace("(anonymous namespace)::", "").split("(")[0].replace("void ", "")
+        c = per.setdefault(k, [0, 0.0])
+        c[0] += 1
+        c[1] += (e - st) / 1e3
+    lines = ["Kernel-busy share of a generation step on small models (durations in microseconds)",
+             "workload: %s; %d generations between the two marker launches" % (rep["workload"], n),
+             "command: %s" % cmd,
+             "per generation: window %.1f (the workload's own wall-clock under the profiler: %.1f), kernels %.1f = %.1f %% busy; %d launches, mean gap "
+             "between launches %.2f" % (window / n, rep["wall_ms_per_generation"] * 1e3, busy / n, 100 * busy / window, len(inside) // n,
+                                        (window - busy) / max(1, len(inside))),
+             "%-60s %9s %12s %9s %7s" % ("kernel", "launches", "total_us", "avg_us", "pct of window")]
+    for k, (c, t) in sorted(per.items(), key=lambda kv: -kv[1][1]):
+        lines.append("%-60s %9d %12.1f %9.2f %7.2f" % (k[:60], c // n, t / n, t / c, 100 * t / window))
+    lines.append("without the profiler: wall-clock per generation %.1f (%.1f tokens/s): the kernel time above is %.1f %% of it, i.e. the kernels run back "
+                 "to back and what separates them is the dispatch of each dependent launch, inside the durations the trace reports"
+                 % (plain["wall_ms_per_generation"] * 1e3, plain["tokens_per_s"], 100 * busy / n / (plain["wall_ms_per_generation"] * 1e3)))
+    lines.append("one pass issued directly / replayed from a HIP graph of the same launches / host time to enqueue it (plain run):")
+    for label, r in plain["graph_replay"].items():
+        lines.append("  %-14s direct %.1f  graph replay %.1f  host enqueue %.1f  (replay wrote the same logits: %s)"
+                     % (label, r["direct_us"], r["graph_replay_us"], r["host_enqueue_us"], r["same_logits"]))
+    with open(out, "w") as f:
+        f.write("\n".join(lines) + "\n")
+    return open(out).read()
+
+
 def main():
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="what", required=True)
@@ -111,7 +154,16 @@ def main():
     c.add_argument("--manifest", required=True)
     c.add_argument("--cmd", required=True, help="the two commands, separated by ' ;; '")
     c.add_argument("--out", required=True)
+    g = sub.add_parser("gap")
+    g.add_argument("db")
+    g.add_argument("--report", required=True, help="the JSON that workloads --config launch-gap printed in the same run")
+    g.add_argument("--plain-report", required=True, help="the JSON of a run of the same workload without the profiler")
+    g.add_argument("--cmd", required=True)
+    g.add_argument("--out", required=True)
     args = ap.parse_args()
+    if args.what == "gap":
+        print(gap(args.db, args.report, args.plain_report, args.cmd, args.out))
+        return
     if args.what == "trace":
         print(trace(args.db, args.cmd, args.out, args.note))
     else:

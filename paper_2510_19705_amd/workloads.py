@@ -7,6 +7,7 @@ networks, up to a 70B-shaped target (140 GB of bf16 weights resident in HBM).
     python -m paper_2510_19705_amd.workloads --config projections     # its four projections alone, 1 to 1024 rows
     python -m paper_2510_19705_amd.workloads --config independent --distill   # drafters = target logits + noise (std 1.0 / 0.5)
     python -m paper_2510_19705_amd.workloads --config counters --shape 70b    # the workload of the hardware-counter runs
+    python -m paper_2510_19705_amd.workloads --config launch-gap              # small models: kernel-busy share of a step, graph replay
 
 Weights are drawn on the device (seeded normal, residual-writing matrices scaled by 0.1); prompts are uniform-random
 ids.  For each workload: pass time and HBM fraction of every candidate (algorithmic bytes / time / 8 TB/s), pairwise
@@ -405,6 +406,79 @@ def counters(shape_name, n_layers, rows, ctx):
             "order_within_layer": ["qkv", "attn", "o", "gateup", "down"], "sites": sites}
 
 
+def launch_gap(seed=20251019):
+    """Where a generation step's time goes when the models are small (the 1B-shaped early-exit hierarchy, exits
+    2 / 6 / 16, T = (4, 1), prompt 512, 256 tokens, temperature 1): wall-clock per generation; and, for two pass shapes,
+    the same pass issued directly against a replay of the pass captured in a HIP graph (what a device-resident
+    driver built from graphs could gain per pass), plus the host time one pass takes to enqueue.
+
+    Run under `rocprofv3 --kernel-trace` the eight timed generations are bracketed by two launches of a kernel that
+    nothing else here uses (the overlap kernel of the calibration), so that `profsum gap` can add up the kernel time
+    inside the bracket: kernel-busy fraction of a generation, and the mean gap between launches."""
+    import torch
+    assert torch.cuda.is_available(), "needs the GPU"
+    from . import hsd, inputs
+    shape = inputs.SHAPES["1b"]
+    prompt_len, gen, exits, T = 512, 256, (2, 6, 16), (4, 1)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):                                  # the models live on a stream a graph can capture
+        model = random_model(hsd, inputs, torch, shape, seed, 1024, rows_copy_layers=exits[0])
+        h = hsd.Hierarchy([(model, e) for e in exits], T, 1.0, seed)
+        prompt = inputs.make_prompt(shape["vocab"], prompt_len, seed=seed + 1)
+        h.prefill(prompt)
+        h.generate(gen)
+        marker_rows = torch.full((2, 1, 8), 0.125, device="cuda")
+        seeds = [seed + 100 + i for i in range(8)]
+        side.synchronize()
+        hsd.overlap(marker_rows)
+        t0 = time.perf_counter()
+        for sd in seeds:
+            h.set_seed(sd)
+            h.rewind(prompt_len)
+            h.generate(gen)
+        side.synchronize()
+        wall = (time.perf_counter() - t0) / len(seeds)
+        hsd.overlap(marker_rows)
+        side.synchronize()
+        st = h.stats()
+        out = {"config": "launch-gap", "workload": "1B-shaped early-exit hierarchy, exits 2/6/16, T (4, 1), prompt 512, 256 tokens",
+               "generations_between_markers": len(seeds), "wall_ms_per_generation": wall * 1e3, "tokens_per_s": gen / wall,
+               "passes_last_generation": [st.passes[i] for i in range(3)], "marker_kernel": "overlap_kernel", "graph_replay": {}}
+        tok = torch.from_numpy(prompt.astype(np.int32)).cuda()
+        for label, e, m in (("exit2_1row", 2, 1), ("exit6_5rows", 6, 5), ("exit16_6rows", 16, 6)):
+            pos0 = prompt_len - m
+            tk = tok[pos0:prompt_len].contiguous()
+            fn = lambda: model.model_pass(tk, pos0, e, m)
+            direct = _time_on(torch, side, fn, 50)
+            t1 = time.perf_counter()
+            for _ in range(50):
+                fn()
+            host_us = (time.perf_counter() - t1) / 50 * 1e6          # time to enqueue, nothing waited for
+            side.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                ref = model.model_pass(tk, pos0, e, m)
+            replay = _time_on(torch, side, g.replay, 50)
+            same = bool(torch.equal(ref, fn()))                       # the replayed pass wrote the same logits
+            out["graph_replay"][label] = {"direct_us": direct, "graph_replay_us": replay, "host_enqueue_us": host_us, "same_logits": same}
+            log(label, out["graph_replay"][label])
+        h.close()
+        model.close()
+    return out
+
+
+def _time_on(torch, stream, fn, iters):
+    fn()
+    stream.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(iters):
+        fn()
+    e1.record(stream)
+    stream.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / iters
+
+
 def run_distilled(config, stds, seed=20251019, temperature=1.0, gen=None):
     """The same candidates with synthetic closeness: every drafter's logits are the target's plus Gaussian noise of
     the given standard deviations (hsd_hier_set_distilled), which puts acceptance rates in the 0.5-0.9 range the
@@ -484,7 +558,7 @@ def run_distilled(config, stds, seed=20251019, temperature=1.0, gen=None):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", choices=sorted(CONFIGS) + ["microbench", "projections", "counters"], default="independent")
+    ap.add_argument("--config", choices=sorted(CONFIGS) + ["microbench", "projections", "counters", "launch-gap"], default="independent")
     ap.add_argument("--shape", default="70b", help="counters: model shape")
     ap.add_argument("--layers", type=int, default=2, help="counters: layers of that shape")
     ap.add_argument("--rows", type=int, default=4, help="counters: tokens per verify pass")
@@ -496,6 +570,8 @@ def main():
         out = microbench()
     elif args.config == "projections":
         out = projections()
+    elif args.config == "launch-gap":
+        out = launch_gap()
     elif args.config == "counters":
         out = counters(args.shape, args.layers, args.rows, args.ctx)
     elif args.distill:
