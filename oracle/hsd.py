@@ -2,15 +2,16 @@
 
 TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
 
-Follows Alg. 1 in the paper's order: level 0 drafts T_0 tokens one at a time and
-keeps each full distribution; an intermediate level idx repeatedly asks the
-level below for a batch, verifies it (Alg. 2) and collects the verified tokens
-until it holds at least T_idx of them, then returns ALL it collected (so the
-level above may see more than T_idx tokens: Alg. 1 returns `tokens`, not a
-prefix; the footnote to the definition of gamma in Sec. 3.3 notes the same);
-the top level K does one such batch + verification.  Each recursive call
-starts from empty lists, so what a lower level buffered beyond a rejection is
-discarded.
+What Alg. 1 computes, written as levels that gather tokens up to a quota: level 0
+drafts T_0 tokens one at a time and keeps each full distribution; an
+intermediate level idx repeatedly asks the level below for a batch, verifies it
+(Alg. 2) and keeps the verified tokens until it holds at least T_idx of them,
+then hands up ALL it holds (so the level above may see more than T_idx tokens:
+Alg. 1 returns its whole list, not a prefix; the footnote to the definition of
+gamma in Sec. 3.3 notes the same); the top level K does one such batch +
+verification.  Every call starts with nothing gathered, so what a lower level
+held beyond a rejection is discarded.  Pinned by exact enumeration of the output
+law (Thm 3.1) in tests/test_oracle_hsd.py.
 
 A level is anything with `next_dists(context, n_rows)` returning the fp32 rows
 p(. | context[:len-n_rows+1+r]) for r = 0..n_rows-1.  Random decisions go
@@ -54,32 +55,40 @@ class HSD:
         self.tested[idx] += n + (1 if n < t else 0)
         return list(draft_tokens[:n]) + [m], [p_rows[i] for i in range(n + 1)]
 
+    def _draft(self, context, how_many):
+        """Level 0 of Alg. 1: `how_many` tokens one after the other, each with the full row it was drawn from."""
+        drawn, rows = [], []
+        for _ in range(how_many):
+            row = self.levels[0].next_dists(list(context) + drawn, 1)[0]
+            self.passes[0] += 1
+            step = self.calls[0]
+            self.calls[0] += 1
+            drawn.append(self.chooser.sample(0, step, 0, row, None))
+            rows.append(row)
+        return drawn, rows
+
     def run(self, idx, context):
-        """HSD(idx, context) -> (tokens, probs)."""
-        tokens, probs, count = [], [], 0
+        """HSD(idx, context) -> (tokens, probs).
+
+        Written as "a level gathers verified tokens until it has its quota": the lowest level's quota is T_0 drafts;
+        an intermediate level keeps asking the level below for a batch behind what it has gathered so far and keeps
+        what its own Verify lets through, until it holds T_idx tokens, and hands up everything it holds (or exactly
+        T_idx with truncate); the target's quota is one batch."""
         if idx == 0:
-            while count < (self.T[0] if self.K > 0 else 1):
-                p = self.levels[0].next_dists(list(context) + tokens, 1)[0]
-                self.passes[0] += 1
-                call = self.calls[0]
-                self.calls[0] += 1
-                tokens.append(self.chooser.sample(0, call, 0, p, None))
-                probs.append(p)
-                count += 1
-        elif idx == self.K:
-            dt, dp = self.run(idx - 1, context)
-            tokens, probs = self._verify(idx, dt, dp, context)
-        else:
-            while count < self.T[idx]:
-                ctx = list(context) + tokens
-                dt, dp = self.run(idx - 1, ctx)
-                vt, vp = self._verify(idx, dt, dp, ctx)
-                tokens.extend(vt)
-                probs.extend(vp)
-                count += len(vt)
-            if self.truncate:
-                tokens, probs = tokens[:self.T[idx]], probs[:self.T[idx]]
-        return tokens, probs
+            return self._draft(context, self.T[0] if self.K > 0 else 1)
+        top = idx == self.K
+        gathered, rows = [], []
+        while top or len(gathered) < self.T[idx]:
+            behind = list(context) + gathered
+            batch, batch_rows = self.run(idx - 1, behind)
+            kept, kept_rows = self._verify(idx, batch, batch_rows, behind)
+            gathered += kept
+            rows += kept_rows
+            if top:
+                break
+        if self.truncate and not top:
+            gathered, rows = gathered[:self.T[idx]], rows[:self.T[idx]]
+        return gathered, rows
 
     def generate(self, prompt, n_tokens):
         """Call HSD(K, context) until n_tokens are produced; the last round is cut at n_tokens.
