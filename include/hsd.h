@@ -299,6 +299,8 @@ typedef struct {
     int64_t accepted[HSD_MAX_LEVELS];  /* of those, accepted */
     int64_t tested[HSD_MAX_LEVELS];    /* accept tests evaluated (up to and including the first rejection of a call):
                                           accepted / tested is the per-test acceptance frequency */
+    int64_t reused_rows[HSD_MAX_LEVELS]; /* rows of the level's passes that resumed from the hidden states kept by the level
+                                          below instead of recomputing the shallower layers (hsd_hier_set_reuse) */
     int64_t rounds;                    /* HSD(K, .) calls */
     int64_t tokens;                    /* tokens emitted by the target level */
 } hsd_stats;
@@ -306,6 +308,16 @@ typedef struct {
 /* Calls HSD(K, .) until n_tokens are produced; the last round is cut at n_tokens (the sequence keeps
  * the surplus).  out: cap n_tokens.  stats may be NULL. */
 int hsd_generate(hsd_hier*, int n_tokens, int32_t* out, hsd_stats* stats);
+
+/* Hidden-state reuse between early exits of one network (Sec. 5.1: the drafters of the paper's main workload are
+ * earlier exits of the target).  Where the level below a verifier is a shallower exit of the verifier's own network,
+ * every pass through that exit's layer keeps its residual rows by position, and with on != 0 the verifier's pass sends
+ * only the tokens no pass has seen yet (the newest draft or the token a Verify has just emitted) through the shallower
+ * layers and resumes all its rows above them.  The weights of the shallower layers are streamed either way (the newest
+ * token needs them), so at batch 1 this saves arithmetic and activation traffic, not weight traffic.  Results: the
+ * same distributions up to the summation order of kernels chosen for a different row count (fp32 storage: bit for
+ * bit).  Default off.  Takes effect from the next pass. */
+int hsd_hier_set_reuse(hsd_hier*, int on);
 
 /* The two simplifications the latency analysis makes, as switches (appendix "Examining the assumptions of HSD";
  * Thm 3.2).  coin: NULL restores Alg. 2's accept test; otherwise [n_levels] floats, entry i in [0, 1] makes level

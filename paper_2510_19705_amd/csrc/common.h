@@ -105,6 +105,8 @@ struct GemmArgs {
     float eps;
     // outputs
     float* out_f32;                     // EPI_STORE: y [M, N]; EPI_RESID: residual rows [M, N], updated in place
+    float* tap;                         // EPI_RESID: if not null, the new residual rows are also stored here [M, N] (hidden states
+                                        // kept for a deeper exit of the same network to resume from)
     unsigned long long* ss_out;         // EPI_RESID: per row, += sum of squares of the new residual times 2^24
     const float* norm_w;                // EPI_RESID: weight of the norm that reads the new residual
     bf16_t* out_bf16;                   // EPI_RESID: bf16(new residual * norm_w) [M, N] (or null); EPI_SWIGLU: h [M, N/2];

@@ -33,6 +33,11 @@ struct LevelState {
     uint32_t call;      // Philox call index: Verify calls (draft steps at level 0)
     int distill_src;    // >= 0: this level's logits are that level's logits plus noise (synthetic drafter), else -1
     float distill_std;
+    // Hidden-state reuse: when the level above is a deeper exit of the same network, the residual rows after this level's
+    // exit layer are kept by position (every pass of the network through that layer stores them), and the level above
+    // resumes from them instead of recomputing the shallower layers.  Rows [hid_lo, hid_hi) match the current tokens.
+    float* hidden;      // [max_seq, d] fp32, or null
+    int hid_lo, hid_hi;
 };
 
 struct hsd_hier {
@@ -63,6 +68,7 @@ struct hsd_hier {
     bool exactly_T;               // intermediate levels hand up exactly T tokens (ablation)
     bool skip_target_rows;        // set while hsd_generate runs
     hsd_driver_tuning tuning;     // hsd_hier_set_tuning
+    bool reuse_hidden;            // hsd_hier_set_reuse
     hsd_stats stats;
 };
 
@@ -83,9 +89,14 @@ int rows_cap_of(int n_levels, const int* T, int level) {
 }
 
 struct HierLayout {
-    size_t tok, logits, rows[HSD_MAX_LEVELS], result, sampler, softmax, total;
+    size_t tok, logits, rows[HSD_MAX_LEVELS], hidden[HSD_MAX_LEVELS], result, sampler, softmax, total;
     int logit_rows, max_seq, V;
 };
+
+// The level above `i` is a deeper exit of the same network: level i keeps its hidden states for it.
+bool keeps_hidden(int n_levels, const hsd_level* levels, int i) {
+    return i + 1 < n_levels && levels[i + 1].model == levels[i].model && levels[i + 1].exit_layer > levels[i].exit_layer;
+}
 
 int hier_layout(int n_levels, const hsd_level* levels, const int* T, HierLayout* L) {
     if (n_levels < 1 || n_levels > HSD_MAX_LEVELS) HSD_FAIL(HSD_EINVAL, "hierarchy: %d levels outside 1..%d", n_levels, HSD_MAX_LEVELS);
@@ -122,6 +133,10 @@ int hier_layout(int n_levels, const hsd_level* levels, const int* T, HierLayout*
         L->rows[i] = o;
         o += align_up((size_t)rows_cap_of(n_levels, T, i) * L->V * 4, 256);
     }
+    for (int i = 0; i < n_levels; ++i) {
+        L->hidden[i] = o;
+        if (keeps_hidden(n_levels, levels, i)) o += align_up((size_t)L->max_seq * levels[i].model->desc.d * sizeof(float), 256);
+    }
     L->result = o;  o += 256;
     L->sampler = o; o += hsd_sampler_scratch_bytes(L->V);
     L->softmax = o; o += softmax_scratch_bytes(L->logit_rows, L->V);
@@ -137,6 +152,44 @@ int effective_cached(const hsd_hier* h, int idx) {
     return c;
 }
 
+// One pass of `model` over sequence tokens [pos, pos + rows) through `exit_layer` layers (from `from_layer`, resuming
+// from kept hidden rows, if > 0).  Every level that keeps hidden states of this network at a layer the pass goes
+// through gets the rows of this pass, and its interval of valid rows is extended.
+int hier_pass(hsd_hier* h, hsd_model* model, int pos, int rows, int exit_layer, int n_logit_rows, float* logits, bool embedded,
+              int from_layer = 0, const float* resume_rows = nullptr) {
+    PassOpts o;
+    o.from_layer = from_layer;
+    o.resume_rows = resume_rows;
+    int who[HSD_MAX_LEVELS];
+    for (int j = 0; j < h->K && h->reuse_hidden; ++j) {
+        LevelState& J = h->lv[j];
+        if (!J.hidden || J.model != model || J.exit_layer <= from_layer || J.exit_layer > exit_layer) continue;
+        bool dup = false;                                 // two levels may keep the same layer of one network: one copy each
+        for (int t = 0; t < o.n_taps; ++t) dup = dup || o.tap_layer[t] == J.exit_layer;
+        if (dup) continue;
+        who[o.n_taps] = j;
+        o.tap_layer[o.n_taps] = J.exit_layer;
+        o.tap_rows[o.n_taps] = J.hidden + (size_t)pos * model->desc.d;
+        ++o.n_taps;
+    }
+    const bool plain = o.n_taps == 0 && from_layer == 0;
+    if (int rc = model_pass(model, h->tok_dev + pos, pos, rows, exit_layer, n_logit_rows, logits, embedded, plain ? nullptr : &o)) return rc;
+    for (int t = 0; t < o.n_taps; ++t) {
+        LevelState& J = h->lv[who[t]];
+        if (J.hid_hi > J.hid_lo && pos >= J.hid_lo && pos <= J.hid_hi) J.hid_hi = std::max(J.hid_hi, pos + rows);
+        else { J.hid_lo = pos; J.hid_hi = pos + rows; }
+    }
+    return HSD_OK;
+}
+
+// No kept hidden row beyond the first `valid` tokens matches the sequence any more.
+void clamp_hidden(hsd_hier* h, int valid) {
+    for (int j = 0; j <= h->K; ++j) {
+        h->lv[j].hid_hi = std::min(h->lv[j].hid_hi, valid);
+        if (h->lv[j].hid_hi <= h->lv[j].hid_lo) h->lv[j].hid_lo = h->lv[j].hid_hi = 0;
+    }
+}
+
 // Feeds sequence tokens [start, len) through the level; logits of the last n_logit_rows.
 int level_pass(hsd_hier* h, int idx, int start, int n_logit_rows) {
     LevelState& L = h->lv[idx];
@@ -145,13 +198,29 @@ int level_pass(hsd_hier* h, int idx, int start, int n_logit_rows) {
     while (h->len - pos > max_rows) {
         int chunk = std::min(max_rows, h->len - pos - n_logit_rows);      // keep the logit rows for the last chunk
         if (chunk < 1) HSD_FAIL(HSD_ECAPACITY, "pass: %d logit rows do not fit a pass of %d rows", n_logit_rows, max_rows);
-        if (int rc = model_pass(L.model, h->tok_dev + pos, pos, chunk, L.exit_layer, 0, nullptr)) return rc;
+        if (int rc = hier_pass(h, L.model, pos, chunk, L.exit_layer, 0, nullptr, false)) return rc;
         h->stats.passes[idx]++;
         h->stats.pass_rows[idx] += chunk;
         pos += chunk;
     }
-    const bool embedded = h->pre_model == L.model && h->pre_serial == L.model->pass_serial && h->pre_pos == pos && h->len - pos == 1;
-    if (int rc = model_pass(L.model, h->tok_dev + pos, pos, h->len - pos, L.exit_layer, n_logit_rows, h->logits, embedded)) return rc;
+    // Hidden-state reuse: the level below is a shallower exit of this network and has kept its residual rows for a
+    // prefix [pos, r) of this pass: only the rows from r on go through the shallower layers (they are the tokens no
+    // pass has seen yet: the newest draft, or the token a Verify has just emitted), then all rows resume above them.
+    const LevelState* B = idx > 0 ? &h->lv[idx - 1] : nullptr;
+    if (h->reuse_hidden && B && B->hidden && B->hid_lo <= pos && B->hid_hi > pos) {
+        const int r = std::min(B->hid_hi, h->len);
+        if (r < h->len) {
+            const bool emb = h->pre_model == L.model && h->pre_serial == L.model->pass_serial && h->pre_pos == r && h->len - r == 1;
+            if (int rc = hier_pass(h, L.model, r, h->len - r, B->exit_layer, 0, nullptr, emb)) return rc;
+        }
+        if (int rc = hier_pass(h, L.model, pos, h->len - pos, L.exit_layer, n_logit_rows, h->logits, false, B->exit_layer,
+                               B->hidden + (size_t)pos * L.model->desc.d))
+            return rc;
+        h->stats.reused_rows[idx] += r - pos;
+    } else {
+        const bool embedded = h->pre_model == L.model && h->pre_serial == L.model->pass_serial && h->pre_pos == pos && h->len - pos == 1;
+        if (int rc = hier_pass(h, L.model, pos, h->len - pos, L.exit_layer, n_logit_rows, h->logits, embedded)) return rc;
+    }
     h->stats.passes[idx]++;
     h->stats.pass_rows[idx] += h->len - pos;
     if (L.distill_src < 0 || n_logit_rows == 0) return HSD_OK;
@@ -164,10 +233,10 @@ int level_pass(hsd_hier* h, int idx, int start, int n_logit_rows) {
     while (h->len - sp > smax) {
         const int chunk = std::min(smax, h->len - sp - n_logit_rows);
         if (chunk < 1) HSD_FAIL(HSD_ECAPACITY, "pass: %d logit rows do not fit a pass of %d rows of the source level", n_logit_rows, smax);
-        if (int rc = model_pass(S.model, h->tok_dev + sp, sp, chunk, S.exit_layer, 0, nullptr)) return rc;
+        if (int rc = hier_pass(h, S.model, sp, chunk, S.exit_layer, 0, nullptr, false)) return rc;
         sp += chunk;
     }
-    if (int rc = model_pass(S.model, h->tok_dev + sp, sp, h->len - sp, S.exit_layer, n_logit_rows, h->logits)) return rc;
+    if (int rc = hier_pass(h, S.model, sp, h->len - sp, S.exit_layer, n_logit_rows, h->logits, false)) return rc;
     return launch_add_noise(h->logits, n_logit_rows, h->V, h->seed, (uint32_t)idx, h->len - n_logit_rows, L.distill_std, h->stream);
 }
 
@@ -273,6 +342,7 @@ int verify_step(hsd_hier* h, int idx, int t, const float* q_dev, int* n_out) {
         if (J.model == L.model && J.exit_layer <= L.exit_layer) J.cached_len = valid;
         else J.cached_len = std::min(J.cached_len, valid);
     }
+    clamp_hidden(h, valid);
     L.count += n + 1;
     h->stats.drafted[idx] += t;
     h->stats.accepted[idx] += n;
@@ -306,6 +376,7 @@ int run_level(hsd_hier* h, int idx, int* count_out) {
             h->len -= L.count - h->T[idx];
             L.count = h->T[idx];
             for (int j = 0; j <= h->K; ++j) h->lv[j].cached_len = std::min(h->lv[j].cached_len, h->len);
+            clamp_hidden(h, h->len);
             h->pre_model = nullptr;
         }
     }
@@ -366,7 +437,8 @@ extern "C" int hsd_hier_create(int n_levels, const hsd_level* levels, const int*
     h->sampler_scratch = wb + L.sampler;
     h->softmax_scratch = (float*)(wb + L.softmax);
     for (int i = 0; i < n_levels; ++i) {
-        h->lv[i] = LevelState{levels[i].model, levels[i].exit_layer, 0, (float*)(wb + L.rows[i]), rows_cap_of(n_levels, T, i), 0, 0u, -1, 0.f};
+        h->lv[i] = LevelState{levels[i].model, levels[i].exit_layer, 0, (float*)(wb + L.rows[i]), rows_cap_of(n_levels, T, i), 0, 0u, -1, 0.f,
+                              keeps_hidden(n_levels, levels, i) ? (float*)(wb + L.hidden[i]) : nullptr, 0, 0};
         if (i < h->K) h->T[i] = T[i];
     }
     h->tok_host.assign(h->max_seq, 0);
@@ -378,6 +450,7 @@ extern "C" int hsd_hier_create(int n_levels, const hsd_level* levels, const int*
     h->exactly_T = false;
     h->skip_target_rows = false;
     h->tuning = default_driver_tuning();
+    h->reuse_hidden = false;
     for (int i = 0; i < HSD_MAX_LEVELS; ++i) h->coin[i] = -1.f;
     reset_counters(h);
     hipError_t e = hipHostMalloc((void**)&h->mailbox, 68 * sizeof(int32_t), hipHostMallocMapped);
@@ -422,6 +495,13 @@ extern "C" int hsd_hier_set_tuning(hsd_hier* h, const hsd_driver_tuning* t) {
     return HSD_OK;
 }
 
+extern "C" int hsd_hier_set_reuse(hsd_hier* h, int on) {
+    if (!h) HSD_FAIL(HSD_EINVAL, "hsd_hier_set_reuse: null pointer");
+    h->reuse_hidden = on != 0;
+    clamp_hidden(h, 0);             // rows are kept from the next pass on
+    return HSD_OK;
+}
+
 extern "C" int hsd_hier_set_ablation(hsd_hier* h, const float* coin, int exactly_T) {
     if (!h) HSD_FAIL(HSD_EINVAL, "hsd_hier_set_ablation: null pointer");
     if (coin)
@@ -449,6 +529,7 @@ static int prefill_from(hsd_hier* h, const int32_t* prompt, int n, int n_cached,
     HSD_HIP(hipMemcpyAsync(h->tok_dev, h->tok_host.data(), (size_t)n * 4, hipMemcpyHostToDevice, h->stream));
     HSD_HIP(hipStreamSynchronize(h->stream));
     reset_counters(h);
+    clamp_hidden(h, 0);
     // every network once, through its deepest exit in the hierarchy
     for (int i = 0; i <= h->K; ++i) {
         bool deepest = true;
@@ -460,7 +541,7 @@ static int prefill_from(hsd_hier* h, const int32_t* prompt, int n, int n_cached,
         const int max_rows = h->lv[i].model->desc.max_rows;
         for (int pos = n_cached; pos < n - 1; pos += max_rows) {
             const int chunk = std::min(max_rows, n - 1 - pos);
-            if (int rc = model_pass(h->lv[i].model, h->tok_dev + pos, pos, chunk, h->lv[i].exit_layer, 0, nullptr)) return rc;
+            if (int rc = hier_pass(h, h->lv[i].model, pos, chunk, h->lv[i].exit_layer, 0, nullptr, false)) return rc;
         }
     }
     HSD_HIP(hipStreamSynchronize(h->stream));
@@ -491,6 +572,7 @@ extern "C" int hsd_rewind(hsd_hier* h, int n) {
     h->len = n;
     h->pre_model = nullptr;
     for (int i = 0; i <= h->K; ++i) h->lv[i].cached_len = std::min(h->lv[i].cached_len, n - 1);
+    clamp_hidden(h, n - 1);
     reset_counters(h);
     return HSD_OK;
 }

@@ -352,6 +352,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
                 if constexpr (EPI == EPI_RESID) {
                     v = pre_x[i] + s;
                     if (g.out_bf16) g.out_bf16[(size_t)ml * N + n] = (bf16_t)(v * pre_nw[i]);
+                    if (g.tap) g.tap[(size_t)ml * N + n] = v;
                 } else {
                     v = s * pre_inv[i];
                 }
@@ -490,6 +491,7 @@ __global__ __launch_bounds__(512) void gemv_bf16_kernel(const GemmArgs g) {
             v = pre_x + s;
             g.out_f32[at] = v;
             if (g.out_bf16) g.out_bf16[at] = (bf16_t)(v * pre_nw);
+            if (g.tap) g.tap[at] = v;
         }
         if (tid < R * MB) sq[er][em] = v * v;
         __syncthreads();
@@ -725,6 +727,7 @@ int launch_gemv_bf16(const GemmArgs& g0, int epi, hipStream_t s) {
         } else {
             g.out_f32 = g0.out_f32 + (size_t)m0 * g0.N;
             if (g0.out_bf16) g.out_bf16 = g0.out_bf16 + (size_t)m0 * g0.N;
+            if (g0.tap) g.tap = g0.tap + (size_t)m0 * g0.N;
         }
         int rc;
         if (epi == EPI_ROPE) rc = launch_gemv_mb<2, EPI_ROPE>(g, s);

@@ -43,6 +43,31 @@ __global__ void embed_kernel(const int32_t* __restrict__ tok, const T* __restric
     }
 }
 
+// The pass resumes above an exit another pass has already reached (hidden-state reuse between exits of one
+// network): x[m, :] = rows[m, :], the residual stream kept at that exit, and, with ss != null, what the next layer's
+// normalising GEMM reads, exactly as the embedding kernel leaves it for the first layer.
+__global__ void resume_rows_kernel(const float* __restrict__ rows, float* __restrict__ x, int d, unsigned long long* __restrict__ ss,
+                                   unsigned long long* __restrict__ ss_other, const float* __restrict__ norm_w, bf16_t* __restrict__ xn) {
+    __shared__ float sh[16];
+    const float* src = rows + (size_t)blockIdx.x * d;
+    float* dst = x + (size_t)blockIdx.x * d;
+    float acc = 0.f;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) {
+        const float v = src[i];
+        dst[i] = v;
+        if (xn) xn[(size_t)blockIdx.x * d + i] = (bf16_t)(v * norm_w[i]);
+        acc += v * v;
+    }
+    if (ss) {
+        acc = block_sum_256(acc, sh);
+        if (threadIdx.x < SS_SLOTS) {
+            const int at = threadIdx.x * HSD_MAX_PASS_ROWS + blockIdx.x;
+            ss[at] = threadIdx.x == 0 ? (unsigned long long)((double)acc * 16777216.0 + 0.5) : 0ull;
+            ss_other[at] = 0ull;
+        }
+    }
+}
+
 // Row r (grid.x) of x: x += sum_s part[s][r] (fixed order; part may be null), then
 // xn[r] = x * w / sqrt(mean(x^2) + eps).  `part` rows and xn rows are indexed from 0, x rows from row0.
 template <typename T>
@@ -228,6 +253,13 @@ int launch_embed(const int32_t* tok, const void* E, float* x, int m, int d, int 
         embed_kernel<bf16_t><<<m, 256, 0, s>>>(tok, (const bf16_t*)E, x, d, vocab, ss, ss_other, norm_w, (bf16_t*)xn);
     else
         embed_kernel<float><<<m, 256, 0, s>>>(tok, (const float*)E, x, d, vocab, nullptr, nullptr, nullptr, nullptr);
+    HSD_LAUNCH_CHECK();
+    return HSD_OK;
+}
+
+int launch_resume_rows(const float* rows, float* x, int m, int d, unsigned long long* ss, unsigned long long* ss_other,
+                       const float* norm_w, void* xn, hipStream_t s) {
+    resume_rows_kernel<<<m, 256, 0, s>>>(rows, x, d, ss, ss_other, norm_w, (bf16_t*)xn);
     HSD_LAUNCH_CHECK();
     return HSD_OK;
 }

@@ -54,8 +54,18 @@ struct hsd_model {
     std::vector<int> prof_site;
 };
 
+// Hidden-state reuse between exits of one network: a pass may start above layer `from_layer`, from the residual rows
+// another pass kept there (`resume_rows` [rows, d] fp32), and may keep its own residual rows after given layers
+// (`tap_rows[i]` [rows, d] receives them after layer `tap_layer[i]`, from_layer < tap_layer[i] <= exit layer).
+struct PassOpts {
+    int from_layer = 0;
+    const float* resume_rows = nullptr;
+    int n_taps = 0;
+    int tap_layer[HSD_MAX_LEVELS] = {};
+    float* tap_rows[HSD_MAX_LEVELS] = {};
+};
 int model_pass(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows, int exit_layer, int n_logit_rows,
-               float* logits_dev, bool embedded = false);
+               float* logits_dev, bool embedded = false, const PassOpts* opts = nullptr);
 // The same pass through the deepest of `exits` (ascending layer counts), with the last n_logit_rows rows' logits of
 // every listed exit: logits_dev [n_exits][n_logit_rows][vocab].
 int model_pass_exits(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows, const int* exits, int n_exits,
@@ -64,6 +74,8 @@ int model_pass_exits(hsd_model* m, const int32_t* tokens_dev, int pos0, int rows
 // kernels_layer.hip
 int launch_embed(const int32_t* tok, const void* E, float* x, int m, int d, int vocab, int dtype, unsigned long long* ss,
                  unsigned long long* ss_other, const float* norm_w, void* xn, hipStream_t s);
+int launch_resume_rows(const float* rows, float* x, int m, int d, unsigned long long* ss, unsigned long long* ss_other,
+                       const float* norm_w, void* xn, hipStream_t s);
 int launch_resid_rmsnorm(float* x, const float* part, int ksplit, int part_rows, int part_row0, const float* w, void* xn,
                          int rows, int row0, int d, float eps, int dtype, hipStream_t s);
 int launch_rope_kv(const float* part, int ksplit, int m, void* q, void* kv_layer, const int32_t* pages, int pos0, int n_q,

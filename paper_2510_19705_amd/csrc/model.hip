@@ -338,9 +338,16 @@ struct BatchGeom {
     int batch, m_seq, max_len;
 };
 
+static float* tap_after_layer(const PassOpts* o, int layer_count) {
+    if (o)
+        for (int i = 0; i < o->n_taps; ++i)
+            if (o->tap_layer[i] == layer_count) return o->tap_rows[i];
+    return nullptr;
+}
+
 // fp32 storage: plain kernels, one per step (the small correctness configuration).
 static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
-                    float* logits, bool embedded, const BatchGeom* bg) {
+                    float* logits, bool embedded, const BatchGeom* bg, const PassOpts* opts) {
     const hsd_model_desc& d = m->desc;
     hipStream_t s = m->stream;
     const int nq = d.n_q * d.hd, nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
@@ -348,9 +355,14 @@ static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, const 
     const size_t logit_stride = (size_t)n_logit_rows * d.vocab;
     int ei = 0;
     int rc;
-    if (!embedded && (rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, nullptr, nullptr, nullptr, nullptr, s))) return rc;
+    const int l0 = opts ? opts->from_layer : 0;
+    if (l0 > 0) {       // resume above an exit another pass has reached: its residual rows are this pass's
+        HSD_HIP(hipMemcpyAsync(m->x, opts->resume_rows, (size_t)rows * d.d * sizeof(float), hipMemcpyDeviceToDevice, s));
+    } else if (!embedded && (rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, nullptr, nullptr, nullptr, nullptr, s))) {
+        return rc;
+    }
     const float* pending = nullptr;     // output of the previous down projection, not yet added to x
-    for (int l = 0; l < exit_layer; ++l) {
+    for (int l = l0; l < exit_layer; ++l) {
         const LayerWeights& L = m->layers[l];
         void* kv_layer = m->kv + m->kv_layer_bytes * l;
         if ((rc = launch_resid_rmsnorm(m->x, pending, 1, rows, 0, L.norm1, m->xn, rows, 0, d.d, d.eps, d.dtype, s))) return rc;
@@ -388,6 +400,13 @@ static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, const 
             if ((rc = launch_gemm_f32((const float*)m->h, (const float*)L.wd, m->part, rows, d.d, d.ffn, false, s))) return rc;
         }
         pending = m->part;
+        if (float* tap = tap_after_layer(opts, l + 1)) {
+            // the residual rows after this layer are kept: the pending projection goes into x now (the same addition the
+            // next step would make; the normalised rows it also writes are overwritten there)
+            if ((rc = launch_resid_rmsnorm(m->x, pending, 1, rows, 0, m->norm_f, m->xn, rows, 0, d.d, d.eps, d.dtype, s))) return rc;
+            pending = nullptr;
+            HSD_HIP(hipMemcpyAsync(tap, m->x, (size_t)rows * d.d * sizeof(float), hipMemcpyDeviceToDevice, s));
+        }
         if (l + 1 == exits[ei] && l + 1 < exit_layer) {
             // an exit on the way: the pending projection goes into x for every row (the deeper layers need them
             // all), the final norm of all rows into xn, the head reads the logit rows
@@ -413,7 +432,8 @@ static int pass_f32(hsd_model* m, const int32_t* tok, int pos0, int rows, const 
 // RMSNorm: they store bf16(x * w_norm) into m->xn and add the rows' sums of squares into m->ss[1]
 // (second norm of the layer) or m->ss[0] (first norm of the next layer, or the final norm at the exit);
 // the GEMM that consumes m->xn multiplies by 1/rms in its epilogue.
-static int launch_site_bf16(hsd_model* m, int site, int l, int pos0, int rows, const float* next_norm_w, const BatchGeom* bg = nullptr) {
+static int launch_site_bf16(hsd_model* m, int site, int l, int pos0, int rows, const float* next_norm_w, const BatchGeom* bg = nullptr,
+                            float* tap = nullptr) {
     const hsd_model_desc& d = m->desc;
     hipStream_t s = m->stream;
     const int nq = d.n_q * d.hd, nqkv = (d.n_q + 2 * d.n_kv) * d.hd;
@@ -449,7 +469,7 @@ static int launch_site_bf16(hsd_model* m, int site, int l, int pos0, int rows, c
             return launch_gemm_bf16(g, EPI_SWIGLU, gemm_plan(rows, 2 * d.ffn, d.d, EPI_SWIGLU, tn), s);
         case HSD_SITE_DOWN:
             g.a = (const bf16_t*)m->h; g.wp = (const bf16x8*)(rowk ? L.wd_rows : L.wd); g.N = d.d; g.K = d.ffn;
-            g.out_f32 = m->x; g.ss_out = m->ss[0]; g.norm_w = next_norm_w; g.out_bf16 = (bf16_t*)m->xn;
+            g.out_f32 = m->x; g.ss_out = m->ss[0]; g.norm_w = next_norm_w; g.out_bf16 = (bf16_t*)m->xn; g.tap = tap;
             return rowk ? launch_gemv_bf16(g, EPI_RESID, s) : launch_gemm_bf16(g, EPI_RESID, gemm_plan(rows, d.d, d.ffn, EPI_RESID, tn), s);
         default:
             HSD_FAIL(HSD_EINVAL, "unknown site %d", site);
@@ -469,20 +489,25 @@ static int launch_head_bf16(hsd_model* m, const void* xn, int rows, int n_logit_
 }
 
 static int pass_bf16(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
-                     float* logits, bool embedded, const BatchGeom* bg) {
+                     float* logits, bool embedded, const BatchGeom* bg, const PassOpts* opts) {
     const hsd_model_desc& d = m->desc;
     const int exit_layer = exits[n_exits - 1];
     const size_t logit_stride = (size_t)n_logit_rows * d.vocab;
     int ei = 0;
     int rc;
-    if (!embedded &&
-        (rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, m->ss[0], m->ss[1], m->layers[0].norm1, m->xn, m->stream)))
+    const int l0 = opts ? opts->from_layer : 0;
+    if (l0 > 0) {       // resume above an exit another pass has reached, from the residual rows it kept there
+        if ((rc = launch_resume_rows(opts->resume_rows, m->x, rows, d.d, m->ss[0], m->ss[1], m->layers[l0].norm1, m->xn, m->stream))) return rc;
+    } else if (!embedded &&
+               (rc = launch_embed(tok, m->embed, m->x, rows, d.d, d.vocab, d.dtype, m->ss[0], m->ss[1], m->layers[0].norm1, m->xn, m->stream))) {
         return rc;
-    for (int l = 0; l < exit_layer; ++l) {
+    }
+    for (int l = l0; l < exit_layer; ++l) {
         const float* next_norm = l + 1 == exit_layer ? m->norm_f : m->layers[l + 1].norm1;
         for (int site = HSD_SITE_QKV; site <= HSD_SITE_DOWN; ++site) {
             SiteTimer t(m, site);
-            if ((rc = launch_site_bf16(m, site, l, pos0, rows, next_norm, bg))) return rc;
+            // the down projection's epilogue also stores the residual rows a deeper exit may resume from
+            if ((rc = launch_site_bf16(m, site, l, pos0, rows, next_norm, bg, site == HSD_SITE_DOWN ? tap_after_layer(opts, l + 1) : nullptr))) return rc;
         }
         if (l + 1 == exits[ei] && l + 1 < exit_layer) {
             // an exit on the way: m->xn holds x scaled by the next layer's norm weights, the head needs the final
@@ -552,12 +577,13 @@ extern "C" int hsd_site_kernel(const hsd_model* m, int site, int rows, char* nam
 
 // One pass: rows tokens at positions pos0.., layers [0, exit_layer), logits of the last n_logit_rows rows.
 static int pass_checked(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
-                        float* logits, bool embedded, const BatchGeom* bg = nullptr);
+                        float* logits, bool embedded, const BatchGeom* bg = nullptr, const PassOpts* opts = nullptr);
 
 // embedded: row 0 of the residual stream (and, bf16, of the normalised input and the sums of squares) already holds
 // the one token of this pass, left there by the fused sampler (EmbedNext); only for rows == 1.
-int model_pass(hsd_model* m, const int32_t* tok, int pos0, int rows, int exit_layer, int n_logit_rows, float* logits, bool embedded) {
-    return pass_checked(m, tok, pos0, rows, &exit_layer, 1, n_logit_rows, logits, embedded && rows == 1);
+int model_pass(hsd_model* m, const int32_t* tok, int pos0, int rows, int exit_layer, int n_logit_rows, float* logits, bool embedded,
+               const PassOpts* opts) {
+    return pass_checked(m, tok, pos0, rows, &exit_layer, 1, n_logit_rows, logits, embedded && rows == 1, nullptr, opts);
 }
 
 int model_pass_exits(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
@@ -573,7 +599,7 @@ EmbedNext embed_next_of(const hsd_model* m) {
 }
 
 static int pass_checked(hsd_model* m, const int32_t* tok, int pos0, int rows, const int* exits, int n_exits, int n_logit_rows,
-                        float* logits, bool embedded, const BatchGeom* bg) {
+                        float* logits, bool embedded, const BatchGeom* bg, const PassOpts* opts) {
     const hsd_model_desc& d = m->desc;
     if (!exits || n_exits < 1 || n_exits > d.n_layers) HSD_FAIL(HSD_EINVAL, "pass: %d exits", n_exits);
     for (int i = 0; i < n_exits; ++i)
@@ -589,9 +615,18 @@ static int pass_checked(hsd_model* m, const int32_t* tok, int pos0, int rows, co
     if (!m->head_loaded) HSD_FAIL(HSD_ESTATE, "pass: embedding / head not loaded");
     for (int l = 0; l < exit_layer; ++l)
         if (!m->layer_loaded[l]) HSD_FAIL(HSD_ESTATE, "pass: layer %d not loaded", l);
+    if (opts) {
+        if (opts->from_layer < 0 || opts->from_layer >= exit_layer || (opts->from_layer > 0 && !opts->resume_rows))
+            HSD_FAIL(HSD_EINVAL, "pass: resume layer %d outside 0..%d or without rows", opts->from_layer, exit_layer - 1);
+        if (opts->n_taps < 0 || opts->n_taps > HSD_MAX_LEVELS) HSD_FAIL(HSD_EINVAL, "pass: %d taps", opts->n_taps);
+        for (int i = 0; i < opts->n_taps; ++i)
+            if (opts->tap_layer[i] <= opts->from_layer || opts->tap_layer[i] > exit_layer || !opts->tap_rows[i])
+                HSD_FAIL(HSD_EINVAL, "pass: tap %d after layer %d outside %d..%d", i, opts->tap_layer[i], opts->from_layer + 1, exit_layer);
+        if (opts->from_layer > 0 && embedded) HSD_FAIL(HSD_EINVAL, "pass: a resumed pass embeds nothing");
+    }
     ++m->pass_serial;
-    return d.dtype == HSD_BF16 ? pass_bf16(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits, embedded, bg)
-                               : pass_f32(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits, embedded, bg);
+    return d.dtype == HSD_BF16 ? pass_bf16(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits, embedded, bg, opts)
+                               : pass_f32(m, tok, pos0, rows, exits, n_exits, n_logit_rows, logits, embedded, bg, opts);
 }
 
 extern "C" int hsd_model_set_tuning(hsd_model* m, const hsd_kernel_tuning* t) {

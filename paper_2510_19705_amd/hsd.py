@@ -60,7 +60,8 @@ class DriverTuning(C.Structure):
 class Stats(C.Structure):
     _fields_ = [("passes", C.c_int64 * MAX_LEVELS), ("pass_rows", C.c_int64 * MAX_LEVELS),
                 ("drafted", C.c_int64 * MAX_LEVELS), ("accepted", C.c_int64 * MAX_LEVELS),
-                ("tested", C.c_int64 * MAX_LEVELS), ("rounds", C.c_int64), ("tokens", C.c_int64)]
+                ("tested", C.c_int64 * MAX_LEVELS), ("reused_rows", C.c_int64 * MAX_LEVELS), ("rounds", C.c_int64),
+                ("tokens", C.c_int64)]
 
 
 _vp, _i, _sz, _f, _d = C.c_void_p, C.c_int, C.c_size_t, C.c_float, C.c_double
@@ -77,6 +78,7 @@ _SIGS = {
     "hsd_model_pass": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
     "hsd_model_set_batch": (_i, [_vp, _i, _i, C.POINTER(C.c_int32)]),
     "hsd_model_pass_batch": (_i, [_vp, _vp, C.POINTER(C.c_int32), _i, _i, _i, _vp]),
+    "hsd_hier_set_reuse": (_i, [_vp, _i]),
     "hsd_hier_set_ablation": (_i, [_vp, C.POINTER(C.c_float), _i]),
     "hsd_hier_set_distilled": (_i, [_vp, _i, _i, _f]),
     "hsd_stats_cost": (C.c_double, [C.POINTER(Stats), _i, C.POINTER(C.c_double)]),
@@ -533,6 +535,10 @@ class Hierarchy:
     def set_tuning(self, **settings):
         """hsd_hier_set_tuning: the driver's choices for this hierarchy = the defaults with `settings` replaced."""
         _check(lib.hsd_hier_set_tuning(self.handle, C.byref(driver_tuning(**settings)) if settings else None))
+
+    def set_reuse(self, on=True):
+        """hsd_hier_set_reuse: verifier passes resume from the hidden states the shallower exit below has kept."""
+        _check(lib.hsd_hier_set_reuse(self.handle, int(on)))
 
     def set_ablation(self, coin=None, exactly_T=False):
         """hsd_hier_set_ablation: coin = per-level fixed acceptance probabilities (entry 0 ignored, negative = real)."""
