@@ -198,6 +198,26 @@ def big_configuration(args, torch, hsd, inputs, workloads):
                 "sites_ms_in_32_tokens": {k: round(v[1], 3) for k, v in sites.items()},
                 "sites_launches_in_32_tokens": {k: v[0] for k, v in sites.items()}}
     h.close()
+    # ---- the same networks with synthetic closeness along the chain 1B -> 8B -> 70B ------------------------------------
+    # Random-init networks of different shapes overlap by chance only (alpha ~ 0.48 above, whatever the pair), so the
+    # calibrated selection can only ever be a single draft.  Trained model families are graded: a model is closest to
+    # the next size up.  Stand-in: the 8B-shaped level takes the target's logits + noise of std 0.3, the 1B-shaped one
+    # the 8B level's + noise of std 0.8 (hsd_hier_set_distilled), each still running (and being priced at) its own pass.
+    chain = None
+    if not args.brief:
+        sub = [0, 2, K]
+        d = workloads.distilled_study(hsd, [levels[i] for i in sub], [names[i] for i in sub], [cost[i] for i in sub], prompt,
+                                      [0.8, 0.3], True, 64, TEMPERATURE, SEED, n_cached=prompt_len - 1)
+        chain = {"workload": "the headline's 1B / 8B / 70B-shaped networks (same prompt, 64 tokens per run), drafters made close "
+                             "synthetically: 8B level = the target's logits + Gaussian noise of std 0.3, 1B level = the 8B level's + "
+                             "noise of std 0.8; every run priced with the calibrated cost per pass (the side passes that produce "
+                             "the source logits make wall-clock meaningless)",
+                 "cost_ms": d["cost_ms"], "alpha": d["alpha"], "selected": d["selected"],
+                 "artificial_ms_per_token": {k: round(v["artificial_ms_per_token"], 4) for k, v in d["runs"].items()},
+                 "per_test_acceptance": {k: v["per_test_acceptance"] for k, v in d["runs"].items()},
+                 "selected_vs_best_single_draft": d["selected_vs_best_single_draft"]}
+        log("chain-distilled study: selected %s T %s, %.3f x the best single draft" % (
+            d["selected"]["levels"], d["selected"]["T"], d["selected_vs_best_single_draft"]))
     best_single = None
     for k, v in results.items():
         if k.startswith("single_draft_") and (best_single is None or v["tokens_per_s"] > best_single["tokens_per_s"]):
@@ -209,7 +229,8 @@ def big_configuration(args, torch, hsd, inputs, workloads):
            "hsd": results["selected"], "best_single_draft": best_single, "autoregressive": results.get("autoregressive"),
            "full_hierarchy": results.get("full_hierarchy"),
            "runs": {k: round(v["tokens_per_s"], 2) for k, v in results.items()},
-           "verify_pass": verify_pass, "verify_pass_selected": passes, "roofline": roofline, "acc_stats": st}
+           "verify_pass": verify_pass, "verify_pass_selected": passes, "roofline": roofline, "acc_stats": st,
+           "chain_distilled": chain}
     for m in models.values():
         m.close()
     del models, levels, h, tokens
@@ -433,6 +454,7 @@ def main():
         "verify_pass": big["verify_pass"], "verify_pass_selected": big["verify_pass_selected"],
         "verify_pass_7b_shaped_4_layers_ctx4096": stack7b, "verify_pass_8b_shaped_4_layers_ctx8192": stack8b,
         "mfma_util": mfma,
+        "config_5_networks_chain_distilled": big["chain_distilled"],
         "config_1b_early_exit": small, "config_3_networks_distilled": distilled,
         "roofline": big["roofline"], "cpu_baseline": cpu,
     }

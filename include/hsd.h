@@ -330,10 +330,13 @@ int hsd_hier_set_ablation(hsd_hier*, const float* coin, int exactly_T);
 /* Synthetic drafter (workload construction for hierarchies of random-init networks, whose distributions would
  * otherwise overlap by chance only; Sec. 5 works with drafters whose acceptance rates are 0.6-0.9): level `level`
  * (below the target) still runs its own pass, which is what it costs and what the statistics count, but takes as
- * its logits those of level `source_level` (above it, not synthetic itself) at the same contexts plus
+ * its logits those of level `source_level` (above it) at the same contexts plus
  * noise_std * n(level, position, vocabulary entry), n standard normal from Philox4x32-10 blocks with counter
- * (entry / 4, position, level | 2^31, 0x4E4F4953) by Box-Muller.  The source's side passes are not counted, so only
- * the fixed-cost accounting (hsd_stats_cost) is meaningful for such a run, not its wall-clock time.
+ * (entry / 4, position, level | 2^31, 0x4E4F4953) by Box-Muller.  The source may be synthetic itself: then its logits
+ * are its own source's plus its own noise, and so on up to a real network, so that a chain of sources gives levels
+ * that each differ from the next one up by one noise term (neighbouring levels close, distant ones less so: the
+ * structure a hierarchy exploits, Sec. 3.2).  The side passes of the real network at the chain's end are not counted,
+ * so only the fixed-cost accounting (hsd_stats_cost) is meaningful for such a run, not its wall-clock time.
  * source_level < 0 switches it off. */
 int hsd_hier_set_distilled(hsd_hier*, int level, int source_level, float noise_std);
 

@@ -7,6 +7,8 @@ The paper's drafters are smaller trained models whose distributions are close to
 description asks for the closeness to be produced synthetically: level i's next-token logits are the source level's
 logits at the same context plus N(0, std_i^2) noise per vocabulary entry, fixed by (seed, level, position), so that a
 level is still a deterministic function of its context, as the problem statement of Sec. 3.2 requires of a model.
+The source may be synthetic itself (a chain: each level is the next one up plus one noise term, so neighbours are
+close and distant levels less so).
 Nothing here is from the paper beyond that requirement; the generator is spelled out so that the library can
 reproduce it:
     block   = Philox4x32-10(key = seed, counter = (v // 4, pos, level | 2^31, 0x4E4F4953))
@@ -50,12 +52,21 @@ class DistilledLevel(_decoder.Level):
         super().__init__(own_decoder, own_exit, temperature)
         self.source, self.level_index, self.std, self.seed = source, level_index, float(std), int(seed)
 
-    def next_dists(self, context, n_rows):
-        z = np.array(self.source.decoder.next_logits(context, n_rows, self.source.exit_layer), dtype=np.float64)
+    def logit_rows(self, context, n_rows):
+        """The level's logits for the last n_rows prefixes of `context`: the source's (a real network's, or another
+        synthetic level's, which then carries its own noise already) plus this level's noise."""
+        if isinstance(self.source, DistilledLevel):
+            z = self.source.logit_rows(context, n_rows)
+        else:
+            z = np.array(self.source.decoder.next_logits(context, n_rows, self.source.exit_layer), dtype=np.float64)
         L = len(context)
         for r in range(n_rows):
             pos = L - n_rows + r                    # position of the last token of this row's context
             z[r] += self.std * gaussian_noise(self.seed, self.level_index, pos, z.shape[1])
+        return z
+
+    def next_dists(self, context, n_rows):
+        z = self.logit_rows(context, n_rows)
         self.last_logits = z
         top2 = np.partition(z, -2, axis=-1)[:, -2:]
         self.min_top2_gap = min(self.min_top2_gap, float(np.min(top2[:, 1] - top2[:, 0])))

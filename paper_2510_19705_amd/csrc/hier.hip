@@ -224,12 +224,19 @@ int level_pass(hsd_hier* h, int idx, int start, int n_logit_rows) {
     h->stats.passes[idx]++;
     h->stats.pass_rows[idx] += h->len - pos;
     if (L.distill_src < 0 || n_logit_rows == 0) return HSD_OK;
-    // Synthetic drafter: the pass above is what the level costs; its distribution comes from the source level's
-    // logits at the same contexts (a side pass that is not counted and does not move the source's cached length;
-    // the K/V it writes are those of the current tokens) plus the level's noise.
-    const LevelState& S = h->lv[L.distill_src];
+    // Synthetic drafter: the pass above is what the level costs; its distribution comes from the logits of the level its
+    // chain of sources ends at (a real network), at the same contexts (a side pass that is not counted and does not move
+    // that level's cached length; the K/V it writes are those of the current tokens), plus the noise of every synthetic
+    // level of the chain from the top down to this one: a level whose source is synthetic too differs from it by its
+    // own noise only.
+    int chain[HSD_MAX_LEVELS], n_chain = 0, root = idx;
+    while (h->lv[root].distill_src >= 0) {
+        chain[n_chain++] = root;
+        root = h->lv[root].distill_src;
+    }
+    const LevelState& S = h->lv[root];
     const int smax = S.model->desc.max_rows;
-    int sp = std::max(0, std::min(effective_cached(h, L.distill_src), h->len - n_logit_rows));
+    int sp = std::max(0, std::min(effective_cached(h, root), h->len - n_logit_rows));
     while (h->len - sp > smax) {
         const int chunk = std::min(smax, h->len - sp - n_logit_rows);
         if (chunk < 1) HSD_FAIL(HSD_ECAPACITY, "pass: %d logit rows do not fit a pass of %d rows of the source level", n_logit_rows, smax);
@@ -237,7 +244,11 @@ int level_pass(hsd_hier* h, int idx, int start, int n_logit_rows) {
         sp += chunk;
     }
     if (int rc = hier_pass(h, S.model, sp, h->len - sp, S.exit_layer, n_logit_rows, h->logits, false)) return rc;
-    return launch_add_noise(h->logits, n_logit_rows, h->V, h->seed, (uint32_t)idx, h->len - n_logit_rows, L.distill_std, h->stream);
+    for (int c = n_chain - 1; c >= 0; --c)
+        if (int rc = launch_add_noise(h->logits, n_logit_rows, h->V, h->seed, (uint32_t)chain[c], h->len - n_logit_rows,
+                                      h->lv[chain[c]].distill_std, h->stream))
+            return rc;
+    return HSD_OK;
 }
 
 int check_room(const hsd_hier* h, int extra) {
@@ -481,7 +492,6 @@ extern "C" int hsd_hier_set_distilled(hsd_hier* h, int level, int source_level, 
         return HSD_OK;
     }
     if (source_level <= level || source_level > h->K) HSD_FAIL(HSD_EINVAL, "hsd_hier_set_distilled: source level %d must lie in %d..%d", source_level, level + 1, h->K);
-    if (h->lv[source_level].distill_src >= 0) HSD_FAIL(HSD_EINVAL, "hsd_hier_set_distilled: source level %d is synthetic itself", source_level);
     if (!(noise_std >= 0.f)) HSD_FAIL(HSD_EINVAL, "hsd_hier_set_distilled: noise_std %g", noise_std);
     h->lv[level].distill_src = source_level;
     h->lv[level].distill_std = noise_std;

@@ -479,42 +479,33 @@ def _time_on(torch, stream, fn, iters):
     return e0.elapsed_time(e1) * 1e3 / iters
 
 
-def run_distilled(config, stds, seed=20251019, temperature=1.0, gen=None):
-    """The same candidates with synthetic closeness: every drafter's logits are the target's plus Gaussian noise of
-    the given standard deviations (hsd_hier_set_distilled), which puts acceptance rates in the 0.5-0.9 range the
-    paper works in.  The target's side passes make wall-clock meaningless, so every run is priced with the fixed
-    cost per pass measured beforehand (the appendix's artificial-cost accounting): ms per token = sum of passes x
-    cost / tokens.  Acceptance rates are the per-test frequencies of the runs themselves."""
+def distilled_study(hsd, levels, names, cost, prompt, stds, chain, gen, temperature, seed, n_cached=None):
+    """Hierarchies over candidates with synthetic closeness (hsd_hier_set_distilled), priced with the fixed cost per
+    pass measured beforehand (the appendix's artificial-cost accounting: ms per token = sum of passes x cost / tokens;
+    the side passes that produce the source logits make wall-clock meaningless).
+    chain = False: every drafter's logits are the target's plus noise of std stds[i].
+    chain = True: candidate i's logits are candidate i+1's plus noise of std stds[i] (the top drafter's: the target's),
+    so neighbours are close and distant candidates less so; in a hierarchy that leaves candidates out, a level's
+    noise towards the next level kept has the skipped steps' variances added.
+    Acceptance rates are the per-test frequencies of the runs themselves.  n_cached: the networks already hold the K/V
+    of that many prompt tokens (hsd_prefill_cached)."""
     import itertools
-    import torch
-    assert torch.cuda.is_available(), "needs the GPU"
-    from . import hsd, inputs
-    cfg = CONFIGS[config]
-    shp = shapes(inputs)
-    prompt_len = cfg["prompt"]
-    gen = gen or cfg["gen"]
-    max_seq = (prompt_len + gen + 128 + 63) // 64 * 64
-    models = {name: random_model(hsd, inputs, torch, shp[name], seed + i, max_seq) for i, name in enumerate(cfg["models"])}
-    levels = [(models[name], e) for name, e in cfg["levels"]]
-    names = ["%s/exit%d" % ne for ne in cfg["levels"]]
     K = len(levels) - 1
-    assert len(stds) == K
-    prompt = inputs.make_prompt(shp[cfg["models"][0]]["vocab"], prompt_len, seed=seed + 100)
-    tokens = torch.from_numpy(prompt.astype(np.int32)).cuda()
-    cost = []
-    for (model, e) in levels:                                   # fixed cost: a 4-token pass at the end of the prompt
-        for p0 in range(0, prompt_len, 64):
-            model.model_pass(tokens[p0:p0 + min(64, prompt_len - p0)], p0, e, 0)
-        tk = tokens[prompt_len - 4:]
-        cost.append(_time(torch, lambda: model.model_pass(tk, prompt_len - 4, e, 4), 5) / 1e3)
-    log("cost ms", cost)
+    assert len(stds) == K and len(cost) == K + 1
     results = {}
 
     def measure(label, idx, T):
         h = hsd.Hierarchy([levels[i] for i in idx], T, temperature, seed)
-        for j, i in enumerate(idx[:-1]):
-            h.set_distilled(j, len(idx) - 1, stds[i])
-        h.prefill(prompt)
+        top = len(idx) - 1
+        for j in range(top - 1, -1, -1):                         # sources first: a chain is set from the top down
+            if chain:
+                h.set_distilled(j, j + 1, float(np.sqrt(sum(stds[i] ** 2 for i in range(idx[j], idx[j + 1])))))
+            else:
+                h.set_distilled(j, top, stds[idx[j]])
+        if n_cached is None:
+            h.prefill(prompt)
+        else:
+            h.prefill_cached(prompt, n_cached)
         _, st = h.generate(gen)
         n = len(idx)
         results[label] = {"levels": [names[i] for i in idx], "T": list(T),
@@ -549,11 +540,41 @@ def run_distilled(config, stds, seed=20251019, temperature=1.0, gen=None):
             if best is None or l < best[0]:
                 best = (l, T)
         measure("full_hierarchy", list(range(K + 1)), list(best[1]))
+    singles = [v["artificial_ms_per_token"] for k, v in results.items() if k.startswith("single_draft_")]
+    return {"noise_std": list(stds), "noise": "each candidate = the next one up + noise" if chain else "each drafter = the target + noise",
+            "candidates": names, "cost_ms": list(cost), "alpha": [[round(float(v), 4) for v in row] for row in alpha],
+            "selected": {"levels": [names[i] for i in sigma], "T": list(Tsel), "predicted_ms_per_token": lat}, "runs": results,
+            "selected_vs_best_single_draft": min(singles) / results["selected"]["artificial_ms_per_token"]}
+
+
+def run_distilled(config, stds, seed=20251019, temperature=1.0, gen=None, chain=False):
+    """distilled_study on the candidates of a configuration (which puts acceptance rates in the 0.5-0.9 range the
+    paper works in); the fixed costs are 4-token passes at the end of the prompt."""
+    import torch
+    assert torch.cuda.is_available(), "needs the GPU"
+    from . import hsd, inputs
+    cfg = CONFIGS[config]
+    shp = shapes(inputs)
+    prompt_len = cfg["prompt"]
+    gen = gen or cfg["gen"]
+    max_seq = (prompt_len + gen + 128 + 63) // 64 * 64
+    models = {name: random_model(hsd, inputs, torch, shp[name], seed + i, max_seq) for i, name in enumerate(cfg["models"])}
+    levels = [(models[name], e) for name, e in cfg["levels"]]
+    names = ["%s/exit%d" % ne for ne in cfg["levels"]]
+    prompt = inputs.make_prompt(shp[cfg["models"][0]]["vocab"], prompt_len, seed=seed + 100)
+    tokens = torch.from_numpy(prompt.astype(np.int32)).cuda()
+    cost = []
+    for (model, e) in levels:                                   # fixed cost: a 4-token pass at the end of the prompt
+        for p0 in range(0, prompt_len, 64):
+            model.model_pass(tokens[p0:p0 + min(64, prompt_len - p0)], p0, e, 0)
+        tk = tokens[prompt_len - 4:]
+        cost.append(_time(torch, lambda: model.model_pass(tk, prompt_len - 4, e, 4), 5) / 1e3)
+    log("cost ms", cost)
+    out = distilled_study(hsd, levels, names, cost, prompt, stds, chain, gen, temperature, seed)
     for m in models.values():
         m.close()
-    return {"config": config + " (distilled)", "noise_std": list(stds), "candidates": names, "cost_ms": cost,
-            "alpha": [[round(float(v), 4) for v in row] for row in alpha],
-            "selected": {"levels": [names[i] for i in sigma], "T": list(Tsel), "predicted_ms_per_token": lat}, "runs": results}
+    out["config"] = config + (" (chain-distilled)" if chain else " (distilled)")
+    return out
 
 
 def main():
@@ -564,6 +585,7 @@ def main():
     ap.add_argument("--rows", type=int, default=4, help="counters: tokens per verify pass")
     ap.add_argument("--ctx", type=int, default=8192, help="counters: cached positions")
     ap.add_argument("--distill", action="store_true", help="synthetic drafters: target logits + noise, fixed-cost accounting")
+    ap.add_argument("--chain", action="store_true", help="with --distill: every candidate = the next one up + noise")
     ap.add_argument("--gen", type=int, default=0)
     args = ap.parse_args()
     if args.config == "microbench":
@@ -576,8 +598,8 @@ def main():
         out = counters(args.shape, args.layers, args.rows, args.ctx)
     elif args.distill:
         K = len(CONFIGS[args.config]["levels"]) - 1
-        stds = [1.0, 0.5, 0.35, 0.25][:K] if K > 1 else [0.7]
-        out = run_distilled(args.config, stds, gen=args.gen or None)
+        stds = ([0.8, 0.3, 0.3, 0.25] if args.chain else [1.0, 0.5, 0.35, 0.25])[:K] if K > 1 else [0.7]
+        out = run_distilled(args.config, stds, gen=args.gen or None, chain=args.chain)
     else:
         out = run(args.config)
     print(json.dumps(out), flush=True)

@@ -11,6 +11,11 @@ this script is how the values they use were found and how they can be found agai
     python tests/scan_stream_seeds.py --search         # for every case: the first value of the scanned range that qualifies
     python tests/scan_stream_seeds.py --search --case vocab_128256_t1
 
+The two tests with synthetic drafters (test_distilled_drafters_follow_the_oracle, seed 1301, and
+test_chain_of_distilled_drafters_follows_the_oracle, seed 1403) draw noise from the same seed as the sampler, so their
+seed is found by running the test's own oracle block over consecutive seeds from 1300 / 1400 and taking the first
+one whose margins pass the test's assertion.
+
 At temperature 0 the sampling seed is irrelevant and the PROMPT seed is scanned; at temperature 1 the prompt is kept
 and the SAMPLING seed is scanned.  Nothing here touches the GPU or the library.
 """

@@ -505,6 +505,34 @@ def test_distilled_drafters_follow_the_oracle():
     mb.close()
 
 
+def test_chain_of_distilled_drafters_follows_the_oracle(tiny):
+    """A chain of synthetic drafters over exits of one network (exit 2 = exit 4's logits + noise, exit 4 = the target's
+    + noise): stream, pass counts and acceptance counters against the oracle, whose chained level adds the two noise
+    rows to the target's logits; neighbours accept more than the single-noise configuration's ends would."""
+    from oracle import distill
+    from paper_2510_19705_amd import hsd
+    w, prompt, model = tiny
+    dec = oracle_decoder(TINY, w, 256)
+    seed, T = 1403, (3, 2)
+    tgt = decoder.Level(dec, 8, 1.0)
+    mid = distill.DistilledLevel(dec, 4, tgt, 1, 0.5, seed, 1.0)
+    low = distill.DistilledLevel(dec, 2, mid, 0, 0.5, seed, 1.0)
+    ch = specsample.PhiloxChooser(seed)
+    o = ohsd.HSD([low, mid, tgt], T, ch)
+    ref = o.generate([int(t) for t in prompt], 48)
+    say("chain: oracle margins accept %.2e sample %.2e; accepted %s of %s" % (min(ch.accept_margins), min(ch.sample_margins), o.accepted, o.drafted))
+    assert min(ch.accept_margins) > 3e-4 and min(ch.sample_margins) > 3e-6
+    h = hsd.Hierarchy([(model, 2), (model, 4), (model, 8)], T, 1.0, seed)
+    h.set_distilled(1, 2, 0.5)
+    h.set_distilled(0, 1, 0.5)
+    h.prefill(prompt)
+    got, st = h.generate(48)
+    assert got.tolist() == ref
+    assert [st.passes[i] for i in range(3)] == o.passes
+    assert [st.accepted[i] for i in range(3)] == o.accepted and [st.tested[i] for i in range(3)] == o.tested
+    h.close()
+
+
 def test_set_seed_switches_the_sample_path(tiny):
     """hsd_hier_set_seed + rewind continue the same prompt along the sample path of another seed: equal to a
     hierarchy created with that seed, and back to the first path with the first seed."""

@@ -24,3 +24,22 @@ def test_smoke_configuration_runs():
             assert r["tokens_per_s"] > 0 and r["passes"][-1] > 0, key
     for p in out["verify_pass"].values():
         assert 0 < p["hbm_frac"] < 1
+
+
+@pytest.mark.parametrize("chain", [False, True], ids=["noise_from_target", "noise_chain"])
+def test_distilled_study_runs_on_the_small_configuration(chain):
+    """Synthetic closeness on the stand-in configuration: every run generates the tokens asked for, fixed-cost prices
+    are positive, acceptance rates are frequencies, and with a chain of noise steps neighbouring candidates accept
+    more than the two ends of the chain."""
+    from paper_2510_19705_amd import workloads
+    out = workloads.run_distilled("smoke", [0.8, 0.3], gen=48, chain=chain)
+    runs = out["runs"]
+    assert {"autoregressive", "selected"} <= set(runs)
+    for key, r in runs.items():
+        assert r["tokens"] >= 48 and r["artificial_ms_per_token"] > 0, key
+        assert all(0 <= a <= 1 for a in r["per_test_acceptance"]), key
+    alpha = np.array(out["alpha"])
+    assert np.allclose(alpha, alpha.T) and np.allclose(np.diag(alpha), 1)
+    if chain:
+        assert alpha[1, 2] > alpha[0, 2]                    # one noise step against two
+    assert out["selected_vs_best_single_draft"] > 0

@@ -54,3 +54,25 @@ def test_distilled_levels_give_graded_acceptance_and_leave_the_target_law():
     greedy = ohsd.HSD([decoder.Level(dec, 8, 0.0)], (), specsample.PhiloxChooser(1)).generate(prompt, 24)
     assert got == greedy
     assert 0 < o.accepted[2] < o.drafted[2]
+
+
+def test_a_chain_of_synthetic_levels_adds_one_noise_term_per_step():
+    """A level whose source is synthetic too: its logits are the real network's plus the noise rows of every level of
+    the chain (each identified by its own level index), so neighbours overlap more than the ends of the chain, and
+    the overlap of the ends equals that of a single level with the summed noise."""
+    shape = inputs.SHAPES["tiny"]
+    w = inputs.make_weights(shape, seed=1, bf16=False)
+    dec = oracle_decoder(shape, w, 128)
+    prompt = [int(t) for t in inputs.make_prompt(shape["vocab"], 24, seed=10)]
+    target = decoder.Level(dec, 8, 1.0)
+    mid = distill.DistilledLevel(dec, 4, target, 1, 0.5, 3, 1.0)
+    low = distill.DistilledLevel(dec, 2, mid, 0, 0.75, 3, 1.0)
+    z_t = np.array(dec.next_logits(prompt, 3, 8), dtype=np.float64)
+    z_low = low.logit_rows(prompt, 3)
+    for r in range(3):
+        pos = len(prompt) - 3 + r
+        want = z_t[r] + 0.5 * distill.gaussian_noise(3, 1, pos, shape["vocab"]) + 0.75 * distill.gaussian_noise(3, 0, pos, shape["vocab"])
+        assert np.allclose(z_low[r], want, rtol=0, atol=1e-12)
+    p, pm, pl = target.next_dists(prompt, 3), mid.next_dists(prompt, 3), low.next_dists(prompt, 3)
+    ov = lambda a, b: np.mean([calibrate.overlap(a[r], b[r]) for r in range(3)])
+    assert ov(pl, pm) > ov(pl, p) and ov(pm, p) > ov(pl, p)
