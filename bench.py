@@ -13,9 +13,10 @@ One step = one full generation of 256 tokens by that hierarchy from the prefille
 draft pass, verify pass, softmax, accept / reject / resample kernel and the round driver), each step along its own
 sample path (sampling seed + step index).  Before the timed steps, untimed: calibration, selection, one generation
 each of plain decoding, every single draft, the full four-level hierarchy.  After them, as extra keys: per-pass HBM
-fractions, the roofline of the dominant kernel, the 1B-shaped early-exit configuration (its (T_0, T_1) sweep), the
-three-network configuration with synthetic drafters, verify passes of a 7B-shaped layer stack, the many-row MFMA
-figure, and the CPU oracle's baseline.
+fractions, the roofline of the dominant kernel, the headline's networks with drafters made close synthetically along
+the chain 1B -> 8B -> 70B (where three levels beat every single draft, priced per pass), the 1B-shaped early-exit
+configuration (its (T_0, T_1) sweep), the three-network configuration with synthetic drafters, verify passes of
+7B- and 8B-shaped layer stacks, the many-row MFMA figure, and the CPU oracle's baseline.
 
 Prints ONE JSON line.  `value` = generated tokens per second of the selected hierarchy.
 """
@@ -207,8 +208,8 @@ def big_configuration(args, torch, hsd, inputs, workloads):
     if not args.brief:
         sub = [0, 2, K]
         d = workloads.distilled_study(hsd, [levels[i] for i in sub], [names[i] for i in sub], [cost[i] for i in sub], prompt,
-                                      [0.8, 0.3], True, 64, TEMPERATURE, SEED, n_cached=prompt_len - 1)
-        chain = {"workload": "the headline's 1B / 8B / 70B-shaped networks (same prompt, 64 tokens per run), drafters made close "
+                                      [0.8, 0.3], True, 128, TEMPERATURE, SEED, n_cached=prompt_len - 1)
+        chain = {"workload": "the headline's 1B / 8B / 70B-shaped networks (same prompt, 128 tokens per run), drafters made close "
                              "synthetically: 8B level = the target's logits + Gaussian noise of std 0.3, 1B level = the 8B level's + "
                              "noise of std 0.8; every run priced with the calibrated cost per pass (the side passes that produce "
                              "the source logits make wall-clock meaningless)",
