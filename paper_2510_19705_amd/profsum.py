@@ -1,7 +1,7 @@
 """Turns rocprofv3 result databases into the short text summaries kept under profiles/.  CPU only.
 
     # per-kernel calls / total / mean duration of a run made with `rocprofv3 --kernel-trace --stats -d DIR -o NAME -- ...`
-    python -m paper_2510_19705_amd.profsum trace DIR/NAME_results.db --cmd "<the command>" --out profiles/<file>.txt
+    python -m paper_2510_19705_amd.profsum trace DIR/NAME_results.db --cmd "<the command>" --out profiles/<file>.txt [--by-grid]
 
     # HBM bytes per launch of the layer kernels, from two runs of `workloads --config counters` (one with
     # `--pmc FETCH_SIZE --kernel-trace`, one with `--pmc WRITE_SIZE --kernel-trace`) and the manifest that workload printed
@@ -21,9 +21,29 @@ def _tables(cur):
     return [r[0] for r in cur.execute("select name from sqlite_master where type in ('table', 'view')")]
 
 
-def trace(db, cmd, out, note=""):
+def trace(db, cmd, out, note="", by_grid=False):
+    """by_grid: one line per (kernel, launch shape) instead of per kernel, so that launches of one template instance
+    on matrices of different sizes (the same instance serves every model of a hierarchy) are told apart."""
     cur = sqlite3.connect(db).cursor()
-    rows = list(cur.execute("select name, total_calls, total_duration, average, percentage from top_kernels"))
+    if by_grid:
+        cols = [r[1] for r in cur.execute("pragma table_info(kernels)")]
+        gx = "grid_x" if "grid_x" in cols else ("grid_size_x" if "grid_size_x" in cols else None)
+        wx = "workgroup_x" if "workgroup_x" in cols else ("workgroup_size_x" if "workgroup_size_x" in cols else None)
+        if gx is None or wx is None:
+            raise SystemExit("no grid / workgroup columns in the kernels view: %s" % cols)
+        gy, wy = gx.replace("_x", "_y"), wx.replace("_x", "_y")
+        agg = {}
+        for n, st, en, a, b, c, d in cur.execute("select name, start, end, %s, %s, %s, %s from kernels" % (gx, gy, wx, wy)):
+            # the profiler reports the grid in work-items: workgroups = items / workgroup size
+            key = (n, "%dx%d" % (a // max(1, c), b // max(1, d)))
+            e = agg.setdefault(key, [0, 0.0])
+            e[0] += 1
+            e[1] += (en - st) / 1e3
+        total = sum(v[1] for v in agg.values())
+        rows = [("%s [%s workgroups]" % (k[0].replace("bool _Accum", "bf16").split("(")[0], k[1]), v[0], v[1], v[1] / v[0], 100 * v[1] / total)
+                for k, v in sorted(agg.items(), key=lambda kv: -kv[1][1])]
+    else:
+        rows = list(cur.execute("select name, total_calls, total_duration, average, percentage from top_kernels"))
     with open(out, "w") as f:
         f.write("rocprofv3 --kernel-trace --stats summary (durations in microseconds)\n")
         f.write("command: %s\n" % cmd)
@@ -147,6 +167,7 @@ def main():
     t.add_argument("db")
     t.add_argument("--cmd", required=True)
     t.add_argument("--note", default="")
+    t.add_argument("--by-grid", action="store_true", help="one line per (kernel, launch shape)")
     t.add_argument("--out", required=True)
     c = sub.add_parser("traffic")
     c.add_argument("--fetch", required=True)
@@ -165,7 +186,7 @@ def main():
         print(gap(args.db, args.report, args.plain_report, args.cmd, args.out))
         return
     if args.what == "trace":
-        print(trace(args.db, args.cmd, args.out, args.note))
+        print(trace(args.db, args.cmd, args.out, args.note, args.by_grid))
     else:
         print(traffic(args.fetch, args.write, args.manifest, args.cmd, args.out))
 
