@@ -409,9 +409,14 @@ def main():
     t_start = time.time()
     big = big_configuration(args, torch, hsd, inputs, workloads)
     log("headline configuration done at %.0f s" % (time.time() - t_start))
-    small = distilled = stack7b = stack8b = mfma = cpu = None
+    small = batched = distilled = stack7b = stack8b = mfma = cpu = None
     if not args.brief:
         small, _ = small_configuration(args, torch, hsd, inputs, workloads)
+        batched = {"workload": "the same 1B-shaped early-exit hierarchy, T = (4, 1), over 1 / 4 / 8 sequences in lockstep (hsd_batch_*): own "
+                               "prompt of 512 tokens and own sampling seed per sequence, 256 tokens each, temperature 1; tokens/s summed "
+                               "over the sequences",
+                   **workloads.batch_throughput(hsd, inputs, torch, dict(inputs.SHAPES["1b"]), (2, 6, 16), (4, 1), (1, 4, 8), 512, 256)}
+        torch.cuda.empty_cache()
         log("1B-shaped configuration done at %.0f s" % (time.time() - t_start))
         torch.cuda.empty_cache()
         d = workloads.run_distilled("independent", [1.0, 0.5], gen=128)
@@ -456,7 +461,7 @@ def main():
         "verify_pass_7b_shaped_4_layers_ctx4096": stack7b, "verify_pass_8b_shaped_4_layers_ctx8192": stack8b,
         "mfma_util": mfma,
         "config_5_networks_chain_distilled": big["chain_distilled"],
-        "config_1b_early_exit": small, "config_3_networks_distilled": distilled,
+        "config_1b_early_exit": small, "config_1b_early_exit_batched": batched, "config_3_networks_distilled": distilled,
         "roofline": big["roofline"], "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

@@ -309,6 +309,35 @@ typedef struct {
  * the surplus).  out: cap n_tokens.  stats may be NULL. */
 int hsd_generate(hsd_hier*, int n_tokens, int32_t* out, hsd_stats* stats);
 
+/* ---------------------------------------------------------------------------------------------
+ * HSD over a batch of sequences in lockstep.  The paper decodes one sequence (Sec. 5: batch size 1); its own
+ * argument for drafting (Sec. 3.1: a pass costs the weights it loads, however many tokens it scores) extends across
+ * sequences, so one pass of a level here feeds the pending tokens of every sequence that is at that point of
+ * Alg. 1.  Every sequence b is decoded exactly as hsd_generate would decode it alone with seed seeds[b]: its own
+ * Philox counters, Verify calls (Alg. 2) and cached lengths; the results differ from that run only by the summation
+ * order of kernels chosen for another row count.  An intermediate level repeats (level below, Verify) while any
+ * of its sequences is short of T_level tokens; sequences that have theirs, or have generated what was asked, sit the
+ * pass out as padding rows after their last token (attention is causal: padding never reaches a real row, and
+ * its K/V lands beyond the valid length).
+ *
+ * hsd_batch_create shares each network's KV pages out among the sequences (hsd_model_set_batch: sequence b owns
+ * pages [b, b + 1) * max_len / HSD_KV_PAGE), so every model needs max_seq >= batch * max_len, and a pass of
+ * batch * (most drafts of a Verify + 2) rows must fit the models' max_rows.  The models must not be used by another
+ * hierarchy meanwhile.  workspace_dev: hsd_batch_workspace_bytes bytes, 256-byte aligned, caller-owned.
+ * hsd_batch_prefill: prompts (host) [batch, stride], lens[b] tokens each (ragged prompts allowed).
+ * hsd_batch_generate: n_tokens more tokens of every sequence, out (host) [batch, n_tokens]; stats (may be NULL) count
+ * passes once per batched pass, rows / drafted / accepted / tested summed over the sequences, tokens over all of them.
+ * Not supported here: the ablation switches, synthetic drafters, hidden-state reuse.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct hsd_batch hsd_batch;
+size_t hsd_batch_workspace_bytes(int n_levels, const hsd_level* levels, const int* T, int batch, int max_len);
+int hsd_batch_create(int n_levels, const hsd_level* levels, const int* T, int batch, int max_len, float temperature,
+                     const uint64_t* seeds, void* workspace_dev, size_t workspace_bytes, void* stream, hsd_batch** out);
+void hsd_batch_destroy(hsd_batch*);
+int hsd_batch_prefill(hsd_batch*, const int32_t* prompts, int stride, const int* lens);
+int hsd_batch_generate(hsd_batch*, int n_tokens, int32_t* out, hsd_stats* stats);
+int hsd_batch_sequence_length(const hsd_batch*, int sequence);
+
 /* Hidden-state reuse between early exits of one network (Sec. 5.1: the drafters of the paper's main workload are
  * earlier exits of the target).  Where the level below a verifier is a shallower exit of the verifier's own network,
  * every pass through that exit's layer keeps its residual rows by position, and with on != 0 the verifier's pass sends

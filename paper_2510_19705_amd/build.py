@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libhsd.so")
 OBJ = os.path.join(os.path.dirname(HERE), "_build")
-SOURCES = ["kernels_gemm.hip", "kernels_gemm_wide.hip", "kernels_layer.hip", "kernels_attn.hip", "kernels_sampler.hip", "model.hip", "hier.hip", "calibrate.hip",
+SOURCES = ["kernels_gemm.hip", "kernels_gemm_wide.hip", "kernels_layer.hip", "kernels_attn.hip", "kernels_sampler.hip", "model.hip", "hier.hip", "hier_batch.hip", "calibrate.hip",
            "select.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-command-line-argument",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -8,6 +8,8 @@
 //  * accept_resample_small_kernel (vocabulary <= 32768): the same in one workgroup that holds the row in registers;
 //  * softmax_verify_kernel (vocabulary <= 32768): softmax of the logit rows, the accept tests and the draw fused, one
 //    workgroup per row, plus what the driver needs next (results in pinned host memory, the emitted token embedded).
+#include <algorithm>
+
 #include "common.h"
 #include "softmax_row.h"
 #include "model.h"
@@ -373,19 +375,17 @@ __global__ __launch_bounds__(SMALL_THREADS) void accept_resample_small_kernel(co
 // last workgroup to take a ticket publishes them (result, x[n], and a pinned host mailbox if given) and
 // resets key and ticket.  The ticket increment depends on the returned value of the max, so the max is
 // performed before the ticket is taken.
-__global__ __launch_bounds__(SMALL_THREADS) void softmax_verify_kernel(const float* __restrict__ z, const float* __restrict__ q,
-                                                                       int32_t* __restrict__ x, int t, int V, float temperature,
-                                                                       uint32_t k0, uint32_t k1, uint32_t level, uint32_t call,
-                                                                       float* __restrict__ p_out, int32_t* __restrict__ result,
-                                                                       uint32_t* ticket, unsigned long long* key,
-                                                                       int32_t* __restrict__ mailbox, const EmbedNext next, float coin,
-                                                                       int mailbox_seq) {
+__device__ __forceinline__ void softmax_verify_row(const int row, const float* __restrict__ z, const float* __restrict__ q,
+                                                   int32_t* __restrict__ x, int t, int V, float temperature, uint32_t k0, uint32_t k1,
+                                                   uint32_t level, uint32_t call, float* __restrict__ p_out, int32_t* __restrict__ result,
+                                                   uint32_t* ticket, unsigned long long* key, int32_t* __restrict__ mailbox,
+                                                   const EmbedNext& next, float coin, int mailbox_seq) {
     __shared__ float shv[16];
     __shared__ int shi[16];
     __shared__ SearchShared sh;
     __shared__ int sh_reject;
     __shared__ int sh_last, sh_emit;
-    const int row = blockIdx.x, tid = threadIdx.x;
+    const int tid = threadIdx.x;
     const float* zr = z + (size_t)row * V;
     const float* qr = row < t ? q + (size_t)row * V : nullptr;
     float* pr = p_out ? p_out + (size_t)row * V : nullptr;
@@ -490,6 +490,28 @@ __global__ __launch_bounds__(SMALL_THREADS) void softmax_verify_kernel(const flo
     }
 }
 
+__global__ __launch_bounds__(SMALL_THREADS) void softmax_verify_kernel(const float* __restrict__ z, const float* __restrict__ q,
+                                                                       int32_t* __restrict__ x, int t, int V, float temperature,
+                                                                       uint32_t k0, uint32_t k1, uint32_t level, uint32_t call,
+                                                                       float* __restrict__ p_out, int32_t* __restrict__ result,
+                                                                       uint32_t* ticket, unsigned long long* key,
+                                                                       int32_t* __restrict__ mailbox, const EmbedNext next, float coin,
+                                                                       int mailbox_seq) {
+    softmax_verify_row((int)blockIdx.x, z, q, x, t, V, temperature, k0, k1, level, call, p_out, result, ticket, key, mailbox, next, coin,
+                       mailbox_seq);
+}
+
+// The same for several independent calls (the sequences of a batch) in one launch: grid (most rows of a call, calls);
+// call c has its own rows, tokens, seed, call index, result, mailbox and its own ticket / key pair at scratch + 16 c.
+__global__ __launch_bounds__(SMALL_THREADS) void softmax_verify_batch_kernel(const VerifyCalls calls, int V, float temperature,
+                                                                             uint32_t level, char* scratch) {
+    const VerifyCall& c = calls.c[blockIdx.y];
+    if ((int)blockIdx.x > c.t) return;
+    softmax_verify_row((int)blockIdx.x, c.z, c.q, c.x, c.t, V, temperature, (uint32_t)c.seed, (uint32_t)(c.seed >> 32), level, c.call,
+                       c.p_out, c.result, (uint32_t*)(scratch + 16 * blockIdx.y), (unsigned long long*)(scratch + 16 * blockIdx.y + 8),
+                       c.mailbox, EmbedNext{}, -1.f, 0);
+}
+
 // z[r, v] += std * n(level, pos0 + r, v): the synthetic closeness of a drafter to a deeper level (workload
 // construction, not part of the method).  n = Box-Muller on the words of the Philox block with counter
 // (v / 4, position, level | 2^31, 0x4E4F4953), two normals per word pair, evaluated in fp64.
@@ -554,6 +576,24 @@ int launch_softmax_verify(const float* z, const float* q, int32_t* x, int t, int
                                                           call, p_out, result, (uint32_t*)scratch,
                                                           (unsigned long long*)((char*)scratch + 8), mailbox, next, coin, mailbox_seq);
     HSD_LAUNCH_CHECK();
+    return HSD_OK;
+}
+
+int launch_softmax_verify_batch(const VerifyCall* calls, int n_calls, int vocab, float temperature, uint32_t level, void* scratch,
+                                hipStream_t s) {
+    if (!softmax_verify_supported(vocab)) HSD_FAIL(HSD_ECAPACITY, "fused softmax + verify: vocabulary %d above %d", vocab, SMALL_MAX_V);
+    for (int c0 = 0; c0 < n_calls; c0 += VERIFY_CALLS_MAX) {
+        VerifyCalls group;
+        const int n = std::min(VERIFY_CALLS_MAX, n_calls - c0);
+        int rows = 1;
+        for (int c = 0; c < n; ++c) {
+            group.c[c] = calls[c0 + c];
+            if (group.c[c].t < 0 || group.c[c].t > 64) HSD_FAIL(HSD_EINVAL, "fused softmax + verify: t=%d outside 0..64", group.c[c].t);
+            rows = std::max(rows, group.c[c].t + 1);
+        }
+        softmax_verify_batch_kernel<<<dim3(rows, n), SMALL_THREADS, 0, s>>>(group, vocab, temperature, level, (char*)scratch + 16 * (size_t)c0);
+        HSD_LAUNCH_CHECK();
+    }
     return HSD_OK;
 }
 

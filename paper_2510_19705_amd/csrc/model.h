@@ -110,6 +110,25 @@ EmbedNext embed_next_of(const hsd_model* m);
 int launch_softmax_verify(const float* z, const float* q, int32_t* x, int t, int vocab, float temperature, uint64_t seed,
                           uint32_t level, uint32_t call, float* p_out, int32_t* result, void* scratch, int32_t* mailbox,
                           const EmbedNext& next, float coin, int mailbox_seq, hipStream_t s);
+// Several independent calls of the fused sampler in one launch (the sequences of a batch at one level): call c uses
+// the ticket / key pair at scratch + 16 c, which must be zero before the first launch (the kernel leaves it zero).
+struct VerifyCall {
+    const float* z;       // [t + 1, vocab] logits
+    const float* q;       // [t, vocab] draft rows (unused for t == 0)
+    int32_t* x;           // the t drafts; x[n] receives the emitted token
+    float* p_out;         // [t + 1, vocab] or null
+    int32_t* result;      // (n, token)
+    int32_t* mailbox;     // pinned host memory or null
+    uint64_t seed;
+    uint32_t call;
+    int t;
+};
+constexpr int VERIFY_CALLS_MAX = 16;
+struct VerifyCalls {
+    VerifyCall c[VERIFY_CALLS_MAX];
+};
+int launch_softmax_verify_batch(const VerifyCall* calls, int n_calls, int vocab, float temperature, uint32_t level, void* scratch,
+                                hipStream_t s);
 // With mailbox_seq != 0 the kernel ends its mailbox writes by storing mailbox_seq into this slot of the mailbox
 // (which then must have MAILBOX_SEQ_SLOT + 1 entries), after a system-scope release: a host may poll it.
 constexpr int MAILBOX_SEQ_SLOT = 67;

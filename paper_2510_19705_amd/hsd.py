@@ -125,6 +125,12 @@ _SIGS = {
     "hsd_verify": (_i, [_vp, _i, C.POINTER(C.c_int32), _vp, _i, _i, C.POINTER(C.c_int32), _ip, C.POINTER(_vp)]),
     "hsd_run": (_i, [_vp, _i, C.POINTER(C.c_int32), _i, _ip, C.POINTER(_vp)]),
     "hsd_generate": (_i, [_vp, _i, C.POINTER(C.c_int32), C.POINTER(Stats)]),
+    "hsd_batch_workspace_bytes": (_sz, [_i, C.POINTER(Level), _ip, _i, _i]),
+    "hsd_batch_create": (_i, [_i, C.POINTER(Level), _ip, _i, _i, _f, C.POINTER(C.c_uint64), _vp, _sz, _vp, C.POINTER(_vp)]),
+    "hsd_batch_destroy": (None, [_vp]),
+    "hsd_batch_prefill": (_i, [_vp, C.POINTER(C.c_int32), _i, _ip]),
+    "hsd_batch_generate": (_i, [_vp, _i, C.POINTER(C.c_int32), C.POINTER(Stats)]),
+    "hsd_batch_sequence_length": (_i, [_vp, _i]),
     "hsd_get_stats": (_i, [_vp, C.POINTER(Stats)]),
     "hsd_sequence_length": (_i, [_vp]),
     "hsd_measure_pass": (_i, [_vp, _i, _i, _i, _dp]),
@@ -562,6 +568,53 @@ class Hierarchy:
 
 
 # ---- host-side latency model ------------------------------------------------------------------
+class BatchHierarchy:
+    """hsd_batch_*: HSD over several sequences in lockstep; sequence b is decoded as Hierarchy would decode it alone
+    with seeds[b].  Every model needs max_seq >= batch * max_len."""
+
+    def __init__(self, levels, T, temperature, seeds, max_len):
+        self.models = [m for m, _ in levels]
+        self.n, self.K, self.B = len(levels), len(levels) - 1, len(seeds)
+        self.vocab = levels[0][0].desc.vocab
+        self._lv = (Level * self.n)(*[Level(m.handle, e) for m, e in levels])
+        self._T = (C.c_int * max(1, self.K))(*list(T))
+        self._seeds = (C.c_uint64 * self.B)(*[int(x) for x in seeds])
+        nbytes = lib.hsd_batch_workspace_bytes(self.n, self._lv, self._T, self.B, max_len)
+        self.handle = C.c_void_p()
+        if nbytes == 0:      # invalid configuration: let create report the status code
+            _check(lib.hsd_batch_create(self.n, self._lv, self._T, self.B, max_len, float(temperature), self._seeds, None, 0,
+                                        self.models[0].stream, C.byref(self.handle)))
+        self.workspace = _buf(nbytes)
+        _check(lib.hsd_batch_create(self.n, self._lv, self._T, self.B, max_len, float(temperature), self._seeds,
+                                    self.workspace.data_ptr(), self.workspace.numel(), self.models[0].stream, C.byref(self.handle)))
+
+    def close(self):
+        if self.handle:
+            lib.hsd_batch_destroy(self.handle)
+            self.handle = C.c_void_p()
+            for m in set(self.models):
+                m.set_batch(0)
+
+    def prefill(self, prompts):
+        """prompts: one sequence of token ids per batch entry (lengths may differ)."""
+        assert len(prompts) == self.B
+        lens = np.array([len(p) for p in prompts], dtype=np.int32)
+        flat = np.zeros((self.B, int(lens.max())), dtype=np.int32)
+        for b, p in enumerate(prompts):
+            flat[b, :len(p)] = np.asarray(p, dtype=np.int32)
+        _check(lib.hsd_batch_prefill(self.handle, flat.ctypes.data_as(C.POINTER(C.c_int32)), flat.shape[1],
+                                     lens.ctypes.data_as(C.POINTER(C.c_int))))
+
+    def generate(self, n_tokens):
+        out = np.zeros((self.B, n_tokens), dtype=np.int32)
+        st = Stats()
+        _check(lib.hsd_batch_generate(self.handle, n_tokens, out.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(st)))
+        return out, st
+
+    def sequence_length(self, b):
+        return lib.hsd_batch_sequence_length(self.handle, b)
+
+
 def stats_cost(st, cost):
     """hsd_stats_cost: sum of passes[i] * cost[i]."""
     c, cp = _f64(cost)

@@ -479,6 +479,33 @@ def _time_on(torch, stream, fn, iters):
     return e0.elapsed_time(e1) * 1e3 / iters
 
 
+def batch_throughput(hsd, inputs, torch, shape, exits, T, batches, prompt_len, gen, seed=20251019, temperature=1.0):
+    """Generated tokens per second, summed over the sequences, of HSD over a batch of sequences in lockstep
+    (hsd_batch_*): one early-exit hierarchy of one network, every sequence with its own prompt and sampling seed."""
+    max_len = (prompt_len + gen + 128 + 63) // 64 * 64
+    model = random_model(hsd, inputs, torch, shape, seed, max(batches) * max_len)
+    out = {}
+    for B in batches:
+        prompts = [inputs.make_prompt(shape["vocab"], prompt_len, seed=seed + 200 + b) for b in range(B)]
+        h = hsd.BatchHierarchy([(model, e) for e in exits], T, temperature, [seed + b for b in range(B)], max_len)
+        h.prefill(prompts)
+        h.generate(16)                                          # warm-up
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        _, st = h.generate(gen)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        n = len(exits)
+        out["batch_%d" % B] = {"tokens_per_s": B * gen / dt, "per_sequence_tokens_per_s": gen / dt,
+                               "passes": [st.passes[i] for i in range(n)],
+                               "mean_pass_rows": [st.pass_rows[i] / max(1, st.passes[i]) for i in range(n)],
+                               "acceptance": [st.accepted[i] / max(1, st.drafted[i]) for i in range(1, n)]}
+        log("batch %d: %.0f tokens/s" % (B, out["batch_%d" % B]["tokens_per_s"]), out["batch_%d" % B])
+        h.close()
+    model.close()
+    return out
+
+
 def distilled_study(hsd, levels, names, cost, prompt, stds, chain, gen, temperature, seed, n_cached=None):
     """Hierarchies over candidates with synthetic closeness (hsd_hier_set_distilled), priced with the fixed cost per
     pass measured beforehand (the appendix's artificial-cost accounting: ms per token = sum of passes x cost / tokens;
