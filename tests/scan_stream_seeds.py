@@ -10,6 +10,7 @@ this script is how the values they use were found and how they can be found agai
     python tests/scan_stream_seeds.py                  # check the values in use (prints the margins of each case)
     python tests/scan_stream_seeds.py --search         # for every case: the first value of the scanned range that qualifies
     python tests/scan_stream_seeds.py --search --case vocab_128256_t1
+    python tests/scan_stream_seeds.py --batch          # the (prompt, length, seed) triples of tests/test_gpu_batch.py
 
 The two tests with synthetic drafters (test_distilled_drafters_follow_the_oracle, seed 1301, and
 test_chain_of_distilled_drafters_follows_the_oracle, seed 1403) draw noise from the same seed as the sampler, so their
@@ -94,12 +95,37 @@ def qualifies(case, m):
     return m[1] > case["acc"] and m[2] > case["samp"]
 
 
+def batch_sequences():
+    """The (prompt seed, prompt length, sampling seed) triples of tests/test_gpu_batch.py: 48 tokens, T = (4, 2), prompt
+    lengths 24 / 32 / 40 by prompt seed; temperature 1: for prompt seeds 2..7 the first sampling seed from
+    200 + 10 * prompt seed on that qualifies; temperature 0: the prompt seeds from 10 on whose greedy run qualifies."""
+    case = dict(CASES["tiny_t1_T4_2"], n=48)
+    decoders = [oracle_decoder(shape, inputs.make_weights(shape, seed=ws, bf16=False), 40 + 48 + 64) for shape, ws in case["nets"]]
+    for pseed in range(2, 8):
+        case["n_prompt"] = 24 + (pseed % 3) * 8
+        for v in range(60):
+            m = margins(case, decoders, pseed, 200 + 10 * pseed + v)
+            if qualifies(case, m):
+                print("temperature 1: (%d, %d, %d)  accept %.2e sample %.2e" % (pseed, case["n_prompt"], 200 + 10 * pseed + v, m[1], m[2]), flush=True)
+                break
+    case0 = dict(CASES["tiny_t0"], T=[(4, 2)], n=48)
+    for pseed in range(10, 30):
+        case0["n_prompt"] = 24 + (pseed % 3) * 8
+        m = margins(case0, decoders, pseed, 1)
+        if qualifies(case0, m):
+            print("temperature 0: (%d, %d, 1)  top-2 gap %.2e" % (pseed, case0["n_prompt"], m[0]), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--search", action="store_true", help="scan for the first qualifying value instead of checking the one in use")
     ap.add_argument("--case", action="append", help="only these cases (default: all)")
     ap.add_argument("--limit", type=int, default=400, help="values scanned per case")
+    ap.add_argument("--batch", action="store_true", help="the sequences of tests/test_gpu_batch.py")
     args = ap.parse_args()
+    if args.batch:
+        batch_sequences()
+        return
     for name, case in CASES.items():
         if args.case and name not in args.case:
             continue

@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 TINY = inputs.SHAPES["tiny"]
 EXITS = (2, 4, 8)
 MAX_LEN = 192
-# (prompt seed, prompt length, sampling seed): found with the oracle alone (the procedure of tests/scan_stream_seeds.py
+# (prompt seed, prompt length, sampling seed): found with the oracle alone (python tests/scan_stream_seeds.py --batch:
 # on 48 tokens, T = (4, 2)) for the margins asserted below; ragged prompt lengths
 T1_SEQUENCES = [(2, 40, 220), (3, 24, 231), (4, 32, 240), (5, 40, 250), (6, 24, 264), (7, 32, 274)]
 T0_SEQUENCES = [(10, 32, 1), (11, 40, 1), (13, 32, 1), (15, 24, 1), (21, 24, 1), (26, 40, 1)]
