@@ -49,6 +49,9 @@ typedef struct {
                                 per workgroup of the tiled GEMM, 0 = heuristic */
     int gemm_ksplit[4];      /* per epilogue kind: workgroups along K (partial tiles exchanged through memory), 0 = heuristic */
     int gemm_deep;           /* 1 / -1: twice / once the loads per batch whatever K; 0 = by K */
+    int gemm_interleave[4];  /* per epilogue kind: 2, 4 or 8: groups of that many waves of a workgroup take the 32-wide
+                                k-steps of their part of K round-robin (8: the workgroup's requests of a round are one
+                                contiguous run per tile); -1 or 1: each wave takes a contiguous slice of K; 0 = heuristic */
     int gemv_max_m_qkv, gemv_max_m_o, gemv_max_m_down;   /* most tokens of a pass that a projection with a row-major copy
                                 serves with the row kernel (defaults 0, 1, 2) */
     int halves_max_groups;   /* residual / RoPE projections of at most this many column groups get two workgroups per

@@ -97,6 +97,7 @@ struct GemmArgs {
     float* part;                        // split-K partial tiles (ksplit > 1)
     size_t part_bytes;                  // capacity of `part`: a plan that needs more runs unsplit
     int* tickets;                       // one arrival counter per column group, zero between launches
+    int interleave;                     // set by the launcher from the plan: waves take the k-steps round-robin instead of contiguous slices
     int halves;                         // set by the launcher from the plan: workgroup b owns columns 8 (b & 1) .. + 8 of the tiles of group b >> 1
     // consumers of a normalised input: rows of `a` are x * w_norm, the 1/rms factor is applied in the epilogue
     const unsigned long long* ss_in;    // [SS_SLOTS][HSD_MAX_PASS_ROWS]: per row, sum of squares of x times 2^24, spread over the
@@ -139,6 +140,7 @@ struct GemmPlan {
     int waves;    // waves per workgroup; they split the workgroup's K slice
     int halves;   // 1: two workgroups per column group, each owning 8 of the 16 columns of its tiles (ksplit = 1 only)
     int deep;     // 1 / -1: the deeper / shallower load batches whatever K; 0: by K
+    int interleave;   // 2, 4, 8: groups of that many waves take the k-steps of the group's run round-robin; 0, 1: contiguous slices
 };
 const hsd_kernel_tuning& default_kernel_tuning();
 const hsd_driver_tuning& default_driver_tuning();

@@ -180,9 +180,16 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
     const int ksplit = gridDim.y;
     const int per_wg = (KT + ksplit - 1) / ksplit;
     const int kt0 = blockIdx.y * per_wg, kt1 = min(KT, kt0 + per_wg);
-    const int per = (kt1 - kt0 + nwaves - 1) / nwaves;
-    const int kb = kt0 + wave * per;
-    const int ke = min(kt1, kb + per);
+    // The waves form groups of kstep (1, 2, 4 or 8) waves: every group owns a contiguous run of the workgroup's k-steps,
+    // and the waves of a group take the steps of that run round-robin (kstep = 1: every wave its own contiguous
+    // slice; kstep = 8: the eight waves' requests of one round are one contiguous 8 KB run per tile).
+    const int kstep = g.interleave > 1 ? g.interleave : 1;
+    const int ngroups = nwaves / kstep;
+    const int per = (kt1 - kt0 + ngroups - 1) / ngroups;
+    const int gbeg = kt0 + (wave / kstep) * per, gend = min(kt1, gbeg + per);
+    const int kb = gbeg + wave % kstep;
+    const int cnt = gend > kb ? (gend - kb + kstep - 1) / kstep : 0;
+    const int ke = kb + kstep * cnt;
     const int row = lane & 15, grp = lane >> 4;
 
     f32x4 acc[MT][NT];
@@ -258,18 +265,18 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
     // Batches of U k-steps: all loads of a batch are issued before its MFMAs.  A last, partial batch requests its
     // missing steps at the wave's last tile again (cache hits) and feeds them zero activations, so that no step is
     // ever a load-wait-multiply round trip of its own.
-    for (int kt = kb; kt < ke; kt += U) {
+    for (int kt = kb; kt < ke; kt += U * kstep) {
         bf16x8 b[U][NT], a[U][MT];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int kk = min(kt + u, ke - 1);
+            const int kk = min(kt + u * kstep, ke - kstep);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) b[u][nt] = load_b(nt, kk);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int kk = min(kt + u, ke - 1);
-            const bool live = kt + u < ke;
+            const int kk = min(kt + u * kstep, ke - kstep);
+            const bool live = kt + u * kstep < ke;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 const bf16x8 v = *reinterpret_cast<const bf16x8*>(ap[mt] + koff(kk));     // row 0 for lanes past M: always mapped
@@ -562,7 +569,7 @@ __global__ void gemm_f32_kernel(const float* __restrict__ x, const float* __rest
 // with two workgroups per column group always wins; attention output 4.4 / 4.9 and 5.2 / 5.0; FFN down 7.8 / 9.4 and
 // 9.5 / 9.5).
 const hsd_kernel_tuning& default_kernel_tuning() {
-    static const hsd_kernel_tuning t = {{0, 0, 0, 0}, {0, 0, 0, 0}, 0, 0, 1, 2, 128, 1 << 30, 0, 256, 1, 0, 0};
+    static const hsd_kernel_tuning t = {{0, 0, 0, 0}, {0, 0, 0, 0}, 0, {0, 0, 0, 0}, 0, 1, 2, 128, 1 << 30, 0, 256, 1, 0, 0};
     return t;
 }
 
@@ -587,7 +594,7 @@ static bool use_wide_kernel(int m, const hsd_kernel_tuning& t) {
 }
 
 GemmPlan gemm_plan(int m, int n, int k, int epi, const hsd_kernel_tuning& t) {
-    GemmPlan p{1, 1, 8, 0, t.gemm_deep};
+    GemmPlan p{1, 1, 8, 0, t.gemm_deep, 0};
     const int mt = m <= 16 ? 1 : (m <= 32 ? 2 : 4);
     const int ntiles = ceil_div(n, 16), KT = k / 32;
     switch (epi) {
@@ -622,6 +629,29 @@ GemmPlan gemm_plan(int m, int n, int k, int epi, const hsd_kernel_tuning& t) {
     if (p.ksplit > 8) p.ksplit = 8;
     if (p.ksplit > KT) p.ksplit = KT;
     if (p.ksplit < 1) p.ksplit = 1;
+    // How the eight waves of a workgroup share its k-steps.  With a contiguous slice per wave a workgroup streams eight
+    // far-apart runs per tile; with the steps dealt round-robin to groups of four waves, the requests of a round are
+    // two contiguous 4 KB runs per tile, which the memory system serves faster once a workgroup's share of K is long
+    // (>= 4096: 16 KB or more per wave and tile) and the pass is a few rows (one row tile).  Measured at 1-8 rows:
+    // 70B-shaped gate/up 151 -> 136 us (6.9 TB/s), 128256 x 8192 head 337 -> 302, 128256 x 4096 head 163 -> 152,
+    // 8B-shaped gate/up 43.5 -> 38.5 and q/k/v 12.4 -> 11.3, 7B-shaped gate/up 35.2 -> 30.2 and q/k/v 23.0 -> 20.0,
+    // 70B-shaped attention output 24.6 -> 23.5; with the deeper load batches it gains less, so those go.  Groups of
+    // two or eight waves gain less or lose; shorter K (1B shape) is indifferent; the FFN down projections (K of 11008
+    // and more in one column tile) and passes of more than 16 rows lose up to 8 %, and keep the contiguous slices.
+    const int k_wg = k / p.ksplit;
+    if (t.gemm_interleave[epi]) {
+        p.interleave = t.gemm_interleave[epi] > 0 ? t.gemm_interleave[epi] : 1;
+    } else if (k_wg >= 4096 && m <= 16 && !p.halves) {
+        if (epi != EPI_RESID) {
+            p.interleave = 4;
+            if (!p.deep) p.deep = -1;
+        } else if (k <= 8192 && m <= 8) {
+            p.interleave = 4;
+        }
+    }
+    if (p.ksplit > 8) p.ksplit = 8;
+    if (p.ksplit > KT) p.ksplit = KT;
+    if (p.ksplit < 1) p.ksplit = 1;
     p.waves = 8;                 // always 512 threads: the epilogue addresses its elements by that stride
     return p;
 }
@@ -644,6 +674,7 @@ static void launch_inst(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     const int ntiles = ceil_div(g.N, 16);
     GemmArgs a = g;
     a.halves = p.halves && p.ksplit == 1;
+    a.interleave = p.interleave;
     dim3 grid(ceil_div(ntiles, NT) * (a.halves ? 2 : 1), p.ksplit);
     const bool deep = p.deep ? p.deep > 0 : (a.K / p.ksplit >= 4096 && a.K / p.ksplit < 8192);
     if (deep)

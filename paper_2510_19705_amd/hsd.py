@@ -46,7 +46,7 @@ class SiteTimes(C.Structure):
 
 class KernelTuning(C.Structure):
     """hsd_kernel_tuning (include/hsd_dev.h): launch heuristics of one model / one stand-alone call."""
-    _fields_ = [("gemm_nt", C.c_int * 4), ("gemm_ksplit", C.c_int * 4), ("gemm_deep", C.c_int),
+    _fields_ = [("gemm_nt", C.c_int * 4), ("gemm_ksplit", C.c_int * 4), ("gemm_deep", C.c_int), ("gemm_interleave", C.c_int * 4),
                 ("gemv_max_m_qkv", C.c_int), ("gemv_max_m_o", C.c_int), ("gemv_max_m_down", C.c_int),
                 ("halves_max_groups", C.c_int), ("attn_qt1_rows", C.c_int), ("attn_steps_per_wave", C.c_int),
                 ("attn_target_wgs", C.c_int), ("attn_fused_merge", C.c_int), ("wide_min_rows", C.c_int), ("wide_cols", C.c_int)]
@@ -158,11 +158,11 @@ def _check(rc):
 
 
 def kernel_tuning(**settings):
-    """The library's default launch heuristics with the given fields replaced (gemm_nt / gemm_ksplit: dict epilogue -> value)."""
+    """The library's default launch heuristics with the given fields replaced (gemm_nt / gemm_ksplit / gemm_interleave: dict epilogue -> value)."""
     k = KernelTuning()
     lib.hsd_kernel_tuning_default(C.byref(k))
     for name, v in settings.items():
-        if name in ("gemm_nt", "gemm_ksplit"):
+        if name in ("gemm_nt", "gemm_ksplit", "gemm_interleave"):
             for epi, val in v.items():
                 getattr(k, name)[epi] = val
         else:

@@ -272,6 +272,25 @@ def test_gemm_many_rows_other_formats(hsd, bf16, layout):
     assert np.abs(got - ref).max() < 4e-6 * np.sqrt(k) * np.abs(ref).max() + 1e-6
 
 
+@pytest.mark.parametrize("group", [1, 2, 4, 8])
+@pytest.mark.parametrize("m,n,k", [(1, 96, 32), (5, 200, 96), (3, 64, 7 * 32), (9, 130, 9 * 32), (16, 48, 130 * 32), (4, 2048, 4096),
+                                   (33, 96, 11 * 32), (64, 160, 19 * 32)])
+def test_gemm_wave_groups(hsd, m, n, k, group):
+    """How the eight waves of a workgroup share its 32-wide k-steps (contiguous slices, or round-robin inside groups of
+    2, 4 or 8 waves) must not change the product: k-step counts below, equal to and not divisible by the number of waves
+    and groups, one to four row tiles, with and without a split of K over workgroups."""
+    import torch
+    rng = np.random.default_rng(m + n + k)
+    x = inputs.bf16_round(rng.standard_normal((m, k)).astype(np.float32))
+    w = inputs.bf16_round((rng.standard_normal((n, k)) / np.sqrt(k)).astype(np.float32))
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    packed = hsd.pack_weight(_cuda(w, torch.bfloat16), hsd.BF16)
+    for ksplit in (0, 3):
+        tn = hsd.kernel_tuning(gemm_interleave={0: group if group > 1 else -1}, gemm_ksplit={0: ksplit})
+        got = hsd.gemm(_cuda(x, torch.bfloat16), packed, n, hsd.BF16, None, 0, tn).cpu().numpy()
+        assert np.abs(got - ref).max() < 4e-6 * np.sqrt(k) * np.abs(ref).max() + 1e-6, (group, ksplit)
+
+
 def test_gemm_split_k_exchange_repeated(hsd):
     """The split-K partial tiles travel through one reused workspace: 60 launches with fresh
     activations each must all match (a stale or early read of a partial would show up here)."""
