@@ -97,6 +97,7 @@ struct GemmArgs {
     float* part;                        // split-K partial tiles (ksplit > 1)
     size_t part_bytes;                  // capacity of `part`: a plan that needs more runs unsplit
     int* tickets;                       // one arrival counter per column group, zero between launches
+    int rotate;                         // set by the launcher: every workgroup walks its k-steps from its own offset (with interleave)
     int interleave;                     // set by the launcher from the plan: waves take the k-steps round-robin instead of contiguous slices
     int halves;                         // set by the launcher from the plan: workgroup b owns columns 8 (b & 1) .. + 8 of the tiles of group b >> 1
     // consumers of a normalised input: rows of `a` are x * w_norm, the 1/rms factor is applied in the epilogue

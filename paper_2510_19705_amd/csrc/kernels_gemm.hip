@@ -188,8 +188,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
     const int per = (kt1 - kt0 + ngroups - 1) / ngroups;
     const int gbeg = kt0 + (wave / kstep) * per, gend = min(kt1, gbeg + per);
     const int kb = gbeg + wave % kstep;
-    const int cnt = gend > kb ? (gend - kb + kstep - 1) / kstep : 0;
-    const int ke = kb + kstep * cnt;
+    const int cnt = gend > kb ? (gend - kb + kstep - 1) / kstep : 0;      // this wave's steps: kb, kb + kstep, ...
     const int row = lane & 15, grp = lane >> 4;
 
     f32x4 acc[MT][NT];
@@ -265,18 +264,27 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
     // Batches of U k-steps: all loads of a batch are issued before its MFMAs.  A last, partial batch requests its
     // missing steps at the wave's last tile again (cache hits) and feeds them zero activations, so that no step is
     // ever a load-wait-multiply round trip of its own.
-    for (int kt = kb; kt < ke; kt += U * kstep) {
+    // With the interleaved order every workgroup also starts its walk at its own offset (a hash of its column group):
+    // column groups lie a power of two apart in memory for the usual K, so workgroups that advance in step would
+    // otherwise ask the same few memory channels at the same moment, which is what held these launches at 6.2 TB/s.
+    const int rot = g.rotate && cnt > 0 ? (int)((blockIdx.x * 2654435761u >> 8) % (unsigned)cnt) : 0;
+    auto step_of = [&](int i) -> int {                 // the wave's i-th step, i < cnt
+        int ii = i + rot;
+        if (ii >= cnt) ii -= cnt;
+        return kb + kstep * ii;
+    };
+    for (int i0 = 0; i0 < cnt; i0 += U) {
         bf16x8 b[U][NT], a[U][MT];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int kk = min(kt + u * kstep, ke - kstep);
+            const int kk = step_of(min(i0 + u, cnt - 1));
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) b[u][nt] = load_b(nt, kk);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int kk = min(kt + u * kstep, ke - kstep);
-            const bool live = kt + u * kstep < ke;
+            const int kk = step_of(min(i0 + u, cnt - 1));
+            const bool live = i0 + u < cnt;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 const bf16x8 v = *reinterpret_cast<const bf16x8*>(ap[mt] + koff(kk));     // row 0 for lanes past M: always mapped
@@ -635,8 +643,9 @@ GemmPlan gemm_plan(int m, int n, int k, int epi, const hsd_kernel_tuning& t) {
     // (>= 4096: 16 KB or more per wave and tile) and the pass is a few rows (one row tile).  Measured at 1-8 rows:
     // 70B-shaped gate/up 151 -> 136 us (6.9 TB/s), 128256 x 8192 head 337 -> 302, 128256 x 4096 head 163 -> 152,
     // 8B-shaped gate/up 43.5 -> 38.5 and q/k/v 12.4 -> 11.3, 7B-shaped gate/up 35.2 -> 30.2 and q/k/v 23.0 -> 20.0,
-    // 70B-shaped attention output 24.6 -> 23.5; with the deeper load batches it gains less, so those go.  Groups of
-    // two or eight waves gain less or lose; shorter K (1B shape) is indifferent; the FFN down projections (K of 11008
+    // 70B-shaped attention output 24.6 -> 23.5; with the deeper load batches it gains less, so those go.  The kernel
+    // then also starts every workgroup's walk at its own offset (another 0.5-1 %).  Groups of two or eight waves gain
+    // less or lose; shorter K (1B shape) is indifferent; the FFN down projections (K of 11008
     // and more in one column tile) and passes of more than 16 rows lose up to 8 %, and keep the contiguous slices.
     const int k_wg = k / p.ksplit;
     if (t.gemm_interleave[epi]) {
@@ -675,6 +684,7 @@ static void launch_inst(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     GemmArgs a = g;
     a.halves = p.halves && p.ksplit == 1;
     a.interleave = p.interleave;
+    a.rotate = p.interleave > 1;
     dim3 grid(ceil_div(ntiles, NT) * (a.halves ? 2 : 1), p.ksplit);
     const bool deep = p.deep ? p.deep > 0 : (a.K / p.ksplit >= 4096 && a.K / p.ksplit < 8192);
     if (deep)

@@ -40,7 +40,8 @@ def trace(db, cmd, out, note="", by_grid=False):
             e[0] += 1
             e[1] += (en - st) / 1e3
         total = sum(v[1] for v in agg.values())
-        rows = [("%s [%s workgroups]" % (k[0].replace("bool _Accum", "bf16").split("(")[0], k[1]), v[0], v[1], v[1] / v[0], 100 * v[1] / total)
+        rows = [("%s [%s workgroups]" % (k[0].replace("bool _Accum", "bf16").replace("(anonymous namespace)::", "").split("(")[0], k[1]),
+                 v[0], v[1], v[1] / v[0], 100 * v[1] / total)
                 for k, v in sorted(agg.items(), key=lambda kv: -kv[1][1])]
     else:
         rows = list(cur.execute("select name, total_calls, total_duration, average, percentage from top_kernels"))
