@@ -607,8 +607,14 @@ GemmPlan gemm_plan(int m, int n, int k, int epi, const hsd_kernel_tuning& t) {
     const int ntiles = ceil_div(n, 16), KT = k / 32;
     switch (epi) {
         case EPI_ROPE: p.nt = 2; break;
-        case EPI_SWIGLU: p.nt = ntiles >= 4096 && mt <= 2 ? 4 : 2; break;
-        case EPI_RESID: p.nt = ntiles >= 2048 ? 2 : 1; break;
+        // from 16 rows on, four tiles per workgroup where that still leaves 448 workgroups: the activations cross the L2
+        // half as often (70B-shaped gate/up at 32 rows 193 -> 176 us, 8B-shaped 59.8 -> 48.9; the 7B shape, 344
+        // workgroups, loses)
+        case EPI_SWIGLU: p.nt = mt <= 2 && (ntiles >= 4096 || (m >= 16 && ntiles >= 1792)) ? 4 : 2; break;
+        // long K (the FFN down projections, the widest attention output): two column tiles per workgroup halve how often
+        // the activations (K values per row, re-read by every workgroup) cross the L2, which at 8 rows and K = 28672 is
+        // as many bytes as the weights (70B-shaped down 78.9 -> 70.1 us at 8 rows, 72.2 -> 70.6 at 4)
+        case EPI_RESID: p.nt = ntiles >= 2048 || (k >= 8192 && ntiles >= 256) ? 2 : 1; break;
         default: p.nt = ntiles >= 8192 && mt <= 2 ? 4 : (ntiles >= 1024 ? 2 : 1); break;
     }
     if (epi != EPI_ROPE && t.gemm_nt[epi]) p.nt = t.gemm_nt[epi];
@@ -617,11 +623,11 @@ GemmPlan gemm_plan(int m, int n, int k, int epi, const hsd_kernel_tuning& t) {
     // Splitting K across workgroups costs a round trip through memory for the partial tiles, which only pays for
     // plain stores of narrow matrices; the fused epilogues keep K inside the workgroup.
     // Two measured exceptions: a RoPE matrix of 128 MB or more in at most 384 groups (1.25-1.5 workgroups per CU:
-    // the uneven second round costs a third of the bandwidth; 4 slices even it out), and a residual matrix with at
+    // the uneven second round costs a third of the bandwidth; 3 slices, 4 above 8 rows, even it out), and a residual matrix with at
     // most 128 groups and K >= 8192 (half the CUs idle; 2 slices).
     const int groups = ceil_div(ntiles, p.nt);
     p.ksplit = epi == EPI_STORE ? (1024 + groups / 2) / groups : 1;
-    if (epi == EPI_ROPE && groups <= 384 && (size_t)n * k * 2 >= ((size_t)128 << 20)) p.ksplit = 4;
+    if (epi == EPI_ROPE && groups <= 384 && (size_t)n * k * 2 >= ((size_t)128 << 20)) p.ksplit = m <= 8 ? 3 : 4;
     if (epi == EPI_RESID && groups <= 128 && k >= 8192) p.ksplit = 2;
     // Narrow matrices (at most 128 column groups: half the CUs would idle) with few rows: two workgroups per group,
     // each owning 8 of the 16 columns of its tiles, instead of slices of K: twice the workgroups without an exchange
@@ -650,7 +656,7 @@ GemmPlan gemm_plan(int m, int n, int k, int epi, const hsd_kernel_tuning& t) {
     const int k_wg = k / p.ksplit;
     if (t.gemm_interleave[epi]) {
         p.interleave = t.gemm_interleave[epi] > 0 ? t.gemm_interleave[epi] : 1;
-    } else if (k_wg >= 4096 && m <= 16 && !p.halves) {
+    } else if (k_wg >= 4096 && (m <= 16 || (epi == EPI_SWIGLU && p.nt == 4 && m <= 32)) && !p.halves) {
         if (epi != EPI_RESID) {
             p.interleave = 4;
             if (!p.deep) p.deep = -1;
