@@ -693,10 +693,20 @@ static void launch_inst(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     a.rotate = p.interleave > 1;
     dim3 grid(ceil_div(ntiles, NT) * (a.halves ? 2 : 1), p.ksplit);
     const bool deep = p.deep ? p.deep > 0 : (a.K / p.ksplit >= 4096 && a.K / p.ksplit < 8192);
+    const size_t lds = gemm_lds_bytes(p, a.M, EPI);
+    // four row tiles x two column tiles of a residual projection need 72 KB: above 64 KB a kernel must be told once
+    if (lds > 64 * 1024) {
+        static bool told[2] = {false, false};
+        if (!told[deep]) {
+            const void* fn = deep ? (const void*)gemm_bf16_kernel<NT, MT, EPI, true> : (const void*)gemm_bf16_kernel<NT, MT, EPI, false>;
+            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess) told[deep] = true;
+            else (void)hipGetLastError();      // the launch below reports what is wrong, if anything
+        }
+    }
     if (deep)
-        gemm_bf16_kernel<NT, MT, EPI, true><<<grid, p.waves * 64, gemm_lds_bytes(p, a.M, EPI), s>>>(a);
+        gemm_bf16_kernel<NT, MT, EPI, true><<<grid, p.waves * 64, lds, s>>>(a);
     else
-        gemm_bf16_kernel<NT, MT, EPI, false><<<grid, p.waves * 64, gemm_lds_bytes(p, a.M, EPI), s>>>(a);
+        gemm_bf16_kernel<NT, MT, EPI, false><<<grid, p.waves * 64, lds, s>>>(a);
 }
 
 // Name of the kernel instance launch_gemm_bf16 runs for a plan, as a profiler prints it.
