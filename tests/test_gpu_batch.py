@@ -119,6 +119,33 @@ def test_batch_bf16_emits_the_targets_greedy_tokens():
     model.close()
 
 
+def test_batch_vocabulary_above_the_fused_sampler_limit():
+    """Vocabulary 33001: the sampler of every sequence is softmax + accept / resample as separate launches, their
+    results copied back per sequence.  Temperature 0, three ragged prompts (chosen with the oracle alone for a top-2
+    gap above 1.5e-3 on 24 tokens, T = (3, 2)): every sequence is the oracle's greedy stream."""
+    from paper_2510_19705_amd import hsd
+    shape = dict(n_layers=4, d=128, n_q=2, n_kv=2, hd=64, ffn=256, vocab=33001)
+    w = inputs.make_weights(shape, seed=71, bf16=False)
+    model = gpu_model(shape, w, False, max_seq=3 * 128, max_rows=64)
+    n, seqs = 24, [(30, 20), (33, 20), (34, 24)]
+    prompts, refs = [], []
+    for pseed, npr in seqs:
+        dec = oracle_decoder(shape, w, 128)
+        levels = [decoder.Level(dec, e, 0.0) for e in (1, 2, 4)]
+        prompt = [int(t) for t in inputs.make_prompt(shape["vocab"], npr, seed=pseed)]
+        refs.append(ohsd.HSD(levels, (3, 2), specsample.PhiloxChooser(1)).generate(prompt, n))
+        assert min(l.min_top2_gap for l in levels) > 1.5e-3, pseed
+        prompts.append(prompt)
+    h = hsd.BatchHierarchy([(model, 1), (model, 2), (model, 4)], (3, 2), 0.0, [1, 2, 3], 128)
+    h.prefill(prompts)
+    got, st = h.generate(n)
+    for b in range(3):
+        assert got[b].tolist() == refs[b], b
+    assert st.accepted[1] > 0 and st.accepted[2] > 0
+    h.close()
+    model.close()
+
+
 def test_batch_error_paths(tiny):
     from paper_2510_19705_amd import hsd
     _, model = tiny
