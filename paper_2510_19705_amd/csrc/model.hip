@@ -441,7 +441,11 @@ static int launch_site_bf16(hsd_model* m, int site, int l, int pos0, int rows, c
     bf16_t* kv_layer = (bf16_t*)(m->kv + m->kv_layer_bytes * l);
     // one or two tokens: some projections stream their row-major copies
     const hsd_kernel_tuning& tn = m->tuning;
-    const bool rowk = L.wqkv_rows && !bg && rows <= (site == HSD_SITE_QKV ? tn.gemv_max_m_qkv : (site == HSD_SITE_O ? tn.gemv_max_m_o : tn.gemv_max_m_down));
+    // (two tokens: only matrices below 64 MB, 1B-shaped down 9.4 against 11.1 us; on the 7B / 8B-shaped down projections the
+    // tile kernel is ahead, 19.9 / 23.3 against 23.1 / 25.3)
+    const size_t site_bytes = site == HSD_SITE_DOWN ? (size_t)d.d * d.ffn * 2 : (size_t)d.d * nq * 2;
+    const bool rowk = L.wqkv_rows && !bg && rows <= (site == HSD_SITE_QKV ? tn.gemv_max_m_qkv : (site == HSD_SITE_O ? tn.gemv_max_m_o : tn.gemv_max_m_down)) &&
+                      (rows == 1 || site_bytes <= ((size_t)64 << 20));
     GemmArgs g = {};
     g.M = rows; g.part = m->part; g.part_bytes = m->part_elems * sizeof(float); g.tickets = m->tickets; g.eps = d.eps;
     switch (site) {
