@@ -119,6 +119,33 @@ def test_batch_bf16_emits_the_targets_greedy_tokens():
     model.close()
 
 
+def test_batch_of_twenty_sequences():
+    """More sequences than one launch of the batched sampler takes (16): twenty short sequences, one drafter with T = 1,
+    temperature 0; every sequence is the target's greedy continuation (the oracle's top-2 gap is asserted per prompt,
+    prompts that do not have it are replaced by the next seed)."""
+    from paper_2510_19705_amd import hsd
+    w = inputs.make_weights(TINY, seed=1, bf16=False)
+    model = gpu_model(TINY, w, False, max_seq=20 * 128, max_rows=64)
+    n, prompts, refs, seed = 12, [], [], 100
+    while len(prompts) < 20:
+        dec = oracle_decoder(TINY, w, 64)
+        lvl = decoder.Level(dec, 8, 0.0)
+        prompt = [int(t) for t in inputs.make_prompt(TINY["vocab"], 8 + seed % 5, seed=seed)]
+        ref = ohsd.HSD([lvl], (), specsample.PhiloxChooser(1)).generate(prompt, n)
+        seed += 1
+        if lvl.min_top2_gap > 1.5e-3:
+            prompts.append(prompt)
+            refs.append(ref)
+    h = hsd.BatchHierarchy([(model, 2), (model, 8)], (1,), 0.0, list(range(20)), 128)
+    h.prefill(prompts)
+    got, st = h.generate(n)
+    for b in range(20):
+        assert got[b].tolist() == refs[b], b
+    assert st.tokens >= 20 * n and st.passes[1] <= n
+    h.close()
+    model.close()
+
+
 def test_batch_vocabulary_above_the_fused_sampler_limit():
     """Vocabulary 33001: the sampler of every sequence is softmax + accept / resample as separate launches, their
     results copied back per sequence.  Temperature 0, three ragged prompts (chosen with the oracle alone for a top-2
