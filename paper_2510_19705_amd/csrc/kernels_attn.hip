@@ -67,7 +67,9 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const bf16_t* __restrict
     constexpr int DT = HD / 16;   // 16-dim tiles of the output
     constexpr int RS = HD + 2;
     constexpr int NV = 8 * SP;    // scores per lane and query tile in one step
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
+    // the wave index is the same in all lanes: telling the compiler so keeps the page-table lookups and the step
+    // arithmetic on the scalar unit
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), NW = blockDim.x >> 6;
     const int j = lane & 15, grp = lane >> 4;
     // One-dimensional grid, decoded so that the query groups of one (sequence, KV head, split) unit sit 8 apart in
     // launch order: workgroups go to the 8 XCDs round-robin, so those groups land on the same XCD one after the
@@ -389,7 +391,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
                                                          int nsplit, int rpad, int M, int n_q, int n_kv, int hd,
                                                          T* __restrict__ att) {
     __shared__ float4 sh_acc[4][64];
-    const int r = blockIdx.x, g = blockIdx.y, b = blockIdx.z, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = blockIdx.x, g = blockIdx.y, b = blockIdx.z, tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int group = n_q / n_kv, i = r / group, hq = r % group;
     const size_t base = ((size_t)b * n_kv + g) * nsplit;
     const int nvec = hd >> 2;                          // float4 chunks of a row, at most 64

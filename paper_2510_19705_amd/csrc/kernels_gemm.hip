@@ -167,7 +167,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(const GemmArgs g) {
     constexpr int UB = (DEEP ? 16 : 8) / (NT * MT);
     constexpr int U = UB > 8 ? 8 : (UB > 0 ? UB : 1);                // k-steps whose loads are issued together
     constexpr int TOTAL = MT * NT * 256;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = blockDim.x >> 6;
     const int M = g.M, N = g.N, K = g.K;
     const int KT = K >> 5;
     const int ntiles = (N + 15) >> 4;
@@ -435,7 +435,7 @@ __global__ __launch_bounds__(512) void gemv_bf16_kernel(const GemmArgs g) {
     constexpr int LPR = 64 / R;                        // lanes per weight row
     __shared__ float red[8][R][MB];
     __shared__ float sq[R][MB];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = blockDim.x >> 6;
     const int M = g.M, N = g.N, K = g.K;
     const int KC = K >> 3;                             // 16-byte chunks per row
     const int n0 = blockIdx.x * R;
