@@ -45,7 +45,7 @@ int hsd_site_kernel(const hsd_model*, int site, int rows, char* name_out, int ca
  * default keeps the heuristic.
  * ------------------------------------------------------------------------------------------- */
 typedef struct {
-    int gemm_nt[4];          /* per epilogue kind (0 store, 1 residual, 2 SwiGLU, 3 RoPE; RoPE ignores it): 16-column tiles
+    int gemm_nt[4];          /* per epilogue kind (0 store, 1 residual, 2 SwiGLU, 3 RoPE: 2 or 4 only): 16-column tiles
                                 per workgroup of the tiled GEMM, 0 = heuristic */
     int gemm_ksplit[4];      /* per epilogue kind: workgroups along K (partial tiles exchanged through memory), 0 = heuristic */
     int gemm_deep;           /* 1 / -1: twice / once the loads per batch whatever K; 0 = by K */

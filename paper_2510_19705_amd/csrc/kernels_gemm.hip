@@ -606,7 +606,11 @@ GemmPlan gemm_plan(int m, int n, int k, int epi, const hsd_kernel_tuning& t) {
     const int mt = m <= 16 ? 1 : (m <= 32 ? 2 : 4);
     const int ntiles = ceil_div(n, 16), KT = k / 32;
     switch (epi) {
-        case EPI_ROPE: p.nt = 2; break;
+        // wide q/k/v matrices (640 tiles and more: the 7B and 70B shapes) in passes of few rows: two rotary pairs per
+        // workgroup and no K split, 160-192 workgroups that each stream 0.5-1 MB in the interleaved order, instead of
+        // 384-960 short ones (70B-shaped 31.6 -> 28.8 us at one row, 32.6 -> 30.6 at four; 7B-shaped 23.8 -> 21.1 at 16);
+        // with K = 8192 it loses from 12 rows on, with 384 tiles (8B shape) or fewer at every row count
+        case EPI_ROPE: p.nt = mt <= 2 && ntiles >= 640 && (m <= 8 || k <= 4096) ? 4 : 2; break;
         // from 16 rows on, four tiles per workgroup where that still leaves 448 workgroups: the activations cross the L2
         // half as often (70B-shaped gate/up at 32 rows 193 -> 176 us, 8B-shaped 59.8 -> 48.9; the 7B shape, 344
         // workgroups, loses)
@@ -617,7 +621,7 @@ GemmPlan gemm_plan(int m, int n, int k, int epi, const hsd_kernel_tuning& t) {
         case EPI_RESID: p.nt = ntiles >= 2048 || (k >= 8192 && ntiles >= 256) ? 2 : 1; break;
         default: p.nt = ntiles >= 8192 && mt <= 2 ? 4 : (ntiles >= 1024 ? 2 : 1); break;
     }
-    if (epi != EPI_ROPE && t.gemm_nt[epi]) p.nt = t.gemm_nt[epi];
+    if (t.gemm_nt[epi] && (epi != EPI_ROPE || t.gemm_nt[epi] == 2 || (t.gemm_nt[epi] == 4 && mt <= 2))) p.nt = t.gemm_nt[epi];
     if (mt == 4 && p.nt > 2) p.nt = 2;
     // about a thousand workgroups: every CU must be pulling for the HBM stream to reach its peak
     // Splitting K across workgroups costs a round trip through memory for the partial tiles, which only pays for
@@ -627,7 +631,7 @@ GemmPlan gemm_plan(int m, int n, int k, int epi, const hsd_kernel_tuning& t) {
     // most 128 groups and K >= 8192 (half the CUs idle; 2 slices).
     const int groups = ceil_div(ntiles, p.nt);
     p.ksplit = epi == EPI_STORE ? (1024 + groups / 2) / groups : 1;
-    if (epi == EPI_ROPE && groups <= 384 && (size_t)n * k * 2 >= ((size_t)128 << 20)) p.ksplit = m <= 8 ? 3 : 4;
+    if (epi == EPI_ROPE && p.nt == 2 && groups <= 384 && (size_t)n * k * 2 >= ((size_t)128 << 20)) p.ksplit = m <= 8 ? 3 : 4;
     if (epi == EPI_RESID && groups <= 128 && k >= 8192) p.ksplit = 2;
     // Narrow matrices (at most 128 column groups: half the CUs would idle) with few rows: two workgroups per group,
     // each owning 8 of the 16 columns of its tiles, instead of slices of K: twice the workgroups without an exchange
@@ -742,7 +746,7 @@ int launch_gemm_bf16(const GemmArgs& g, int epi, const GemmPlan& plan, hipStream
     HSD_MTS(1, EPI_STORE) HSD_MTS(2, EPI_STORE) HSD_CASE(4, 1, EPI_STORE) HSD_CASE(4, 2, EPI_STORE)
     HSD_MTS(1, EPI_RESID) HSD_MTS(2, EPI_RESID)
     HSD_MTS(2, EPI_SWIGLU) HSD_CASE(4, 1, EPI_SWIGLU) HSD_CASE(4, 2, EPI_SWIGLU)
-    HSD_MTS(2, EPI_ROPE)
+    HSD_MTS(2, EPI_ROPE) HSD_CASE(4, 1, EPI_ROPE) HSD_CASE(4, 2, EPI_ROPE)
 #undef HSD_MTS
 #undef HSD_CASE
     HSD_FAIL(HSD_EINVAL, "gemm: no kernel for nt=%d m=%d epilogue=%d", p.nt, g.M, epi);
