@@ -655,8 +655,8 @@ GemmPlan gemm_plan(int m, int n, int k, int epi, const hsd_kernel_tuning& t) {
     // 8B-shaped gate/up 43.5 -> 38.5 and q/k/v 12.4 -> 11.3, 7B-shaped gate/up 35.2 -> 30.2 and q/k/v 23.0 -> 20.0,
     // 70B-shaped attention output 24.6 -> 23.5; with the deeper load batches it gains less, so those go.  The kernel
     // then also starts every workgroup's walk at its own offset (another 0.5-1 %).  Groups of two or eight waves gain
-    // less or lose; shorter K (1B shape) is indifferent; the FFN down projections (K of 11008
-    // and more in one column tile) and passes of more than 16 rows lose up to 8 %, and keep the contiguous slices.
+    // less or lose; shorter K (1B shape) is indifferent; passes of more than 16 rows lose up to 8 % and keep the
+    // contiguous slices, as does the longest residual projection (K = 28672) from five rows on.
     const int k_wg = k / p.ksplit;
     if (t.gemm_interleave[epi]) {
         p.interleave = t.gemm_interleave[epi] > 0 ? t.gemm_interleave[epi] : 1;
@@ -664,7 +664,9 @@ GemmPlan gemm_plan(int m, int n, int k, int epi, const hsd_kernel_tuning& t) {
         if (epi != EPI_RESID) {
             p.interleave = 4;
             if (!p.deep) p.deep = -1;
-        } else if (k <= 8192 && m <= 8) {
+        } else if (m <= 4 || (m <= 8 && k <= 16384) || (k >= 8192 && k <= 16384)) {
+            // residual projections: every K up to four rows (70B-shaped down 70.7 -> 70.1 us), K up to 16384 up to eight
+            // (7B-shaped down 20.4 -> 19.3), 8192..16384 up to sixteen; beyond, the contiguous slices are ahead
             p.interleave = 4;
         }
     }
